@@ -1,0 +1,382 @@
+/*
+ * CPU oracle for the PBSA decode path of "Sparse Forcing" -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, obviously-correct loops written from the paper.  Nothing in the product path may
+ * call this file; it shares no code with the HIP kernels.  Only tests, the smoke check and the
+ * cpu_baseline leg of the benchmark use it.
+ *
+ * Precision.  Everything that decides an integer (pooled representatives, coarse logits, the
+ * persistence scores) is computed in IEEE fp32 in a fixed operation order, because the block
+ * sets and slot assignments it produces are compared bit-for-bit with the GPU:
+ *   pool      acc = acc + x[t] over valid tokens t ascending from 0.0f, then acc / (float)len
+ *   dot       acc = fmaf(q[x], k[x], acc) over x ascending from 0.0f, then acc * scale
+ *   softmax   m = exact max; e = pexp(z - m); sum = sum + e over j ascending; a = e / sum
+ *   col mean  acc = acc + a[i][j] over i ascending, then acc / (float)nqb
+ *   fold      S_sum = S_sum + x over losing blocks in candidate order
+ * (compile with -ffp-contract=off, no fast-math).  The fine attention itself, whose output is
+ * only compared within a tolerance, is computed in fp64.
+ *
+ * Layouts (all host pointers, all dense):
+ *   Q            [H][Nq][d]              bf16 bits, token-major; query block i = tokens iB..iB+len_i-1
+ *   Kl, Vl       [H][n_loc_cap][B][d]    bf16 bits, physical local slots (ring)
+ *   l_map        [n_loc]                 logical local block (oldest first, chunk last) -> physical slot
+ *   l_len, l_id  [n_loc]                 valid tokens / global id of each logical local block
+ *   Kc_l         [H][n_loc_cap][d]       fp32 pooled keys by physical slot
+ *   Kp, Vp       [H][C+1][B][d]          bf16 bits, persistent slots; slot C is the summary block
+ *   p_len        [H][C+1]                valid tokens per slot, 0 = empty
+ *   Kc_p, p_id   [H][C][d] fp32, [H][C] int64
+ *   S_sum, S_cnt [H][2][B][d] fp32 (K then V), [H][B] int32
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct orc_cfg {
+  int32_t H, d, B;        /* heads, head dim, tokens per block                                  */
+  int32_t Nq, nqb;        /* chunk tokens, ceil(Nq/B)                                           */
+  int32_t n_loc;          /* logical local blocks incl. the chunk's nqb (chunk = last nqb)      */
+  int32_t n_loc_cap;      /* physical local slots per head                                      */
+  int32_t C, n_sink;      /* persistent slots (summary = slot C), pinned leading slots          */
+  int32_t k;              /* local blocks selected per query block                              */
+  int32_t causal;         /* 1: query block i sees local blocks 0..n_loc-nqb+i ; 0: all         */
+  int32_t n_evict;        /* leading local blocks leaving the window at this update             */
+  int32_t pool_from;      /* pooled keys of logical blocks >= pool_from are recomputed          */
+  float scale;            /* 1/sqrt(d)                                                          */
+} orc_cfg;
+
+static inline float bf2f(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+static inline uint16_t f2bf(float f) { /* round to nearest even; inputs are finite */
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+/* exp(x) for x <= 0, built from fp32 mul / fma / round-to-nearest-integer only, so that another
+ * implementation of the same steps gives the same bits.  x < -64 gives exactly 0.
+ *   n = rint(x * log2e); r = x - n*ln2 (two-constant split); p = degree-6 Taylor of e^r by
+ *   Horner; result = p * 2^n. */
+float orc_pexp(float x) {
+  if (x < -64.0f) return 0.0f;
+  float n = rintf(x * 0x1.715476p+0f);
+  float r = fmaf(n, -0x1.630000p-1f, x);   /* 0.693359375, exact product */
+  r = fmaf(n, 0x1.bd0106p-13f, r);         /* + n * 2.12194440e-4        */
+  float p = 0x1.6c16c2p-10f;               /* 1/720 */
+  p = fmaf(p, r, 0x1.111112p-7f);          /* 1/120 */
+  p = fmaf(p, r, 0x1.555556p-5f);          /* 1/24  */
+  p = fmaf(p, r, 0x1.555556p-3f);          /* 1/6   */
+  p = fmaf(p, r, 0.5f);
+  p = fmaf(p, r, 1.0f);
+  p = fmaf(p, r, 1.0f);
+  uint32_t sb = (uint32_t)((int32_t)n + 127) << 23;
+  float s;
+  memcpy(&s, &sb, 4);
+  return p * s;
+}
+
+/* Block representative by average pooling (Eq. 6 with the pooling operator of Sec. 4.1):
+ * mean over the block's valid tokens, per dimension.  rows: [len][d] bf16 with row pitch d. */
+void orc_pool_block(const uint16_t* rows, int len, int d, float* out) {
+  for (int x = 0; x < d; ++x) {
+    float acc = 0.0f;
+    for (int t = 0; t < len; ++t) acc = acc + bf2f(rows[(size_t)t * d + x]);
+    out[x] = len > 0 ? acc / (float)len : 0.0f;
+  }
+}
+
+static inline int q_block_len(const orc_cfg* c, int i) {
+  int rem = c->Nq - i * c->B;
+  return rem < c->B ? rem : c->B;
+}
+
+static inline int n_visible(const orc_cfg* c, int i) {
+  return c->causal ? c->n_loc - c->nqb + i + 1 : c->n_loc;
+}
+
+static inline float dot_scaled(const float* q, const float* k, int d, float scale) {
+  float acc = 0.0f;
+  for (int x = 0; x < d; ++x) acc = fmaf(q[x], k[x], acc);
+  return acc * scale;
+}
+
+/* Coarse routing inside the local region (Eq. 10-11): pooled representatives, scaled block
+ * logits, row-wise top-k with ties going to the lowest block index.  Softmax is monotone per
+ * row, so the top-k of the logits is the top-k of Eq. 10's probabilities.
+ * Z (optional, [H][nqb][n_loc]) receives the logits; entries not visible are set to -INFINITY.
+ * sel [H][nqb][k]: selected logical local blocks in ascending order, padded with -1. */
+int orc_select(const orc_cfg* c, const uint16_t* Q, const uint16_t* Kl, const int32_t* l_len,
+               const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Z) {
+  const int d = c->d, B = c->B;
+  float* z = (float*)malloc(sizeof(float) * (size_t)(c->n_loc > 0 ? c->n_loc : 1));
+  char* taken = (char*)malloc((size_t)(c->n_loc > 0 ? c->n_loc : 1));
+  if (!z || !taken) return -1;
+  for (int h = 0; h < c->H; ++h) {
+    for (int l = c->pool_from; l < c->n_loc; ++l) {
+      size_t slot = (size_t)h * c->n_loc_cap + l_map[l];
+      orc_pool_block(Kl + slot * B * d, l_len[l], d, Kc_l + slot * d);
+    }
+    for (int i = 0; i < c->nqb; ++i) {
+      float* qc = Qc + ((size_t)h * c->nqb + i) * d;
+      orc_pool_block(Q + ((size_t)h * c->Nq + (size_t)i * B) * d, q_block_len(c, i), d, qc);
+      const int nvis = n_visible(c, i);
+      for (int l = 0; l < c->n_loc; ++l) {
+        const float* kc = Kc_l + ((size_t)h * c->n_loc_cap + l_map[l]) * d;
+        z[l] = l < nvis ? dot_scaled(qc, kc, d, c->scale) : -INFINITY;
+        if (Z) Z[((size_t)h * c->nqb + i) * c->n_loc + l] = z[l];
+      }
+      memset(taken, 0, (size_t)c->n_loc);
+      const int kk = c->k < nvis ? c->k : nvis;
+      for (int r = 0; r < kk; ++r) {
+        int best = -1;
+        for (int l = 0; l < nvis; ++l)
+          if (!taken[l] && (best < 0 || z[l] > z[best])) best = l; /* strict >: lowest index wins ties */
+        taken[best] = 1;
+      }
+      int32_t* out = sel + ((size_t)h * c->nqb + i) * c->k;
+      int n = 0;
+      for (int l = 0; l < nvis; ++l)
+        if (taken[l]) out[n++] = l;
+      for (; n < c->k; ++n) out[n] = -1;
+    }
+  }
+  free(z);
+  free(taken);
+  return 0;
+}
+
+/* PBSA fine stage (Eq. 3-5) for a list of query rows: one softmax over every valid token of the
+ * occupied persistent slots (0..C, the summary slot included) and every valid token of the local
+ * blocks in the row's block set; everything else is masked out.  fp64 throughout.
+ * rows_h/rows_t [n_rows]: head and chunk-token index of each requested row.
+ * O [n_rows][d] fp64; lse [n_rows] fp64 (natural log of the softmax normaliser), may be NULL.
+ * A row that sees no key at all gets O = 0 and lse = -INFINITY. */
+int orc_attention_rows(const orc_cfg* c, const uint16_t* Q, const uint16_t* Kp, const uint16_t* Vp,
+                       const int32_t* p_len, const uint16_t* Kl, const uint16_t* Vl,
+                       const int32_t* l_len, const int32_t* l_map, const int32_t* sel, int64_t n_rows,
+                       const int32_t* rows_h, const int32_t* rows_t, double* O, double* lse) {
+  const int d = c->d, B = c->B;
+  const size_t max_keys = (size_t)(c->C + 1 + c->k) * B + 1;
+  int fail = 0;
+#pragma omp parallel
+  {
+    double* z = (double*)malloc(sizeof(double) * max_keys);
+    const uint16_t** vrow = (const uint16_t**)malloc(sizeof(void*) * max_keys);
+    double* q = (double*)malloc(sizeof(double) * (size_t)d);
+    if (!z || !vrow || !q) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 16)
+      for (int64_t r = 0; r < n_rows; ++r) {
+        const int h = rows_h[r], t = rows_t[r], i = t / B;
+        const uint16_t* qrow = Q + ((size_t)h * c->Nq + t) * d;
+        for (int x = 0; x < d; ++x) q[x] = (double)bf2f(qrow[x]);
+        size_t n = 0;
+        for (int s = 0; s <= c->C; ++s) {
+          const int len = p_len[(size_t)h * (c->C + 1) + s];
+          const size_t base = ((size_t)h * (c->C + 1) + s) * B * d;
+          for (int u = 0; u < len; ++u) {
+            const uint16_t* krow = Kp + base + (size_t)u * d;
+            double acc = 0.0;
+            for (int x = 0; x < d; ++x) acc += q[x] * (double)bf2f(krow[x]);
+            z[n] = acc * (double)c->scale;
+            vrow[n++] = Vp + base + (size_t)u * d;
+          }
+        }
+        const int32_t* row_sel = sel + ((size_t)h * c->nqb + i) * c->k;
+        for (int j = 0; j < c->k; ++j) {
+          const int l = row_sel[j];
+          if (l < 0) continue;
+          const size_t base = ((size_t)h * c->n_loc_cap + l_map[l]) * B * d;
+          for (int u = 0; u < l_len[l]; ++u) {
+            const uint16_t* krow = Kl + base + (size_t)u * d;
+            double acc = 0.0;
+            for (int x = 0; x < d; ++x) acc += q[x] * (double)bf2f(krow[x]);
+            z[n] = acc * (double)c->scale;
+            vrow[n++] = Vl + base + (size_t)u * d;
+          }
+        }
+        double* o = O + (size_t)r * d;
+        for (int x = 0; x < d; ++x) o[x] = 0.0;
+        if (n == 0) {
+          if (lse) lse[r] = -INFINITY;
+          continue;
+        }
+        double m = z[0];
+        for (size_t j = 1; j < n; ++j) m = z[j] > m ? z[j] : m;
+        double sum = 0.0;
+        for (size_t j = 0; j < n; ++j) {
+          z[j] = exp(z[j] - m);
+          sum += z[j];
+        }
+        for (size_t j = 0; j < n; ++j) {
+          const double p = z[j] / sum;
+          const uint16_t* v = vrow[j];
+          for (int x = 0; x < d; ++x) o[x] += p * (double)bf2f(v[x]);
+        }
+        if (lse) lse[r] = m + log(sum);
+      }
+    }
+    free(z);
+    free(vrow);
+    free(q);
+  }
+  return fail ? -1 : 0;
+}
+
+/* Coarse scoring for persistence (Eq. 7-8): block-level softmax of every query block over
+ * U = occupied persistent slots 0..C-1 (slot order) followed by all n_loc local blocks (no
+ * causal or top-k mask), then the mean over query blocks.
+ * s_p [H][C] (0 for empty slots), s_l [H][n_loc]. */
+int orc_scores(const orc_cfg* c, const float* Qc, const float* Kc_l, const int32_t* l_map,
+               const float* Kc_p, const int32_t* p_len, float* s_p, float* s_l) {
+  const int d = c->d, nU_max = c->C + c->n_loc;
+  const float** kc = (const float**)malloc(sizeof(void*) * (size_t)(nU_max > 0 ? nU_max : 1));
+  float* e = (float*)malloc(sizeof(float) * (size_t)(nU_max > 0 ? nU_max : 1));
+  float* col = (float*)malloc(sizeof(float) * (size_t)(nU_max > 0 ? nU_max : 1));
+  if (!kc || !e || !col) return -1;
+  for (int h = 0; h < c->H; ++h) {
+    int nU = 0;
+    for (int s = 0; s < c->C; ++s)
+      if (p_len[(size_t)h * (c->C + 1) + s] > 0) kc[nU++] = Kc_p + ((size_t)h * c->C + s) * d;
+    for (int l = 0; l < c->n_loc; ++l) kc[nU++] = Kc_l + ((size_t)h * c->n_loc_cap + l_map[l]) * d;
+    for (int j = 0; j < nU; ++j) col[j] = 0.0f;
+    for (int i = 0; i < c->nqb; ++i) {
+      const float* qc = Qc + ((size_t)h * c->nqb + i) * d;
+      float m = -INFINITY;
+      for (int j = 0; j < nU; ++j) {
+        e[j] = dot_scaled(qc, kc[j], d, c->scale);
+        m = e[j] > m ? e[j] : m;
+      }
+      float sum = 0.0f;
+      for (int j = 0; j < nU; ++j) {
+        e[j] = orc_pexp(e[j] - m);
+        sum = sum + e[j];
+      }
+      for (int j = 0; j < nU; ++j) col[j] = col[j] + e[j] / sum;
+    }
+    int j = 0;
+    for (int s = 0; s < c->C; ++s)
+      s_p[(size_t)h * c->C + s] = p_len[(size_t)h * (c->C + 1) + s] > 0 ? col[j++] / (float)c->nqb : 0.0f;
+    for (int l = 0; l < c->n_loc; ++l) s_l[(size_t)h * c->n_loc + l] = col[j++] / (float)c->nqb;
+  }
+  free(kc);
+  free(e);
+  free(col);
+  return 0;
+}
+
+/* Persistent-memory update (Eq. 9 and its footnote, plus the compressed-history block):
+ *  - candidates = occupants of slots n_sink..C-1 (slot order) then the n_evict leading local
+ *    blocks (block order); the top C-n_sink by (score desc, candidate index asc) are kept;
+ *  - a kept occupant stays in its slot; kept newcomers, in ascending block order, fill the vacated
+ *    and empty slots in ascending slot order (K, V, pooled key, len and id move with the block);
+ *  - every dropped candidate is folded, position by position, into the running mean kept as
+ *    S_sum / S_cnt, whose bf16 view becomes slot C (skipped when S_sum is NULL).
+ * scores [H][C+n_evict] (optional): score of slot 0..C-1 (0 if empty) then of each evicted block.
+ * slot_src [H][C]: -1 = slot unchanged, e >= 0 = filled from local block e. */
+int orc_memory_update(const orc_cfg* c, const float* Qc, const float* Kc_l, uint16_t* Kp, uint16_t* Vp,
+                      float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                      const uint16_t* Kl, const uint16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                      const int64_t* l_id, float* scores, int32_t* slot_src) {
+  const int d = c->d, B = c->B, C = c->C, C1 = c->C + 1;
+  const size_t blk = (size_t)B * d;
+  float* s_p = (float*)malloc(sizeof(float) * (size_t)(c->H * C + 1));
+  float* s_l = (float*)malloc(sizeof(float) * (size_t)(c->H * c->n_loc + 1));
+  const int ncand_max = C + c->n_evict;
+  int* cand = (int*)malloc(sizeof(int) * (size_t)(ncand_max + 1));   /* <C: slot, else C+e */
+  float* cs = (float*)malloc(sizeof(float) * (size_t)(ncand_max + 1));
+  char* win = (char*)malloc((size_t)(ncand_max + 1));
+  if (!s_p || !s_l || !cand || !cs || !win) return -1;
+  if (orc_scores(c, Qc, Kc_l, l_map, Kc_p, p_len, s_p, s_l)) return -1;
+  for (int h = 0; h < c->H; ++h) {
+    int32_t* plen = p_len + (size_t)h * C1;
+    if (scores) {
+      for (int s = 0; s < C; ++s) scores[(size_t)h * ncand_max + s] = s_p[(size_t)h * C + s];
+      for (int e = 0; e < c->n_evict; ++e) scores[(size_t)h * ncand_max + C + e] = s_l[(size_t)h * c->n_loc + e];
+    }
+    int nc = 0;
+    for (int s = c->n_sink; s < C; ++s)
+      if (plen[s] > 0) { cand[nc] = s; cs[nc++] = s_p[(size_t)h * C + s]; }
+    for (int e = 0; e < c->n_evict; ++e) { cand[nc] = C + e; cs[nc++] = s_l[(size_t)h * c->n_loc + e]; }
+    const int places = C - c->n_sink;
+    for (int a = 0; a < nc; ++a) {
+      int rank = 0;
+      for (int b = 0; b < nc; ++b)
+        if (cs[b] > cs[a] || (cs[b] == cs[a] && b < a)) ++rank;
+      win[a] = rank < places;
+    }
+    /* fold the losers first: their data is read before any slot is overwritten */
+    if (S_sum) {
+      float* ssum = S_sum + (size_t)h * 2 * blk;
+      int32_t* scnt = S_cnt + (size_t)h * B;
+      int any = 0;
+      for (int a = 0; a < nc; ++a) {
+        if (win[a]) continue;
+        any = 1;
+        const uint16_t *kb, *vb;
+        int len;
+        if (cand[a] < C) {
+          kb = Kp + ((size_t)h * C1 + cand[a]) * blk;
+          vb = Vp + ((size_t)h * C1 + cand[a]) * blk;
+          len = plen[cand[a]];
+        } else {
+          const int e = cand[a] - C;
+          kb = Kl + ((size_t)h * c->n_loc_cap + l_map[e]) * blk;
+          vb = Vl + ((size_t)h * c->n_loc_cap + l_map[e]) * blk;
+          len = l_len[e];
+        }
+        for (int t = 0; t < len; ++t) {
+          for (int x = 0; x < d; ++x) {
+            ssum[(size_t)t * d + x] = ssum[(size_t)t * d + x] + bf2f(kb[(size_t)t * d + x]);
+            ssum[blk + (size_t)t * d + x] = ssum[blk + (size_t)t * d + x] + bf2f(vb[(size_t)t * d + x]);
+          }
+          scnt[t] += 1;
+        }
+      }
+      if (any) {
+        int n = 0;
+        for (int t = 0; t < B; ++t) {
+          if (scnt[t] <= 0) continue;
+          ++n;
+          for (int x = 0; x < d; ++x) {
+            Kp[((size_t)h * C1 + C) * blk + (size_t)t * d + x] = f2bf(ssum[(size_t)t * d + x] / (float)scnt[t]);
+            Vp[((size_t)h * C1 + C) * blk + (size_t)t * d + x] = f2bf(ssum[blk + (size_t)t * d + x] / (float)scnt[t]);
+          }
+        }
+        plen[C] = n;
+      }
+    }
+    /* slot assignment */
+    int32_t* src = slot_src + (size_t)h * C;
+    for (int s = 0; s < C; ++s) src[s] = -1;
+    for (int a = 0; a < nc; ++a)
+      if (!win[a] && cand[a] < C) plen[cand[a]] = 0;   /* vacate */
+    int s = c->n_sink;
+    for (int a = 0; a < nc; ++a) {
+      if (!win[a] || cand[a] < C) continue;
+      const int e = cand[a] - C;
+      while (s < C && plen[s] > 0) ++s;
+      if (s >= C) return -2;                           /* cannot happen: winners <= places */
+      const size_t from = ((size_t)h * c->n_loc_cap + l_map[e]) * blk;
+      const size_t to = ((size_t)h * C1 + s) * blk;
+      memcpy(Kp + to, Kl + from, blk * sizeof(uint16_t));
+      memcpy(Vp + to, Vl + from, blk * sizeof(uint16_t));
+      memcpy(Kc_p + ((size_t)h * C + s) * d, Kc_l + ((size_t)h * c->n_loc_cap + l_map[e]) * d, sizeof(float) * (size_t)d);
+      plen[s] = l_len[e];
+      p_id[(size_t)h * C + s] = l_id[e];
+      src[s] = e;
+    }
+    for (int q = c->n_sink; q < C; ++q)
+      if (plen[q] == 0) p_id[(size_t)h * C + q] = -1;
+  }
+  free(s_p); free(s_l); free(cand); free(cs); free(win);
+  return 0;
+}

@@ -1,0 +1,416 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU needed).
+
+The paper prints no worked numeric example for any PBSA step, so every pin below is a closed
+form, an invariant, a special case that reduces to a textbook routine coded here independently
+in numpy fp64, or brute force on tiny inputs.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle.rollout import OracleState
+from paper_2604_21221_amd import synth
+
+
+def bf(x):
+    return synth.to_bf16_bits(x)
+
+
+def f32(bits):
+    return synth.bf16_bits_to_f32(bits)
+
+
+def rnd(key, *shape):
+    return synth.normals(synth.stream_key(1234, "misc", key), int(np.prod(shape))).reshape(shape)
+
+
+def make_state(seed=0, H=2, d=16, B=8, Nq=20, w=2, C=3, k=2, n_sink=0, causal=1, p_lens=None, fill_chunks=None,
+               fold=True):
+    """Small random problem: window of `w` chunks + the current chunk, C persistent slots (ragged lens)."""
+    st = OracleState(H, d, B, Nq, w, C, k, 1.0 / math.sqrt(d), n_sink=n_sink, causal=causal, fold=fold)
+    nqb = st.nqb
+    lens = np.full(nqb, B, np.int32)
+    lens[-1] = Nq - (nqb - 1) * B
+    if C > 0:
+        Kp = bf(rnd(seed * 100 + 1, H, C, B, d))
+        Vp = bf(rnd(seed * 100 + 2, H, C, B, d))
+        pl = np.full((H, C), B, np.int32) if p_lens is None else np.asarray(p_lens, np.int32)
+        st.set_persistent(Kp, Vp, pl, -100 - np.arange(C)[None, :].repeat(H, 0))
+    n_chunks = (w + 1) if fill_chunks is None else fill_chunks
+    Q = None
+    for g in range(n_chunks):
+        K = bf(rnd(seed * 100 + 10 + 3 * g, H, Nq, d))
+        V = bf(rnd(seed * 100 + 11 + 3 * g, H, Nq, d))
+        Q = bf(rnd(seed * 100 + 12 + 3 * g, H, Nq, d))
+        st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * nqb + np.arange(nqb))
+    return st, Q
+
+
+# ------------------------------------------------------------------------------------------------
+# independent numpy references
+# ------------------------------------------------------------------------------------------------
+def ref_pooled(st, Q):
+    """fp64 pooled representatives: Qc [H][nqb][d], Kc [H][n_loc][d] (logical order)."""
+    l_map, l_len, _ = st._maps()
+    Qf = f32(Q).astype(np.float64)
+    Qc = np.stack([[Qf[h, i * st.B:min((i + 1) * st.B, st.Nq)].mean(0) for i in range(st.nqb)] for h in range(st.H)])
+    Kf = f32(st.Kl).astype(np.float64)
+    Kc = np.stack([[Kf[h, l_map[l], :l_len[l]].mean(0) for l in range(st.n_loc)] for h in range(st.H)])
+    return Qc, Kc
+
+
+def ref_dense_attention(st, Q, sel):
+    """softmax(Q K^T * scale + M) V with the mask matrix of Eq. 5 written out explicitly (fp64)."""
+    l_map, l_len, _ = st._maps()
+    out = np.zeros((st.H, st.Nq, st.d))
+    wsum = np.zeros((st.H, st.Nq))
+    for h in range(st.H):
+        keys, vals, owner = [], [], []          # owner: -1 persistent, else logical local block
+        for s in range(st.C + 1):
+            n = st.p_len[h, s]
+            keys.append(f32(st.Kp[h, s, :n])); vals.append(f32(st.Vp[h, s, :n])); owner += [-1] * n
+        for l in range(st.n_loc):
+            n = l_len[l]
+            keys.append(f32(st.Kl[h, l_map[l], :n])); vals.append(f32(st.Vl[h, l_map[l], :n])); owner += [l] * n
+        Kc = np.concatenate(keys).astype(np.float64)
+        Vc = np.concatenate(vals).astype(np.float64)
+        owner = np.array(owner)
+        M = np.full((st.Nq, len(owner)), -np.inf)
+        for t in range(st.Nq):
+            vis = set(int(x) for x in sel[h, t // st.B] if x >= 0)
+            M[t, (owner < 0) | np.isin(owner, list(vis))] = 0.0
+        S = f32(Q[h]).astype(np.float64) @ Kc.T * st.scale + M
+        P = np.exp(S - S.max(1, keepdims=True))
+        P /= P.sum(1, keepdims=True)
+        out[h] = P @ Vc
+        wsum[h] = P.sum(1)
+    return out, wsum
+
+
+# ------------------------------------------------------------------------------------------------
+# pinned exp
+# ------------------------------------------------------------------------------------------------
+def test_pexp_matches_exp(oracle):
+    xs = np.concatenate([np.linspace(-64, 0, 4001), -np.logspace(-8, 1.8, 500)]).astype(np.float32)
+    worst = 0.0
+    for x in xs:
+        got, want = oracle.pexp(float(x)), math.exp(float(x))
+        worst = max(worst, abs(got - want) / want)
+    assert worst < 4 * 2.0 ** -24          # a few ulp
+    assert oracle.pexp(0.0) == 1.0
+    assert oracle.pexp(-64.5) == 0.0 and oracle.pexp(-1e30) == 0.0
+    ys = [oracle.pexp(float(x)) for x in np.linspace(-20, 0, 2001, dtype=np.float32)]
+    assert all(b >= a for a, b in zip(ys, ys[1:]))
+
+
+# ------------------------------------------------------------------------------------------------
+# pooling + selection (Eq. 6, 10, 11)
+# ------------------------------------------------------------------------------------------------
+def test_pool_is_mean_of_valid_tokens(oracle):
+    x = rnd(7, 8, 16) * 3
+    bits = bf(x)
+    for length in (1, 5, 8):
+        got = oracle.pool_block(bits, length)
+        np.testing.assert_allclose(got, f32(bits[:length]).astype(np.float64).mean(0), rtol=0, atol=2e-6)
+    # padding rows are never trusted: garbage beyond len does not change the result
+    junk = bits.copy(); junk[5:] = bf(np.full((3, 16), 1e6))
+    assert np.array_equal(oracle.pool_block(junk, 5), oracle.pool_block(bits, 5))
+
+
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_select_is_bruteforce_topk(oracle, seed, causal):
+    st, Q = make_state(seed, H=3, d=16, B=8, Nq=28, w=2, C=1, k=3, causal=causal)
+    sel, Z = st.select(Q, want_logits=True)
+    Qc, Kc = ref_pooled(st, Q)
+    n_win = st.n_loc - st.nqb
+    for h in range(st.H):
+        for i in range(st.nqb):
+            nvis = n_win + i + 1 if causal else st.n_loc
+            z = Kc[h, :nvis] @ Qc[h, i] * st.scale
+            np.testing.assert_allclose(Z[h, i, :nvis], z, rtol=0, atol=1e-5)
+            assert np.all(np.isneginf(Z[h, i, nvis:]))
+            order = sorted(range(nvis), key=lambda l: (-z[l], l))           # full sort of (-z, l)
+            want = sorted(order[:st.k])
+            assert [int(x) for x in sel[h, i] if x >= 0] == want
+            # Eq. 10-11 literally: top-k of the softmax probabilities picks the same set
+            p = np.exp(z - z.max()); p /= p.sum()
+            assert sorted(np.argsort(-p, kind="stable")[:st.k].tolist()) == want
+            assert sel[h, i].max() <= (n_win + i if causal else st.n_loc - 1)
+
+
+def test_select_ties_go_to_lowest_index_and_respect_visibility(oracle):
+    st, Q = make_state(3, H=1, d=16, B=8, Nq=32, w=1, C=0, k=6)
+    st.Kl[...] = st.Kl[0, 0, 0]            # every key token identical -> every block logit identical
+    st.stale_from = 0
+    sel, _ = st.select(Q)
+    n_win = st.n_loc - st.nqb               # 4 window blocks, query block i sees n_win + i + 1
+    for i in range(st.nqb):
+        nvis = n_win + i + 1
+        want = list(range(min(st.k, nvis))) + [-1] * max(0, st.k - nvis)
+        assert sel[0, i].tolist() == want
+
+
+def test_select_boosted_block_and_permutation(oracle):
+    st, Q = make_state(4, H=2, d=16, B=8, Nq=24, w=2, C=0, k=2, causal=0)
+    sel0, _ = st.select(Q)
+    Qc, _ = ref_pooled(st, Q)
+    # make local block 5 strongly aligned with every pooled query of head 0 -> selected by all rows
+    direction = Qc[0].mean(0); direction /= np.linalg.norm(direction)
+    for i in range(st.nqb):
+        assert Qc[0, i] @ direction > 0
+    l_map, _, _ = st._maps()
+    st.Kl[0, l_map[5]] = bf(np.tile(60.0 * direction, (st.B, 1)))
+    st.stale_from = 0
+    sel1, _ = st.select(Q)
+    assert all(5 in sel1[0, i] for i in range(st.nqb))
+    assert np.array_equal(sel1[1], sel0[1])                      # heads are independent
+    # reversing the order of the local blocks maps every set through the same permutation
+    n = st.n_loc
+    perm = l_map[::-1].copy()
+    st2, _ = make_state(4, H=2, d=16, B=8, Nq=24, w=2, C=0, k=2, causal=0)
+    st2.Kl[...] = st.Kl
+    import oracle.pbsa_oracle as orc
+    _, l_len, _ = st._maps()
+    Kc = np.zeros_like(st.Kc_l)
+    _, selp, _ = orc.select(st.cfg(), Q, st.Kl, l_len[::-1].copy(), perm, Kc)
+    for h in range(st.H):
+        for i in range(st.nqb):
+            assert sorted(n - 1 - selp[h, i]) == sel1[h, i].tolist()
+
+
+# ------------------------------------------------------------------------------------------------
+# attention (Eq. 3-5)
+# ------------------------------------------------------------------------------------------------
+def test_attention_all_selected_is_dense_block_causal(oracle):
+    st, Q = make_state(5, H=2, d=16, B=8, Nq=20, w=2, C=3, k=99, p_lens=[[8, 3, 0], [5, 8, 8]])
+    st.k = st.n_loc
+    sel, _ = st.select(Q)
+    n_win = st.n_loc - st.nqb
+    for i in range(st.nqb):                  # k >= n_vis: everything visible is selected
+        assert [x for x in sel[0, i] if x >= 0] == list(range(n_win + i + 1))
+    O, lse = st.attention(Q)
+    ref, wsum = ref_dense_attention(st, Q, sel)
+    np.testing.assert_allclose(O, ref, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(wsum, 1.0, atol=1e-12)
+
+
+def test_attention_noncausal_no_memory_is_plain_attention(oracle):
+    st, Q = make_state(6, H=1, d=16, B=8, Nq=24, w=1, C=0, k=6, causal=0)
+    st.select(Q)
+    O, lse = st.attention(Q)
+    l_map, l_len, _ = st._maps()
+    K = np.concatenate([f32(st.Kl[0, l_map[l], :l_len[l]]) for l in range(st.n_loc)]).astype(np.float64)
+    V = np.concatenate([f32(st.Vl[0, l_map[l], :l_len[l]]) for l in range(st.n_loc)]).astype(np.float64)
+    S = f32(Q[0]).astype(np.float64) @ K.T * st.scale
+    P = np.exp(S - S.max(1, keepdims=True)); Z = P.sum(1, keepdims=True)
+    np.testing.assert_allclose(O[0], (P / Z) @ V, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(lse[0], S.max(1) + np.log(Z[:, 0]), rtol=0, atol=1e-12)
+
+
+def test_attention_sparse_mask_semantics(oracle):
+    st, Q = make_state(7, H=2, d=16, B=8, Nq=20, w=2, C=2, k=2, p_lens=[[8, 6], [8, 8]])
+    sel, _ = st.select(Q)
+    O, _ = st.attention(Q)
+    ref, _ = ref_dense_attention(st, Q, sel)
+    np.testing.assert_allclose(O, ref, rtol=0, atol=1e-12)
+    l_map, l_len, _ = st._maps()
+    # convexity: every output row lies inside the per-dimension range of the values it can see
+    for h in range(st.H):
+        for t in range(st.Nq):
+            vs = [f32(st.Vp[h, s, :st.p_len[h, s]]) for s in range(st.C + 1)]
+            vs += [f32(st.Vl[h, l_map[l], :l_len[l]]) for l in sel[h, t // st.B] if l >= 0]
+            vs = np.concatenate(vs)
+            assert np.all(O[h, t] <= vs.max(0) + 1e-12) and np.all(O[h, t] >= vs.min(0) - 1e-12)
+    # a local block nobody selected does not influence any output, bit for bit
+    unused = sorted(set(range(st.n_loc)) - set(int(x) for x in sel[0].ravel() if x >= 0))
+    assert unused
+    Kl_saved, Vl_saved = st.Kl.copy(), st.Vl.copy()
+    st.Kl[0, l_map[unused[0]]] = bf(rnd(99, st.B, st.d) * 5)
+    st.Vl[0, l_map[unused[0]]] = bf(rnd(98, st.B, st.d) * 5)
+    O2, _ = st.attention(Q)
+    assert np.array_equal(O2, O)
+    st.Kl[...] = Kl_saved; st.Vl[...] = Vl_saved
+    # padding rows of ragged blocks are masked: garbage there changes nothing
+    st.Kp[0, 1, 6:] = bf(np.full((2, st.d), 50.0)); st.Vp[0, 1, 6:] = bf(np.full((2, st.d), 50.0))
+    tail = l_len[-1]
+    st.Kl[:, l_map[-1], tail:] = bf(np.full((st.B - tail, st.d), 50.0))
+    O3, _ = st.attention(Q)
+    assert np.array_equal(O3, O)
+    # persistent blocks are visible to every query row (zero block of Eq. 5)
+    st.Vp[0, 0] = bf(f32(st.Vp[0, 0]) + 1.0)
+    O4, _ = st.attention(Q)
+    assert np.all(np.abs(O4[0] - O[0]).max(1) > 0) and np.array_equal(O4[1], O[1])
+
+
+def test_attention_empty_memory_and_no_keys(oracle):
+    st, Q = make_state(8, H=1, d=16, B=8, Nq=16, w=0, C=2, k=0, p_lens=[[0, 0]])
+    st.select(Q)
+    O, lse = st.attention(Q)
+    assert np.all(O == 0) and np.all(np.isneginf(lse))
+
+
+# ------------------------------------------------------------------------------------------------
+# persistence scores (Eq. 7-8)
+# ------------------------------------------------------------------------------------------------
+def test_scores_closed_forms(oracle):
+    st, Q = make_state(9, H=2, d=16, B=8, Nq=28, w=2, C=3, k=2, p_lens=[[8, 0, 4], [8, 8, 8]])
+    st.select(Q)
+    l_map, _, _ = st._maps()
+    s_p, s_l = oracle.scores(st.cfg(), st.Qc, st.Kc_l, l_map, st.Kc_p, st.p_len)
+    # a row-stochastic matrix averaged over rows sums to one; empty slots score 0
+    np.testing.assert_allclose(s_p.sum(1) + s_l.sum(1), 1.0, atol=2e-6)
+    assert s_p[0, 1] == 0.0
+    # fp64 shadow from independently pooled representatives
+    Qc, Kc = ref_pooled(st, Q)
+    for h in range(st.H):
+        occ = [s for s in range(st.C) if st.p_len[h, s] > 0]
+        Kp_c = np.stack([f32(st.Kp[h, s, :st.p_len[h, s]]).astype(np.float64).mean(0) for s in occ])
+        U = np.concatenate([Kp_c, Kc[h]])
+        Zm = Qc[h] @ U.T * st.scale
+        A = np.exp(Zm - Zm.max(1, keepdims=True)); A /= A.sum(1, keepdims=True)
+        s = A.mean(0)
+        np.testing.assert_allclose(s_p[h, occ], s[:len(occ)], rtol=0, atol=1e-6)
+        np.testing.assert_allclose(s_l[h], s[len(occ):], rtol=0, atol=1e-6)
+    # identical representatives everywhere -> uniform 1/|U|
+    st.Kc_l[...] = st.Kc_l[0, 0]
+    st.Kc_p[...] = st.Kc_l[0, 0]
+    s_p, s_l = oracle.scores(st.cfg(), st.Qc, st.Kc_l, l_map, st.Kc_p, st.p_len)
+    nU = [2 + st.n_loc, 3 + st.n_loc]
+    for h in range(st.H):
+        np.testing.assert_allclose(s_l[h], 1.0 / nU[h], rtol=1e-6)
+
+
+# ------------------------------------------------------------------------------------------------
+# retention, slots, summary (Eq. 9 + compressed history)
+# ------------------------------------------------------------------------------------------------
+def run_update(st):
+    before = dict(Kp=st.Kp.copy(), Vp=st.Vp.copy(), p_len=st.p_len.copy(), p_id=st.p_id.copy(),
+                  Kc_p=st.Kc_p.copy(), S_sum=None if st.S_sum is None else st.S_sum.copy(),
+                  S_cnt=None if st.S_cnt is None else st.S_cnt.copy(), Kl=st.Kl.copy(), Vl=st.Vl.copy())
+    before["maps"] = st._maps()
+    before["n_evict"] = st.n_evict_now()
+    sc, src = st.update()
+    return before, sc, src
+
+
+@pytest.mark.parametrize("seed,n_sink", [(10, 0), (11, 1), (12, 2)])
+def test_retention_is_bruteforce_topc(oracle, seed, n_sink):
+    st, Q = make_state(seed, H=3, d=16, B=8, Nq=28, w=2, C=4, k=2, n_sink=n_sink,
+                       p_lens=[[8, 8, 5, 8], [8, 0, 8, 8], [8, 8, 8, 0]])
+    st.select(Q)
+    b, sc, src = run_update(st)
+    l_map, l_len, l_id = b["maps"]
+    ne, C = b["n_evict"], st.C
+    assert ne == st.nqb
+    for h in range(st.H):
+        cands = [("p", s) for s in range(n_sink, C) if b["p_len"][h, s] > 0] + [("e", e) for e in range(ne)]
+        val = [sc[h, s] if kind == "p" else sc[h, C + s] for kind, s in cands]
+        order = sorted(range(len(cands)), key=lambda a: (-val[a], a))
+        winners = set(order[:C - n_sink])
+        # sinks never move
+        for s in range(n_sink):
+            assert src[h, s] == -1 and st.p_id[h, s] == b["p_id"][h, s]
+            assert np.array_equal(st.Kp[h, s], b["Kp"][h, s])
+        # winning occupants keep their slot, losers vacate, newcomers fill ascending
+        free = [s for s in range(n_sink, C) if b["p_len"][h, s] == 0]
+        free += [cands[a][1] for a in range(len(cands)) if cands[a][0] == "p" and a not in winners]
+        free.sort()
+        new = sorted(cands[a][1] for a in winners if cands[a][0] == "e")
+        want_src = np.full(C, -1)
+        for s, e in zip(free, new):
+            want_src[s] = e
+        assert src[h].tolist() == want_src.tolist()
+        for s in range(n_sink, C):
+            if want_src[s] >= 0:
+                e = want_src[s]
+                assert np.array_equal(st.Kp[h, s], b["Kl"][h, l_map[e]]) and np.array_equal(st.Vp[h, s], b["Vl"][h, l_map[e]])
+                assert st.p_len[h, s] == l_len[e] and st.p_id[h, s] == l_id[e]
+                assert np.array_equal(st.Kc_p[h, s], st.Kc_l[h, l_map[e]])
+            elif b["p_len"][h, s] > 0:
+                assert np.array_equal(st.Kp[h, s], b["Kp"][h, s]) and st.p_id[h, s] == b["p_id"][h, s]
+        kept_ids = set(int(x) for x in st.p_id[h] if x != -1)
+        assert kept_ids <= set(int(x) for x in b["p_id"][h]) | set(int(x) for x in l_id[:ne])
+        # summary = position-wise mean of every loser (fp64 batch mean), counts integer-exact
+        losers = [cands[a] for a in range(len(cands)) if a not in winners]
+        cnt = np.zeros(st.B, np.int64); ks = np.zeros((st.B, st.d)); vs = np.zeros((st.B, st.d))
+        for kind, s in losers:
+            if kind == "p":
+                n = b["p_len"][h, s]; kb, vb = b["Kp"][h, s], b["Vp"][h, s]
+            else:
+                n = l_len[s]; kb, vb = b["Kl"][h, l_map[s]], b["Vl"][h, l_map[s]]
+            cnt[:n] += 1; ks[:n] += f32(kb[:n]); vs[:n] += f32(vb[:n])
+        assert st.S_cnt[h].tolist() == cnt.tolist() and st.S_cnt[h].sum() == sum(
+            (b["p_len"][h, s] if kind == "p" else l_len[s]) for kind, s in losers)
+        nz = cnt > 0
+        assert st.p_len[h, C] == nz.sum()
+        np.testing.assert_allclose(st.S_sum[h, 0][nz] / st.S_cnt[h][nz, None], ks[nz] / cnt[nz, None], atol=1e-5)
+        np.testing.assert_allclose(f32(st.Kp[h, C][nz]), ks[nz] / cnt[nz, None], rtol=2 ** -8, atol=1e-6)
+        np.testing.assert_allclose(f32(st.Vp[h, C][nz]), vs[nz] / cnt[nz, None], rtol=2 ** -8, atol=1e-6)
+
+
+def test_update_without_eviction_is_noop_and_room_for_all(oracle):
+    st, Q = make_state(13, H=2, d=16, B=8, Nq=24, w=2, C=3, k=2, fill_chunks=2, p_lens=[[8, 8, 0], [0, 0, 0]])
+    st.select(Q)
+    b, sc, src = run_update(st)
+    assert b["n_evict"] == 0 and np.all(src == -1)
+    for name in ("Kp", "Vp", "p_len", "p_id", "S_sum", "S_cnt"):
+        assert np.array_equal(getattr(st, name), b[name])
+    # more places than candidates: nothing is dropped, summary untouched
+    st2, Q2 = make_state(14, H=1, d=16, B=8, Nq=16, w=1, C=6, k=1, p_lens=[[8, 8, 0, 0, 0, 0]])
+    st2.select(Q2)
+    b2, _, src2 = run_update(st2)
+    assert src2[0].tolist() == [-1, -1, 0, 1, -1, -1]
+    assert st2.S_cnt.sum() == 0 and st2.p_len[0, 6] == 0 and st2.p_id[0, 4] == -1
+
+
+def test_uniform_scores_keep_lowest_candidates(oracle):
+    st, Q = make_state(15, H=1, d=16, B=8, Nq=24, w=1, C=2, k=1)
+    st.select(Q)
+    st.Kc_l[...] = 0.0; st.Kc_p[...] = 0.0            # all representatives equal -> all scores equal
+    b, sc, src = run_update(st)
+    assert len(set(sc[0].tolist())) == 1
+    assert np.all(src == -1) and np.array_equal(st.p_id, b["p_id"])   # occupants are the lowest candidates
+    assert st.S_cnt[0].tolist() == [3] * 8                            # the three evicted blocks were folded
+
+
+def test_fold_of_constant_blocks_is_exact_and_drop_mode(oracle):
+    st, Q = make_state(16, H=1, d=16, B=8, Nq=16, w=1, C=1, k=1)
+    st.select(Q)
+    const = bf(np.tile(np.linspace(-2, 2, 16), (8, 1)))
+    l_map, _, _ = st._maps()
+    st.Kl[0, l_map[:2]] = const; st.Vl[0, l_map[:2]] = const
+    st.Kp[0, 0] = const; st.Vp[0, 0] = const
+    st.update()
+    assert st.S_cnt[0].tolist() == [2] * 8
+    assert np.array_equal(st.Kp[0, 1], const) and np.array_equal(st.Vp[0, 1], const)
+    # S_sum = NULL: losers are simply dropped (the paper's plain Top-C), slot C stays empty
+    st3, Q3 = make_state(16, H=1, d=16, B=8, Nq=16, w=1, C=1, k=1, fold=False)
+    st3.select(Q3)
+    st3.update()
+    assert st3.p_len[0, 1] == 0
+
+
+def test_rollout_summary_counts(oracle):
+    """Cold start over several chunks: window fills, then every update evicts one chunk; counts add up."""
+    H, d, B, Nq, w, C = 1, 16, 8, 20, 2, 2
+    st = OracleState(H, d, B, Nq, w, C, 2, 0.25)
+    nqb = st.nqb
+    lens = np.array([8, 8, 4], np.int32)
+    folded = 0
+    for g in range(7):
+        K = bf(rnd(200 + 3 * g, H, Nq, d)); V = bf(rnd(201 + 3 * g, H, Nq, d)); Q = bf(rnd(202 + 3 * g, H, Nq, d))
+        st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * nqb + np.arange(nqb))
+        st.select(Q)
+        occupied_before = int((st.p_len[0, :C] > 0).sum())
+        ne = st.n_evict_now()
+        assert ne == (nqb if g >= w else 0)
+        st.update()
+        occupied_after = int((st.p_len[0, :C] > 0).sum())
+        if ne:
+            folded += occupied_before + ne - occupied_after
+    assert occupied_after == C
+    assert st.S_cnt[0].max() == folded
+    ids = [int(x) for x in st.p_id[0]]
+    assert len(set(ids)) == C and all(0 <= x < 5 * nqb for x in ids)
