@@ -1,0 +1,150 @@
+/*
+ * pbsa.h -- C ABI of the MI355X (gfx950) Persistent Block-Sparse Attention decode path.
+ *
+ * The path is the per-chunk attention of a causal video DiT over a bounded KV memory
+ * M = P u L (Sec. 3.3, Eq. 2): a persistent set P of at most C blocks that every query attends
+ * densely, and a sliding local region L (window + the chunk being generated) in which each query
+ * block attends only its top-k key blocks.  One layer-chunk step is
+ *
+ *     pbsa_select_blocks  ->  pbsa_attention_fwd  ->  pbsa_memory_update
+ *
+ * Conventions
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller; `const pbsa_params*` and the
+ *    `size_t*` result of pbsa_workspace_bytes are HOST pointers.  The library never allocates,
+ *    frees or synchronises: a call validates its arguments on the host, enqueues kernels on
+ *    `hip_stream` (a hipStream_t, NULL = the default stream) and returns.
+ *  - bf16 tensors are raw 16-bit patterns.  All tensor base pointers must be 16-byte aligned.
+ *  - Block-major cache layout (App. "Rearrange for Locality Preserving", Alg. 3): the B tokens of a
+ *    block are contiguous, [B][d] row-major.  Rows at or beyond a block's valid length are never
+ *    trusted (pooling divides by the valid length, attention masks them).
+ *  - Everything is per head: each head has its own block sets, persistent slots and summary.
+ *  - Return value: PBSA_OK or a negative PBSA_E* code; pbsa_strerror() gives the text.  Validation
+ *    happens before any HIP call, so argument errors are reported even on a machine with no GPU.
+ *  - Results are deterministic: no floating-point atomics, fixed reduction orders.
+ *
+ * Shapes
+ *   Q, O         [H][Nq][d] bf16, element strides (q_stride_h, q_stride_t) / (o_stride_h, o_stride_t),
+ *                last dimension contiguous; query block i = chunk tokens iB .. min((i+1)B, Nq)-1
+ *   Kl, Vl       [H][n_loc_cap][B][d] bf16   physical local slots (ring storage)
+ *   l_map        [n_loc] int32               logical local block (oldest first, the chunk's nqb blocks
+ *                                            last) -> physical slot
+ *   l_len, l_id  [n_loc] int32 / int64       valid tokens (1..B) and global id of each logical block
+ *   Kc_l         [H][n_loc_cap][d] fp32      pooled keys, indexed by physical slot
+ *   Qc           [H][nqb][d] fp32            pooled queries of the chunk
+ *   sel          [H][nqb][k] int32           selected logical local blocks per query block,
+ *                                            ascending, padded with -1
+ *   Kp, Vp       [H][C+1][B][d] bf16         persistent slots; slot C holds the compressed-history
+ *                                            ("summary") block
+ *   p_len        [H][C+1] int32              valid tokens per slot, 0 = empty (skipped)
+ *   Kc_p, p_id   [H][C][d] fp32, [H][C] int64
+ *   S_sum, S_cnt [H][2][B][d] fp32 (K then V), [H][B] int32   running sums / counts of the summary
+ *
+ * Arithmetic that decides an integer (block sets, slot assignment) is specified exactly, in IEEE
+ * binary32 without contraction, so that an independent implementation reproduces it bit for bit:
+ *   pool(X, len)[x]  = ( ...((0 + X[0][x]) + X[1][x]) ... + X[len-1][x]) / (float)len
+ *   dot(q, k)        = fma(q[d-1], k[d-1], ... fma(q[1], k[1], fma(q[0], k[0], 0)) ...) * scale
+ *   pexp(x), x <= 0  = 0 if x < -64, else with n = rint(x * 0x1.715476p+0f),
+ *                      r = fma(n, 0x1.bd0106p-13f, fma(n, -0x1.63p-1f, x)),
+ *                      p = Horner in r by fma of (1/720, 1/120, 1/24, 1/6, 1/2, 1, 1) rounded to
+ *                      binary32, the value p * 2^n
+ *   row softmax      m = max_j z_j; e_j = pexp(z_j - m); s = (...(0 + e_0) + e_1 ...); a_j = e_j / s
+ *   column mean      (...((0 + a_0j) + a_1j) ... + a_(nqb-1)j) / (float)nqb
+ *   summary fold     S_sum = S_sum + x, dropped blocks taken in candidate order
+ * Ties in a ranking go to the lower index.
+ */
+#ifndef PBSA_H
+#define PBSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PBSA_OK      0
+#define PBSA_EINVAL (-1) /* NULL pointer, wrong .size, inconsistent counts                      */
+#define PBSA_ESHAPE (-2) /* d, B, k, C, n_loc ... outside what the kernels support              */
+#define PBSA_EALIGN (-3) /* pointer not 16-byte aligned, or a stride not a multiple of 8 elems  */
+#define PBSA_EWS    (-4) /* workspace missing or smaller than pbsa_workspace_bytes()            */
+#define PBSA_EHIP   (-5) /* a HIP call or kernel launch failed                                   */
+
+#define PBSA_MAX_N_LOC 512 /* logical local blocks          */
+#define PBSA_MAX_C      64 /* persistent slots              */
+#define PBSA_MAX_K     128 /* selected blocks per query block */
+
+typedef struct pbsa_params {
+  uint32_t size;            /* sizeof(pbsa_params); guards against ABI drift                        */
+  int32_t H;                /* heads                                                                */
+  int32_t d;                /* head dim: 64 or 128                                                  */
+  int32_t B;                /* tokens per block: 64 or 128                                          */
+  int32_t Nq;               /* chunk (query) tokens                                                 */
+  int32_t nqb;              /* ceil(Nq / B): query blocks = key blocks the chunk contributes        */
+  int32_t n_loc;            /* logical local blocks, the chunk's nqb included (nqb <= n_loc)        */
+  int32_t n_loc_cap;        /* physical local slots per head (n_loc <= n_loc_cap)                   */
+  int32_t C;                /* persistent slots, excluding the summary slot                         */
+  int32_t n_sink;           /* leading slots that are never evicted (footnote to Eq. 9)             */
+  int32_t k;                /* local blocks selected per query block (Eq. 11, as a count)           */
+  int32_t causal;           /* 1: query block i sees local blocks 0 .. n_loc-nqb+i; 0: all n_loc    */
+  int32_t n_evict;          /* |E_t|: leading local blocks leaving the window at this update        */
+  int32_t pool_from;        /* select: pooled keys of logical blocks >= pool_from are recomputed,   */
+                            /* earlier ones are trusted from Kc_l (normally n_loc - nqb)            */
+  float scale;              /* softmax scale, 1/sqrt(d)                                             */
+  int64_t q_stride_h, q_stride_t;
+  int64_t o_stride_h, o_stride_t;
+} pbsa_params;
+
+/* Bytes of scratch that any call with these parameters may need (device memory, 256-byte aligned,
+ * passed as `ws`).  Contents need not be preserved between calls. */
+int pbsa_workspace_bytes(const pbsa_params* p, size_t* out);
+
+/* Block representatives by average pooling (Eq. 6; pooling operator of Sec. 4.1):
+ * out[n][:] = mean over the first len[n] rows of X[n].  X [n_blocks][B][d] bf16, len [n_blocks]
+ * int32 (0 gives a zero vector), out [n_blocks][d] fp32.  Uses p->B and p->d only.  For seeding the
+ * pooled keys of persistent blocks the caller installs by hand. */
+int pbsa_pool_blocks(const pbsa_params* p, const void* X, const int32_t* len, int32_t n_blocks, float* out,
+                     void* hip_stream);
+
+/* Coarse routing inside the local region (Eq. 10-11).  Pools the chunk's queries into Qc, refreshes
+ * the pooled keys Kc_l of logical blocks >= pool_from, scores every visible local block of every
+ * query block with dot(Qc_i, Kc_l) (the argument of Eq. 10's softmax, which is monotone per row)
+ * and writes the min(k, visible) best blocks of each row to `sel` (ascending, -1 padded; ties to
+ * the lower block).  Kc_l is in/out, Qc and sel are out.  ws may be NULL. */
+int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, const int32_t* l_len,
+                       const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, void* ws, size_t ws_bytes,
+                       void* hip_stream);
+
+/* PBSA fine stage (Eq. 3-5): for each query token one softmax, scaled by p->scale, over every
+ * valid token of every non-empty persistent slot 0..C (summary included) and every valid token of
+ * the local blocks listed in its query block's row of `sel`; O = P V.  bf16 MFMA with fp32
+ * accumulation and fp32 online softmax; O is rounded to bf16 (nearest even).  `lse` (optional,
+ * [H][Nq] fp32) receives the natural-log normaliser.  A row that sees no key gets O = 0,
+ * lse = -inf.  Entries of sel must be -1 or in [0, n_loc).  ws may be NULL. */
+int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                       const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                       const int32_t* sel, void* O, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Persistent-memory update (Eq. 7-9).  Scores: block-level softmax of each pooled query over
+ * U = occupied slots 0..C-1 followed by all n_loc local blocks, averaged over query blocks
+ * (Eq. 7-8).  Candidates: occupants of slots n_sink..C-1 in slot order, then the n_evict leading
+ * local blocks; the best C-n_sink by (score, then lower candidate index) stay (Eq. 9).  A kept
+ * occupant keeps its slot; kept newcomers, in ascending block order, fill vacated and empty slots in
+ * ascending slot order, and K, V, Kc_p, p_len, p_id move with them.  Every dropped candidate is
+ * added position by position to S_sum/S_cnt and slot C is rewritten with their running mean
+ * (bf16), p_len[C] = number of positions with a count; pass S_sum = S_cnt = NULL to drop without
+ * compressing.  Qc and Kc_l are those pbsa_select_blocks produced for this chunk.
+ * Outputs: scores (optional, [H][C+n_evict] fp32: slots 0..C-1, 0 if empty, then evicted blocks),
+ * slot_src [H][C] int32: -1 = slot unchanged, e >= 0 = filled from local block e.
+ * ws is required (pbsa_workspace_bytes). */
+int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l, void* Kp, void* Vp, float* Kc_p,
+                       int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt, const void* Kl,
+                       const void* Vl, const int32_t* l_len, const int32_t* l_map, const int64_t* l_id,
+                       float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream);
+
+const char* pbsa_strerror(int code);
+int pbsa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBSA_H */

@@ -1,0 +1,46 @@
+"""Builds libpbsa.so (HIP kernels + C ABI) in-tree for gfx950 with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+LIB = os.path.join(PKG, "libpbsa.so")
+BUILD_DIR = os.path.join(ROOT, "_build")
+
+# source file -> extra flags.  The coarse/update kernels implement arithmetic that is specified
+# operation by operation, so they are compiled without contraction.
+SOURCES = {
+    "pbsa_api.hip": [],
+    "pbsa_coarse.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
+    "pbsa_attention.hip": [],
+}
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall", "-Wno-unused-command-line-argument",
+          # keep the compiler from forming packed-fp32 instructions
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def _compile(name: str, flags, keep_asm: bool) -> str:
+    obj = os.path.join(BUILD_DIR, name.replace(".hip", ".o"))
+    cmd = ["hipcc", *COMMON, *flags, "-c", os.path.join(CSRC, name), "-o", obj]
+    if keep_asm:
+        cmd += ["-save-temps=obj"]
+    subprocess.run(cmd, check=True, cwd=BUILD_DIR)
+    return obj
+
+
+def build(keep_asm: bool = False) -> str:
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+        objs = list(ex.map(lambda kv: _compile(kv[0], kv[1], keep_asm), SOURCES.items()))
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(keep_asm="--asm" in sys.argv))

@@ -1,0 +1,145 @@
+"""Device-resident KV memory M = P u L (Sec. 3.3, Eq. 2) and the caller side of one layer-chunk step.
+
+PbsaCache owns the torch tensors (device memory only) and plays the caller of Alg. 1: it copies a
+chunk's K/V into the local ring in block-major layout, then issues the three library calls
+pbsa_select_blocks -> pbsa_attention_fwd -> pbsa_memory_update and slides the window.  All
+arithmetic of the method happens inside libpbsa's kernels; this file only moves data and keeps the
+ring bookkeeping (which physical slot holds which logical block).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import pbsa
+
+
+class PbsaCache:
+    def __init__(self, H, d, B, Nq, window_chunks, C, k, scale, n_sink=0, causal=1, fold=True, device="cuda:0"):
+        self.H, self.d, self.B, self.Nq, self.C, self.k = H, d, B, Nq, C, k
+        self.w, self.scale, self.n_sink, self.causal = window_chunks, float(scale), n_sink, causal
+        self.nqb = -(-Nq // B)
+        self.cap = (window_chunks + 1) * self.nqb
+        self.dev = torch.device(device)
+        z = lambda *s, dt=torch.bfloat16: torch.zeros(*s, dtype=dt, device=self.dev)
+        self.Kl, self.Vl = z(H, self.cap, B, d), z(H, self.cap, B, d)
+        self.Kc_l = z(H, self.cap, d, dt=torch.float32)
+        self.Kp, self.Vp = z(H, C + 1, B, d), z(H, C + 1, B, d)
+        self.Kc_p = z(H, max(C, 1), d, dt=torch.float32)
+        self.p_len = z(H, C + 1, dt=torch.int32)
+        self.p_id = torch.full((H, max(C, 1)), -1, dtype=torch.int64, device=self.dev)
+        self.S_sum = z(H, 2, B, d, dt=torch.float32) if fold else None
+        self.S_cnt = z(H, B, dt=torch.int32) if fold else None
+        self.Qc = z(H, self.nqb, d, dt=torch.float32)
+        self.sel = torch.full((H, self.nqb, max(k, 1)), -1, dtype=torch.int32, device=self.dev)
+        self.slot_src = torch.full((H, max(C, 1)), -1, dtype=torch.int32, device=self.dev)
+        self.scores = z(H, C + self.nqb, dt=torch.float32)
+        full = pbsa.make_params(H, d, B, Nq, self.cap, self.cap, C, k, self.scale, n_sink, causal, n_evict=self.nqb)
+        self.ws = torch.empty(max(pbsa.pbsa_workspace_bytes(full), 256), dtype=torch.uint8, device=self.dev)
+        self.chunk_pos = []          # ring position of each chunk in the local region, oldest first
+        self.chunk_ids = []          # global chunk index of each
+        self.n_appended = 0
+        self.stale_from = 0
+        self._maps = {}
+        lens = torch.full((self.nqb,), B, dtype=torch.int32)
+        lens[-1] = Nq - (self.nqb - 1) * B
+        self._chunk_lens = lens
+
+    @property
+    def n_loc(self):
+        return len(self.chunk_pos) * self.nqb
+
+    def _device_maps(self):
+        """l_map / l_len / l_id device tensors of the current ring arrangement (cached per arrangement)."""
+        key = (tuple(self.chunk_pos), tuple(self.chunk_ids))
+        m = self._maps.get(key)
+        if m is None:
+            ar = torch.arange(self.nqb)
+            l_map = torch.cat([p * self.nqb + ar for p in self.chunk_pos]).to(torch.int32)
+            l_len = self._chunk_lens.repeat(len(self.chunk_pos))
+            l_id = torch.cat([g * self.nqb + ar for g in self.chunk_ids]).to(torch.int64)
+            m = (l_map.to(self.dev), l_len.to(self.dev), l_id.to(self.dev))
+            if len(self._maps) > 64:
+                self._maps.clear()
+            self._maps[key] = m
+        return m
+
+    def params(self, n_evict=0, pool_from=0, Q=None, O=None):
+        qs = (Q.stride(0), Q.stride(1)) if Q is not None else None
+        os_ = (O.stride(0), O.stride(1)) if O is not None else None
+        return pbsa.make_params(self.H, self.d, self.B, self.Nq, self.n_loc, self.cap, self.C, self.k, self.scale,
+                                self.n_sink, self.causal, n_evict, pool_from, qs, os_)
+
+    # -- state seeding (data movement + the library's own pooling kernel) ----------------------------
+    def set_persistent(self, Kp, Vp, lens, ids):
+        """Install blocks ([H][c][B][d] bf16) in the first slots; pooled keys come from pbsa_pool_blocks."""
+        c = Kp.shape[1]
+        self.Kp[:, :c] = Kp
+        self.Vp[:, :c] = Vp
+        self.p_len[:, :c] = lens
+        self.p_id[:, :c] = torch.where(self.p_len[:, :c] > 0, ids.to(self.dev), torch.full_like(ids, -1).to(self.dev))
+        flat_len = self.p_len[:, :c].contiguous().view(-1)
+        X = self.Kp[:, :c].contiguous()
+        out = torch.empty(self.H * c, self.d, dtype=torch.float32, device=self.dev)
+        pbsa.pbsa_pool_blocks(self.params(), X, flat_len, self.H * c, out)
+        self.Kc_p[:, :c] = out.view(self.H, c, self.d)
+
+    def set_summary(self, S_sum, S_cnt, Ks_bf16, Vs_bf16, length):
+        """Install a pre-filled compressed-history state (sums, counts and the bf16 view of slot C)."""
+        self.S_sum.copy_(S_sum)
+        self.S_cnt.copy_(S_cnt)
+        self.Kp[:, self.C] = Ks_bf16
+        self.Vp[:, self.C] = Vs_bf16
+        self.p_len[:, self.C] = length
+
+    def append_chunk(self, K, V, chunk_id):
+        """Copy a chunk's K/V ([H][Nq][d] bf16, token-major) into the next ring position, block-major."""
+        assert len(self.chunk_pos) <= self.w, "update() slides the window before the next append"
+        pos = self.n_appended % (self.w + 1)
+        for dst, src in ((self.Kl, K), (self.Vl, V)):
+            view = dst[:, pos * self.nqb:(pos + 1) * self.nqb].view(self.H, self.nqb * self.B, self.d)
+            view[:, :self.Nq] = src
+            if self.nqb * self.B > self.Nq:
+                view[:, self.Nq:] = 0
+        self.chunk_pos.append(pos)
+        self.chunk_ids.append(chunk_id)
+        self.n_appended += 1
+        self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
+
+    # -- the three calls ---------------------------------------------------------------------------
+    def select(self, Q):
+        l_map, l_len, _ = self._device_maps()
+        p = self.params(pool_from=self.stale_from, Q=Q)
+        pbsa.pbsa_select_blocks(p, Q, self.Kl, l_len, l_map, self.Kc_l, self.Qc, self.sel)
+        self.stale_from = self.n_loc
+        return self.sel
+
+    def attention(self, Q, O=None, lse=None):
+        if O is None:
+            O = torch.empty_like(Q)
+        l_map, l_len, _ = self._device_maps()
+        p = self.params(Q=Q, O=O)
+        pbsa.pbsa_attention_fwd(p, Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map, self.sel, O, lse)
+        return O
+
+    def n_evict_now(self):
+        return self.nqb if len(self.chunk_pos) == self.w + 1 else 0
+
+    def update(self):
+        l_map, l_len, l_id = self._device_maps()
+        ne = self.n_evict_now()
+        p = self.params(n_evict=ne)
+        pbsa.pbsa_memory_update(p, self.Qc, self.Kc_l, self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id, self.S_sum,
+                                self.S_cnt, self.Kl, self.Vl, l_len, l_map, l_id, self.scores, self.slot_src, self.ws)
+        if ne:
+            self.chunk_pos.pop(0)
+            self.chunk_ids.pop(0)
+            self.stale_from = self.n_loc
+        return ne
+
+    def step(self, Q, K, V, chunk_id, O=None, lse=None):
+        """One layer-chunk step: append the chunk, select, attend, update (all enqueued, no sync)."""
+        self.append_chunk(K, V, chunk_id)
+        self.select(Q)
+        O = self.attention(Q, O, lse)
+        self.update()
+        return O

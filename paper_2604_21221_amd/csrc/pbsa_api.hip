@@ -1,0 +1,146 @@
+// C-ABI shim of libpbsa: host-side argument validation, then kernel launches.  Validation makes no
+// HIP call, so every argument error is reported on a machine without a GPU as well.
+#include <string.h>
+
+#include "pbsa_internal.h"
+
+namespace {
+
+thread_local char g_hip_msg[256] = "";
+
+int hip_fail(hipError_t e) {
+  snprintf(g_hip_msg, sizeof g_hip_msg, "HIP error %d: %s", (int)e, hipGetErrorString(e));
+  return PBSA_EHIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks that do not depend on which call is made.
+int check_common(const pbsa_params* p) {
+  if (!p) return PBSA_EINVAL;
+  if (p->size != sizeof(pbsa_params)) return PBSA_EINVAL;
+  if (p->H < 1 || p->Nq < 1 || p->n_loc < 0 || p->C < 0 || p->k < 0 || p->n_sink < 0 || p->n_evict < 0 ||
+      p->pool_from < 0)
+    return PBSA_EINVAL;
+  if (p->d != 64 && p->d != 128) return PBSA_ESHAPE;
+  if (p->B != 64 && p->B != 128) return PBSA_ESHAPE;
+  if (p->nqb != (p->Nq + p->B - 1) / p->B) return PBSA_EINVAL;
+  if (p->n_loc < p->nqb || p->n_loc > p->n_loc_cap) return PBSA_EINVAL;
+  if (p->n_sink > p->C || p->n_evict > p->n_loc || p->pool_from > p->n_loc) return PBSA_EINVAL;
+  if (p->causal != 0 && p->causal != 1) return PBSA_EINVAL;
+  if (!(p->scale > 0.0f) || !(p->scale < 1e30f)) return PBSA_EINVAL;
+  if (p->n_loc > PBSA_MAX_N_LOC || p->C > PBSA_MAX_C || p->k > PBSA_MAX_K) return PBSA_ESHAPE;
+  if ((int64_t)p->H * p->n_loc_cap * p->B * p->d >= ((int64_t)1 << 40)) return PBSA_ESHAPE;
+  return PBSA_OK;
+}
+
+int check_strides(int64_t sh, int64_t st, const pbsa_params* p) {
+  if (st < p->d || sh < 0) return PBSA_EINVAL;
+  if (st % 8 != 0 || sh % 8 != 0) return PBSA_EALIGN;
+  return PBSA_OK;
+}
+
+size_t workspace_bytes(const pbsa_params& p) { return pbsa::carve_update_ws(p, nullptr).bytes; }
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int pbsa_version(void) { return 1; }
+
+const char* pbsa_strerror(int code) {
+  switch (code) {
+    case PBSA_OK: return "ok";
+    case PBSA_EINVAL: return "invalid argument (NULL pointer, wrong params.size, or inconsistent counts)";
+    case PBSA_ESHAPE: return "unsupported shape (d and B must be 64 or 128; n_loc, C, k within PBSA_MAX_*)";
+    case PBSA_EALIGN: return "misaligned pointer (16 bytes) or stride (multiple of 8 elements)";
+    case PBSA_EWS: return "workspace missing or too small (see pbsa_workspace_bytes)";
+    case PBSA_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP call failed";
+    default: return "unknown pbsa error code";
+  }
+}
+
+int pbsa_workspace_bytes(const pbsa_params* p, size_t* out) {
+  if (!out) return PBSA_EINVAL;
+  int rc = check_common(p);
+  if (rc) return rc;
+  *out = workspace_bytes(*p);
+  return PBSA_OK;
+}
+
+int pbsa_pool_blocks(const pbsa_params* p, const void* X, const int32_t* len, int32_t n_blocks, float* out,
+                     void* hip_stream) {
+  if (!p || p->size != sizeof(pbsa_params)) return PBSA_EINVAL;
+  if (p->d != 64 && p->d != 128) return PBSA_ESHAPE;
+  if (p->B != 64 && p->B != 128) return PBSA_ESHAPE;
+  if (n_blocks < 0) return PBSA_EINVAL;
+  if (n_blocks > 0 && (!X || !len || !out)) return PBSA_EINVAL;
+  if (!aligned16(X) || !aligned16(out)) return PBSA_EALIGN;
+  hipError_t e = pbsa::launch_pool_blocks(*p, static_cast<const pbsa::bf16_t*>(X), len, n_blocks, out,
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, const int32_t* l_len,
+                       const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, void* ws, size_t ws_bytes,
+                       void* hip_stream) {
+  (void)ws; (void)ws_bytes;
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Q || !Kl || !l_len || !l_map || !Kc_l || !Qc) return PBSA_EINVAL;
+  if (p->k > 0 && !sel) return PBSA_EINVAL;
+  rc = check_strides(p->q_stride_h, p->q_stride_t, p);
+  if (rc) return rc;
+  if (!aligned16(Q) || !aligned16(Kl) || !aligned16(Kc_l) || !aligned16(Qc)) return PBSA_EALIGN;
+  hipError_t e = pbsa::launch_select(*p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kl),
+                                     l_len, l_map, Kc_l, Qc, sel, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                       const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                       const int32_t* sel, void* O, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
+  (void)ws; (void)ws_bytes;
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O) return PBSA_EINVAL;
+  if (p->k > 0 && !sel) return PBSA_EINVAL;
+  rc = check_strides(p->q_stride_h, p->q_stride_t, p);
+  if (rc) return rc;
+  rc = check_strides(p->o_stride_h, p->o_stride_t, p);
+  if (rc) return rc;
+  if (!aligned16(Q) || !aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(O))
+    return PBSA_EALIGN;
+  hipError_t e = pbsa::launch_attention(
+      *p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kp),
+      static_cast<const pbsa::bf16_t*>(Vp), p_len, static_cast<const pbsa::bf16_t*>(Kl),
+      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, sel, static_cast<pbsa::bf16_t*>(O), lse,
+      static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l, void* Kp, void* Vp, float* Kc_p,
+                       int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt, const void* Kl,
+                       const void* Vl, const int32_t* l_len, const int32_t* l_map, const int64_t* l_id,
+                       float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Qc || !Kc_l || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !l_id) return PBSA_EINVAL;
+  if (p->C > 0 && (!Kc_p || !p_id || !slot_src)) return PBSA_EINVAL;
+  if ((S_sum == nullptr) != (S_cnt == nullptr)) return PBSA_EINVAL;
+  if (!aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(Kc_l) ||
+      !aligned16(Kc_p) || !aligned16(Qc) || !aligned16(S_sum))
+    return PBSA_EALIGN;
+  if (!ws || ws_bytes < workspace_bytes(*p)) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  const pbsa::UpdateWs w = pbsa::carve_update_ws(*p, ws);
+  hipError_t e = pbsa::launch_update(*p, Qc, Kc_l, static_cast<pbsa::bf16_t*>(Kp), static_cast<pbsa::bf16_t*>(Vp),
+                                     Kc_p, p_len, p_id, S_sum, S_cnt, static_cast<const pbsa::bf16_t*>(Kl),
+                                     static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, l_id, scores, slot_src, w,
+                                     static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,622 @@
+// Coarse stage and persistent-memory update kernels for gfx950 (HBM / latency bound, no MFMA).
+//
+//   pool_kernel         block representatives by average pooling            (Eq. 6)
+//   select_kernel       coarse logits + row-wise top-k block selection      (Eq. 10-11)
+//   score_rows_kernel   block-level softmax rows over persistent + local    (Eq. 7)
+//   retain_kernel       column mean, Top-C retention, slot assignment       (Eq. 8-9)
+//   fold_promote_kernel dropped blocks -> running-mean summary; kept newcomers -> slots
+//
+// This file is compiled with -ffp-contract=off: every fp32 operation below is exactly the one
+// written (the arithmetic that decides block sets and slots is specified operation by operation
+// in pbsa.h so that an independent implementation reproduces the integers bit for bit).
+#include "pbsa_internal.h"
+
+namespace pbsa {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kXC = 32;   // pooled-key dimensions staged through LDS per step
+
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+__device__ __forceinline__ uint32_t f2bf_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// exp(x) for x <= 0 from fp32 mul / fma / rint only (steps fixed in pbsa.h).
+__device__ __forceinline__ float pexp(float x) {
+  if (x < -64.0f) return 0.0f;
+  float n = __builtin_rintf(x * 0x1.715476p+0f);
+  float r = __builtin_fmaf(n, -0x1.630000p-1f, x);
+  r = __builtin_fmaf(n, 0x1.bd0106p-13f, r);
+  float p = 0x1.6c16c2p-10f;
+  p = __builtin_fmaf(p, r, 0x1.111112p-7f);
+  p = __builtin_fmaf(p, r, 0x1.555556p-5f);
+  p = __builtin_fmaf(p, r, 0x1.555556p-3f);
+  p = __builtin_fmaf(p, r, 0.5f);
+  p = __builtin_fmaf(p, r, 1.0f);
+  p = __builtin_fmaf(p, r, 1.0f);
+  return p * __uint_as_float((uint32_t)((int)n + 127) << 23);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Pooling.  One job = one block; D/8 threads per job, each owning 8 dimensions (one 16-byte load per
+// token) and adding the tokens in ascending order.
+// ------------------------------------------------------------------------------------------------
+struct PoolArgs {
+  int mode;                 // 0: generic blocks, 1: select (local key blocks, then query blocks)
+  int n_jobs;
+  int H, B, Nq, nqb, n_loc, n_loc_cap, pool_from, n_kjobs_per_head;
+  long q_stride_h, q_stride_t;
+  const bf16_t* X;          // mode 0: [n][B][D]; mode 1: Kl
+  const bf16_t* Q;
+  const int32_t* len;       // mode 0: [n]; mode 1: l_len
+  const int32_t* l_map;
+  float* out;               // mode 0: [n][D]; mode 1: Kc_l
+  float* Qc;
+};
+
+template <int D>
+__global__ void __launch_bounds__(kThreads) pool_kernel(PoolArgs a) {
+  constexpr int TPJ = D / 8;
+  const int job = blockIdx.x * (kThreads / TPJ) + threadIdx.x / TPJ;
+  const int c = threadIdx.x % TPJ;
+  if (job >= a.n_jobs) return;
+  const bf16_t* src;
+  long pitch = D;
+  int len;
+  float* dst;
+  if (a.mode == 0) {
+    src = a.X + (size_t)job * a.B * D;
+    len = a.len[job];
+    dst = a.out + (size_t)job * D;
+  } else {
+    // jobs [0, H*nk) pool local key blocks, the rest pool the chunk's query blocks
+    const int nk = a.n_kjobs_per_head;
+    if (job < a.H * nk) {
+      const int h = job / nk, l = a.pool_from + job % nk;
+      const int slot = a.l_map[l];
+      if (slot < 0 || slot >= a.n_loc_cap) return;
+      src = a.X + ((size_t)h * a.n_loc_cap + slot) * a.B * D;
+      len = a.len[l];
+      dst = a.out + ((size_t)h * a.n_loc_cap + slot) * D;
+    } else {
+      const int jq = job - a.H * nk;
+      const int h = jq / a.nqb, i = jq % a.nqb;
+      src = a.Q + (size_t)h * a.q_stride_h + (size_t)i * a.B * a.q_stride_t;
+      pitch = a.q_stride_t;
+      len = min(a.B, a.Nq - i * a.B);
+      dst = a.Qc + ((size_t)h * a.nqb + i) * D;
+    }
+  }
+  len = max(0, min(len, a.B));
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+  const bf16_t* p = src + c * 8;
+#pragma unroll 8
+  for (int t = 0; t < len; ++t) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p + (size_t)t * pitch);
+    acc[0] = acc[0] + bf_lo(v.x); acc[1] = acc[1] + bf_hi(v.x);
+    acc[2] = acc[2] + bf_lo(v.y); acc[3] = acc[3] + bf_hi(v.y);
+    acc[4] = acc[4] + bf_lo(v.z); acc[5] = acc[5] + bf_hi(v.z);
+    acc[6] = acc[6] + bf_lo(v.w); acc[7] = acc[7] + bf_hi(v.w);
+  }
+  const float fl = (float)len;
+  float4 o0, o1;
+  o0.x = len > 0 ? acc[0] / fl : 0.0f; o0.y = len > 0 ? acc[1] / fl : 0.0f;
+  o0.z = len > 0 ? acc[2] / fl : 0.0f; o0.w = len > 0 ? acc[3] / fl : 0.0f;
+  o1.x = len > 0 ? acc[4] / fl : 0.0f; o1.y = len > 0 ? acc[5] / fl : 0.0f;
+  o1.z = len > 0 ? acc[6] / fl : 0.0f; o1.w = len > 0 ? acc[7] / fl : 0.0f;
+  *reinterpret_cast<float4*>(dst + c * 8) = o0;
+  *reinterpret_cast<float4*>(dst + c * 8 + 4) = o1;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Coarse logits.  A workgroup of 4 waves handles 4 query blocks (one per wave) of one head; lane
+// `lane` of a wave owns columns j = lane + 64 m.  The pooled keys of all columns are staged through
+// LDS kXC dimensions at a time, transposed ([x][j], pitch NM*64+2 keeps both the transposing stores
+// and the per-column loads free of bank conflicts), so each accumulator runs the fixed chain
+// acc = fma(q[x], k[x], acc), x ascending.
+// ------------------------------------------------------------------------------------------------
+template <int D, int NM>
+__device__ __forceinline__ void coarse_dots(const float* const* cols, int n_cols, const float* qrow, float* kct,
+                                            float (&acc)[NM]) {
+  constexpr int NPAD = NM * 64 + 2;
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int m = 0; m < NM; ++m) acc[m] = 0.0f;
+  for (int x0 = 0; x0 < D; x0 += kXC) {
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < n_cols * (kXC / 4); idx += kThreads) {
+      const int j = idx / (kXC / 4), xq = idx % (kXC / 4);
+      const float4 v = *reinterpret_cast<const float4*>(cols[j] + x0 + 4 * xq);
+      kct[(4 * xq + 0) * NPAD + j] = v.x;
+      kct[(4 * xq + 1) * NPAD + j] = v.y;
+      kct[(4 * xq + 2) * NPAD + j] = v.z;
+      kct[(4 * xq + 3) * NPAD + j] = v.w;
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int xx = 0; xx < kXC; ++xx) {
+      const float q = qrow[x0 + xx];
+#pragma unroll
+      for (int m = 0; m < NM; ++m) acc[m] = __builtin_fmaf(q, kct[xx * NPAD + lane + 64 * m], acc[m]);
+    }
+  }
+}
+
+__device__ __forceinline__ int lanes_below(uint64_t mask) {   // set bits of `mask` in lanes below this one
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+struct SelectArgs {
+  int H, nqb, n_loc, n_loc_cap, k, causal;
+  float scale;
+  const float* Kc_l;
+  const float* Qc;
+  const int32_t* l_map;
+  int32_t* sel;
+};
+
+template <int D, int NM>
+__global__ void __launch_bounds__(kThreads) select_kernel(SelectArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NPAD = NM * 64 + 2;
+  float* kct = reinterpret_cast<float*>(smem);                                  // [kXC][NPAD]
+  float* qs = kct + kXC * NPAD;                                                 // [4][D]
+  const float** cols = reinterpret_cast<const float**>(qs + 4 * D);            // [NM*64]
+  const int h = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + wave;
+  const bool row_ok = i < a.nqb;
+  for (int j = threadIdx.x; j < a.n_loc; j += kThreads) {
+    int slot = a.l_map[j];
+    slot = min(max(slot, 0), a.n_loc_cap - 1);
+    cols[j] = a.Kc_l + ((size_t)h * a.n_loc_cap + slot) * D;
+  }
+  for (int x = lane; x < D; x += 64) qs[wave * D + x] = row_ok ? a.Qc[((size_t)h * a.nqb + i) * D + x] : 0.0f;
+  float acc[NM];
+  coarse_dots<D, NM>(cols, a.n_loc, qs + wave * D, kct, acc);
+  if (!row_ok) return;
+
+  // order-preserving integer keys; invisible columns get 0, below every real value
+  const int nvis = a.causal ? a.n_loc - a.nqb + i + 1 : a.n_loc;
+  uint32_t key[NM];
+#pragma unroll
+  for (int m = 0; m < NM; ++m) {
+    float z = acc[m] * a.scale;
+    if (z == 0.0f) z = 0.0f;                    // -0 and +0 compare equal: give them one key
+    const uint32_t b = __float_as_uint(z);
+    const uint32_t ordered = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    key[m] = (lane + 64 * m < nvis) ? ordered : 0u;
+  }
+  const int kk = min(a.k, nvis);
+  int32_t* out = a.sel + ((size_t)h * a.nqb + i) * a.k;
+  if (kk > 0) {
+    // T = kk-th largest key, found bit by bit: the largest T with #{key >= T} >= kk
+    uint32_t T = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = T | (1u << bit);
+      int cnt = 0;
+#pragma unroll
+      for (int m = 0; m < NM; ++m) cnt += __popcll(__ballot(key[m] >= cand));
+      if (cnt >= kk) T = cand;
+    }
+    int n_gt = 0;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) n_gt += __popcll(__ballot(key[m] > T));
+    const int need_eq = kk - n_gt;              // ties at T taken in ascending block order
+    int seen_eq = 0, pos = 0;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      const bool eq = key[m] == T;
+      const uint64_t eq_mask = __ballot(eq);
+      const bool take = key[m] > T || (eq && seen_eq + lanes_below(eq_mask) < need_eq);
+      const uint64_t take_mask = __ballot(take);
+      if (take) out[pos + lanes_below(take_mask)] = lane + 64 * m;
+      seen_eq += __popcll(eq_mask);
+      pos += __popcll(take_mask);
+    }
+  }
+  for (int j = kk + lane; j < a.k; j += 64) out[j] = -1;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Persistence scores, rows (Eq. 7): wave per query block; columns U = occupied persistent slots in
+// slot order, then all local blocks.  Row softmax in the pinned order; the sum runs sequentially
+// over the row in LDS.
+// ------------------------------------------------------------------------------------------------
+struct ScoreArgs {
+  int H, nqb, n_loc, n_loc_cap, C, nU_max;
+  float scale;
+  const float* Kc_l;
+  const float* Kc_p;
+  const float* Qc;
+  const int32_t* l_map;
+  const int32_t* p_len;
+  float* A;
+};
+
+template <int D, int NM>
+__global__ void __launch_bounds__(kThreads) score_rows_kernel(ScoreArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NPAD = NM * 64 + 2;
+  float* kct = reinterpret_cast<float*>(smem);
+  float* qs = kct + kXC * NPAD;
+  const float** cols = reinterpret_cast<const float**>(qs + 4 * D);
+  float* erow = reinterpret_cast<float*>(cols + NM * 64);                       // [4][NM*64]
+  __shared__ int nP_s;
+  __shared__ float sum_s[4];
+  const int h = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + wave;
+  const bool row_ok = i < a.nqb;
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int s = 0; s < a.C; ++s)
+      if (a.p_len[(size_t)h * (a.C + 1) + s] > 0) cols[n++] = a.Kc_p + ((size_t)h * a.C + s) * D;
+    nP_s = n;
+  }
+  __syncthreads();
+  const int nP = nP_s, nU = nP + a.n_loc;
+  for (int j = threadIdx.x; j < a.n_loc; j += kThreads) {
+    int slot = a.l_map[j];
+    slot = min(max(slot, 0), a.n_loc_cap - 1);
+    cols[nP + j] = a.Kc_l + ((size_t)h * a.n_loc_cap + slot) * D;
+  }
+  for (int x = lane; x < D; x += 64) qs[wave * D + x] = row_ok ? a.Qc[((size_t)h * a.nqb + i) * D + x] : 0.0f;
+  float acc[NM];
+  coarse_dots<D, NM>(cols, nU, qs + wave * D, kct, acc);
+
+  float mx = -INFINITY;
+#pragma unroll
+  for (int m = 0; m < NM; ++m) {
+    acc[m] = acc[m] * a.scale;
+    if (lane + 64 * m < nU) mx = fmaxf(mx, acc[m]);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  float* er = erow + wave * (NM * 64);
+#pragma unroll
+  for (int m = 0; m < NM; ++m) {
+    acc[m] = (lane + 64 * m < nU) ? pexp(acc[m] - mx) : 0.0f;
+    er[lane + 64 * m] = acc[m];
+  }
+  __syncthreads();
+  if (lane == 0) {
+    float s = 0.0f;
+    for (int j = 0; j < nU; ++j) s = s + er[j];
+    sum_s[wave] = s;
+  }
+  __syncthreads();
+  if (!row_ok) return;
+  const float s = sum_s[wave];
+  float* arow = a.A + ((size_t)h * a.nqb + i) * a.nU_max;
+#pragma unroll
+  for (int m = 0; m < NM; ++m)
+    if (lane + 64 * m < nU) arow[lane + 64 * m] = acc[m] / s;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Retention (Eq. 8-9): one workgroup per head.
+// ------------------------------------------------------------------------------------------------
+constexpr int kMaxCand = PBSA_MAX_C + PBSA_MAX_N_LOC;
+
+struct RetainArgs {
+  int H, nqb, n_loc, n_loc_cap, C, n_sink, n_evict, nU_max, d, B, fold;
+  const float* A;
+  const float* Kc_l;
+  float* Kc_p;
+  int32_t* p_len;
+  int64_t* p_id;
+  int32_t* S_cnt;
+  const int32_t* l_len;
+  const int32_t* l_map;
+  const int64_t* l_id;
+  float* scores;
+  int32_t* slot_src;
+  int32_t* fold_n;
+  int32_t* fold_src;
+  int32_t* fold_len;
+};
+
+__global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
+  __shared__ float s[kMaxCand];           // mean column score, U order
+  __shared__ int cand[kMaxCand];          // < C: slot, else C + local block
+  __shared__ float cs[kMaxCand];
+  __shared__ unsigned char win[kMaxCand];
+  __shared__ int old_len[PBSA_MAX_C + 1];
+  __shared__ int src_s[PBSA_MAX_C];
+  __shared__ int flen[kMaxCand];          // valid tokens of each dropped candidate
+  __shared__ int nP_s, nc_s, nf_s, npos_s;
+  const int h = blockIdx.x, C = a.C, C1 = a.C + 1;
+  int32_t* plen = a.p_len + (size_t)h * C1;
+  for (int c = threadIdx.x; c < C1; c += kThreads) old_len[c] = plen[c];
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int c = 0; c < C; ++c) n += old_len[c] > 0;
+    nP_s = n;
+  }
+  __syncthreads();
+  const int nP = nP_s, nU = nP + a.n_loc;
+  for (int j = threadIdx.x; j < nU; j += kThreads) {
+    float acc = 0.0f;
+    const float* col = a.A + (size_t)h * a.nqb * a.nU_max + j;
+    for (int i = 0; i < a.nqb; ++i) acc = acc + col[(size_t)i * a.nU_max];
+    s[j] = acc / (float)a.nqb;
+  }
+  __syncthreads();
+  const int ncand_max = C + a.n_evict;
+  if (threadIdx.x == 0) {
+    int nc = 0, u = 0;
+    for (int c = 0; c < C; ++c) {
+      const bool occ = old_len[c] > 0;
+      if (a.scores) a.scores[(size_t)h * ncand_max + c] = occ ? s[u] : 0.0f;
+      if (occ && c >= a.n_sink) { cand[nc] = c; cs[nc++] = s[u]; }
+      u += occ;
+    }
+    for (int e = 0; e < a.n_evict; ++e) {
+      if (a.scores) a.scores[(size_t)h * ncand_max + C + e] = s[nP + e];
+      cand[nc] = C + e; cs[nc++] = s[nP + e];
+    }
+    nc_s = nc;
+  }
+  __syncthreads();
+  const int nc = nc_s, places = C - a.n_sink;
+  for (int x = threadIdx.x; x < nc; x += kThreads) {
+    int rank = 0;
+    const float mine = cs[x];
+    for (int y = 0; y < nc; ++y) rank += (cs[y] > mine || (cs[y] == mine && y < x)) ? 1 : 0;
+    win[x] = rank < places;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int nf = 0;
+    for (int x = 0; x < nc; ++x) {
+      if (win[x]) continue;
+      const int len = cand[x] < C ? old_len[cand[x]] : max(0, min(a.l_len[cand[x] - C], a.B));
+      a.fold_src[(size_t)h * ncand_max + nf] = cand[x];
+      a.fold_len[(size_t)h * ncand_max + nf] = len;
+      flen[nf] = len;
+      ++nf;
+      if (cand[x] < C) old_len[cand[x]] = 0;       // vacate
+    }
+    a.fold_n[h] = nf;
+    nf_s = nf;
+    npos_s = 0;
+    for (int c = 0; c < C; ++c) src_s[c] = -1;
+    int slot = a.n_sink;
+    for (int x = 0; x < nc; ++x) {
+      if (!win[x] || cand[x] < C) continue;
+      const int e = cand[x] - C;
+      while (slot < C && old_len[slot] > 0) ++slot;
+      if (slot >= C) break;
+      old_len[slot] = max(0, min(a.l_len[e], a.B));
+      src_s[slot] = e;
+      a.p_id[(size_t)h * C + slot] = a.l_id[e];
+    }
+    for (int c = a.n_sink; c < C; ++c)
+      if (old_len[c] == 0) a.p_id[(size_t)h * C + c] = -1;
+  }
+  __syncthreads();
+  // per-position counts of the summary: every dropped block adds one to each position it has
+  if (a.fold && nf_s > 0) {
+    for (int t = threadIdx.x; t < a.B; t += kThreads) {
+      int cnt = a.S_cnt[(size_t)h * a.B + t];
+      for (int f = 0; f < nf_s; ++f) cnt += t < flen[f] ? 1 : 0;
+      a.S_cnt[(size_t)h * a.B + t] = cnt;
+      if (cnt > 0) atomicAdd(&npos_s, 1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) old_len[C] = npos_s;
+    __syncthreads();
+  }
+  for (int c = threadIdx.x; c < C1; c += kThreads) plen[c] = old_len[c];
+  for (int c = threadIdx.x; c < C; c += kThreads) a.slot_src[(size_t)h * C + c] = src_s[c];
+  for (int idx = threadIdx.x; idx < C * a.d; idx += kThreads) {
+    const int c = idx / a.d, x = idx % a.d;
+    const int e = src_s[c];
+    if (e >= 0) {
+      const int slot = min(max(a.l_map[e], 0), a.n_loc_cap - 1);
+      a.Kc_p[((size_t)h * C + c) * a.d + x] = a.Kc_l[((size_t)h * a.n_loc_cap + slot) * a.d + x];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fold + promote.  One thread owns 4 dimensions of one position t of K or V of one head: it adds
+// the dropped blocks' rows to the running sum in candidate order, rewrites the summary row, then
+// copies row t of every kept newcomer into its slot.  A slot that is both dropped and refilled is
+// read and written by the same thread, in that order.
+// ------------------------------------------------------------------------------------------------
+struct FoldArgs {
+  int H, B, d, C, n_loc_cap, n_evict, fold;
+  bf16_t* Kp;
+  bf16_t* Vp;
+  const bf16_t* Kl;
+  const bf16_t* Vl;
+  const int32_t* l_map;
+  float* S_sum;
+  const int32_t* S_cnt;
+  const int32_t* slot_src;
+  const int32_t* fold_n;
+  const int32_t* fold_src;
+  const int32_t* fold_len;
+};
+
+__global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
+  const int tpr = a.d / 4;                                     // threads per row
+  const int rows_per_wg = kThreads / tpr;
+  const int row = blockIdx.x * rows_per_wg + threadIdx.x / tpr; // over [2][B]
+  const int xc = (threadIdx.x % tpr) * 4;
+  const int h = blockIdx.y;
+  if (row >= 2 * a.B) return;
+  const int kv = row / a.B, t = row % a.B;
+  const int C = a.C, C1 = a.C + 1, ncand_max = a.C + a.n_evict;
+  const size_t blk = (size_t)a.B * a.d;
+  bf16_t* P = kv ? a.Vp : a.Kp;
+  const bf16_t* L = kv ? a.Vl : a.Kl;
+  const size_t rowoff = (size_t)t * a.d + xc;
+  const int nf = a.fold_n[h];
+  if (a.fold && nf > 0) {
+    float* ssum = a.S_sum + ((size_t)h * 2 + kv) * blk + rowoff;
+    float4 acc = *reinterpret_cast<float4*>(ssum);
+    const int cnt = a.S_cnt[(size_t)h * a.B + t];     // already the new count (retain_kernel)
+    for (int f = 0; f < nf; ++f) {
+      const int src = a.fold_src[(size_t)h * ncand_max + f];
+      const int len = a.fold_len[(size_t)h * ncand_max + f];
+      if (t >= len) continue;
+      const bf16_t* blkp;
+      if (src < C) {
+        blkp = P + ((size_t)h * C1 + src) * blk;
+      } else {
+        const int slot = min(max(a.l_map[src - C], 0), a.n_loc_cap - 1);
+        blkp = L + ((size_t)h * a.n_loc_cap + slot) * blk;
+      }
+      const uint2 v = *reinterpret_cast<const uint2*>(blkp + rowoff);
+      acc.x = acc.x + bf_lo(v.x); acc.y = acc.y + bf_hi(v.x);
+      acc.z = acc.z + bf_lo(v.y); acc.w = acc.w + bf_hi(v.y);
+    }
+    *reinterpret_cast<float4*>(ssum) = acc;
+    if (cnt > 0) {
+      const float fc = (float)cnt;
+      uint2 o;
+      o.x = f2bf_rne(acc.x / fc) | (f2bf_rne(acc.y / fc) << 16);
+      o.y = f2bf_rne(acc.z / fc) | (f2bf_rne(acc.w / fc) << 16);
+      *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + C) * blk + rowoff) = o;
+    }
+  }
+  for (int c = 0; c < C; ++c) {
+    const int e = a.slot_src[(size_t)h * C + c];
+    if (e < 0) continue;
+    const int slot = min(max(a.l_map[e], 0), a.n_loc_cap - 1);
+    *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + c) * blk + rowoff) =
+        *reinterpret_cast<const uint2*>(L + ((size_t)h * a.n_loc_cap + slot) * blk + rowoff);
+  }
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes);
+}
+
+template <int NM>
+size_t coarse_lds_bytes(int d, bool with_rows) {
+  size_t b = (size_t)kXC * (NM * 64 + 2) * 4 + (size_t)4 * d * 4 + (size_t)NM * 64 * 8;
+  if (with_rows) b += (size_t)4 * NM * 64 * 4;
+  return b;
+}
+
+}  // namespace
+
+UpdateWs carve_update_ws(const pbsa_params& p, void* base) {
+  UpdateWs w;
+  char* b = static_cast<char*>(base);
+  size_t off = 0;
+  const size_t nU_max = (size_t)p.C + p.n_loc, ncand = (size_t)p.C + p.n_evict;
+  w.A = reinterpret_cast<float*>(b + off);          off += align256((size_t)p.H * p.nqb * nU_max * 4);
+  w.fold_n = reinterpret_cast<int32_t*>(b + off);   off += align256((size_t)p.H * 4);
+  w.fold_src = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * ncand * 4);
+  w.fold_len = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * ncand * 4);
+  w.bytes = off;
+  return w;
+}
+
+hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32_t* len, int32_t n_blocks,
+                              float* out, hipStream_t stream) {
+  if (n_blocks == 0) return hipSuccess;
+  PoolArgs a{};
+  a.mode = 0; a.n_jobs = n_blocks; a.B = p.B; a.X = X; a.len = len; a.out = out;
+  const int jpw = kThreads / (p.d / 8);
+  const dim3 grid((n_blocks + jpw - 1) / jpw);
+  if (p.d == 128) hipLaunchKernelGGL(pool_kernel<128>, grid, dim3(kThreads), 0, stream, a);
+  else hipLaunchKernelGGL(pool_kernel<64>, grid, dim3(kThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+template <int D, int NM>
+static hipError_t launch_select_t(const SelectArgs& a, hipStream_t stream) {
+  const size_t lds = coarse_lds_bytes<NM>(D, false);
+  hipError_t e = allow_lds(select_kernel<D, NM>, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((select_kernel<D, NM>), dim3((a.nqb + 3) / 4, a.H), dim3(kThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
+                         const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, hipStream_t stream) {
+  PoolArgs pa{};
+  pa.mode = 1; pa.H = p.H; pa.B = p.B; pa.Nq = p.Nq; pa.nqb = p.nqb; pa.n_loc = p.n_loc; pa.n_loc_cap = p.n_loc_cap;
+  pa.pool_from = p.pool_from; pa.n_kjobs_per_head = p.n_loc - p.pool_from;
+  pa.n_jobs = p.H * (pa.n_kjobs_per_head + p.nqb);
+  pa.q_stride_h = p.q_stride_h; pa.q_stride_t = p.q_stride_t;
+  pa.X = Kl; pa.Q = Q; pa.len = l_len; pa.l_map = l_map; pa.out = Kc_l; pa.Qc = Qc;
+  const int jpw = kThreads / (p.d / 8);
+  const dim3 grid((pa.n_jobs + jpw - 1) / jpw);
+  if (p.d == 128) hipLaunchKernelGGL(pool_kernel<128>, grid, dim3(kThreads), 0, stream, pa);
+  else hipLaunchKernelGGL(pool_kernel<64>, grid, dim3(kThreads), 0, stream, pa);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (p.k == 0) return hipSuccess;
+
+  SelectArgs a{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.k, p.causal, p.scale, Kc_l, Qc, l_map, sel};
+  const int nm = (p.n_loc + 63) / 64;
+  if (p.d == 128) {
+    if (nm <= 2) return launch_select_t<128, 2>(a, stream);
+    if (nm <= 5) return launch_select_t<128, 5>(a, stream);
+    return launch_select_t<128, 8>(a, stream);
+  }
+  if (nm <= 2) return launch_select_t<64, 2>(a, stream);
+  if (nm <= 5) return launch_select_t<64, 5>(a, stream);
+  return launch_select_t<64, 8>(a, stream);
+}
+
+template <int D, int NM>
+static hipError_t launch_rows_t(const ScoreArgs& a, hipStream_t stream) {
+  const size_t lds = coarse_lds_bytes<NM>(D, true);
+  hipError_t e = allow_lds(score_rows_kernel<D, NM>, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((score_rows_kernel<D, NM>), dim3((a.nqb + 3) / 4, a.H), dim3(kThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, bf16_t* Kp, bf16_t* Vp,
+                         float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                         const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                         const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
+                         hipStream_t stream) {
+  const int nU_max = p.C + p.n_loc;
+  ScoreArgs sa{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.C, nU_max, p.scale, Kc_l, Kc_p, Qc, l_map, p_len, ws.A};
+  const int nm = (nU_max + 63) / 64;
+  hipError_t e;
+  if (p.d == 128) {
+    e = nm <= 2 ? launch_rows_t<128, 2>(sa, stream) : nm <= 5 ? launch_rows_t<128, 5>(sa, stream)
+                                                              : launch_rows_t<128, 9>(sa, stream);
+  } else {
+    e = nm <= 2 ? launch_rows_t<64, 2>(sa, stream) : nm <= 5 ? launch_rows_t<64, 5>(sa, stream)
+                                                             : launch_rows_t<64, 9>(sa, stream);
+  }
+  if (e != hipSuccess) return e;
+
+  const int fold = S_sum != nullptr;
+  RetainArgs ra{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.C, p.n_sink, p.n_evict, nU_max, p.d, p.B, fold, ws.A, Kc_l,
+                Kc_p, p_len, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n, ws.fold_src, ws.fold_len};
+  hipLaunchKernelGGL(retain_kernel, dim3(p.H), dim3(kThreads), 0, stream, ra);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  FoldArgs fa{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, fold, Kp, Vp, Kl, Vl, l_map, S_sum, S_cnt, slot_src,
+              ws.fold_n, ws.fold_src, ws.fold_len};
+  const int rows_per_wg = kThreads / (p.d / 4);
+  hipLaunchKernelGGL(fold_promote_kernel, dim3((2 * p.B + rows_per_wg - 1) / rows_per_wg, p.H), dim3(kThreads), 0,
+                     stream, fa);
+  return hipGetLastError();
+}
+
+}  // namespace pbsa

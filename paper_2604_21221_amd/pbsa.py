@@ -1,0 +1,146 @@
+"""Thin ctypes binding of libpbsa.so: argument marshalling only, same names as include/pbsa.h.
+
+Tensor arguments are torch tensors living on the GPU (their data_ptr() is passed through) or plain
+integers holding a device address.  Nothing is computed here and there is no fallback: if the HIP
+library is missing the import of the library fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libpbsa.so")
+
+PBSA_OK, PBSA_EINVAL, PBSA_ESHAPE, PBSA_EALIGN, PBSA_EWS, PBSA_EHIP = 0, -1, -2, -3, -4, -5
+PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_K = 512, 64, 128
+
+EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
+           "pbsa_memory_update", "pbsa_strerror", "pbsa_version")
+
+
+class pbsa_params(ctypes.Structure):
+    _fields_ = [("size", ctypes.c_uint32), ("H", ctypes.c_int32), ("d", ctypes.c_int32), ("B", ctypes.c_int32),
+                ("Nq", ctypes.c_int32), ("nqb", ctypes.c_int32), ("n_loc", ctypes.c_int32),
+                ("n_loc_cap", ctypes.c_int32), ("C", ctypes.c_int32), ("n_sink", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("causal", ctypes.c_int32), ("n_evict", ctypes.c_int32),
+                ("pool_from", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_stride_h", ctypes.c_int64), ("q_stride_t", ctypes.c_int64),
+                ("o_stride_h", ctypes.c_int64), ("o_stride_t", ctypes.c_int64)]
+
+
+def make_params(H, d, B, Nq, n_loc, n_loc_cap, C, k, scale, n_sink=0, causal=1, n_evict=0, pool_from=0,
+                q_strides=None, o_strides=None) -> pbsa_params:
+    qs = q_strides or (Nq * d, d)
+    os_ = o_strides or (Nq * d, d)
+    return pbsa_params(ctypes.sizeof(pbsa_params), H, d, B, Nq, -(-Nq // B), n_loc, n_loc_cap, C, n_sink, k, causal,
+                       n_evict, pool_from, scale, qs[0], qs[1], os_[0], os_[1])
+
+
+class PbsaError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"pbsa error {code}: {pbsa_strerror(code)}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libpbsa.so (built in-tree by paper_2604_21221_amd/build.py).  No fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_21221_amd.build` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        pp = ctypes.POINTER(pbsa_params)
+        L.pbsa_version.restype = ctypes.c_int
+        L.pbsa_version.argtypes = []
+        L.pbsa_strerror.restype = ctypes.c_char_p
+        L.pbsa_strerror.argtypes = [ctypes.c_int]
+        L.pbsa_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+        L.pbsa_pool_blocks.argtypes = [pp, vp, vp, i32, vp, vp]
+        L.pbsa_select_blocks.argtypes = [pp] + [vp] * 8 + [sz, vp]
+        L.pbsa_attention_fwd.argtypes = [pp] + [vp] * 12 + [sz, vp]
+        L.pbsa_memory_update.argtypes = [pp] + [vp] * 17 + [sz, vp]
+        for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
+                     "pbsa_memory_update"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(x):
+    """Device address of a tensor (must be on the GPU), or an int / None passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    if not x.is_cuda:
+        raise TypeError("pbsa: tensor arguments must live on the GPU")
+    if not x.is_contiguous() and x.dim() < 3:
+        raise TypeError("pbsa: small tensors must be contiguous")
+    return ctypes.c_void_p(x.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    if isinstance(ws, tuple):
+        return ctypes.c_void_p(ws[0]), ws[1]
+    return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def _check(rc: int):
+    if rc != PBSA_OK:
+        raise PbsaError(rc)
+
+
+def pbsa_version() -> int:
+    return lib().pbsa_version()
+
+
+def pbsa_strerror(code: int) -> str:
+    return lib().pbsa_strerror(code).decode()
+
+
+def pbsa_workspace_bytes(p: pbsa_params) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().pbsa_workspace_bytes(ctypes.byref(p), ctypes.byref(out)))
+    return out.value
+
+
+def pbsa_pool_blocks(p, X, length, n_blocks, out, stream=None):
+    _check(lib().pbsa_pool_blocks(ctypes.byref(p), _ptr(X), _ptr(length), n_blocks, _ptr(out), _stream(stream)))
+
+
+def pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, ws=None, stream=None):
+    w, wb = _ws(ws)
+    _check(lib().pbsa_select_blocks(ctypes.byref(p), _ptr(Q), _ptr(Kl), _ptr(l_len), _ptr(l_map), _ptr(Kc_l),
+                                    _ptr(Qc), _ptr(sel), w, wb, _stream(stream)))
+
+
+def pbsa_attention_fwd(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse=None, ws=None, stream=None):
+    w, wb = _ws(ws)
+    _check(lib().pbsa_attention_fwd(ctypes.byref(p), _ptr(Q), _ptr(Kp), _ptr(Vp), _ptr(p_len), _ptr(Kl), _ptr(Vl),
+                                    _ptr(l_len), _ptr(l_map), _ptr(sel), _ptr(O), _ptr(lse), w, wb, _stream(stream)))
+
+
+def pbsa_memory_update(p, Qc, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id, scores,
+                       slot_src, ws, stream=None):
+    w, wb = _ws(ws)
+    _check(lib().pbsa_memory_update(ctypes.byref(p), _ptr(Qc), _ptr(Kc_l), _ptr(Kp), _ptr(Vp), _ptr(Kc_p),
+                                    _ptr(p_len), _ptr(p_id), _ptr(S_sum), _ptr(S_cnt), _ptr(Kl), _ptr(Vl),
+                                    _ptr(l_len), _ptr(l_map), _ptr(l_id), _ptr(scores), _ptr(slot_src), w, wb,
+                                    _stream(stream)))

@@ -20,6 +20,7 @@ from __future__ import annotations
 
 import functools
 import math
+import os
 from dataclasses import dataclass
 
 import numpy as np
@@ -65,23 +66,55 @@ def uniforms(key: int, n: int) -> np.ndarray:
     return (bits >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))
 
 
+def _normals_into(out: np.ndarray, key: int, s: int, e: int) -> None:
+    """Fill out[2s:2e] with the normals of pair counters s..e-1."""
+    with np.errstate(over="ignore"):
+        ctr = np.arange(s, e, dtype=np.uint64)
+        ctr *= np.uint64(2)
+        ctr *= np.uint64(_GOLD)
+        ctr += np.uint64(key)
+        a = _mix_arr(ctr)
+        ctr += np.uint64(_GOLD)
+        b = _mix_arr(ctr)
+    a >>= np.uint64(11)
+    b >>= np.uint64(11)
+    u1 = a.astype(np.float64)
+    u1 += 1.0
+    u1 *= 1.0 / (1 << 53)                  # (0, 1]
+    th = b.astype(np.float64)
+    th *= (2.0 * math.pi) / (1 << 53)      # 2 pi u2, u2 in [0, 1)
+    np.log(u1, out=u1)
+    u1 *= -2.0
+    np.sqrt(u1, out=u1)
+    out[2 * s:2 * e:2] = u1 * np.cos(th)
+    np.sin(th, out=th)
+    th *= u1
+    out[2 * s + 1:2 * e:2] = th
+
+
+_POOL = None
+_N_THREADS = max(1, min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else 4))
+
+
 def normals(key: int, n: int) -> np.ndarray:
-    """n standard normals (fp64) by Box-Muller on pairs of counter-based uniforms."""
+    """n standard normals (fp64) by Box-Muller on pairs of counter-based uniforms.
+
+    Element i depends only on (key, i); large requests are split over a few threads, which changes
+    nothing in the result.
+    """
+    global _POOL
     npair = (n + 1) // 2
     out = np.empty(2 * npair, dtype=np.float64)
-    step = 1 << 22
-    for s in range(0, npair, step):
-        e = min(npair, s + step)
-        with np.errstate(over="ignore"):
-            ctr = (np.arange(s, e, dtype=np.uint64) * np.uint64(2)) * np.uint64(_GOLD) + np.uint64(key)
-            a = _mix_arr(ctr)
-            b = _mix_arr(ctr + np.uint64(_GOLD))
-        u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / (1 << 53))  # (0, 1]
-        u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))          # [0, 1)
-        r = np.sqrt(-2.0 * np.log(u1))
-        th = (2.0 * math.pi) * u2
-        out[2 * s:2 * e:2] = r * np.cos(th)
-        out[2 * s + 1:2 * e:2] = r * np.sin(th)
+    step = 1 << 18
+    spans = [(s, min(npair, s + step)) for s in range(0, npair, step)]
+    if len(spans) <= 1 or _N_THREADS == 1:
+        for s, e in spans:
+            _normals_into(out, key, s, e)
+    else:
+        if _POOL is None:
+            from concurrent.futures import ThreadPoolExecutor
+            _POOL = ThreadPoolExecutor(max_workers=_N_THREADS)
+        list(_POOL.map(lambda se: _normals_into(out, key, se[0], se[1]), spans))
     return out[:n]
 
 
@@ -189,6 +222,7 @@ def _heavy_flags(w: Workload, layer: int, n_blocks: int) -> np.ndarray:
     return u < w.heavy_prob
 
 
+@functools.lru_cache(maxsize=6)
 def chunk_qkv(w: Workload, layer: int, chunk: int):
     """bf16 bit patterns (uint16) of Q, K, V for global chunk index `chunk`: each [H][Nq][d], token-major.
 
@@ -196,6 +230,7 @@ def chunk_qkv(w: Workload, layer: int, chunk: int):
     bias_scale * sum_r c[g][r] u[r] added (Q and K share the basis u, V has its own); with
     heavy_prob > 0 a (head, block) is heavy with that probability and its Q and K tokens are
     multiplied by heavy_scale (V is left alone so outputs stay in bf16's fine range).
+    The returned arrays are cached and read-only.
     """
     H, Nq, d, B, nqb = w.H, w.Nq, w.d, w.B, w.nqb
     if not 0 <= chunk < MAX_CHUNKS:
@@ -216,7 +251,9 @@ def chunk_qkv(w: Workload, layer: int, chunk: int):
         if w.heavy_prob > 0 and tag != "v":
             mul = np.where(heavy, w.heavy_scale, 1.0)[:, np.arange(Nq) // B]     # [H][Nq]
             x *= mul[:, :, None]
-        out.append(to_bf16_bits(x))
+        bits = to_bf16_bits(x)
+        bits.setflags(write=False)
+        out.append(bits)
     return tuple(out)
 
 

@@ -1,0 +1,139 @@
+"""C-ABI checks that need no GPU: the library loads, exports what include/pbsa.h declares, and
+rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_21221_amd import pbsa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(pbsa.LIB_PATH):
+        from paper_2604_21221_amd import build
+        build.build()
+    return pbsa.lib()
+
+
+def good(**kw):
+    a = dict(H=2, d=128, B=64, Nq=200, n_loc=16, n_loc_cap=16, C=4, k=3, scale=0.088)
+    a.update(kw)
+    return pbsa.make_params(**a)
+
+
+def test_exports_match_header(L):
+    text = open(os.path.join(ROOT, "include", "pbsa.h")).read()
+    declared = set(re.findall(r"\b(pbsa_[a-z_]+)\s*\(", text))
+    assert declared == set(pbsa.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name)
+    assert pbsa.pbsa_version() >= 1
+    assert ctypes.sizeof(pbsa.pbsa_params) == 92 or ctypes.sizeof(pbsa.pbsa_params) == 96
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(pbsa.pbsa_strerror(code), str) and pbsa.pbsa_strerror(code)
+
+
+def test_header_constants_match_binding():
+    text = open(os.path.join(ROOT, "include", "pbsa.h")).read()
+    for name in ("PBSA_MAX_N_LOC", "PBSA_MAX_C", "PBSA_MAX_K"):
+        assert int(re.search(rf"#define {name}\s+(\d+)", text).group(1)) == getattr(pbsa, name)
+    for name in ("PBSA_EINVAL", "PBSA_ESHAPE", "PBSA_EALIGN", "PBSA_EWS", "PBSA_EHIP"):
+        assert int(re.search(rf"#define {name}\s+\((-\d+)\)", text).group(1)) == getattr(pbsa, name)
+
+
+def test_workspace_bytes(L):
+    n = pbsa.pbsa_workspace_bytes(good(n_evict=4))
+    assert n >= 2 * 4 * (4 + 16) * 4 and n % 256 == 0
+    with pytest.raises(pbsa.PbsaError) as e:
+        pbsa.pbsa_workspace_bytes(good(d=96))
+    assert e.value.code == pbsa.PBSA_ESHAPE
+
+
+P = 0x10000  # a fake, 16-byte aligned, non-NULL device address: validation must fail before it is touched
+
+
+def call_select(p, Q=P, Kl=P, l_len=P, l_map=P, Kc_l=P, Qc=P, sel=P):
+    pbsa.pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, None, stream=0)
+
+
+def call_attn(p, Q=P, Kp=P, Vp=P, p_len=P, Kl=P, Vl=P, l_len=P, l_map=P, sel=P, O=P):
+    pbsa.pbsa_attention_fwd(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, None, None, stream=0)
+
+
+def call_update(p, ws=(0x10000, 1 << 30), S_sum=P, S_cnt=P, Qc=P):
+    pbsa.pbsa_memory_update(p, Qc, P, P, P, P, P, P, S_sum, S_cnt, P, P, P, P, P, None, P, ws, stream=0)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=96), pbsa.PBSA_ESHAPE), (dict(B=32), pbsa.PBSA_ESHAPE), (dict(k=129), pbsa.PBSA_ESHAPE),
+    (dict(C=65), pbsa.PBSA_ESHAPE), (dict(n_loc=513, n_loc_cap=513), pbsa.PBSA_ESHAPE),
+    (dict(n_loc=2), pbsa.PBSA_EINVAL),               # fewer local blocks than the chunk itself has
+    (dict(n_loc=17), pbsa.PBSA_EINVAL),              # more than the physical capacity
+    (dict(n_sink=5), pbsa.PBSA_EINVAL), (dict(n_evict=17), pbsa.PBSA_EINVAL), (dict(causal=2), pbsa.PBSA_EINVAL),
+    (dict(scale=0.0), pbsa.PBSA_EINVAL), (dict(H=0), pbsa.PBSA_EINVAL), (dict(pool_from=17), pbsa.PBSA_EINVAL),
+    (dict(q_strides=(200 * 128, 100)), pbsa.PBSA_EINVAL), (dict(q_strides=(200 * 132, 132)), pbsa.PBSA_EALIGN),
+])
+def test_bad_params_rejected_by_every_call(L, kw, code):
+    p = good(**kw)
+    for call in (call_select, call_attn):
+        with pytest.raises(pbsa.PbsaError) as e:
+            call(p)
+        assert e.value.code == code
+    if "q_strides" not in kw:
+        with pytest.raises(pbsa.PbsaError) as e:
+            call_update(p)
+        assert e.value.code == code
+
+
+def test_wrong_struct_size_and_nqb(L):
+    p = good()
+    p.size = 8
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_select(p)
+    assert e.value.code == pbsa.PBSA_EINVAL
+    p = good()
+    p.nqb = 3
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_attn(p)
+    assert e.value.code == pbsa.PBSA_EINVAL
+
+
+def test_null_and_misaligned_pointers(L):
+    p = good()
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_select(p, Q=None)
+    assert e.value.code == pbsa.PBSA_EINVAL
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_select(p, Kl=P + 2)
+    assert e.value.code == pbsa.PBSA_EALIGN
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_attn(p, O=None)
+    assert e.value.code == pbsa.PBSA_EINVAL
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_attn(p, Vl=P + 8)
+    assert e.value.code == pbsa.PBSA_EALIGN
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_update(p, S_cnt=None)                 # S_sum without S_cnt
+    assert e.value.code == pbsa.PBSA_EINVAL
+
+
+def test_workspace_checks(L):
+    p = good(n_evict=4)
+    need = pbsa.pbsa_workspace_bytes(p)
+    for ws in (None, (0x10000, need - 1)):
+        with pytest.raises(pbsa.PbsaError) as e:
+            call_update(p, ws=ws)
+        assert e.value.code == pbsa.PBSA_EWS
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_update(p, ws=(0x10010, need))
+    assert e.value.code == pbsa.PBSA_EALIGN
+
+
+def test_binding_refuses_host_tensors(L):
+    import torch
+    with pytest.raises(TypeError):
+        pbsa.pbsa_select_blocks(good(), torch.zeros(4), P, P, P, P, P, P, None, stream=0)

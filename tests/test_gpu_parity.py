@@ -1,0 +1,252 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar: block sets, slot assignments, ids, lengths and counts bit-exact; the fp32 quantities that decide
+them (pooled representatives, persistence scores, running sums) bit-exact too, because both sides
+follow the same operation order; attention outputs within max-abs 2e-2 and mean-abs 2e-3 of the
+fp64 oracle (bf16 P and bf16 O are the only roundings the kernel adds).
+"""
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle.rollout import OracleState, state_for_workload  # noqa: E402
+from paper_2604_21221_amd import synth  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2604_21221_amd import cache, pbsa, workloads
+    pbsa.lib()
+    return dict(cache=cache, pbsa=pbsa, wl=workloads)
+
+
+def rnd(key, *shape, scale=1.0):
+    return synth.to_bf16_bits(scale * synth.normals(synth.stream_key(4321, "misc", key), int(np.prod(shape))).reshape(shape))
+
+
+def check_attention(O_gpu, O_ref, what):
+    err = np.abs(O_gpu.astype(np.float64) - O_ref)
+    print(f"{what}: max-abs {err.max():.3e} mean-abs {err.mean():.3e} max|O| {np.abs(O_ref).max():.2f}", flush=True)
+    assert np.isfinite(O_gpu).all(), what
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, what
+
+
+def compare_select(c, st, what):
+    sel = c.sel.cpu().numpy()[:, :, :st.k]
+    assert np.array_equal(sel, st.sel), f"{what}: block sets differ"
+    assert np.array_equal(c.Qc.cpu().numpy().view(np.uint32), st.Qc.view(np.uint32)), f"{what}: pooled queries differ"
+    assert np.array_equal(c.Kc_l.cpu().numpy().view(np.uint32), st.Kc_l.view(np.uint32)), f"{what}: pooled keys differ"
+
+
+def compare_update(c, st, wl, sc_ref, src_ref, ne, what):
+    H, C = st.H, st.C
+    if C > 0:
+        assert np.array_equal(c.slot_src.cpu().numpy()[:, :C], src_ref), f"{what}: slot assignment differs"
+        sc = c.scores.view(-1)[:H * (C + ne)].view(H, C + ne).cpu().numpy()
+        assert np.array_equal(sc.view(np.uint32), sc_ref.view(np.uint32)), f"{what}: persistence scores differ"
+        assert np.array_equal(c.p_id.cpu().numpy()[:, :C], st.p_id), f"{what}: ids differ"
+        assert np.array_equal(c.Kc_p.cpu().numpy()[:, :C].view(np.uint32), st.Kc_p.view(np.uint32)), what
+    assert np.array_equal(c.p_len.cpu().numpy(), st.p_len), f"{what}: slot lengths differ"
+    assert np.array_equal(wl.bits_of(c.Kp), st.Kp) and np.array_equal(wl.bits_of(c.Vp), st.Vp), f"{what}: slots differ"
+    if st.S_sum is not None:
+        assert np.array_equal(c.S_cnt.cpu().numpy(), st.S_cnt), f"{what}: summary counts differ"
+        assert np.array_equal(c.S_sum.cpu().numpy().view(np.uint32), st.S_sum.view(np.uint32)), f"{what}: sums differ"
+
+
+def run_both(gpu, c, st, Q, K, V, g, rows, what, lse_check=True):
+    """One layer-chunk step on both sides; compares everything; rows = 'all' or (heads, tokens)."""
+    wl = gpu["wl"]
+    B = st.B
+    lens = np.full(st.nqb, B, np.int32); lens[-1] = st.Nq - (st.nqb - 1) * B
+    print(f"[case] {what} chunk {g}", flush=True)
+    st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * st.nqb + np.arange(st.nqb))
+    Qd, Kd, Vd = (wl.bf16_tensor(x, DEV) for x in (Q, K, V))
+    c.append_chunk(Kd, Vd, g)
+    st.select(Q)
+    c.select(Qd)
+    compare_select(c, st, what)
+    if rows is not None:
+        lse = torch.empty(st.H, st.Nq, dtype=torch.float32, device=DEV)
+        O = c.attention(Qd, lse=lse)
+        Og = O.float().cpu().numpy()
+        if isinstance(rows, str):
+            Oref, lref = st.attention(Q)
+            check_attention(Og, Oref, what)
+            lg = lse.cpu().numpy()
+        else:
+            Oref, lref = st.attention_rows(Q, rows[0], rows[1])
+            check_attention(Og[rows[0], rows[1]], Oref, what)
+            lg = lse.cpu().numpy()[rows[0], rows[1]]
+        if lse_check:
+            fin = np.isfinite(lref)
+            assert np.array_equal(np.isfinite(lg), fin)
+            assert np.abs(lg[fin] - lref[fin]).max() < 2e-3, what
+    ne = st.n_evict_now()
+    sc_ref, src_ref = st.update()
+    assert c.update() == ne
+    compare_update(c, st, wl, sc_ref, src_ref, ne, what)
+
+
+def sample_rows(H, Nq, B, per_head=48, seed=0):
+    """Rows spread over every head: the first and last rows of the chunk, block edges, and random ones."""
+    u = synth.uniforms(synth.stream_key(seed, "misc", 77), H * per_head).reshape(H, per_head)
+    toks = (u * Nq).astype(np.int32)
+    toks[:, 0] = 0; toks[:, 1] = Nq - 1; toks[:, 2] = B - 1; toks[:, 3] = B; toks[:, 4] = ((Nq - 1) // B) * B
+    toks[:, 5] = 127; toks[:, 6] = 128; toks[:, 7] = Nq // 2
+    hh = np.repeat(np.arange(H, dtype=np.int32), per_head)
+    return hh, np.minimum(toks, Nq - 1).ravel().astype(np.int32)
+
+
+# ------------------------------------------------------------------------------------------------
+# small cases, every element compared: several tiles, ragged tails, degenerate settings
+# ------------------------------------------------------------------------------------------------
+SMALL = [
+    # name,           H, d,   B,   Nq,  w, C, k, n_sink, causal, p_lens
+    ("d64_B64",       2, 64,  64,  200, 2, 3, 3, 0, 1, [64, 17, 0]),
+    ("d128_B64",      2, 128, 64,  333, 2, 4, 5, 1, 1, [64, 64, 1, 40]),
+    ("d128_B128",     2, 128, 128, 333, 2, 3, 4, 0, 1, [128, 70, 64]),
+    ("d64_B128",      1, 64,  128, 300, 1, 2, 2, 1, 0, [100, 128]),
+    ("noncausal_all", 2, 128, 64,  200, 1, 2, 64, 0, 0, [64, 64]),     # k > n_loc: every block selected
+    ("no_memory",     1, 128, 64,  130, 2, 0, 2, 0, 1, []),
+    ("k_zero",        1, 64,  64,  100, 1, 2, 0, 0, 1, [64, 30]),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_small_rollout_every_element(gpu, case):
+    name, H, d, B, Nq, w, C, k, n_sink, causal, p_lens = case
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal, device=DEV)
+    if C > 0:
+        Kp, Vp = rnd(1, H, C, B, d), rnd(2, H, C, B, d)
+        # garbage (even non-finite patterns) beyond the valid length must never matter
+        for s, n in enumerate(p_lens):
+            Kp[:, s, n:] = 0x7FC0; Vp[:, s, n:] = 0x7F80
+        pl = np.tile(np.array(p_lens, np.int32), (H, 1))
+        ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+        st.set_persistent(Kp, Vp, pl, ids)
+        c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV),
+                         torch.from_numpy(pl).to(DEV), torch.from_numpy(ids))
+        assert np.array_equal(c.Kc_p.cpu().numpy()[:, :C].view(np.uint32), st.Kc_p.view(np.uint32))
+    for g in range(w + 4):       # cold start, fill, then four evicting updates
+        Q, K, V = rnd(10 + 3 * g, H, Nq, d), rnd(11 + 3 * g, H, Nq, d, scale=1.5), rnd(12 + 3 * g, H, Nq, d)
+        run_both(gpu, c, st, Q, K, V, g, "all", name)
+
+
+def test_empty_memory_and_no_selection_gives_zero(gpu):
+    """No persistent block and k = 0: no key is visible; O = 0 and lse = -inf."""
+    H, d, B, Nq = 1, 64, 64, 100
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, 1, 2, 0, 0.125, device=DEV)
+    Q, K, V = (gpu["wl"].bf16_tensor(rnd(50 + i, H, Nq, d), DEV) for i in range(3))
+    c.append_chunk(K, V, 0)
+    c.select(Q)
+    lse = torch.zeros(H, Nq, dtype=torch.float32, device=DEV)
+    O = c.attention(Q, lse=lse)
+    assert torch.all(O == 0) and torch.all(torch.isinf(lse) & (lse < 0))
+
+
+def test_strided_q_and_o(gpu):
+    """Q and O as views into a fused [Nq][H][3d]-style buffer (token-major, head-strided)."""
+    H, d, B, Nq, w, C, k = 2, 128, 64, 200, 1, 2, 3
+    scale = np.float32(1 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    wl = gpu["wl"]
+    for g in range(2):
+        Q, K, V = rnd(60 + 3 * g, H, Nq, d), rnd(61 + 3 * g, H, Nq, d), rnd(62 + 3 * g, H, Nq, d)
+        lens = np.array([64, 64, 64, 8], np.int32)
+        st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * 4 + np.arange(4))
+        c.append_chunk(wl.bf16_tensor(K, DEV), wl.bf16_tensor(V, DEV), g)
+    fused = torch.zeros(Nq, H, 2 * d, dtype=torch.bfloat16, device=DEV)
+    Qv = fused[:, :, :d].permute(1, 0, 2)           # [H][Nq][d] view, strides (2d, 2Hd, 1)
+    Qv.copy_(wl.bf16_tensor(Q, DEV))
+    out = torch.zeros(Nq, H, d + 8, dtype=torch.bfloat16, device=DEV)
+    Ov = out[:, :, :d].permute(1, 0, 2)
+    st.select(Q)
+    c.select(Qv)
+    compare_select(c, st, "strided")
+    c.attention(Qv, O=Ov)
+    Oref, _ = st.attention(Q)
+    check_attention(Ov.float().cpu().numpy(), Oref, "strided")
+    assert torch.all(out[:, :, d:] == 0)            # nothing written outside the view
+
+
+def test_determinism(gpu):
+    """Same inputs, repeated launches: bit-identical outputs."""
+    w = synth.WORKLOADS["cfg1"]
+    c, g0 = gpu["wl"].cache_for_workload(w, device=DEV)
+    Q, K, V = (gpu["wl"].bf16_tensor(x, DEV) for x in synth.chunk_qkv(w, 0, g0))
+    c.append_chunk(K, V, g0)
+    c.select(Q)
+    sel0 = c.sel.clone()
+    O0 = c.attention(Q).clone()
+    for _ in range(5):
+        c.stale_from = 0
+        c.select(Q)
+        assert torch.equal(c.sel, sel0)
+        assert torch.equal(c.attention(Q), O0)
+
+
+# ------------------------------------------------------------------------------------------------
+# the five workloads
+# ------------------------------------------------------------------------------------------------
+def test_cfg1_every_element(gpu):
+    w = synth.WORKLOADS["cfg1"]
+    st, g0 = state_for_workload(w)
+    c, g0b = gpu["wl"].cache_for_workload(w, device=DEV)
+    assert g0 == g0b
+    assert np.array_equal(c.Kc_p.cpu().numpy().view(np.uint32), st.Kc_p.view(np.uint32))
+    for g in range(g0, g0 + 5):
+        Q, K, V = synth.chunk_qkv(w, 0, g)
+        run_both(gpu, c, st, Q, K, V, g, "all", "cfg1")
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_full_size_single_step(gpu, name):
+    """Full BASELINE shapes, the launch configuration the benchmark times; attention on sampled rows."""
+    w = synth.WORKLOADS[name]
+    st, g0 = state_for_workload(w)
+    c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
+    rows = sample_rows(w.H, w.Nq, w.B)
+    for g in range(g0, g0 + 2):
+        Q, K, V = synth.chunk_qkv(w, 0, g)
+        run_both(gpu, c, st, Q, K, V, g, rows, name)
+
+
+def test_cfg3_layers(gpu):
+    """30 independently seeded layers back to back; selection and update exact on every layer,
+    attention rows sampled on layers 0, 14 and 29."""
+    w = synth.WORKLOADS["cfg3"]
+    rows = sample_rows(w.H, w.Nq, w.B, per_head=24)
+    for layer in range(w.n_layers):
+        st, g0 = state_for_workload(w, layer)
+        c, _ = gpu["wl"].cache_for_workload(w, layer, device=DEV)
+        Q, K, V = synth.chunk_qkv(w, layer, g0)
+        run_both(gpu, c, st, Q, K, V, g0, rows if layer in (0, 14, 29) else None, f"cfg3 layer {layer}")
+        del c
+    torch.cuda.empty_cache()
+
+
+def test_cfg5_rollout(gpu):
+    """Cold start at the 1-minute shape: the window and the persistent set fill during chunks 0-3,
+    eviction and compression start at chunk 3.  Selection and update exact on every chunk; attention
+    rows sampled on a cold, a filling, the first evicting, and steady-state chunks."""
+    w = synth.WORKLOADS["cfg5"]
+    st, g0 = state_for_workload(w)
+    c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
+    rows = sample_rows(w.H, w.Nq, w.B, per_head=32)
+    n_chunks = 12
+    for g in range(n_chunks):
+        Q, K, V = synth.chunk_qkv(w, 0, g)
+        run_both(gpu, c, st, Q, K, V, g, rows if g in (0, 1, 3, 4, 11) else None, "cfg5")
+    assert int(st.S_cnt.max()) > 0 and (st.p_len[:, :w.C] > 0).all()
