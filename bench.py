@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the PBSA layer-chunk step on one MI355X.
+
+A step is one pass of the whole hot path over one chunk of synthetic input, all resident in HBM:
+pbsa_select_blocks -> pbsa_attention_fwd -> pbsa_memory_update, enqueued back to back on one stream.
+Prints ONE JSON line: effective TFLOP/s on the executed (sparse) attention FLOPs over the whole step,
+ms per step, the roofline of the dominant kernel (attention, bf16 MFMA) from HIP events recorded
+around that kernel inside the timed region, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def executed_flops(sel, p_len, l_len_by_block, rows_per_qblock, d):
+    """4 d sum_h sum_i rows_i (valid persistent tokens + valid tokens of the selected blocks)."""
+    import torch
+    persistent = p_len.to(torch.int64).sum(1)                                   # [H]
+    ok = sel >= 0
+    lens = l_len_by_block.to(torch.int64)[sel.clamp(min=0).to(torch.int64)] * ok
+    per_qblock = lens.sum(2) + persistent[:, None]                              # [H][nqb]
+    return int(4 * d * (per_qblock * rows_per_qblock[None, :].to(torch.int64)).sum().item())
+
+
+def cpu_baseline(w, n_rows=1536):
+    """The oracle on the host cores: one full selection and update plus attention on a sample of rows,
+    attention scaled to the whole chunk.  Runs on a steady-state state reached by the oracle itself."""
+    import numpy as np
+    from oracle import rollout
+    from paper_2604_21221_amd import synth
+    st, g0 = rollout.state_for_workload(w)
+    lens = synth.block_lens(w)
+    n_setup = (w.window_chunks + 2) if w.cold_start else 1
+    for g in range(g0, g0 + n_setup):
+        Q, K, V = synth.chunk_qkv(w, 0, g)
+        st.append_chunk(synth.to_blocks(K, w.B), synth.to_blocks(V, w.B), lens, g * w.nqb + np.arange(w.nqb))
+        st.select(Q)
+        st.update()
+    g = g0 + n_setup
+    Q, K, V = synth.chunk_qkv(w, 0, g)
+    st.append_chunk(synth.to_blocks(K, w.B), synth.to_blocks(V, w.B), lens, g * w.nqb + np.arange(w.nqb))
+    t0 = time.perf_counter()
+    st.select(Q)
+    t_sel = time.perf_counter() - t0
+    per_head = n_rows // w.H
+    hh = np.repeat(np.arange(w.H, dtype=np.int32), per_head)
+    tt = np.tile(np.linspace(0, w.Nq - 1, per_head).astype(np.int32), w.H)
+    t0 = time.perf_counter()
+    st.attention_rows(Q, hh, tt)
+    t_att = (time.perf_counter() - t0) * (w.H * w.Nq) / len(hh)
+    t0 = time.perf_counter()
+    st.update()
+    t_upd = time.perf_counter() - t0
+    return t_sel, t_att, t_upd, len(hh)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards by head without exchange; "
+                 "no multi-GPU figure is produced). Use --gpus 1.")
+    import numpy as np
+    import torch
+    from paper_2604_21221_amd import synth, workloads
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+
+    # ---- state: reach steady state (full window, full persistent set, non-empty summary) untimed ----
+    c, g0 = workloads.cache_for_workload(w, device=dev)
+    n_ring = w.window_chunks + 1
+    n_setup = n_ring + 2 if w.cold_start else n_ring
+    Q_at = {}                  # ring position -> the query chunk that goes with the K/V sitting there
+    for g in range(g0, g0 + n_setup):
+        Q, Kc, Vc = synth.chunk_qkv(w, 0, g)
+        Qd = workloads.bf16_tensor(Q, dev)
+        c.step(Qd, workloads.bf16_tensor(Kc, dev), workloads.bf16_tensor(Vc, dev), g)
+        Q_at[(c.n_appended - 1) % n_ring] = Qd
+    g_next = g0 + n_setup
+    torch.cuda.synchronize()
+
+    O = torch.empty(w.H, w.Nq, w.d, dtype=torch.bfloat16, device=dev)
+    n_total = W + K
+    sel_hist = torch.full((n_total,) + tuple(c.sel.shape), -1, dtype=torch.int32, device=dev)
+    plen_hist = torch.zeros((n_total,) + tuple(c.p_len.shape), dtype=torch.int32, device=dev)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    stream = torch.cuda.current_stream()
+
+    def one_step(i, timed_idx=None):
+        # the producer has written the next chunk's K/V into the ring position that was just freed
+        # (here: the data already there serves as the new chunk); its queries are the matching Q
+        g = g_next + i
+        c.adopt_chunk(g)
+        Qd = Q_at[(c.n_appended - 1) % n_ring]
+        c.sel = sel_hist[i]
+        c.select(Qd)
+        plen_hist[i].copy_(c.p_len, non_blocking=True)
+        if timed_idx is not None:
+            ev[timed_idx][0].record(stream)
+        c.attention(Qd, O)
+        if timed_idx is not None:
+            ev[timed_idx][1].record(stream)
+        c.update()
+
+    for i in range(W):
+        one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        one_step(W + i, i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    step_s = (t1 - t0) / K
+    attn_ms = sum(a.elapsed_time(b) for a, b in ev) / K
+    rows = torch.from_numpy(synth.block_lens(w)).to(dev)
+    # lengths by logical block are the same for every arrangement (each chunk has the same block lens)
+    l_len = torch.from_numpy(np.tile(synth.block_lens(w), n_ring)).to(dev)
+    flops = [executed_flops(sel_hist[W + i], plen_hist[W + i], l_len, rows, w.d) for i in range(K)]
+    mean_flops = float(np.mean(flops))
+    tflops_step = mean_flops / step_s / 1e12
+    tflops_attn = mean_flops / (attn_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "effective TFLOP/s on executed (sparse) attention FLOPs per layer-chunk step (select+attention+update)",
+        "value": round(tflops_step, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(step_s * 1e3, 5), "us_per_layer_chunk": round(step_s * 1e6, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "pct_bf16_mfma_peak_step": round(100 * tflops_step / PEAK_BF16_TFLOPS, 3),
+        "config": {"workload": f"{w.name} steady state: H={w.H} d={w.d} B={w.B} Nq={w.Nq} C={w.C}+summary "
+                               f"window={w.window_chunks} chunks ({w.n_win} blocks) k={w.k}",
+                   "executed_gflop_per_step": round(mean_flops / 1e9, 3)},
+        "roofline": {"kernel": "pbsa_attention_fwd", "bound": "mfma", "achieved": round(tflops_attn, 3),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 5),
+                     "traffic": None, "us_per_launch": round(attn_ms * 1e3, 2)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import pbsa_oracle as orc
+        t_sel, t_att, t_upd, n_rows = cpu_baseline(w)
+        cpu_s = t_sel + t_att + t_upd
+        out["cpu_baseline"] = {
+            "value": round(mean_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(),
+            "kind": "oracle", "seconds_per_layer_chunk": round(cpu_s, 3),
+            "sample": f"full selection ({t_sel:.3f} s) and update ({t_upd:.3f} s) of one {w.name} steady-state chunk; "
+                      f"attention on {n_rows} of {w.H * w.Nq} rows, scaled to the chunk ({t_att:.2f} s)"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -45,6 +45,13 @@ typedef struct orc_cfg {
   float scale;            /* 1/sqrt(d)                                                          */
 } orc_cfg;
 
+#ifdef _OPENMP
+#include <omp.h>
+int orc_num_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_num_threads(void) { return 1; }
+#endif
+
 static inline float bf2f(uint16_t b) {
   uint32_t u = (uint32_t)b << 16;
   float f;

@@ -81,6 +81,11 @@ def _p(a, dtype, shape=None):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
+def num_threads() -> int:
+    """Threads the OpenMP loops of the oracle use."""
+    return int(lib().orc_num_threads())
+
+
 def pexp(x: float) -> float:
     return float(lib().orc_pexp(ctypes.c_float(x)))
 

@@ -40,6 +40,7 @@ class PbsaCache:
         self.n_appended = 0
         self.stale_from = 0
         self._maps = {}
+        self._arange64 = None
         lens = torch.full((self.nqb,), B, dtype=torch.int32)
         lens[-1] = Nq - (self.nqb - 1) * B
         self._chunk_lens = lens
@@ -49,19 +50,26 @@ class PbsaCache:
         return len(self.chunk_pos) * self.nqb
 
     def _device_maps(self):
-        """l_map / l_len / l_id device tensors of the current ring arrangement (cached per arrangement)."""
-        key = (tuple(self.chunk_pos), tuple(self.chunk_ids))
+        """l_map / l_len / l_id device tensors of the current ring arrangement.  The map and the lengths
+        depend only on the ring positions and are cached per arrangement; ids of consecutive chunks are
+        an arange plus an offset, formed on the device (no host-to-device copy in steady state)."""
+        key = tuple(self.chunk_pos)
         m = self._maps.get(key)
         if m is None:
             ar = torch.arange(self.nqb)
             l_map = torch.cat([p * self.nqb + ar for p in self.chunk_pos]).to(torch.int32)
             l_len = self._chunk_lens.repeat(len(self.chunk_pos))
-            l_id = torch.cat([g * self.nqb + ar for g in self.chunk_ids]).to(torch.int64)
-            m = (l_map.to(self.dev), l_len.to(self.dev), l_id.to(self.dev))
-            if len(self._maps) > 64:
-                self._maps.clear()
+            m = (l_map.to(self.dev), l_len.to(self.dev))
             self._maps[key] = m
-        return m
+        ids = self.chunk_ids
+        if all(b == a + 1 for a, b in zip(ids, ids[1:])):
+            if self._arange64 is None:
+                self._arange64 = torch.arange(self.cap, dtype=torch.int64, device=self.dev)
+            l_id = self._arange64[:self.n_loc] + ids[0] * self.nqb
+        else:
+            ar = torch.arange(self.nqb)
+            l_id = torch.cat([g * self.nqb + ar for g in ids]).to(torch.int64).to(self.dev)
+        return m[0], m[1], l_id
 
     def params(self, n_evict=0, pool_from=0, Q=None, O=None):
         qs = (Q.stride(0), Q.stride(1)) if Q is not None else None
@@ -101,6 +109,15 @@ class PbsaCache:
             if self.nqb * self.B > self.Nq:
                 view[:, self.Nq:] = 0
         self.chunk_pos.append(pos)
+        self.chunk_ids.append(chunk_id)
+        self.n_appended += 1
+        self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
+
+    def adopt_chunk(self, chunk_id):
+        """Declare the next ring position to hold chunk `chunk_id` whose K/V the producer has already
+        written there in block-major layout (zero-copy append)."""
+        assert len(self.chunk_pos) <= self.w, "update() slides the window before the next append"
+        self.chunk_pos.append(self.n_appended % (self.w + 1))
         self.chunk_ids.append(chunk_id)
         self.n_appended += 1
         self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
