@@ -26,7 +26,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kThreads = 256;
 constexpr int kRowsPerWg = 128;
 constexpr int kTile = 64;                 // keys per staged tile
-constexpr int kMaxTiles = 2 * (PBSA_MAX_C + 1) + 2 * 2 * PBSA_MAX_K;
+constexpr int kMaxTiles = 2 * (PBSA_MAX_C + 1) + 2 * PBSA_MAX_K;   // persistent + local 64-key tiles
 constexpr float kNegBig = -1.0e30f;
 
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {   // set bits of `mask` below this lane
@@ -50,25 +50,49 @@ struct AttnArgs {
   float* lse;
 };
 
+// LDS layouts of a 64-key tile.
+//  K: row pitch D+8 elements: the 16-byte reads of 16 consecutive rows at one column fall in 16
+//     distinct 4-bank groups.
+//  V: read with ds_read_b64_tr_b16, where within 16 lanes lane s supplies the address of row s/4,
+//     columns 4(s%4)..+3 and lane j receives column j of those 4 rows.  D = 128: rows are unpadded
+//     (256 bytes) and 16-byte chunk c of row r sits at chunk c ^ 4(r%4), so the 4 rows x 64 bytes a
+//     half-wave reads cover all 64 banks.  D = 64: plain rows of pitch D+32.
+template <int D>
+__device__ __forceinline__ int v_byte_offset(int row, int chunk) {
+  if constexpr (D == 128) return row * 256 + ((chunk ^ ((row & 3) << 2)) << 4);
+  else return row * ((D + 32) * 2) + (chunk << 4);
+}
+
 template <int D, int B>
-__global__ void __launch_bounds__(kThreads) attention_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(kThreads, 2) attention_kernel(AttnArgs a) {
   constexpr int G = kRowsPerWg / B;        // query blocks per workgroup
   constexpr int SUB = B / kTile;           // 64-key tiles per block
-  constexpr int PITCH = D + 8;             // LDS row pitch in elements (16-byte skew per row)
+  constexpr int KPITCH = D + 8;            // K row pitch in elements
   constexpr int KS = D / 16;               // MFMA k-steps of Q K^T
   constexpr int DT = D / 32;               // 32-wide output tiles of O^T
+  constexpr int K_BYTES = kTile * KPITCH * 2;
+  constexpr int V_BYTES = D == 128 ? kTile * 256 : kTile * (D + 32) * 2;
+  constexpr int CPT = kTile * (D / 8) / kThreads;   // 16-byte chunks per thread per tile (K or V)
 
-  __shared__ __align__(16) bf16_t Ks[kTile * PITCH];
-  __shared__ __align__(16) bf16_t Vs[kTile * PITCH];
+  __shared__ __align__(16) unsigned char Ks[2][K_BYTES];
+  __shared__ __align__(16) unsigned char Vs[2][V_BYTES];
   __shared__ int t_src[kMaxTiles];         // bit 31: local, bits 0..: (slot * SUB + sub)
   __shared__ int t_len[kMaxTiles];
   __shared__ int t_mask[kMaxTiles];        // which of the G query blocks attend the tile
-  __shared__ int lflag[PBSA_MAX_N_LOC];
   __shared__ int n_tiles_s;
+  int* lflag = reinterpret_cast<int*>(&Ks[0][0]);   // setup scratch, dead before the first tile is staged
+  static_assert(PBSA_MAX_N_LOC * 4 <= 2 * K_BYTES, "flag scratch must fit");
 
-  const int h = blockIdx.y;
+  // XCD-aware mapping: consecutive workgroup ids go round-robin to the 8 XCDs, so give XCD x the
+  // contiguous range [x * per, (x+1) * per) of (head, query tile) pairs: neighbours share K/V in L2.
+  const int n_qt = (a.Nq + kRowsPerWg - 1) / kRowsPerWg;
+  const int n_wg = a.H * n_qt;
+  const int per = (n_wg + 7) / 8;
+  const int logical = (blockIdx.x % 8) * per + blockIdx.x / 8;
+  if (logical >= n_wg) return;
+  const int h = logical / n_qt;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int T0 = blockIdx.x * kRowsPerWg;
+  const int T0 = (logical % n_qt) * kRowsPerWg;
   const int i0 = T0 / B;
   const int my_g = (wave * 32) / B;
 
@@ -140,87 +164,134 @@ __global__ void __launch_bounds__(kThreads) attention_kernel(AttnArgs a) {
   float m_run = kNegBig, l_run = 0.0f;
   const float c2 = a.scale * 1.4426950408889634f;
 
+  // staging: thread owns chunks c = tid + 256 n of the 64 x D tile: row c / (D/8), 16-byte chunk c % (D/8).
+  // Named registers (not an array) so the prefetched tile stays in VGPRs across the compute phase.
+  uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
+  kr0 = kr1 = kr2 = kr3 = vr0 = vr1 = vr2 = vr3 = make_uint4(0u, 0u, 0u, 0u);
+#define PBSA_LOAD_TILE(IT)                                                                              \
+  {                                                                                                     \
+    const int src_ = t_src[IT];                                                                         \
+    const bool local_ = src_ < 0;                                                                       \
+    const int idx_ = src_ & 0x7FFFFFFF;                                                                 \
+    const size_t boff_ = (local_ ? ((size_t)h * a.n_loc_cap + idx_ / SUB) : ((size_t)h * (a.C + 1) + idx_ / SUB)) * \
+                             B * D + (size_t)(idx_ % SUB) * kTile * D;                                  \
+    const uint4* kb_ = reinterpret_cast<const uint4*>((local_ ? a.Kl : a.Kp) + boff_) + tid;            \
+    const uint4* vb_ = reinterpret_cast<const uint4*>((local_ ? a.Vl : a.Vp) + boff_) + tid;            \
+    kr0 = kb_[0]; vr0 = vb_[0];                                                                         \
+    kr1 = kb_[kThreads]; vr1 = vb_[kThreads];                                                           \
+    if constexpr (CPT > 2) {                                                                            \
+      kr2 = kb_[2 * kThreads]; vr2 = vb_[2 * kThreads];                                                 \
+      kr3 = kb_[3 * kThreads]; vr3 = vb_[3 * kThreads];                                                 \
+    }                                                                                                   \
+  }
+  // V rows past the valid length become zeros: they meet p = 0, which must not see NaN / Inf bits
+#define PBSA_STORE_ONE(N, KR, VR, BUF, TLEN)                                                            \
+  {                                                                                                     \
+    const int c_ = tid + kThreads * N;                                                                  \
+    const int r_ = c_ / (D / 8), cc_ = c_ % (D / 8);                                                    \
+    *reinterpret_cast<uint4*>(&Ks[BUF][(r_ * KPITCH + cc_ * 8) * 2]) = KR;                              \
+    *reinterpret_cast<uint4*>(&Vs[BUF][v_byte_offset<D>(r_, cc_)]) = r_ < TLEN ? VR : make_uint4(0u, 0u, 0u, 0u); \
+  }
+#define PBSA_STORE_TILE(IT, BUF)                                                                        \
+  {                                                                                                     \
+    const int tlen_ = t_len[IT];                                                                        \
+    PBSA_STORE_ONE(0, kr0, vr0, BUF, tlen_)                                                             \
+    PBSA_STORE_ONE(1, kr1, vr1, BUF, tlen_)                                                             \
+    if constexpr (CPT > 2) {                                                                            \
+      PBSA_STORE_ONE(2, kr2, vr2, BUF, tlen_)                                                           \
+      PBSA_STORE_ONE(3, kr3, vr3, BUF, tlen_)                                                           \
+    }                                                                                                   \
+  }
+  static_assert(CPT == 2 || CPT == 4, "staging assumes 2 or 4 chunks per thread");
+
+  if (n_tiles > 0) {
+    PBSA_LOAD_TILE(0)
+    __syncthreads();               // lflag (aliasing Ks) is dead
+    PBSA_STORE_TILE(0, 0)
+  }
+  __syncthreads();
+
+  // per-lane pieces of the V^T operand address: 16-lane group s -> row s/4, chunk pair 2q + (s%4)/2
+  const int s16 = lane & 15, q16 = (lane >> 4) & 1;
+  const int v_row0 = 4 * half + (s16 >> 2);
+  const int v_sub = 2 * q16 + ((s16 & 3) >> 1);
+  const int v_lo = (s16 & 1) * 8;
+
   for (int it = 0; it < n_tiles; ++it) {
-    const int src = t_src[it], tlen = t_len[it], tmask = t_mask[it];
-    const bool local = src < 0;
-    const int idx = src & 0x7FFFFFFF;
-    const int slot = idx / SUB, sub = idx % SUB;
-    const size_t boff = local ? ((size_t)h * a.n_loc_cap + slot) * B * D : ((size_t)h * (a.C + 1) + slot) * B * D;
-    const bf16_t* kb = (local ? a.Kl : a.Kp) + boff + (size_t)sub * kTile * D;
-    const bf16_t* vb = (local ? a.Vl : a.Vp) + boff + (size_t)sub * kTile * D;
-    __syncthreads();
-    // stage K and V tiles: 64 rows x D, 16 bytes per thread per step; V rows past the valid length
-    // become zeros (they are multiplied by p = 0, which must not meet a NaN or Inf pattern)
-#pragma unroll
-    for (int c = tid; c < kTile * (D / 8); c += kThreads) {
-      const int r = c / (D / 8), x = (c % (D / 8)) * 8;
-      const uint4 kv = *reinterpret_cast<const uint4*>(kb + (size_t)r * D + x);
-      uint4 vv = *reinterpret_cast<const uint4*>(vb + (size_t)r * D + x);
-      if (r >= tlen) vv = make_uint4(0u, 0u, 0u, 0u);
-      *reinterpret_cast<uint4*>(&Ks[r * PITCH + x]) = kv;
-      *reinterpret_cast<uint4*>(&Vs[r * PITCH + x]) = vv;
-    }
-    __syncthreads();
-    if (!((tmask >> my_g) & 1)) continue;
+    const int buf = it & 1;
+    const int tlen = t_len[it], tmask = t_mask[it];
+    if (it + 1 < n_tiles) PBSA_LOAD_TILE(it + 1)
 
-    // S^T for two 32-key sub-tiles
-    f32x16 s[2];
+    if ((tmask >> my_g) & 1) {
+      // S^T for two 32-key sub-tiles
+      f32x16 s[2];
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
+      for (int st = 0; st < 2; ++st) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[st][v] = 0.0f;
-      const bf16_t* krow = &Ks[(32 * st + qn) * PITCH + 8 * half];
+        for (int v = 0; v < 16; ++v) s[st][v] = 0.0f;
+        const unsigned char* krow = &Ks[buf][((32 * st + qn) * KPITCH + 8 * half) * 2];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + 16 * ks);
-        s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[st], 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
+          s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[st], 0, 0, 0);
+        }
       }
-    }
-    // mask ragged keys, tile max.  accumulator element v of sub-tile st is key 32 st + 8 (v/4) + 4 half + v%4
-    float tmax = kNegBig;
+      // accumulator element v of sub-tile st is key 32 st + 8 (v/4) + 4 half + v%4
+      if (tlen < kTile) {
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
+        for (int st = 0; st < 2; ++st)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = 32 * st + 8 * (v / 4) + 4 * half + (v % 4);
-        if (key >= tlen) s[st][v] = kNegBig;
-        tmax = fmaxf(tmax, s[st][v]);
+          for (int v = 0; v < 16; ++v)
+            if (32 * st + 8 * (v / 4) + 4 * half + (v % 4) >= tlen) s[st][v] = kNegBig;
       }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-    const float mc = -m_new * c2;
-    m_run = m_new;
-    float psum = 0.0f;
+      float tmax = s[0][0];
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
+      for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[0][v]);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[st][v], c2, mc));
-        s[st][v] = p;
-        psum += p;
+      for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[1][v]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(m_run, tmax);
+      const float mc = -m_new * c2;
+      float psum = 0.0f;
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[st][v], c2, mc));
+          s[st][v] = p;
+          psum += p;
+        }
+      if (__any(m_new != m_run)) {        // the running max moved for some row: rescale
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+        m_run = m_new;
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+      l_run += psum;
 
-    // O^T += V^T P^T, 4 k-steps of 16 keys
+      // O^T += V^T P^T, 4 k-steps of 16 keys; V^T fragments by transposing LDS reads
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      bf16x8 pf;
+      for (int j = 0; j < 4; ++j) {
+        bf16x8 pf;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[j / 2][8 * (j % 2) + e];
-      const int kbase = 32 * (j / 2) + 16 * (j % 2) + 4 * half;
+        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[j / 2][8 * (j % 2) + e];
+        const int r0 = 16 * j + v_row0;            // keys r0..r0+3 and r0+8..r0+11 of the tile
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        union { bf16x8 v; uint16_t u[8]; } vf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vf.u[e] = Vs[(kbase + 8 * (e / 4) + (e % 4)) * PITCH + 32 * dt + qn];
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, o[dt], 0, 0, 0);
+        for (int dt = 0; dt < DT; ++dt) {
+          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+              (bf16x4 __attribute__((address_space(3)))*)(&Vs[buf][v_byte_offset<D>(r0, 4 * dt + v_sub) + v_lo]));
+          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+              (bf16x4 __attribute__((address_space(3)))*)(&Vs[buf][v_byte_offset<D>(r0 + 8, 4 * dt + v_sub) + v_lo]));
+          const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[dt], 0, 0, 0);
+        }
       }
     }
+    if (it + 1 < n_tiles) PBSA_STORE_TILE(it + 1, buf ^ 1)
+    __syncthreads();
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
@@ -249,7 +320,8 @@ hipError_t launch_attention(const pbsa_params& p, const bf16_t* Q, const bf16_t*
                             const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, hipStream_t stream) {
   AttnArgs a{p.H, p.Nq, p.nqb, p.n_loc, p.n_loc_cap, p.C, p.k, p.scale, p.q_stride_h, p.q_stride_t,
              p.o_stride_h, p.o_stride_t, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse};
-  const dim3 grid((p.Nq + kRowsPerWg - 1) / kRowsPerWg, p.H), block(kThreads);
+  const int n_wg = p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
+  const dim3 grid(8 * ((n_wg + 7) / 8)), block(kThreads);
   if (p.d == 128 && p.B == 128) hipLaunchKernelGGL((attention_kernel<128, 128>), grid, block, 0, stream, a);
   else if (p.d == 128 && p.B == 64) hipLaunchKernelGGL((attention_kernel<128, 64>), grid, block, 0, stream, a);
   else if (p.d == 64 && p.B == 128) hipLaunchKernelGGL((attention_kernel<64, 128>), grid, block, 0, stream, a);
