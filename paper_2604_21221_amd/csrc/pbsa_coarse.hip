@@ -323,17 +323,19 @@ struct RetainArgs {
 };
 
 __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
-  __shared__ float s[kMaxCand];           // mean column score, U order
+  __shared__ float s[kMaxCand];           // mean column score of slot / evicted-block columns, U order
   __shared__ int cand[kMaxCand];          // < C: slot, else C + local block
   __shared__ float cs[kMaxCand];
   __shared__ unsigned char win[kMaxCand];
   __shared__ int old_len[PBSA_MAX_C + 1];
   __shared__ int src_s[PBSA_MAX_C];
   __shared__ int flen[kMaxCand];          // valid tokens of each dropped candidate
+  __shared__ int e_len[PBSA_MAX_N_LOC];   // valid tokens of the evicted blocks
   __shared__ int nP_s, nc_s, nf_s, npos_s;
   const int h = blockIdx.x, C = a.C, C1 = a.C + 1;
   int32_t* plen = a.p_len + (size_t)h * C1;
   for (int c = threadIdx.x; c < C1; c += kThreads) old_len[c] = plen[c];
+  for (int e = threadIdx.x; e < a.n_evict; e += kThreads) e_len[e] = max(0, min(a.l_len[e], a.B));
   __syncthreads();
   if (threadIdx.x == 0) {
     int n = 0;
@@ -341,11 +343,21 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
     nP_s = n;
   }
   __syncthreads();
-  const int nP = nP_s, nU = nP + a.n_loc;
-  for (int j = threadIdx.x; j < nU; j += kThreads) {
+  // Column means (Eq. 8) of the columns that can be candidates: the occupied slots and the evicted
+  // blocks, i.e. the first nP + n_evict columns of U.  Rows are added in ascending order; the loads
+  // of 16 rows are issued together.
+  const int nP = nP_s, n_need = nP + a.n_evict;
+  for (int j = threadIdx.x; j < n_need; j += kThreads) {
     float acc = 0.0f;
     const float* col = a.A + (size_t)h * a.nqb * a.nU_max + j;
-    for (int i = 0; i < a.nqb; ++i) acc = acc + col[(size_t)i * a.nU_max];
+    for (int i0 = 0; i0 < a.nqb; i0 += 16) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = i0 + u < a.nqb ? col[(size_t)(i0 + u) * a.nU_max] : 0.0f;
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        if (i0 + u < a.nqb) acc = acc + v[u];
+    }
     s[j] = acc / (float)a.nqb;
   }
   __syncthreads();
@@ -358,14 +370,16 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
       if (occ && c >= a.n_sink) { cand[nc] = c; cs[nc++] = s[u]; }
       u += occ;
     }
-    for (int e = 0; e < a.n_evict; ++e) {
-      if (a.scores) a.scores[(size_t)h * ncand_max + C + e] = s[nP + e];
-      cand[nc] = C + e; cs[nc++] = s[nP + e];
-    }
     nc_s = nc;
   }
   __syncthreads();
-  const int nc = nc_s, places = C - a.n_sink;
+  const int ncP = nc_s, nc = ncP + a.n_evict, places = C - a.n_sink;
+  for (int e = threadIdx.x; e < a.n_evict; e += kThreads) {
+    if (a.scores) a.scores[(size_t)h * ncand_max + C + e] = s[nP + e];
+    cand[ncP + e] = C + e;
+    cs[ncP + e] = s[nP + e];
+  }
+  __syncthreads();
   for (int x = threadIdx.x; x < nc; x += kThreads) {
     int rank = 0;
     const float mine = cs[x];
@@ -377,7 +391,7 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
     int nf = 0;
     for (int x = 0; x < nc; ++x) {
       if (win[x]) continue;
-      const int len = cand[x] < C ? old_len[cand[x]] : max(0, min(a.l_len[cand[x] - C], a.B));
+      const int len = cand[x] < C ? old_len[cand[x]] : e_len[cand[x] - C];
       a.fold_src[(size_t)h * ncand_max + nf] = cand[x];
       a.fold_len[(size_t)h * ncand_max + nf] = len;
       flen[nf] = len;
@@ -389,17 +403,14 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
     npos_s = 0;
     for (int c = 0; c < C; ++c) src_s[c] = -1;
     int slot = a.n_sink;
-    for (int x = 0; x < nc; ++x) {
-      if (!win[x] || cand[x] < C) continue;
+    for (int x = ncP; x < nc; ++x) {               // kept newcomers, ascending block order
+      if (!win[x]) continue;
       const int e = cand[x] - C;
       while (slot < C && old_len[slot] > 0) ++slot;
       if (slot >= C) break;
-      old_len[slot] = max(0, min(a.l_len[e], a.B));
+      old_len[slot] = e_len[e];
       src_s[slot] = e;
-      a.p_id[(size_t)h * C + slot] = a.l_id[e];
     }
-    for (int c = a.n_sink; c < C; ++c)
-      if (old_len[c] == 0) a.p_id[(size_t)h * C + c] = -1;
   }
   __syncthreads();
   // per-position counts of the summary: every dropped block adds one to each position it has
@@ -415,7 +426,12 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
     __syncthreads();
   }
   for (int c = threadIdx.x; c < C1; c += kThreads) plen[c] = old_len[c];
-  for (int c = threadIdx.x; c < C; c += kThreads) a.slot_src[(size_t)h * C + c] = src_s[c];
+  for (int c = threadIdx.x; c < C; c += kThreads) {
+    const int e = src_s[c];
+    a.slot_src[(size_t)h * C + c] = e;
+    if (e >= 0) a.p_id[(size_t)h * C + c] = a.l_id[e];
+    else if (c >= a.n_sink && old_len[c] == 0) a.p_id[(size_t)h * C + c] = -1;
+  }
   for (int idx = threadIdx.x; idx < C * a.d; idx += kThreads) {
     const int c = idx / a.d, x = idx % a.d;
     const int e = src_s[c];
@@ -465,20 +481,34 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
     float* ssum = a.S_sum + ((size_t)h * 2 + kv) * blk + rowoff;
     float4 acc = *reinterpret_cast<float4*>(ssum);
     const int cnt = a.S_cnt[(size_t)h * a.B + t];     // already the new count (retain_kernel)
-    for (int f = 0; f < nf; ++f) {
-      const int src = a.fold_src[(size_t)h * ncand_max + f];
-      const int len = a.fold_len[(size_t)h * ncand_max + f];
-      if (t >= len) continue;
-      const bf16_t* blkp;
-      if (src < C) {
-        blkp = P + ((size_t)h * C1 + src) * blk;
-      } else {
-        const int slot = min(max(a.l_map[src - C], 0), a.n_loc_cap - 1);
-        blkp = L + ((size_t)h * a.n_loc_cap + slot) * blk;
+    const int32_t* fsrc = a.fold_src + (size_t)h * ncand_max;
+    const int32_t* flen = a.fold_len + (size_t)h * ncand_max;
+    // rows are loaded 8 at a time (row t exists in every block, valid or not) and added in order,
+    // the add predicated on t < len
+    for (int f0 = 0; f0 < nf; f0 += 8) {
+      uint2 v[8];
+      bool on[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int f = min(f0 + u, nf - 1);
+        const int src = fsrc[f];
+        on[u] = f0 + u < nf && t < flen[f];
+        const bf16_t* blkp;
+        if (src < C) {
+          blkp = P + ((size_t)h * C1 + src) * blk;
+        } else {
+          const int slot = min(max(a.l_map[src - C], 0), a.n_loc_cap - 1);
+          blkp = L + ((size_t)h * a.n_loc_cap + slot) * blk;
+        }
+        v[u] = *reinterpret_cast<const uint2*>(blkp + rowoff);
       }
-      const uint2 v = *reinterpret_cast<const uint2*>(blkp + rowoff);
-      acc.x = acc.x + bf_lo(v.x); acc.y = acc.y + bf_hi(v.x);
-      acc.z = acc.z + bf_lo(v.y); acc.w = acc.w + bf_hi(v.y);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (on[u]) {
+          acc.x = acc.x + bf_lo(v[u].x); acc.y = acc.y + bf_hi(v[u].x);
+          acc.z = acc.z + bf_lo(v[u].y); acc.w = acc.w + bf_hi(v[u].y);
+        }
+      }
     }
     *reinterpret_cast<float4*>(ssum) = acc;
     if (cnt > 0) {
