@@ -33,6 +33,9 @@
  *   Qc           [H][nqb][d] fp32            pooled queries of the chunk
  *   sel          [H][nqb][k] int32           selected logical local blocks per query block,
  *                                            ascending, padded with -1
+ *   Zl           [H][nqb][n_loc] fp32        coarse logits dot(Qc_i, Kc_l) * scale of every local block
+ *                                            (no visibility mask); optional hand-over from the
+ *                                            selection call to the update call of the same chunk
  *   Kp, Vp       [H][C+1][B][d] bf16         persistent slots; slot C holds the compressed-history
  *                                            ("summary") block
  *   p_len        [H][C+1] int32              valid tokens per slot, 0 = empty (skipped)
@@ -109,10 +112,11 @@ int pbsa_pool_blocks(const pbsa_params* p, const void* X, const int32_t* len, in
  * the pooled keys Kc_l of logical blocks >= pool_from, scores every visible local block of every
  * query block with dot(Qc_i, Kc_l) (the argument of Eq. 10's softmax, which is monotone per row)
  * and writes the min(k, visible) best blocks of each row to `sel` (ascending, -1 padded; ties to
- * the lower block).  Kc_l is in/out, Qc and sel are out.  ws may be NULL. */
+ * the lower block).  Kc_l is in/out, Qc and sel are out.  Zl (optional out) receives the logits of
+ * all n_loc local blocks of every row, for pbsa_memory_update.  ws may be NULL. */
 int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, const int32_t* l_len,
-                       const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, void* ws, size_t ws_bytes,
-                       void* hip_stream);
+                       const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl, void* ws,
+                       size_t ws_bytes, void* hip_stream);
 
 /* PBSA fine stage (Eq. 3-5): for each query token one softmax, scaled by p->scale, over every
  * valid token of every non-empty persistent slot 0..C (summary included) and every valid token of
@@ -132,14 +136,17 @@ int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, cons
  * ascending slot order, and K, V, Kc_p, p_len, p_id move with them.  Every dropped candidate is
  * added position by position to S_sum/S_cnt and slot C is rewritten with their running mean
  * (bf16), p_len[C] = number of positions with a count; pass S_sum = S_cnt = NULL to drop without
- * compressing.  Qc and Kc_l are those pbsa_select_blocks produced for this chunk.
+ * compressing.  Qc and Kc_l are those pbsa_select_blocks produced for this chunk; Zl (optional) is
+ * the logits array it produced with the same n_loc: given, the local columns of Eq. 7 are taken from
+ * it (they are the same numbers) and only the persistent columns are multiplied again.
  * Outputs: scores (optional, [H][C+n_evict] fp32: slots 0..C-1, 0 if empty, then evicted blocks),
  * slot_src [H][C] int32: -1 = slot unchanged, e >= 0 = filled from local block e.
  * ws is required (pbsa_workspace_bytes). */
-int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l, void* Kp, void* Vp, float* Kc_p,
-                       int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt, const void* Kl,
-                       const void* Vl, const int32_t* l_len, const int32_t* l_map, const int64_t* l_id,
-                       float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream);
+int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l, const float* Zl, void* Kp,
+                       void* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                       const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                       const int64_t* l_id, float* scores, int32_t* slot_src, void* ws, size_t ws_bytes,
+                       void* hip_stream);
 
 const char* pbsa_strerror(int code);
 int pbsa_version(void);

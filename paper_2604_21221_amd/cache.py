@@ -14,7 +14,8 @@ from . import pbsa
 
 
 class PbsaCache:
-    def __init__(self, H, d, B, Nq, window_chunks, C, k, scale, n_sink=0, causal=1, fold=True, device="cuda:0"):
+    def __init__(self, H, d, B, Nq, window_chunks, C, k, scale, n_sink=0, causal=1, fold=True, device="cuda:0",
+                 pass_logits=True):
         self.H, self.d, self.B, self.Nq, self.C, self.k = H, d, B, Nq, C, k
         self.w, self.scale, self.n_sink, self.causal = window_chunks, float(scale), n_sink, causal
         self.nqb = -(-Nq // B)
@@ -30,6 +31,8 @@ class PbsaCache:
         self.S_sum = z(H, 2, B, d, dt=torch.float32) if fold else None
         self.S_cnt = z(H, B, dt=torch.int32) if fold else None
         self.Qc = z(H, self.nqb, d, dt=torch.float32)
+        # coarse logits handed from the selection call to the update call (None: update recomputes them)
+        self.Zl = z(H * self.nqb * self.cap, dt=torch.float32) if pass_logits else None
         self.sel = torch.full((H, self.nqb, max(k, 1)), -1, dtype=torch.int32, device=self.dev)
         self.slot_src = torch.full((H, max(C, 1)), -1, dtype=torch.int32, device=self.dev)
         self.scores = z(H, C + self.nqb, dt=torch.float32)
@@ -126,7 +129,7 @@ class PbsaCache:
     def select(self, Q):
         l_map, l_len, _ = self._device_maps()
         p = self.params(pool_from=self.stale_from, Q=Q)
-        pbsa.pbsa_select_blocks(p, Q, self.Kl, l_len, l_map, self.Kc_l, self.Qc, self.sel)
+        pbsa.pbsa_select_blocks(p, Q, self.Kl, l_len, l_map, self.Kc_l, self.Qc, self.sel, self.Zl)
         self.stale_from = self.n_loc
         return self.sel
 
@@ -145,7 +148,7 @@ class PbsaCache:
         l_map, l_len, l_id = self._device_maps()
         ne = self.n_evict_now()
         p = self.params(n_evict=ne)
-        pbsa.pbsa_memory_update(p, self.Qc, self.Kc_l, self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id, self.S_sum,
+        pbsa.pbsa_memory_update(p, self.Qc, self.Kc_l, self.Zl, self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id, self.S_sum,
                                 self.S_cnt, self.Kl, self.Vl, l_len, l_map, l_id, self.scores, self.slot_src, self.ws)
         if ne:
             self.chunk_pos.pop(0)

@@ -83,8 +83,8 @@ int pbsa_pool_blocks(const pbsa_params* p, const void* X, const int32_t* len, in
 }
 
 int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, const int32_t* l_len,
-                       const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, void* ws, size_t ws_bytes,
-                       void* hip_stream) {
+                       const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
   (void)ws; (void)ws_bytes;
   int rc = check_common(p);
   if (rc) return rc;
@@ -94,7 +94,7 @@ int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, cons
   if (rc) return rc;
   if (!aligned16(Q) || !aligned16(Kl) || !aligned16(Kc_l) || !aligned16(Qc)) return PBSA_EALIGN;
   hipError_t e = pbsa::launch_select(*p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kl),
-                                     l_len, l_map, Kc_l, Qc, sel, static_cast<hipStream_t>(hip_stream));
+                                     l_len, l_map, Kc_l, Qc, sel, Zl, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
@@ -120,10 +120,11 @@ int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, cons
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
-int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l, void* Kp, void* Vp, float* Kc_p,
-                       int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt, const void* Kl,
-                       const void* Vl, const int32_t* l_len, const int32_t* l_map, const int64_t* l_id,
-                       float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream) {
+int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l, const float* Zl, void* Kp,
+                       void* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                       const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                       const int64_t* l_id, float* scores, int32_t* slot_src, void* ws, size_t ws_bytes,
+                       void* hip_stream) {
   int rc = check_common(p);
   if (rc) return rc;
   if (!Qc || !Kc_l || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !l_id) return PBSA_EINVAL;
@@ -135,7 +136,7 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
   if (!ws || ws_bytes < workspace_bytes(*p)) return PBSA_EWS;
   if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
   const pbsa::UpdateWs w = pbsa::carve_update_ws(*p, ws);
-  hipError_t e = pbsa::launch_update(*p, Qc, Kc_l, static_cast<pbsa::bf16_t*>(Kp), static_cast<pbsa::bf16_t*>(Vp),
+  hipError_t e = pbsa::launch_update(*p, Qc, Kc_l, Zl, static_cast<pbsa::bf16_t*>(Kp), static_cast<pbsa::bf16_t*>(Vp),
                                      Kc_p, p_len, p_id, S_sum, S_cnt, static_cast<const pbsa::bf16_t*>(Kl),
                                      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, l_id, scores, slot_src, w,
                                      static_cast<hipStream_t>(hip_stream));

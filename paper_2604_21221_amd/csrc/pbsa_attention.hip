@@ -199,6 +199,9 @@ __device__ __forceinline__ void softmax_tile(f32x16& s0, f32x16& s1, int tlen, i
   }
 }
 
+// (the kernel marks dead accumulators by assigning an uninitialised value on purpose)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wuninitialized"
 template <int D, int B>
 __global__ void __launch_bounds__(kThreads) attention_kernel(AttnArgs a) {
   constexpr int G = kRowsPerWg / B;        // query blocks per workgroup
@@ -450,6 +453,8 @@ __global__ void __launch_bounds__(kThreads) attention_kernel(AttnArgs a) {
       a.lse[(size_t)h * a.Nq + tok] = l_tot > 0.0f ? m_run * a.scale + __logf(l_tot) : -INFINITY;
   }
 }
+
+#pragma clang diagnostic pop
 
 }  // namespace
 

@@ -126,20 +126,40 @@ template <int D, int NM>
 __device__ __forceinline__ void coarse_dots(const float* const* cols, int n_cols, const float* qrow, float* kct,
                                             float (&acc)[NM]) {
   constexpr int NPAD = NM * 64 + 2;
+  constexpr int P = NM * 64 * (kXC / 4) / kThreads;     // float4 loads per thread per round
   const int lane = threadIdx.x & 63;
 #pragma unroll
   for (int m = 0; m < NM; ++m) acc[m] = 0.0f;
+  __syncthreads();                                       // cols[] and qrow are visible
+  // the global loads of round r+1 are in flight while round r is multiplied
+  float4 pre[P];
+#pragma unroll
+  for (int u = 0; u < P; ++u) {
+    const int idx = threadIdx.x + u * kThreads;
+    if (idx < n_cols * (kXC / 4)) pre[u] = *reinterpret_cast<const float4*>(cols[idx / (kXC / 4)] + 4 * (idx % (kXC / 4)));
+  }
   for (int x0 = 0; x0 < D; x0 += kXC) {
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < n_cols * (kXC / 4); idx += kThreads) {
-      const int j = idx / (kXC / 4), xq = idx % (kXC / 4);
-      const float4 v = *reinterpret_cast<const float4*>(cols[j] + x0 + 4 * xq);
-      kct[(4 * xq + 0) * NPAD + j] = v.x;
-      kct[(4 * xq + 1) * NPAD + j] = v.y;
-      kct[(4 * xq + 2) * NPAD + j] = v.z;
-      kct[(4 * xq + 3) * NPAD + j] = v.w;
+    if (x0 > 0) __syncthreads();                         // previous round's reads of kct are done
+#pragma unroll
+    for (int u = 0; u < P; ++u) {
+      const int idx = threadIdx.x + u * kThreads;
+      if (idx < n_cols * (kXC / 4)) {
+        const int j = idx / (kXC / 4), xq = idx % (kXC / 4);
+        kct[(4 * xq + 0) * NPAD + j] = pre[u].x;
+        kct[(4 * xq + 1) * NPAD + j] = pre[u].y;
+        kct[(4 * xq + 2) * NPAD + j] = pre[u].z;
+        kct[(4 * xq + 3) * NPAD + j] = pre[u].w;
+      }
     }
     __syncthreads();
+    if (x0 + kXC < D) {
+#pragma unroll
+      for (int u = 0; u < P; ++u) {
+        const int idx = threadIdx.x + u * kThreads;
+        if (idx < n_cols * (kXC / 4))
+          pre[u] = *reinterpret_cast<const float4*>(cols[idx / (kXC / 4)] + x0 + kXC + 4 * (idx % (kXC / 4)));
+      }
+    }
 #pragma unroll 4
     for (int xx = 0; xx < kXC; ++xx) {
       const float q = qrow[x0 + xx];
@@ -160,6 +180,7 @@ struct SelectArgs {
   const float* Qc;
   const int32_t* l_map;
   int32_t* sel;
+  float* Zl;                // optional out: scaled logits of every local block, [H][nqb][n_loc]
 };
 
 template <int D, int NM>
@@ -182,6 +203,12 @@ __global__ void __launch_bounds__(kThreads) select_kernel(SelectArgs a) {
   coarse_dots<D, NM>(cols, a.n_loc, qs + wave * D, kct, acc);
   if (!row_ok) return;
 
+  if (a.Zl) {
+    float* zrow = a.Zl + ((size_t)h * a.nqb + i) * a.n_loc;
+#pragma unroll
+    for (int m = 0; m < NM; ++m)
+      if (lane + 64 * m < a.n_loc) zrow[lane + 64 * m] = acc[m] * a.scale;
+  }
   // order-preserving integer keys; invisible columns get 0, below every real value
   const int nvis = a.causal ? a.n_loc - a.nqb + i + 1 : a.n_loc;
   uint32_t key[NM];
@@ -230,11 +257,12 @@ __global__ void __launch_bounds__(kThreads) select_kernel(SelectArgs a) {
 // over the row in LDS.
 // ------------------------------------------------------------------------------------------------
 struct ScoreArgs {
-  int H, nqb, n_loc, n_loc_cap, C, nU_max;
+  int H, nqb, nqb_pad, n_loc, n_loc_cap, C, nU_max, n_evict;
   float scale;
   const float* Kc_l;
   const float* Kc_p;
   const float* Qc;
+  const float* Zl;          // optional: scaled local logits [H][nqb][n_loc] from the selection call
   const int32_t* l_map;
   const int32_t* p_len;
   float* A;
@@ -293,10 +321,70 @@ __global__ void __launch_bounds__(kThreads) score_rows_kernel(ScoreArgs a) {
   __syncthreads();
   if (!row_ok) return;
   const float s = sum_s[wave];
-  float* arow = a.A + ((size_t)h * a.nqb + i) * a.nU_max;
+  // stored column-major (A^T[h][j][i]) so the column means read contiguous rows
+  // (only the columns that can be candidates are needed downstream: slots, then evicted blocks)
+  float* acol = a.A + (size_t)h * a.nU_max * a.nqb_pad + i;
+  const int n_need = nP + a.n_evict;
 #pragma unroll
   for (int m = 0; m < NM; ++m)
-    if (lane + 64 * m < nU) arow[lane + 64 * m] = acc[m] / s;
+    if (lane + 64 * m < n_need) acol[(size_t)(lane + 64 * m) * a.nqb_pad] = acc[m] / s;
+}
+
+// Same rows when the selection call has left the local logits in Zl: only the (at most 64) persistent
+// columns are multiplied here; lane `lane` owns persistent column `lane` and local columns lane + 64 m.
+template <int D, int NML>
+__global__ void __launch_bounds__(kThreads) score_rows_z_kernel(ScoreArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NPAD = 64 + 2;
+  float* kct = reinterpret_cast<float*>(smem);                                  // [kXC][NPAD]
+  float* qs = kct + kXC * NPAD;                                                 // [4][D]
+  const float** cols = reinterpret_cast<const float**>(qs + 4 * D);            // [64]
+  float* erow = reinterpret_cast<float*>(cols + 64);                            // [4][64 + NML*64]
+  __shared__ float sum_s[4];
+  const int h = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + wave;
+  const bool row_ok = i < a.nqb;
+  const bool occ = lane < a.C && a.p_len[(size_t)h * (a.C + 1) + lane] > 0;
+  const uint64_t occ_mask = __ballot(occ);
+  const int nP = __popcll(occ_mask), nU = nP + a.n_loc;
+  if (wave == 0 && occ) cols[lanes_below(occ_mask)] = a.Kc_p + ((size_t)h * a.C + lane) * D;
+  for (int x = lane; x < D; x += 64) qs[wave * D + x] = row_ok ? a.Qc[((size_t)h * a.nqb + i) * D + x] : 0.0f;
+  float zl[NML];
+  const float* zrow = a.Zl + ((size_t)h * a.nqb + min(i, a.nqb - 1)) * a.n_loc;
+#pragma unroll
+  for (int m = 0; m < NML; ++m) zl[m] = lane + 64 * m < a.n_loc ? zrow[lane + 64 * m] : 0.0f;
+  float accp[1];
+  coarse_dots<D, 1>(cols, nP, qs + wave * D, kct, accp);
+  const float zp = accp[0] * a.scale;
+
+  float mx = lane < nP ? zp : -INFINITY;
+#pragma unroll
+  for (int m = 0; m < NML; ++m)
+    if (lane + 64 * m < a.n_loc) mx = fmaxf(mx, zl[m]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  float* er = erow + wave * (64 + NML * 64);
+  const float ep = lane < nP ? pexp(zp - mx) : 0.0f;
+  if (lane < nP) er[lane] = ep;
+#pragma unroll
+  for (int m = 0; m < NML; ++m) {
+    zl[m] = (lane + 64 * m < a.n_loc) ? pexp(zl[m] - mx) : 0.0f;
+    if (lane + 64 * m < a.n_loc) er[nP + lane + 64 * m] = zl[m];
+  }
+  __syncthreads();
+  if (lane == 0) {
+    float s = 0.0f;
+    for (int j = 0; j < nU; ++j) s = s + er[j];
+    sum_s[wave] = s;
+  }
+  __syncthreads();
+  if (!row_ok) return;
+  const float s = sum_s[wave];
+  float* acol = a.A + (size_t)h * a.nU_max * a.nqb_pad + i;
+  if (lane < nP) acol[(size_t)lane * a.nqb_pad] = ep / s;
+#pragma unroll
+  for (int m = 0; m < NML; ++m)
+    if (lane + 64 * m < a.n_evict) acol[(size_t)(nP + lane + 64 * m) * a.nqb_pad] = zl[m] / s;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -305,8 +393,8 @@ __global__ void __launch_bounds__(kThreads) score_rows_kernel(ScoreArgs a) {
 constexpr int kMaxCand = PBSA_MAX_C + PBSA_MAX_N_LOC;
 
 struct RetainArgs {
-  int H, nqb, n_loc, n_loc_cap, C, n_sink, n_evict, nU_max, d, B, fold;
-  const float* A;
+  int H, nqb, nqb_pad, n_loc, n_loc_cap, C, n_sink, n_evict, nU_max, d, B, fold;
+  const float* A;           // A^T [H][nU_max][nqb_pad]
   const float* Kc_l;
   float* Kc_p;
   int32_t* p_len;
@@ -318,62 +406,78 @@ struct RetainArgs {
   float* scores;
   int32_t* slot_src;
   int32_t* fold_n;
-  int32_t* fold_src;
+  int32_t* fold_src;        // dropped candidate: < C persistent slot, else C + PHYSICAL local slot
   int32_t* fold_len;
+  int32_t* promo_slot;      // [H][C] physical local slot a persistent slot is refilled from, or -1
 };
 
+// position of the n-th (0-based) set bit of mask
+__device__ __forceinline__ int nth_set_bit(uint64_t mask, int n) {
+  for (int i = 0; i < n; ++i) mask &= mask - 1;
+  return __ffsll((unsigned long long)mask) - 1;
+}
+
 __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
+  __shared__ __align__(16) float cs[kMaxCand + 4];   // candidate scores
   __shared__ float s[kMaxCand];           // mean column score of slot / evicted-block columns, U order
   __shared__ int cand[kMaxCand];          // < C: slot, else C + local block
-  __shared__ float cs[kMaxCand];
   __shared__ unsigned char win[kMaxCand];
   __shared__ int old_len[PBSA_MAX_C + 1];
   __shared__ int src_s[PBSA_MAX_C];
   __shared__ int flen[kMaxCand];          // valid tokens of each dropped candidate
-  __shared__ int e_len[PBSA_MAX_N_LOC];   // valid tokens of the evicted blocks
-  __shared__ int nP_s, nc_s, nf_s, npos_s;
+  __shared__ int e_len[PBSA_MAX_N_LOC];   // valid tokens / physical slot of the evicted blocks
+  __shared__ int e_map[PBSA_MAX_N_LOC];
+  __shared__ int nf_s, npos_s;
   const int h = blockIdx.x, C = a.C, C1 = a.C + 1;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int32_t* plen = a.p_len + (size_t)h * C1;
   for (int c = threadIdx.x; c < C1; c += kThreads) old_len[c] = plen[c];
-  for (int e = threadIdx.x; e < a.n_evict; e += kThreads) e_len[e] = max(0, min(a.l_len[e], a.B));
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int n = 0;
-    for (int c = 0; c < C; ++c) n += old_len[c] > 0;
-    nP_s = n;
+  for (int e = threadIdx.x; e < a.n_evict; e += kThreads) {
+    e_len[e] = max(0, min(a.l_len[e], a.B));
+    e_map[e] = min(max(a.l_map[e], 0), a.n_loc_cap - 1);
   }
+  if (threadIdx.x == 0) npos_s = 0;
   __syncthreads();
+  // occupied slots: U position of slot c = number of occupied slots below it (C <= 64: one ballot)
+  const bool occ = lane < C && old_len[lane] > 0;
+  const uint64_t occ_mask = __ballot(occ);
+  const int nP = __popcll(occ_mask), u_pos = lanes_below(occ_mask);
   // Column means (Eq. 8) of the columns that can be candidates: the occupied slots and the evicted
-  // blocks, i.e. the first nP + n_evict columns of U.  Rows are added in ascending order; the loads
-  // of 16 rows are issued together.
-  const int nP = nP_s, n_need = nP + a.n_evict;
+  // blocks, i.e. the first nP + n_evict columns of U.  A column is contiguous in A^T: its rows are
+  // fetched 64 at a time and added in ascending order.
+  const int n_need = nP + a.n_evict;
   for (int j = threadIdx.x; j < n_need; j += kThreads) {
     float acc = 0.0f;
-    const float* col = a.A + (size_t)h * a.nqb * a.nU_max + j;
-    for (int i0 = 0; i0 < a.nqb; i0 += 16) {
-      float v[16];
+    const float4* col = reinterpret_cast<const float4*>(a.A + ((size_t)h * a.nU_max + j) * a.nqb_pad);
+    for (int i0 = 0; i0 < a.nqb; i0 += 64) {
+      float4 v[16];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = i0 + u < a.nqb ? col[(size_t)(i0 + u) * a.nU_max] : 0.0f;
+      for (int u = 0; u < 16; ++u) v[u] = i0 + 4 * u < a.nqb ? col[i0 / 4 + u] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int u = 0; u < 16; ++u)
-        if (i0 + u < a.nqb) acc = acc + v[u];
+      for (int u = 0; u < 16; ++u) {
+        const int i = i0 + 4 * u;
+        if (i + 0 < a.nqb) acc = acc + v[u].x;
+        if (i + 1 < a.nqb) acc = acc + v[u].y;
+        if (i + 2 < a.nqb) acc = acc + v[u].z;
+        if (i + 3 < a.nqb) acc = acc + v[u].w;
+      }
     }
     s[j] = acc / (float)a.nqb;
   }
   __syncthreads();
+  // candidates: occupants of slots >= n_sink in slot order, then the evicted blocks
   const int ncand_max = C + a.n_evict;
-  if (threadIdx.x == 0) {
-    int nc = 0, u = 0;
-    for (int c = 0; c < C; ++c) {
-      const bool occ = old_len[c] > 0;
-      if (a.scores) a.scores[(size_t)h * ncand_max + c] = occ ? s[u] : 0.0f;
-      if (occ && c >= a.n_sink) { cand[nc] = c; cs[nc++] = s[u]; }
-      u += occ;
+  const bool is_cand = occ && lane >= a.n_sink;
+  const uint64_t cand_mask = __ballot(is_cand);
+  const int ncP = __popcll(cand_mask), nc = ncP + a.n_evict, places = C - a.n_sink;
+  if (wave == 0) {
+    if (lane < C && a.scores) a.scores[(size_t)h * ncand_max + lane] = occ ? s[u_pos] : 0.0f;
+    if (is_cand) {
+      const int x = lanes_below(cand_mask);
+      cand[x] = lane;
+      cs[x] = s[u_pos];
     }
-    nc_s = nc;
   }
-  __syncthreads();
-  const int ncP = nc_s, nc = ncP + a.n_evict, places = C - a.n_sink;
   for (int e = threadIdx.x; e < a.n_evict; e += kThreads) {
     if (a.scores) a.scores[(size_t)h * ncand_max + C + e] = s[nP + e];
     cand[ncP + e] = C + e;
@@ -383,33 +487,62 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   for (int x = threadIdx.x; x < nc; x += kThreads) {
     int rank = 0;
     const float mine = cs[x];
-    for (int y = 0; y < nc; ++y) rank += (cs[y] > mine || (cs[y] == mine && y < x)) ? 1 : 0;
+    const float4* c4 = reinterpret_cast<const float4*>(cs);
+    for (int y = 0; y < nc; y += 4) {
+      const float4 v = c4[y >> 2];
+      rank += (y + 0 < nc && (v.x > mine || (v.x == mine && y + 0 < x))) ? 1 : 0;
+      rank += (y + 1 < nc && (v.y > mine || (v.y == mine && y + 1 < x))) ? 1 : 0;
+      rank += (y + 2 < nc && (v.z > mine || (v.z == mine && y + 2 < x))) ? 1 : 0;
+      rank += (y + 3 < nc && (v.w > mine || (v.w == mine && y + 3 < x))) ? 1 : 0;
+    }
     win[x] = rank < places;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
+  // wave 0: dropped candidates, in candidate order, go to the fold list; then kept newcomers, in
+  // ascending block order, take the vacated and empty slots in ascending slot order
+  if (wave == 0) {
     int nf = 0;
-    for (int x = 0; x < nc; ++x) {
-      if (win[x]) continue;
-      const int len = cand[x] < C ? old_len[cand[x]] : e_len[cand[x] - C];
-      a.fold_src[(size_t)h * ncand_max + nf] = cand[x];
-      a.fold_len[(size_t)h * ncand_max + nf] = len;
-      flen[nf] = len;
-      ++nf;
-      if (cand[x] < C) old_len[cand[x]] = 0;       // vacate
+    uint64_t vacated = 0;                      // slots whose occupant was dropped
+    for (int x0 = 0; x0 < nc; x0 += 64) {
+      const int x = x0 + lane;
+      const bool lose = x < nc && !win[x];
+      const uint64_t lm = __ballot(lose);
+      if (lose) {
+        const int f = nf + lanes_below(lm);
+        const bool slot_cand = cand[x] < C;
+        const int len = slot_cand ? old_len[cand[x]] : e_len[cand[x] - C];
+        a.fold_src[(size_t)h * ncand_max + f] = slot_cand ? cand[x] : C + e_map[cand[x] - C];
+        a.fold_len[(size_t)h * ncand_max + f] = len;
+        flen[f] = len;
+      }
+      const uint64_t vm = __ballot(lose && cand[min(x, nc - 1)] < C);
+      // bit positions of vm are candidate indices; turn them into slot numbers
+      for (uint64_t m = vm; m; m &= m - 1) vacated |= 1ull << cand[x0 + __ffsll((unsigned long long)m) - 1];
+      nf += __popcll(lm);
     }
-    a.fold_n[h] = nf;
-    nf_s = nf;
-    npos_s = 0;
-    for (int c = 0; c < C; ++c) src_s[c] = -1;
-    int slot = a.n_sink;
-    for (int x = ncP; x < nc; ++x) {               // kept newcomers, ascending block order
-      if (!win[x]) continue;
-      const int e = cand[x] - C;
-      while (slot < C && old_len[slot] > 0) ++slot;
-      if (slot >= C) break;
-      old_len[slot] = e_len[e];
-      src_s[slot] = e;
+    if (lane == 0) { a.fold_n[h] = nf; nf_s = nf; }
+    // free slots = (empty or vacated) and >= n_sink
+    const bool is_free = lane < C && lane >= a.n_sink && (old_len[lane] <= 0 || ((vacated >> lane) & 1));
+    const uint64_t free_mask = __ballot(is_free);
+    if (lane < C) {
+      src_s[lane] = -1;
+      if ((vacated >> lane) & 1) old_len[lane] = 0;
+    }
+    int taken = 0;
+    for (int x0 = ncP; x0 < nc; x0 += 64) {
+      const int x = x0 + lane;
+      const bool keep = x < nc && win[x];
+      const uint64_t km = __ballot(keep);
+      if (keep) {
+        const int r = taken + lanes_below(km);       // r-th kept newcomer takes the r-th free slot
+        if (r < __popcll(free_mask)) {
+          const int slot = nth_set_bit(free_mask, r);
+          const int e = cand[x] - C;
+          old_len[slot] = e_len[e];
+          src_s[slot] = e;
+        }
+      }
+      taken += __popcll(km);
     }
   }
   __syncthreads();
@@ -429,21 +562,23 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   for (int c = threadIdx.x; c < C; c += kThreads) {
     const int e = src_s[c];
     a.slot_src[(size_t)h * C + c] = e;
+    a.promo_slot[(size_t)h * C + c] = e >= 0 ? e_map[e] : -1;
     if (e >= 0) a.p_id[(size_t)h * C + c] = a.l_id[e];
     else if (c >= a.n_sink && old_len[c] == 0) a.p_id[(size_t)h * C + c] = -1;
   }
-  for (int idx = threadIdx.x; idx < C * a.d; idx += kThreads) {
-    const int c = idx / a.d, x = idx % a.d;
+  // pooled keys move with the promoted blocks: independent float4 copies
+  const int d4 = a.d / 4;
+  for (int idx = threadIdx.x; idx < C * d4; idx += kThreads) {
+    const int c = idx / d4, x = idx % d4;
     const int e = src_s[c];
-    if (e >= 0) {
-      const int slot = min(max(a.l_map[e], 0), a.n_loc_cap - 1);
-      a.Kc_p[((size_t)h * C + c) * a.d + x] = a.Kc_l[((size_t)h * a.n_loc_cap + slot) * a.d + x];
-    }
+    if (e >= 0)
+      reinterpret_cast<float4*>(a.Kc_p + ((size_t)h * C + c) * a.d)[x] =
+          reinterpret_cast<const float4*>(a.Kc_l + ((size_t)h * a.n_loc_cap + e_map[e]) * a.d)[x];
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Fold + promote.  One thread owns 4 dimensions of one position t of K or V of one head: it adds
+// Fold + promote.  One thread owns 2 dimensions of one position t of K or V of one head: it adds
 // the dropped blocks' rows to the running sum in candidate order, rewrites the summary row, then
 // copies row t of every kept newcomer into its slot.  A slot that is both dropped and refilled is
 // read and written by the same thread, in that order.
@@ -454,77 +589,91 @@ struct FoldArgs {
   bf16_t* Vp;
   const bf16_t* Kl;
   const bf16_t* Vl;
-  const int32_t* l_map;
   float* S_sum;
   const int32_t* S_cnt;
-  const int32_t* slot_src;
   const int32_t* fold_n;
   const int32_t* fold_src;
   const int32_t* fold_len;
+  const int32_t* promo_slot;
 };
 
 __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
-  const int tpr = a.d / 4;                                     // threads per row
+  __shared__ int fsrc_s[kMaxCand], flen_s[kMaxCand], promo_s[PBSA_MAX_C];
+  const int h = blockIdx.y;
+  const int C = a.C, C1 = a.C + 1, ncand_max = a.C + a.n_evict;
+  const int nf = a.fold && a.S_sum ? a.fold_n[h] : 0;
+  for (int f = threadIdx.x; f < nf; f += kThreads) {
+    fsrc_s[f] = a.fold_src[(size_t)h * ncand_max + f];
+    flen_s[f] = a.fold_len[(size_t)h * ncand_max + f];
+  }
+  for (int c = threadIdx.x; c < C; c += kThreads) promo_s[c] = a.promo_slot[(size_t)h * C + c];
+  __syncthreads();
+  const int tpr = a.d / 2;                                     // threads per row: 2 dimensions each
   const int rows_per_wg = kThreads / tpr;
   const int row = blockIdx.x * rows_per_wg + threadIdx.x / tpr; // over [2][B]
-  const int xc = (threadIdx.x % tpr) * 4;
-  const int h = blockIdx.y;
+  const int xc = (threadIdx.x % tpr) * 2;
   if (row >= 2 * a.B) return;
   const int kv = row / a.B, t = row % a.B;
-  const int C = a.C, C1 = a.C + 1, ncand_max = a.C + a.n_evict;
   const size_t blk = (size_t)a.B * a.d;
   bf16_t* P = kv ? a.Vp : a.Kp;
   const bf16_t* L = kv ? a.Vl : a.Kl;
   const size_t rowoff = (size_t)t * a.d + xc;
-  const int nf = a.fold_n[h];
-  if (a.fold && nf > 0) {
-    float* ssum = a.S_sum + ((size_t)h * 2 + kv) * blk + rowoff;
-    float4 acc = *reinterpret_cast<float4*>(ssum);
-    const int cnt = a.S_cnt[(size_t)h * a.B + t];     // already the new count (retain_kernel)
-    const int32_t* fsrc = a.fold_src + (size_t)h * ncand_max;
-    const int32_t* flen = a.fold_len + (size_t)h * ncand_max;
-    // rows are loaded 8 at a time (row t exists in every block, valid or not) and added in order,
-    // the add predicated on t < len
-    for (int f0 = 0; f0 < nf; f0 += 8) {
-      uint2 v[8];
-      bool on[8];
+  const bf16_t* Ph = P + (size_t)h * C1 * blk + rowoff;
+  const bf16_t* Lh = L + (size_t)h * a.n_loc_cap * blk + rowoff;
+  // promoted rows are independent of the fold: fetch the first 16 before it starts
+  uint32_t pv[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int f = min(f0 + u, nf - 1);
-        const int src = fsrc[f];
-        on[u] = f0 + u < nf && t < flen[f];
-        const bf16_t* blkp;
-        if (src < C) {
-          blkp = P + ((size_t)h * C1 + src) * blk;
-        } else {
-          const int slot = min(max(a.l_map[src - C], 0), a.n_loc_cap - 1);
-          blkp = L + ((size_t)h * a.n_loc_cap + slot) * blk;
-        }
-        v[u] = *reinterpret_cast<const uint2*>(blkp + rowoff);
+  for (int u = 0; u < 16; ++u) {
+    const int ps = u < C ? promo_s[u] : -1;
+    pv[u] = ps >= 0 ? *reinterpret_cast<const uint32_t*>(Lh + (size_t)ps * blk) : 0u;
+  }
+  if (nf > 0) {
+    float* ssum = a.S_sum + ((size_t)h * 2 + kv) * blk + rowoff;
+    float2 acc = *reinterpret_cast<float2*>(ssum);
+    const int cnt = a.S_cnt[(size_t)h * a.B + t];     // already the new count (retain_kernel)
+    // rows are loaded 32 at a time (row t exists in every block, valid or not) and added in
+    // candidate order, the add predicated on t < len
+    for (int f0 = 0; f0 < nf; f0 += 32) {
+      uint32_t v[32];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) {
+        const int src = fsrc_s[min(f0 + u, nf - 1)];
+        const bf16_t* blkp = src < C ? Ph + (size_t)src * blk : Lh + (size_t)(src - C) * blk;
+        v[u] = *reinterpret_cast<const uint32_t*>(blkp);
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        if (on[u]) {
-          acc.x = acc.x + bf_lo(v[u].x); acc.y = acc.y + bf_hi(v[u].x);
-          acc.z = acc.z + bf_lo(v[u].y); acc.w = acc.w + bf_hi(v[u].y);
+      for (int u = 0; u < 32; ++u) {
+        if (f0 + u < nf && t < flen_s[f0 + u]) {
+          acc.x = acc.x + bf_lo(v[u]);
+          acc.y = acc.y + bf_hi(v[u]);
         }
       }
     }
-    *reinterpret_cast<float4*>(ssum) = acc;
+    *reinterpret_cast<float2*>(ssum) = acc;
     if (cnt > 0) {
       const float fc = (float)cnt;
-      uint2 o;
-      o.x = f2bf_rne(acc.x / fc) | (f2bf_rne(acc.y / fc) << 16);
-      o.y = f2bf_rne(acc.z / fc) | (f2bf_rne(acc.w / fc) << 16);
-      *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + C) * blk + rowoff) = o;
+      *reinterpret_cast<uint32_t*>(P + ((size_t)h * C1 + C) * blk + rowoff) =
+          f2bf_rne(acc.x / fc) | (f2bf_rne(acc.y / fc) << 16);
     }
   }
-  for (int c = 0; c < C; ++c) {
-    const int e = a.slot_src[(size_t)h * C + c];
-    if (e < 0) continue;
-    const int slot = min(max(a.l_map[e], 0), a.n_loc_cap - 1);
-    *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + c) * blk + rowoff) =
-        *reinterpret_cast<const uint2*>(L + ((size_t)h * a.n_loc_cap + slot) * blk + rowoff);
+  // promoted rows: stores after the fold's loads (a refilled slot was read above by this thread)
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const int ps = u < C ? promo_s[u] : -1;
+    if (ps >= 0) *reinterpret_cast<uint32_t*>(P + ((size_t)h * C1 + u) * blk + rowoff) = pv[u];
+  }
+  for (int c0 = 16; c0 < C; c0 += 16) {
+    uint32_t w[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int ps = c0 + u < C ? promo_s[c0 + u] : -1;
+      w[u] = ps >= 0 ? *reinterpret_cast<const uint32_t*>(Lh + (size_t)ps * blk) : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int ps = c0 + u < C ? promo_s[c0 + u] : -1;
+      if (ps >= 0) *reinterpret_cast<uint32_t*>(P + ((size_t)h * C1 + c0 + u) * blk + rowoff) = w[u];
+    }
   }
 }
 
@@ -550,10 +699,12 @@ UpdateWs carve_update_ws(const pbsa_params& p, void* base) {
   char* b = static_cast<char*>(base);
   size_t off = 0;
   const size_t nU_max = (size_t)p.C + p.n_loc, ncand = (size_t)p.C + p.n_evict;
-  w.A = reinterpret_cast<float*>(b + off);          off += align256((size_t)p.H * p.nqb * nU_max * 4);
+  const size_t nqb_pad = ((size_t)p.nqb + 3) & ~(size_t)3;
+  w.A = reinterpret_cast<float*>(b + off);          off += align256((size_t)p.H * nU_max * nqb_pad * 4);
   w.fold_n = reinterpret_cast<int32_t*>(b + off);   off += align256((size_t)p.H * 4);
   w.fold_src = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * ncand * 4);
   w.fold_len = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * ncand * 4);
+  w.promo_slot = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * (p.C + 1) * 4);
   w.bytes = off;
   return w;
 }
@@ -580,7 +731,8 @@ static hipError_t launch_select_t(const SelectArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
-                         const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, hipStream_t stream) {
+                         const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
+                         hipStream_t stream) {
   PoolArgs pa{};
   pa.mode = 1; pa.H = p.H; pa.B = p.B; pa.Nq = p.Nq; pa.nqb = p.nqb; pa.n_loc = p.n_loc; pa.n_loc_cap = p.n_loc_cap;
   pa.pool_from = p.pool_from; pa.n_kjobs_per_head = p.n_loc - p.pool_from;
@@ -593,9 +745,9 @@ hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl
   else hipLaunchKernelGGL(pool_kernel<64>, grid, dim3(kThreads), 0, stream, pa);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (p.k == 0) return hipSuccess;
+  if (p.k == 0 && !Zl) return hipSuccess;
 
-  SelectArgs a{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.k, p.causal, p.scale, Kc_l, Qc, l_map, sel};
+  SelectArgs a{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.k, p.causal, p.scale, Kc_l, Qc, l_map, sel, Zl};
   const int nm = (p.n_loc + 63) / 64;
   if (p.d == 128) {
     if (nm <= 2) return launch_select_t<128, 2>(a, stream);
@@ -616,34 +768,54 @@ static hipError_t launch_rows_t(const ScoreArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, bf16_t* Kp, bf16_t* Vp,
+template <int D, int NML>
+static hipError_t launch_rows_z_t(const ScoreArgs& a, hipStream_t stream) {
+  const size_t lds = (size_t)kXC * 66 * 4 + (size_t)4 * D * 4 + 64 * 8 + (size_t)4 * (64 + NML * 64) * 4;
+  hipError_t e = allow_lds(score_rows_z_kernel<D, NML>, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((score_rows_z_kernel<D, NML>), dim3((a.nqb + 3) / 4, a.H), dim3(kThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, bf16_t* Kp,
+                         bf16_t* Vp,
                          float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
                          const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
                          const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
                          hipStream_t stream) {
   const int nU_max = p.C + p.n_loc;
-  ScoreArgs sa{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.C, nU_max, p.scale, Kc_l, Kc_p, Qc, l_map, p_len, ws.A};
+  const int nqb_pad = (p.nqb + 3) & ~3;
+  ScoreArgs sa{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, nU_max, p.n_evict, p.scale, Kc_l, Kc_p, Qc, Zl, l_map, p_len, ws.A};
   const int nm = (nU_max + 63) / 64;
   hipError_t e;
-  if (p.d == 128) {
-    e = nm <= 2 ? launch_rows_t<128, 2>(sa, stream) : nm <= 5 ? launch_rows_t<128, 5>(sa, stream)
+  if (Zl) {
+    const int nml = (p.n_loc + 63) / 64;
+    if (p.d == 128)
+      e = nml <= 2 ? launch_rows_z_t<128, 2>(sa, stream) : nml <= 5 ? launch_rows_z_t<128, 5>(sa, stream)
+                                                                   : launch_rows_z_t<128, 8>(sa, stream);
+    else
+      e = nml <= 2 ? launch_rows_z_t<64, 2>(sa, stream) : nml <= 5 ? launch_rows_z_t<64, 5>(sa, stream)
+                                                                  : launch_rows_z_t<64, 8>(sa, stream);
+  } else if (p.d == 128) {
+    e = nm <= 2 ? launch_rows_t<128, 2>(sa, stream) : nm <= 6 ? launch_rows_t<128, 6>(sa, stream)
                                                               : launch_rows_t<128, 9>(sa, stream);
   } else {
-    e = nm <= 2 ? launch_rows_t<64, 2>(sa, stream) : nm <= 5 ? launch_rows_t<64, 5>(sa, stream)
+    e = nm <= 2 ? launch_rows_t<64, 2>(sa, stream) : nm <= 6 ? launch_rows_t<64, 6>(sa, stream)
                                                              : launch_rows_t<64, 9>(sa, stream);
   }
   if (e != hipSuccess) return e;
 
   const int fold = S_sum != nullptr;
-  RetainArgs ra{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.C, p.n_sink, p.n_evict, nU_max, p.d, p.B, fold, ws.A, Kc_l,
-                Kc_p, p_len, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n, ws.fold_src, ws.fold_len};
+  RetainArgs ra{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, p.n_sink, p.n_evict, nU_max, p.d, p.B, fold, ws.A,
+                Kc_l, Kc_p, p_len, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n, ws.fold_src,
+                ws.fold_len, ws.promo_slot};
   hipLaunchKernelGGL(retain_kernel, dim3(p.H), dim3(kThreads), 0, stream, ra);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
-  FoldArgs fa{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, fold, Kp, Vp, Kl, Vl, l_map, S_sum, S_cnt, slot_src,
-              ws.fold_n, ws.fold_src, ws.fold_len};
-  const int rows_per_wg = kThreads / (p.d / 4);
+  FoldArgs fa{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, fold, Kp, Vp, Kl, Vl, S_sum, S_cnt, ws.fold_n,
+              ws.fold_src, ws.fold_len, ws.promo_slot};
+  const int rows_per_wg = kThreads / (p.d / 2);
   hipLaunchKernelGGL(fold_promote_kernel, dim3((2 * p.B + rows_per_wg - 1) / rows_per_wg, p.H), dim3(kThreads), 0,
                      stream, fa);
   return hipGetLastError();

@@ -13,9 +13,10 @@ typedef uint16_t bf16_t;   // raw bf16 bit pattern
 
 // Scratch layout of pbsa_memory_update inside the caller's workspace (all offsets 256-byte aligned).
 struct UpdateWs {
-  float* A;           // [H][nqb][nU_max] row-softmax of the coarse logits, nU_max = C + n_loc
+  float* A;           // [H][nU_max][nqb_pad] row-softmax of the coarse logits, column-major; nU_max = C + n_loc
   int32_t* fold_n;    // [H] number of dropped candidates
-  int32_t* fold_src;  // [H][C + n_evict] dropped candidate: < C persistent slot, else C + local block
+  int32_t* fold_src;  // [H][C + n_evict] dropped candidate: < C persistent slot, else C + physical local slot
+  int32_t* promo_slot;  // [H][C] physical local slot a persistent slot is refilled from, or -1
   int32_t* fold_len;  // [H][C + n_evict] its valid tokens (read before p_len is rewritten)
   size_t bytes;
 };
@@ -24,11 +25,13 @@ UpdateWs carve_update_ws(const pbsa_params& p, void* base);
 hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32_t* len, int32_t n_blocks,
                               float* out, hipStream_t stream);
 hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
-                         const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, hipStream_t stream);
+                         const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
+                         hipStream_t stream);
 hipError_t launch_attention(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
                             const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
                             const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, hipStream_t stream);
-hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, bf16_t* Kp, bf16_t* Vp,
+hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, bf16_t* Kp,
+                         bf16_t* Vp,
                          float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
                          const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
                          const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,

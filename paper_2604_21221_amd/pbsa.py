@@ -62,9 +62,9 @@ def lib() -> ctypes.CDLL:
         L.pbsa_strerror.argtypes = [ctypes.c_int]
         L.pbsa_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.pbsa_pool_blocks.argtypes = [pp, vp, vp, i32, vp, vp]
-        L.pbsa_select_blocks.argtypes = [pp] + [vp] * 8 + [sz, vp]
+        L.pbsa_select_blocks.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.pbsa_attention_fwd.argtypes = [pp] + [vp] * 12 + [sz, vp]
-        L.pbsa_memory_update.argtypes = [pp] + [vp] * 17 + [sz, vp]
+        L.pbsa_memory_update.argtypes = [pp] + [vp] * 18 + [sz, vp]
         for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
                      "pbsa_memory_update"):
             getattr(L, name).restype = ctypes.c_int
@@ -125,10 +125,10 @@ def pbsa_pool_blocks(p, X, length, n_blocks, out, stream=None):
     _check(lib().pbsa_pool_blocks(ctypes.byref(p), _ptr(X), _ptr(length), n_blocks, _ptr(out), _stream(stream)))
 
 
-def pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, ws=None, stream=None):
+def pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, Zl=None, ws=None, stream=None):
     w, wb = _ws(ws)
     _check(lib().pbsa_select_blocks(ctypes.byref(p), _ptr(Q), _ptr(Kl), _ptr(l_len), _ptr(l_map), _ptr(Kc_l),
-                                    _ptr(Qc), _ptr(sel), w, wb, _stream(stream)))
+                                    _ptr(Qc), _ptr(sel), _ptr(Zl), w, wb, _stream(stream)))
 
 
 def pbsa_attention_fwd(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse=None, ws=None, stream=None):
@@ -137,10 +137,10 @@ def pbsa_attention_fwd(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse=No
                                     _ptr(l_len), _ptr(l_map), _ptr(sel), _ptr(O), _ptr(lse), w, wb, _stream(stream)))
 
 
-def pbsa_memory_update(p, Qc, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id, scores,
+def pbsa_memory_update(p, Qc, Kc_l, Zl, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id, scores,
                        slot_src, ws, stream=None):
     w, wb = _ws(ws)
-    _check(lib().pbsa_memory_update(ctypes.byref(p), _ptr(Qc), _ptr(Kc_l), _ptr(Kp), _ptr(Vp), _ptr(Kc_p),
+    _check(lib().pbsa_memory_update(ctypes.byref(p), _ptr(Qc), _ptr(Kc_l), _ptr(Zl), _ptr(Kp), _ptr(Vp), _ptr(Kc_p),
                                     _ptr(p_len), _ptr(p_id), _ptr(S_sum), _ptr(S_cnt), _ptr(Kl), _ptr(Vl),
                                     _ptr(l_len), _ptr(l_map), _ptr(l_id), _ptr(scores), _ptr(slot_src), w, wb,
                                     _stream(stream)))

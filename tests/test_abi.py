@@ -57,7 +57,7 @@ P = 0x10000  # a fake, 16-byte aligned, non-NULL device address: validation must
 
 
 def call_select(p, Q=P, Kl=P, l_len=P, l_map=P, Kc_l=P, Qc=P, sel=P):
-    pbsa.pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, None, stream=0)
+    pbsa.pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, None, None, stream=0)
 
 
 def call_attn(p, Q=P, Kp=P, Vp=P, p_len=P, Kl=P, Vl=P, l_len=P, l_map=P, sel=P, O=P):
@@ -65,7 +65,7 @@ def call_attn(p, Q=P, Kp=P, Vp=P, p_len=P, Kl=P, Vl=P, l_len=P, l_map=P, sel=P, 
 
 
 def call_update(p, ws=(0x10000, 1 << 30), S_sum=P, S_cnt=P, Qc=P):
-    pbsa.pbsa_memory_update(p, Qc, P, P, P, P, P, P, S_sum, S_cnt, P, P, P, P, P, None, P, ws, stream=0)
+    pbsa.pbsa_memory_update(p, Qc, P, None, P, P, P, P, P, S_sum, S_cnt, P, P, P, P, P, None, P, ws, stream=0)
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -136,4 +136,4 @@ def test_workspace_checks(L):
 def test_binding_refuses_host_tensors(L):
     import torch
     with pytest.raises(TypeError):
-        pbsa.pbsa_select_blocks(good(), torch.zeros(4), P, P, P, P, P, P, None, stream=0)
+        pbsa.pbsa_select_blocks(good(), torch.zeros(4), P, P, P, P, P, P, None, None, stream=0)

@@ -126,7 +126,9 @@ def test_small_rollout_every_element(gpu, case):
     name, H, d, B, Nq, w, C, k, n_sink, causal, p_lens = case
     scale = np.float32(1.0 / math.sqrt(d))
     st = OracleState(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal)
-    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal, device=DEV)
+    # the update call either takes the coarse logits from the selection call or recomputes them
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal, device=DEV,
+                               pass_logits=name not in ("d64_B64", "d128_B128"))
     if C > 0:
         Kp, Vp = rnd(1, H, C, B, d), rnd(2, H, C, B, d)
         # garbage (even non-finite patterns) beyond the valid length must never matter
