@@ -19,6 +19,12 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 
+# HBM bytes per pbsa_attention_fwd launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE, KiB per dispatch, each scaled by what the same counter reads for a 1 GiB copy:
+# FETCH_SIZE reads half the bytes there, WRITE_SIZE all of them).  Counters cannot be read from inside
+# this process, so the figures are the ones of the summaries under profiles/ for the same command.
+HBM_TRAFFIC_BYTES = {"cfg5": int((106900 * 2.0 + 14040 * 1.0) * 1024)}
+
 
 def executed_flops(sel, p_len, l_len_by_block, rows_per_qblock, d):
     """4 d sum_h sum_i rows_i (valid persistent tokens + valid tokens of the selected blocks)."""
@@ -69,6 +75,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run three 1 GiB device copies and exit: the known-size kernel that the HBM byte "
+                         "counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards by head without exchange; "
@@ -78,6 +87,14 @@ def main():
     from paper_2604_21221_amd import synth, workloads
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = "cuda:0"
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": b.numel() * 4, "copies": 3}))
+        return
     w = synth.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
 
@@ -147,7 +164,7 @@ def main():
                    "executed_gflop_per_step": round(mean_flops / 1e9, 3)},
         "roofline": {"kernel": "pbsa_attention_fwd", "bound": "mfma", "achieved": round(tflops_attn, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 5),
-                     "traffic": None, "us_per_launch": round(attn_ms * 1e3, 2)},
+                     "traffic": HBM_TRAFFIC_BYTES.get(w.name), "us_per_launch": round(attn_ms * 1e3, 2)},
     }
     if not args.no_cpu_baseline:
         from oracle import pbsa_oracle as orc
