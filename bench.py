@@ -18,6 +18,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM bytes per pbsa_attention_fwd launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE, KiB per dispatch, each scaled by what the same counter reads for a 1 GiB copy:
@@ -112,36 +113,50 @@ def main():
     torch.cuda.synchronize()
 
     O = torch.empty(w.H, w.Nq, w.d, dtype=torch.bfloat16, device=dev)
-    n_total = W + K
+    K2 = min(K, 20)            # extra steps after the timed region: per-call split of select and update
+    n_total = W + K + K2
     sel_hist = torch.full((n_total,) + tuple(c.sel.shape), -1, dtype=torch.int32, device=dev)
+    src_hist = torch.full((n_total,) + tuple(c.slot_src.shape), -1, dtype=torch.int32, device=dev)
     plen_hist = torch.zeros((n_total,) + tuple(c.p_len.shape), dtype=torch.int32, device=dev)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    new_ev = lambda n: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    ev, ev_sel, ev_upd = new_ev(K), new_ev(K2), new_ev(K2)
     stream = torch.cuda.current_stream()
 
-    def one_step(i, timed_idx=None):
+    def one_step(i, attn_ev=None, sel_ev=None, upd_ev=None):
         # the producer has written the next chunk's K/V into the ring position that was just freed
         # (here: the data already there serves as the new chunk); its queries are the matching Q
         g = g_next + i
         c.adopt_chunk(g)
         Qd = Q_at[(c.n_appended - 1) % n_ring]
-        c.sel = sel_hist[i]
+        c.sel, c.slot_src = sel_hist[i], src_hist[i]
+        if sel_ev is not None:
+            sel_ev[0].record(stream)
         c.select(Qd)
+        if sel_ev is not None:
+            sel_ev[1].record(stream)
         plen_hist[i].copy_(c.p_len, non_blocking=True)
-        if timed_idx is not None:
-            ev[timed_idx][0].record(stream)
+        if attn_ev is not None:
+            attn_ev[0].record(stream)
         c.attention(Qd, O)
-        if timed_idx is not None:
-            ev[timed_idx][1].record(stream)
+        if attn_ev is not None:
+            attn_ev[1].record(stream)
+        if upd_ev is not None:
+            upd_ev[0].record(stream)
         c.update()
+        if upd_ev is not None:
+            upd_ev[1].record(stream)
 
     for i in range(W):
         one_step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        one_step(W + i, i)
+        one_step(W + i, attn_ev=ev[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    for i in range(K2):
+        one_step(W + K + i, sel_ev=ev_sel[i], upd_ev=ev_upd[i])
+    torch.cuda.synchronize()
 
     step_s = (t1 - t0) / K
     attn_ms = sum(a.elapsed_time(b) for a, b in ev) / K
@@ -152,6 +167,23 @@ def main():
     mean_flops = float(np.mean(flops))
     tflops_step = mean_flops / step_s / 1e12
     tflops_attn = mean_flops / (attn_ms * 1e-3) / 1e12
+
+    # HBM-bound calls: algorithmic bytes over the event-bracketed duration.  Selection reads the chunk's
+    # Q and K once and writes sel and the logits; the update reads the logits, reads K and V of every
+    # folded block, reads and writes K and V of every promoted block and the summary sums and slot.
+    sel_us = sum(a.elapsed_time(b) for a, b in ev_sel) / K2 * 1e3
+    upd_us = sum(a.elapsed_time(b) for a, b in ev_upd) / K2 * 1e3
+    blk = w.B * w.d * 2
+    n_loc = n_ring * w.nqb
+    sel_bytes = 2 * w.H * w.Nq * w.d * 2 + w.H * w.nqb * (w.k + n_loc) * 4
+    upd_bytes = []
+    for i in range(W + K, n_total):
+        occupied = int((plen_hist[i][:, :w.C] > 0).sum().item())
+        promoted = int((src_hist[i] >= 0).sum().item())
+        folded = occupied + w.H * w.nqb - min(w.H * w.C, occupied + w.H * w.nqb)
+        upd_bytes.append(w.H * w.nqb * n_loc * 4 + folded * 2 * blk + promoted * 4 * blk
+                         + w.H * (2 * 2 * w.B * w.d * 4 + 2 * blk))
+    upd_b = float(np.mean(upd_bytes))
 
     out = {
         "metric": "effective TFLOP/s on executed (sparse) attention FLOPs per layer-chunk step (select+attention+update)",
@@ -164,7 +196,16 @@ def main():
                    "executed_gflop_per_step": round(mean_flops / 1e9, 3)},
         "roofline": {"kernel": "pbsa_attention_fwd", "bound": "mfma", "achieved": round(tflops_attn, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 5),
-                     "traffic": HBM_TRAFFIC_BYTES.get(w.name), "us_per_launch": round(attn_ms * 1e3, 2)},
+                     "traffic": HBM_TRAFFIC_BYTES.get(w.name), "traffic_unit": "bytes per launch",
+                     "us_per_launch": round(attn_ms * 1e3, 2)},
+        "hbm_bound_calls": {
+            "pbsa_select_blocks": {"us_per_call": round(sel_us, 2), "algorithmic_bytes": sel_bytes,
+                                   "achieved": round(sel_bytes / sel_us / 1e3, 1), "peak": PEAK_HBM_GBS,
+                                   "unit": "GB/s", "frac": round(sel_bytes / sel_us / 1e3 / PEAK_HBM_GBS, 4)},
+            "pbsa_memory_update": {"us_per_call": round(upd_us, 2), "algorithmic_bytes": int(upd_b),
+                                   "achieved": round(upd_b / upd_us / 1e3, 1), "peak": PEAK_HBM_GBS,
+                                   "unit": "GB/s", "frac": round(upd_b / upd_us / 1e3 / PEAK_HBM_GBS, 4)},
+            "note": f"{K2} steps after the timed region, HIP events around each call"},
     }
     if not args.no_cpu_baseline:
         from oracle import pbsa_oracle as orc

@@ -13,7 +13,8 @@
  *    `size_t*` result of pbsa_workspace_bytes are HOST pointers.  The library never allocates,
  *    frees or synchronises: a call validates its arguments on the host, enqueues kernels on
  *    `hip_stream` (a hipStream_t, NULL = the default stream) and returns.
- *  - bf16 tensors are raw 16-bit patterns.  All tensor base pointers must be 16-byte aligned.
+ *  - bf16 tensors are raw 16-bit patterns.  bf16 and fp32 tensor base pointers and the workspace must be
+ *    16-byte (workspace: 256-byte) aligned; integer arrays need only their natural alignment.
  *  - Block-major cache layout (App. "Rearrange for Locality Preserving", Alg. 3): the B tokens of a
  *    block are contiguous, [B][d] row-major.  Rows at or beyond a block's valid length are never
  *    trusted (pooling divides by the valid length, attention masks them).

@@ -52,10 +52,11 @@ class PbsaCache:
     def n_loc(self):
         return len(self.chunk_pos) * self.nqb
 
-    def _device_maps(self):
-        """l_map / l_len / l_id device tensors of the current ring arrangement.  The map and the lengths
-        depend only on the ring positions and are cached per arrangement; ids of consecutive chunks are
-        an arange plus an offset, formed on the device (no host-to-device copy in steady state)."""
+    def _device_maps(self, want_ids=False):
+        """l_map / l_len (and on request l_id) device tensors of the current ring arrangement.  The map
+        and the lengths depend only on the ring positions and are cached per arrangement; ids of
+        consecutive chunks are a window of one device-resident arange, so the steady state issues no
+        copy and no kernel here."""
         key = tuple(self.chunk_pos)
         m = self._maps.get(key)
         if m is None:
@@ -64,11 +65,14 @@ class PbsaCache:
             l_len = self._chunk_lens.repeat(len(self.chunk_pos))
             m = (l_map.to(self.dev), l_len.to(self.dev))
             self._maps[key] = m
+        if not want_ids:
+            return m[0], m[1], None
         ids = self.chunk_ids
-        if all(b == a + 1 for a, b in zip(ids, ids[1:])):
-            if self._arange64 is None:
-                self._arange64 = torch.arange(self.cap, dtype=torch.int64, device=self.dev)
-            l_id = self._arange64[:self.n_loc] + ids[0] * self.nqb
+        if ids[0] >= 0 and all(b == a + 1 for a, b in zip(ids, ids[1:])):
+            lo, hi = ids[0] * self.nqb, (ids[-1] + 1) * self.nqb
+            if self._arange64 is None or self._arange64.numel() < hi:
+                self._arange64 = torch.arange(max(2 * hi, 64 * self.cap), dtype=torch.int64, device=self.dev)
+            l_id = self._arange64[lo:hi]
         else:
             ar = torch.arange(self.nqb)
             l_id = torch.cat([g * self.nqb + ar for g in ids]).to(torch.int64).to(self.dev)
@@ -145,7 +149,7 @@ class PbsaCache:
         return self.nqb if len(self.chunk_pos) == self.w + 1 else 0
 
     def update(self):
-        l_map, l_len, l_id = self._device_maps()
+        l_map, l_len, l_id = self._device_maps(want_ids=True)
         ne = self.n_evict_now()
         p = self.params(n_evict=ne)
         pbsa.pbsa_memory_update(p, self.Qc, self.Kc_l, self.Zl, self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id, self.S_sum,
