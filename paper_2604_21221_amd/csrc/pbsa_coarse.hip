@@ -43,8 +43,8 @@ __device__ __forceinline__ float pexp(float x) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Pooling.  One job = one block; D/8 threads per job, each owning 8 dimensions (one 16-byte load per
-// token) and adding the tokens in ascending order.
+// Pooling.  One job = one block; D/2 threads per job, each owning 2 dimensions (one 4-byte load per
+// token) and adding the tokens in ascending order.  The loads of 64 tokens are in flight together.
 // ------------------------------------------------------------------------------------------------
 struct PoolArgs {
   int mode;                 // 0: generic blocks, 1: select (local key blocks, then query blocks)
@@ -61,7 +61,7 @@ struct PoolArgs {
 
 template <int D>
 __global__ void __launch_bounds__(kThreads) pool_kernel(PoolArgs a) {
-  constexpr int TPJ = D / 8;
+  constexpr int TPJ = D / 2;
   const int job = blockIdx.x * (kThreads / TPJ) + threadIdx.x / TPJ;
   const int c = threadIdx.x % TPJ;
   if (job >= a.n_jobs) return;
@@ -93,26 +93,26 @@ __global__ void __launch_bounds__(kThreads) pool_kernel(PoolArgs a) {
     }
   }
   len = max(0, min(len, a.B));
-  float acc[8];
+  float acc0 = 0.0f, acc1 = 0.0f;
+  const bf16_t* p = src + c * 2;
+  for (int t0 = 0; t0 < len; t0 += 64) {
+    uint32_t v[64];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
-  const bf16_t* p = src + c * 8;
-#pragma unroll 8
-  for (int t = 0; t < len; ++t) {
-    const uint4 v = *reinterpret_cast<const uint4*>(p + (size_t)t * pitch);
-    acc[0] = acc[0] + bf_lo(v.x); acc[1] = acc[1] + bf_hi(v.x);
-    acc[2] = acc[2] + bf_lo(v.y); acc[3] = acc[3] + bf_hi(v.y);
-    acc[4] = acc[4] + bf_lo(v.z); acc[5] = acc[5] + bf_hi(v.z);
-    acc[6] = acc[6] + bf_lo(v.w); acc[7] = acc[7] + bf_hi(v.w);
+    for (int u = 0; u < 64; ++u)
+      v[u] = *reinterpret_cast<const uint32_t*>(p + (size_t)min(t0 + u, len - 1) * pitch);
+#pragma unroll
+    for (int u = 0; u < 64; ++u) {
+      if (t0 + u < len) {
+        acc0 = acc0 + bf_lo(v[u]);
+        acc1 = acc1 + bf_hi(v[u]);
+      }
+    }
   }
   const float fl = (float)len;
-  float4 o0, o1;
-  o0.x = len > 0 ? acc[0] / fl : 0.0f; o0.y = len > 0 ? acc[1] / fl : 0.0f;
-  o0.z = len > 0 ? acc[2] / fl : 0.0f; o0.w = len > 0 ? acc[3] / fl : 0.0f;
-  o1.x = len > 0 ? acc[4] / fl : 0.0f; o1.y = len > 0 ? acc[5] / fl : 0.0f;
-  o1.z = len > 0 ? acc[6] / fl : 0.0f; o1.w = len > 0 ? acc[7] / fl : 0.0f;
-  *reinterpret_cast<float4*>(dst + c * 8) = o0;
-  *reinterpret_cast<float4*>(dst + c * 8 + 4) = o1;
+  float2 o;
+  o.x = len > 0 ? acc0 / fl : 0.0f;
+  o.y = len > 0 ? acc1 / fl : 0.0f;
+  *reinterpret_cast<float2*>(dst + c * 2) = o;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -183,72 +183,139 @@ struct SelectArgs {
   float* Zl;                // optional out: scaled logits of every local block, [H][nqb][n_loc]
 };
 
-template <int D, int NM>
-__global__ void __launch_bounds__(kThreads) select_kernel(SelectArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int NPAD = NM * 64 + 2;
-  float* kct = reinterpret_cast<float*>(smem);                                  // [kXC][NPAD]
-  float* qs = kct + kXC * NPAD;                                                 // [4][D]
-  const float** cols = reinterpret_cast<const float**>(qs + 4 * D);            // [NM*64]
-  const int h = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i = blockIdx.x * 4 + wave;
-  const bool row_ok = i < a.nqb;
-  for (int j = threadIdx.x; j < a.n_loc; j += kThreads) {
-    int slot = a.l_map[j];
-    slot = min(max(slot, 0), a.n_loc_cap - 1);
-    cols[j] = a.Kc_l + ((size_t)h * a.n_loc_cap + slot) * D;
-  }
-  for (int x = lane; x < D; x += 64) qs[wave * D + x] = row_ok ? a.Qc[((size_t)h * a.nqb + i) * D + x] : 0.0f;
-  float acc[NM];
-  coarse_dots<D, NM>(cols, a.n_loc, qs + wave * D, kct, acc);
-  if (!row_ok) return;
+// One wave-wide global -> LDS load of 16 bytes per lane: LDS bytes [lds_off, lds_off + 1024) receive
+// lane i's 16 bytes, fetched from base + voff, at lds_off + 16 i.  Completion is tracked by the issuing
+// wave's vmcnt.  Earlier LDS reads of this wave are complete before the load is issued.
+__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds_off) {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_off), "v"(voff), "s"(base)
+               : "memory");
+}
 
-  if (a.Zl) {
-    float* zrow = a.Zl + ((size_t)h * a.nqb + i) * a.n_loc;
+// Selection (Eq. 10-11).  A workgroup handles 4 query blocks of one head; its NM waves split the local
+// blocks: lane `lane` of wave w owns column j = 64 w + lane and runs the four chains
+// acc_r = fma(q_r[x], k_j[x], acc_r), x ascending.  The pooled keys reach LDS by direct global -> LDS
+// loads, kDX dimensions (128 bytes per column) per round, double buffered; a wave stages exactly the 64
+// columns it consumes, so the rounds need no workgroup barrier.  Within a column's 128 bytes the
+// 16-byte chunks are permuted (logical chunk c of column j sits at c ^ ((j / 2) % 8)), which makes the
+// per-lane 16-byte reads of 16 consecutive columns hit 16 distinct bank groups.  The logits then go
+// to LDS and wave r ranks row r.
+constexpr int kDX = 32;
+
+template <int D, int NM>
+__global__ void __launch_bounds__(64 * NM) select_kernel(SelectArgs a) {
+  extern __shared__ __align__(1024) unsigned char smem[];
+  constexpr int NCP = NM * 64;                        // padded columns
+  constexpr int BUF = NCP * kDX * 4;                  // one round of every column
+  constexpr int NR = D / kDX;
+  float* qs = reinterpret_cast<float*>(smem + 2 * BUF);                         // [4][D]
+  float* zs = qs + 4 * D;                                                       // [4][NCP]
+  const int h = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i0 = blockIdx.x * 4;
+
+  // this lane's share of the staging: instruction n fills columns 64 wave + 8 n + lane / 8, physical chunk lane % 8
+  uint32_t goff[8];
 #pragma unroll
-    for (int m = 0; m < NM; ++m)
-      if (lane + 64 * m < a.n_loc) zrow[lane + 64 * m] = acc[m] * a.scale;
+  for (int n = 0; n < 8; ++n) {
+    const int j = 64 * wave + 8 * n + (lane >> 3);
+    int slot = a.l_map[min(j, a.n_loc - 1)];
+    slot = min(max(slot, 0), a.n_loc_cap - 1);
+    const int chunk = (lane & 7) ^ ((j >> 1) & 7);
+    goff[n] = (uint32_t)(((size_t)h * a.n_loc_cap + slot) * D * 4 + chunk * 16);
   }
-  // order-preserving integer keys; invisible columns get 0, below every real value
-  const int nvis = a.causal ? a.n_loc - a.nqb + i + 1 : a.n_loc;
-  uint32_t key[NM];
-#pragma unroll
-  for (int m = 0; m < NM; ++m) {
-    float z = acc[m] * a.scale;
-    if (z == 0.0f) z = 0.0f;                    // -0 and +0 compare equal: give them one key
-    const uint32_t b = __float_as_uint(z);
-    const uint32_t ordered = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-    key[m] = (lane + 64 * m < nvis) ? ordered : 0u;
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_lds + wave * (64 * kDX * 4));
+  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(a.Kc_l);
+#define PBSA_STAGE(R_)                                                                                 \
+  _Pragma("unroll") for (int n_ = 0; n_ < 8; ++n_)                                                      \
+      dma16(kbase + (R_) * (kDX * 4), goff[n_], wave_lds + ((R_) & 1) * BUF + n_ * 1024);
+  PBSA_STAGE(0)
+  if (NR > 1) PBSA_STAGE(1)
+
+  for (int idx = threadIdx.x; idx < 4 * D; idx += 64 * NM) {
+    const int r = idx / D, x = idx % D;
+    qs[idx] = i0 + r < a.nqb ? a.Qc[((size_t)h * a.nqb + i0 + r) * D + x] : 0.0f;
   }
-  const int kk = min(a.k, nvis);
-  int32_t* out = a.sel + ((size_t)h * a.nqb + i) * a.k;
-  if (kk > 0) {
-    // T = kk-th largest key, found bit by bit: the largest T with #{key >= T} >= kk
-    uint32_t T = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = T | (1u << bit);
-      int cnt = 0;
+  __syncthreads();
+
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  const int jcol = 64 * wave + lane;
+  const int sw = (jcol >> 1) & 7;
+#pragma unroll 1
+  for (int r0 = 0; r0 < NR; ++r0) {
+    if (r0 + 1 < NR) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const unsigned char* kb = smem + (r0 & 1) * BUF + jcol * (kDX * 4);
 #pragma unroll
-      for (int m = 0; m < NM; ++m) cnt += __popcll(__ballot(key[m] >= cand));
-      if (cnt >= kk) T = cand;
+    for (int c = 0; c < kDX / 4; ++c) {
+      const float4 k4 = *reinterpret_cast<const float4*>(kb + ((c ^ sw) << 4));
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float4 q4 = *reinterpret_cast<const float4*>(qs + r * D + r0 * kDX + 4 * c);
+        acc[r] = __builtin_fmaf(q4.x, k4.x, acc[r]);
+        acc[r] = __builtin_fmaf(q4.y, k4.y, acc[r]);
+        acc[r] = __builtin_fmaf(q4.z, k4.z, acc[r]);
+        acc[r] = __builtin_fmaf(q4.w, k4.w, acc[r]);
+      }
+      if (c % 2 == 1) __builtin_amdgcn_sched_barrier(0);   // keep the operand reads close to their use
     }
-    int n_gt = 0;
+    if (r0 + 2 < NR) PBSA_STAGE(r0 + 2)
+  }
+#undef PBSA_STAGE
+
 #pragma unroll
-    for (int m = 0; m < NM; ++m) n_gt += __popcll(__ballot(key[m] > T));
-    const int need_eq = kk - n_gt;              // ties at T taken in ascending block order
-    int seen_eq = 0, pos = 0;
+  for (int r = 0; r < 4; ++r) {
+    const float z = acc[r] * a.scale;
+    zs[r * NCP + jcol] = z;
+    if (a.Zl && i0 + r < a.nqb && jcol < a.n_loc) a.Zl[((size_t)h * a.nqb + i0 + r) * a.n_loc + jcol] = z;
+  }
+  __syncthreads();
+
+  for (int r = wave; r < 4; r += NM) {
+    const int i = i0 + r;
+    if (i >= a.nqb) break;
+    // order-preserving integer keys; invisible columns get 0, below every real value
+    const int nvis = a.causal ? a.n_loc - a.nqb + i + 1 : a.n_loc;
+    uint32_t key[NM];
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      const bool eq = key[m] == T;
-      const uint64_t eq_mask = __ballot(eq);
-      const bool take = key[m] > T || (eq && seen_eq + lanes_below(eq_mask) < need_eq);
-      const uint64_t take_mask = __ballot(take);
-      if (take) out[pos + lanes_below(take_mask)] = lane + 64 * m;
-      seen_eq += __popcll(eq_mask);
-      pos += __popcll(take_mask);
+      float z = zs[r * NCP + lane + 64 * m];
+      if (z == 0.0f) z = 0.0f;                    // -0 and +0 compare equal: give them one key
+      const uint32_t b = __float_as_uint(z);
+      const uint32_t ordered = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+      key[m] = (lane + 64 * m < nvis) ? ordered : 0u;
     }
+    const int kk = min(a.k, nvis);
+    int32_t* out = a.sel + ((size_t)h * a.nqb + i) * a.k;
+    if (kk > 0) {
+      // T = kk-th largest key, found bit by bit: the largest T with #{key >= T} >= kk
+      uint32_t T = 0;
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) cnt += __popcll(__ballot(key[m] >= cand));
+        if (cnt >= kk) T = cand;
+      }
+      int n_gt = 0;
+#pragma unroll
+      for (int m = 0; m < NM; ++m) n_gt += __popcll(__ballot(key[m] > T));
+      const int need_eq = kk - n_gt;              // ties at T taken in ascending block order
+      int seen_eq = 0, pos = 0;
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        const bool eq = key[m] == T;
+        const uint64_t eq_mask = __ballot(eq);
+        const bool take = key[m] > T || (eq && seen_eq + lanes_below(eq_mask) < need_eq);
+        const uint64_t take_mask = __ballot(take);
+        if (take) out[pos + lanes_below(take_mask)] = lane + 64 * m;
+        seen_eq += __popcll(eq_mask);
+        pos += __popcll(take_mask);
+      }
+    }
+    for (int j = kk + lane; j < a.k; j += 64) out[j] = -1;
   }
-  for (int j = kk + lane; j < a.k; j += 64) out[j] = -1;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -315,6 +382,7 @@ __global__ void __launch_bounds__(kThreads) score_rows_kernel(ScoreArgs a) {
   __syncthreads();
   if (lane == 0) {
     float s = 0.0f;
+#pragma unroll 16
     for (int j = 0; j < nU; ++j) s = s + er[j];
     sum_s[wave] = s;
   }
@@ -335,9 +403,8 @@ __global__ void __launch_bounds__(kThreads) score_rows_kernel(ScoreArgs a) {
 template <int D, int NML>
 __global__ void __launch_bounds__(kThreads) score_rows_z_kernel(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int NPAD = 64 + 2;
-  float* kct = reinterpret_cast<float*>(smem);                                  // [kXC][NPAD]
-  float* qs = kct + kXC * NPAD;                                                 // [4][D]
+  float* kct = reinterpret_cast<float*>(smem);                                  // [64][D + 4]
+  float* qs = kct + 64 * (D + 4);                                               // [4][D]
   const float** cols = reinterpret_cast<const float**>(qs + 4 * D);            // [64]
   float* erow = reinterpret_cast<float*>(cols + 64);                            // [4][64 + NML*64]
   __shared__ float sum_s[4];
@@ -353,9 +420,29 @@ __global__ void __launch_bounds__(kThreads) score_rows_z_kernel(ScoreArgs a) {
   const float* zrow = a.Zl + ((size_t)h * a.nqb + min(i, a.nqb - 1)) * a.n_loc;
 #pragma unroll
   for (int m = 0; m < NML; ++m) zl[m] = lane + 64 * m < a.n_loc ? zrow[lane + 64 * m] : 0.0f;
-  float accp[1];
-  coarse_dots<D, 1>(cols, nP, qs + wave * D, kct, accp);
-  const float zp = accp[0] * a.scale;
+  // the occupied slots' pooled keys, whole, [nP][D + 4] (the pitch spreads the 16-byte reads of 16
+  // lanes over all banks); then lane c runs the chain of column c
+  __syncthreads();                                       // cols[] and qs are visible
+  constexpr int KP = D + 4;
+  for (int idx = threadIdx.x; idx < nP * (D / 4); idx += kThreads) {
+    const int u = idx / (D / 4), x4 = idx % (D / 4);
+    *reinterpret_cast<float4*>(kct + u * KP + 4 * x4) = reinterpret_cast<const float4*>(cols[u])[x4];
+  }
+  __syncthreads();
+  float accp = 0.0f;
+  if (lane < nP) {
+    const float4* q4p = reinterpret_cast<const float4*>(qs + wave * D);
+    const float4* k4p = reinterpret_cast<const float4*>(kct + lane * KP);
+#pragma unroll 8
+    for (int x4 = 0; x4 < D / 4; ++x4) {
+      const float4 q = q4p[x4], k = k4p[x4];
+      accp = __builtin_fmaf(q.x, k.x, accp);
+      accp = __builtin_fmaf(q.y, k.y, accp);
+      accp = __builtin_fmaf(q.z, k.z, accp);
+      accp = __builtin_fmaf(q.w, k.w, accp);
+    }
+  }
+  const float zp = accp * a.scale;
 
   float mx = lane < nP ? zp : -INFINITY;
 #pragma unroll
@@ -374,6 +461,7 @@ __global__ void __launch_bounds__(kThreads) score_rows_z_kernel(ScoreArgs a) {
   __syncthreads();
   if (lane == 0) {
     float s = 0.0f;
+#pragma unroll 16
     for (int j = 0; j < nU; ++j) s = s + er[j];
     sum_s[wave] = s;
   }
@@ -443,9 +531,9 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   const uint64_t occ_mask = __ballot(occ);
   const int nP = __popcll(occ_mask), u_pos = lanes_below(occ_mask);
   // Column means (Eq. 8) of the columns that can be candidates: the occupied slots and the evicted
-  // blocks, i.e. the first nP + n_evict columns of U.  A column is contiguous in A^T: its rows are
-  // fetched 64 at a time and added in ascending order.
+  // blocks, i.e. the first nP + n_evict columns of U.
   const int n_need = nP + a.n_evict;
+  // A column is contiguous in A^T: its rows are fetched 64 at a time and added in ascending order.
   for (int j = threadIdx.x; j < n_need; j += kThreads) {
     float acc = 0.0f;
     const float4* col = reinterpret_cast<const float4*>(a.A + ((size_t)h * a.nU_max + j) * a.nqb_pad);
@@ -597,6 +685,8 @@ struct FoldArgs {
   const int32_t* promo_slot;
 };
 
+constexpr int kFoldBatch = 80;
+
 __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   __shared__ int fsrc_s[kMaxCand], flen_s[kMaxCand], promo_s[PBSA_MAX_C];
   const int h = blockIdx.y;
@@ -620,10 +710,10 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   const size_t rowoff = (size_t)t * a.d + xc;
   const bf16_t* Ph = P + (size_t)h * C1 * blk + rowoff;
   const bf16_t* Lh = L + (size_t)h * a.n_loc_cap * blk + rowoff;
-  // promoted rows are independent of the fold: fetch the first 16 before it starts
-  uint32_t pv[16];
+  // promoted rows are independent of the fold: fetch them all before it starts
+  uint32_t pv[PBSA_MAX_C];
 #pragma unroll
-  for (int u = 0; u < 16; ++u) {
+  for (int u = 0; u < PBSA_MAX_C; ++u) {
     const int ps = u < C ? promo_s[u] : -1;
     pv[u] = ps >= 0 ? *reinterpret_cast<const uint32_t*>(Lh + (size_t)ps * blk) : 0u;
   }
@@ -631,18 +721,18 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
     float* ssum = a.S_sum + ((size_t)h * 2 + kv) * blk + rowoff;
     float2 acc = *reinterpret_cast<float2*>(ssum);
     const int cnt = a.S_cnt[(size_t)h * a.B + t];     // already the new count (retain_kernel)
-    // rows are loaded 32 at a time (row t exists in every block, valid or not) and added in
+    // rows are loaded kFoldBatch at a time (row t exists in every block, valid or not) and added in
     // candidate order, the add predicated on t < len
-    for (int f0 = 0; f0 < nf; f0 += 32) {
-      uint32_t v[32];
+    for (int f0 = 0; f0 < nf; f0 += kFoldBatch) {
+      uint32_t v[kFoldBatch];
 #pragma unroll
-      for (int u = 0; u < 32; ++u) {
+      for (int u = 0; u < kFoldBatch; ++u) {
         const int src = fsrc_s[min(f0 + u, nf - 1)];
         const bf16_t* blkp = src < C ? Ph + (size_t)src * blk : Lh + (size_t)(src - C) * blk;
         v[u] = *reinterpret_cast<const uint32_t*>(blkp);
       }
 #pragma unroll
-      for (int u = 0; u < 32; ++u) {
+      for (int u = 0; u < kFoldBatch; ++u) {
         if (f0 + u < nf && t < flen_s[f0 + u]) {
           acc.x = acc.x + bf_lo(v[u]);
           acc.y = acc.y + bf_hi(v[u]);
@@ -658,22 +748,9 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   }
   // promoted rows: stores after the fold's loads (a refilled slot was read above by this thread)
 #pragma unroll
-  for (int u = 0; u < 16; ++u) {
+  for (int u = 0; u < PBSA_MAX_C; ++u) {
     const int ps = u < C ? promo_s[u] : -1;
     if (ps >= 0) *reinterpret_cast<uint32_t*>(P + ((size_t)h * C1 + u) * blk + rowoff) = pv[u];
-  }
-  for (int c0 = 16; c0 < C; c0 += 16) {
-    uint32_t w[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int ps = c0 + u < C ? promo_s[c0 + u] : -1;
-      w[u] = ps >= 0 ? *reinterpret_cast<const uint32_t*>(Lh + (size_t)ps * blk) : 0u;
-    }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int ps = c0 + u < C ? promo_s[c0 + u] : -1;
-      if (ps >= 0) *reinterpret_cast<uint32_t*>(P + ((size_t)h * C1 + c0 + u) * blk + rowoff) = w[u];
-    }
   }
 }
 
@@ -714,7 +791,7 @@ hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32
   if (n_blocks == 0) return hipSuccess;
   PoolArgs a{};
   a.mode = 0; a.n_jobs = n_blocks; a.B = p.B; a.X = X; a.len = len; a.out = out;
-  const int jpw = kThreads / (p.d / 8);
+  const int jpw = kThreads / (p.d / 2);
   const dim3 grid((n_blocks + jpw - 1) / jpw);
   if (p.d == 128) hipLaunchKernelGGL(pool_kernel<128>, grid, dim3(kThreads), 0, stream, a);
   else hipLaunchKernelGGL(pool_kernel<64>, grid, dim3(kThreads), 0, stream, a);
@@ -723,10 +800,10 @@ hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32
 
 template <int D, int NM>
 static hipError_t launch_select_t(const SelectArgs& a, hipStream_t stream) {
-  const size_t lds = coarse_lds_bytes<NM>(D, false);
+  const size_t lds = (size_t)2 * NM * 64 * kDX * 4 + (size_t)4 * D * 4 + (size_t)4 * NM * 64 * 4;
   hipError_t e = allow_lds(select_kernel<D, NM>, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((select_kernel<D, NM>), dim3((a.nqb + 3) / 4, a.H), dim3(kThreads), lds, stream, a);
+  hipLaunchKernelGGL((select_kernel<D, NM>), dim3((a.nqb + 3) / 4, a.H), dim3(64 * NM), lds, stream, a);
   return hipGetLastError();
 }
 
@@ -739,7 +816,7 @@ hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl
   pa.n_jobs = p.H * (pa.n_kjobs_per_head + p.nqb);
   pa.q_stride_h = p.q_stride_h; pa.q_stride_t = p.q_stride_t;
   pa.X = Kl; pa.Q = Q; pa.len = l_len; pa.l_map = l_map; pa.out = Kc_l; pa.Qc = Qc;
-  const int jpw = kThreads / (p.d / 8);
+  const int jpw = kThreads / (p.d / 2);
   const dim3 grid((pa.n_jobs + jpw - 1) / jpw);
   if (p.d == 128) hipLaunchKernelGGL(pool_kernel<128>, grid, dim3(kThreads), 0, stream, pa);
   else hipLaunchKernelGGL(pool_kernel<64>, grid, dim3(kThreads), 0, stream, pa);
@@ -770,7 +847,7 @@ static hipError_t launch_rows_t(const ScoreArgs& a, hipStream_t stream) {
 
 template <int D, int NML>
 static hipError_t launch_rows_z_t(const ScoreArgs& a, hipStream_t stream) {
-  const size_t lds = (size_t)kXC * 66 * 4 + (size_t)4 * D * 4 + 64 * 8 + (size_t)4 * (64 + NML * 64) * 4;
+  const size_t lds = (size_t)64 * (D + 4) * 4 + (size_t)4 * D * 4 + 64 * 8 + (size_t)4 * (64 + NML * 64) * 4;
   hipError_t e = allow_lds(score_rows_z_kernel<D, NML>, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((score_rows_z_kernel<D, NML>), dim3((a.nqb + 3) / 4, a.H), dim3(kThreads), lds, stream, a);
