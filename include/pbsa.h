@@ -122,8 +122,9 @@ int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, cons
 /* PBSA fine stage (Eq. 3-5): for each query token one softmax, scaled by p->scale, over every
  * valid token of every non-empty persistent slot 0..C (summary included) and every valid token of
  * the local blocks listed in its query block's row of `sel`; O = P V.  bf16 MFMA with fp32
- * accumulation and fp32 online softmax; O is rounded to bf16 (nearest even).  `lse` (optional,
- * [H][Nq] fp32) receives the natural-log normaliser.  A row that sees no key gets O = 0,
+ * accumulation and fp32 online softmax; the probabilities are rounded to bf16 for the second product and
+ * the normaliser is their sum after rounding; O is rounded to bf16 (nearest even).  `lse` (optional,
+ * [H][Nq] fp32) receives the natural log of that normaliser (within 4e-3 of the exact one).  A row that sees no key gets O = 0,
  * lse = -inf.  Entries of sel must be -1 or in [0, n_loc).  ws may be NULL. */
 int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
                        const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,

@@ -1,20 +1,18 @@
 // PBSA fine stage (Eq. 3-5) for gfx950: block-sparse flash attention on bf16 MFMA.
 //
-// One workgroup = 8 waves = 128 consecutive query tokens of one head (one query block when B = 128,
-// two when B = 64).  The workgroup walks a tile list: first every non-empty persistent slot (the
-// dense part of the mask, visible to all rows), then the union, in ascending order, of the local
-// blocks selected by its query blocks; a wave skips a tile its own query block did not select.
-// K/V tiles of 64 keys go from global memory straight into LDS (global_load_lds, no register
-// round trip) through rings three tiles deep, so an L2 miss has three slots to arrive.
+// One workgroup = 2 waves = 128 consecutive query tokens of one head (one query block when B = 128,
+// two when B = 64).  A wave owns 64 query rows as two row groups of 32: group g of wave w holds rows
+// 64 g + 32 w .. + 31 of the workgroup, so with B = 64 group g of BOTH waves belongs to query block g
+// and the two waves always have the same amount of work.  Two workgroups share a CU, one wave per
+// SIMD, so a wave has the whole 512-entry register file of its SIMD.
 //
-// The 8 waves form two sets of 4 (one wave of each set per SIMD).  Both sets own the same 128 query
-// rows (32 per wave) but alternate tiles: set 0 takes the even tiles, set 1 the odd ones, each with
-// its own running max / sum / output accumulators, merged at the end.  Time is cut into slots
-// separated by workgroup barriers; in slot s the set whose turn it is runs its matrix phase
-// (O^T += V^T P^T of its previous tile, then S^T = K Q^T of tile s) while the other set runs the
-// softmax of the tile it multiplied one slot earlier.  The two waves sharing a SIMD are thereby
-// always in opposite phases, so the MFMA pipe and the VALU (exp2, max, sums, conversions) overlap
-// instead of queueing behind each other.
+// The workgroup walks a tile list of 64-key tiles: every non-empty persistent slot (the dense part of
+// the mask, visible to all rows) and the union of the local blocks selected by its query blocks.  The
+// list is sorted by who attends a tile: first the full tiles both row groups attend, then those only
+// group 0 attends, then those only group 1 attends, last the ragged tiles (fewer than 64 valid keys).
+// The order of keys does not matter to an online softmax, and within a class every step runs the same
+// straight-line code.  K/V tiles go from global memory straight into LDS (global_load_lds, no
+// register round trip), two tiles per operand.
 //
 // MFMA arrangement (v_mfma_f32_32x32x16_bf16, wave64):
 //   S^T = K Q^T   A = K tile rows (32 keys x 16 dims), B = Q^T (16 dims x 32 query rows).
@@ -23,7 +21,18 @@
 //   O^T = V^T P^T A = V^T (32 dims x 16 keys), B = P^T (16 keys x 32 query rows) taken straight
 //                 from the S^T accumulators: the contraction index (key) is enumerated in the order
 //                 the accumulator holds it, and V^T is read from LDS with the same enumeration.
-// Softmax is online, fp32, base 2 (the scale and log2 e are folded into one fma).
+//   A K or V^T fragment read from LDS feeds the MFMAs of both row groups, which halves the LDS
+//   traffic per flop: at one fragment per MFMA the LDS (128 bytes per clock per CU) cannot keep four
+//   matrix pipes busy.
+//
+// Software pipeline.  The unit is a sub-tile of 32 keys.  In step u a wave runs, as one straight
+// stretch of code cut into slots (one MFMA plus a slice of vector work each), the softmax of
+// sub-tile u (exp2, max, conversions; S^T(u) -> P^T(u)) together with the MFMAs that do not depend
+// on it: O^T += V^T P^T of sub-tile u-1 and S^T = K Q^T of sub-tile u+1.  S^T and P^T are double
+// buffered.  Each class of the list is one pipelined run with its own template instance (which row
+// groups take part, whether keys must be masked); the pipeline drains between classes.  Softmax is online, fp32, base 2 (scale and log2 e folded into one fma); row sums are
+// taken over the bf16-rounded probabilities (two per v_dot2c_f32_bf16), the same numbers the second
+// product uses.
 #include "pbsa_internal.h"
 
 namespace pbsa {
@@ -31,13 +40,20 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kThreads = 512;
+constexpr int kThreads = 128;
 constexpr int kRowsPerWg = 128;
 constexpr int kTile = 64;                 // keys per staged tile
 constexpr int kMaxTiles = 2 * (PBSA_MAX_C + 1) + 2 * PBSA_MAX_K;   // persistent + local 64-key tiles
-constexpr float kNegBig = -1.0e30f;
+constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
+constexpr float kInitMax = -1.0e29f;       // running max of a row that has seen no key: above kMasked, below any score
+// The softmax reference of a row follows its running max lazily: it moves (and the output
+// accumulators are rescaled) only when a new score exceeds it by more than kSlack in base-2 exponent
+// units, so probabilities stay below 2^kSlack -- harmless in bf16 / fp32 -- and rescales are rare.
+constexpr float kSlack = 8.0f;
 
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {   // set bits of `mask` below this lane
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -69,6 +85,8 @@ struct AttnArgs {
 //  V (ds_read_b64_tr_b16: within 16 lanes, lane s supplies the address of row s/4, columns
 //    4(s%4)..+3, and lane j receives column j of those 4 rows): the 4 rows x 64 bytes a half wave
 //    reads must cover all 64 banks: D = 128: f(r) = 4 (r mod 4); D = 64: f(r) = 4 ((r/2) mod 2).
+// Both f are unchanged by adding a multiple of 8 to the row, so a lane's address within a tile is one
+// per-lane base plus compile-time offsets for the sub-tile, the k-step and the row pair.
 template <int D>
 __device__ __forceinline__ int k_swz(int row) { return row & (D / 8 - 1); }
 template <int D>
@@ -76,17 +94,14 @@ __device__ __forceinline__ int v_swz(int row) {
   if constexpr (D == 128) return (row & 3) << 2;
   else return ((row >> 1) & 1) << 2;
 }
-template <int D>
-__device__ __forceinline__ int v_byte_offset(int row, int chunk) {
-  return row * (D * 2) + ((chunk ^ v_swz<D>(row)) << 4);
-}
 
 // One wave-wide global -> LDS load of 16 bytes per lane: LDS bytes [lds_off, lds_off + 1024) receive
 // lane i's 16 bytes at lds_off + 16 i.  Completion is tracked by the issuing wave's vmcnt.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+// The global address is a scalar base plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
-               : "s"(lds_off), "v"(gptr)
+               : "s"(lds_off), "v"(lane_off), "s"(base)
                : "memory");
 }
 
@@ -94,133 +109,236 @@ template <int D>
 struct Geo {
   static constexpr int KS = D / 16;                 // MFMA k-steps of Q K^T
   static constexpr int DT = D / 32;                 // 32-wide output tiles of O^T
+  static constexpr int ROW = D * 2;                 // bytes of a tile row
   static constexpr int TILE_BYTES = kTile * D * 2;  // one K or V tile in LDS
-  static constexpr int NI = D / 64;                 // global_load_lds instructions per wave per tile
+  static constexpr int SUB_BYTES = 32 * D * 2;      // a 32-key sub-tile
 };
 
-// S^T (two 32-key sub-tiles) = K tile x Q^T.
-template <int D>
-__device__ __forceinline__ void qk_tile(const unsigned char* kbuf, const bf16x8 (&qf)[Geo<D>::KS], int qn, int half,
-                                        f32x16& s0, f32x16& s1) {
-  const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  // chunk (2 ks + half) ^ f(row) = (half ^ f(row)) ^ 2 ks: one per-lane base, one xor per k-step; rows qn
-  // and 32 + qn share the permutation
-  const int base = qn * (D * 2) + ((half ^ k_swz<D>(qn)) << 4);
-#pragma unroll
-  for (int ks = 0; ks < Geo<D>::KS; ++ks) {
-    const unsigned char* r0 = kbuf + (base ^ (ks << 5));
-    const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(r0);
-    const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(r0 + 32 * (D * 2));
-    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], ks == 0 ? zero : s0, 0, 0, 0);
-    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], ks == 0 ? zero : s1, 0, 0, 0);
-  }
-  // operand reads run 4 k-steps (8 MFMAs) ahead of the MFMAs: an LDS read takes several MFMA times
-  constexpr int AHEAD = Geo<D>::KS < 4 ? Geo<D>::KS : 4;
-  __builtin_amdgcn_sched_group_barrier(0x100, 2 * AHEAD, 0);
-#pragma unroll
-  for (int ks = 0; ks < Geo<D>::KS - AHEAD; ++ks) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x008, 2 * AHEAD, 0);
-}
+typedef __attribute__((address_space(3))) const bf16x8* lds_b128_t;
+typedef __attribute__((address_space(3))) bf16x4* lds_tr_t;
 
-// O^T += V^T P^T: 4 k-steps of 16 keys; V^T fragments by transposing LDS reads.  The fragment of
-// k-step j holds keys 16 j + 4 half + {0..3} (lo) and + 8 (hi).
-template <int D>
-__device__ __forceinline__ void pv_tile(const unsigned char* vbuf, const bf16x8 (&pf)[4], f32x16 (&o)[Geo<D>::DT],
-                                        int v_row0, int v_sub, int v_lo) {
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int r0 = 16 * j + v_row0;            // this lane's address rows: r0 and r0 + 8
-#pragma unroll
-    for (int dt = 0; dt < Geo<D>::DT; ++dt) {
-      const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-          (bf16x4 __attribute__((address_space(3)))*)(vbuf + v_byte_offset<D>(r0, 4 * dt + v_sub) + v_lo));
-      const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-          (bf16x4 __attribute__((address_space(3)))*)(vbuf + v_byte_offset<D>(r0 + 8, 4 * dt + v_sub) + v_lo));
-      const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[j], o[dt], 0, 0, 0);
-    }
-  }
-  // operand reads (two per MFMA) run 8 MFMAs ahead: an LDS read takes several MFMA times
-  constexpr int N = 4 * Geo<D>::DT, AHEAD = N < 8 ? N : 8;
-  __builtin_amdgcn_sched_group_barrier(0x100, 2 * AHEAD, 0);
-#pragma unroll
-  for (int i = 0; i < N - AHEAD; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x008, AHEAD, 0);
+__device__ __forceinline__ bf16x8 lds_read_k(uint32_t addr) { return *(lds_b128_t)(uintptr_t)addr; }
+// V^T fragment of 16 keys: two transposing reads, rows r and r + 8 of the 16
+template <int ROW>
+__device__ __forceinline__ bf16x8 lds_read_vt(uint32_t addr) {
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_tr_t)(uintptr_t)addr);
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_tr_t)(uintptr_t)(addr + 8 * ROW));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& w) { return __builtin_bit_cast(bf16x8, w); }
 
-// Online softmax of one tile: S^T accumulators -> bf16 P^T operands; updates the running max and
-// the in-lane partial row sum, rescaling the output accumulators only when some row's max moved.
-// Accumulator element v of sub-tile st is key 32 st + 8 (v/4) + 4 half + v%4.
+// O^T accumulators live in the accumulator half of the register file for the whole kernel: the
+// second product is issued as an instruction with an accumulator-register destination, so the
+// architectural half is left to S^T, P^T, the operand fragments and the softmax.  The compiler does
+// not see a matrix instruction here: code that reads or rewrites these accumulators with vector
+// instructions waits out the matrix pipeline itself (acc_settle).
+__device__ __forceinline__ void pv_mfma(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// The wait is tied to the accumulators it protects, so their reads and writes cannot be moved across it.
 template <int DT>
-__device__ __forceinline__ void softmax_tile(f32x16& s0, f32x16& s1, int tlen, int half, float c2, float& m_run,
-                                             float& l_run, f32x16 (&o)[DT], bf16x8 (&pf)[4]) {
-  if (tlen < kTile) {
+__device__ __forceinline__ void acc_settle(f32x16 (&o)[DT]) {
+  static_assert(DT == 2 || DT == 4, "two or four output tiles per row group");
+  if constexpr (DT == 4)
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
+  else
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o[0]), "+a"(o[1]));
+}
+
+// max over the 16 keys a lane holds of one row, then with the other half-wave's 16
+__device__ __forceinline__ float row_max(const f32x16& s) {
+  float t = fmaxf(fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (8 * (v / 4) + 4 * half + (v % 4) >= tlen) s0[v] = kNegBig;
-      if (32 + 8 * (v / 4) + 4 * half + (v % 4) >= tlen) s1[v] = kNegBig;
+  for (int v = 3; v < 15; v += 2) t = fmaxf(fmaxf(t, s[v]), s[v + 1]);
+  t = fmaxf(t, s[15]);
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// probabilities of two neighbouring keys: exp2, round to bf16, add to the row sum
+__device__ __forceinline__ uint32_t prob_pair(float s0, float s1, float c2, float mc, float& psum) {
+  bf16x2 pk;
+  pk[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s0, c2, mc));
+  pk[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s1, c2, mc));
+  bf16x2 one;
+  one[0] = (__bf16)1.0f;
+  one[1] = (__bf16)1.0f;
+  psum = __builtin_amdgcn_fdot2_f32_bf16(pk, one, psum, false);
+  return __builtin_bit_cast(uint32_t, pk);
+}
+
+template <int DT>
+__device__ __forceinline__ void rescale(f32x16 (&o)[2][DT], const float (&alpha)[2], int gm) {
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    if (((gm >> g) & 1) && __any(alpha[g] != 1.0f)) {
+      acc_settle<DT>(o[g]);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[g][dt][v] *= alpha[g];
+      acc_settle<DT>(o[g]);
     }
-  }
-  float tmax = fmaxf(s0[0], s1[0]);
-#pragma unroll
-  for (int v = 1; v < 16; ++v) tmax = fmaxf(fmaxf(tmax, s0[v]), s1[v]);
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-  const float m_new = fmaxf(m_run, tmax);
-  const float mc = -m_new * c2;
-  float psum = 0.0f;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    s0[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[v], c2, mc));
-    s1[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[v], c2, mc));
-    psum += s0[v] + s1[v];
-  }
-  if (__any(m_new != m_run)) {
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-    l_run *= alpha;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
-    m_run = m_new;
-  }
-  l_run += psum;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    pf[0][e] = (__bf16)s0[e];
-    pf[1][e] = (__bf16)s0[8 + e];
-    pf[2][e] = (__bf16)s1[e];
-    pf[3][e] = (__bf16)s1[8 + e];
   }
 }
 
-// (the kernel marks dead accumulators by assigning an uninitialised value on purpose)
+// ------------------------------------------------------------------------------------------------
+// One pipeline step: up to three parts on three different sub-tiles, for the row groups GM.
+//   SM  softmax of the current sub-tile: s_cur -> p_cur (RAGGED: keys at or beyond lim[g] are masked)
+//   PV  O^T += V^T P^T of the previous sub-tile (p_prev, V fragments at vaddr + V_OFF)
+//   QK  S^T = K Q^T of the next sub-tile (s_next, K fragments at kaddr + K_OFF)
+// The step is a sequence of MFMA pairs, PV and QK alternating when both are present; the MFMAs of a
+// pair (one per row group) share one LDS fragment, read AHEAD pairs earlier.  After every MFMA comes
+// a slice of the softmax, so the matrix pipe works while the VALU computes.  Nothing is allowed to
+// move across slot boundaries.
+// ------------------------------------------------------------------------------------------------
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED>
+struct StepCtx {
+  static constexpr int NG = (GM & 1) + ((GM >> 1) & 1);
+  static constexpr int G0 = (GM & 1) ? 0 : 1;       // first row group taking part
+  static constexpr int NP = (PV ? Geo<D>::KS : 0) + (QK ? Geo<D>::KS : 0);   // MFMA pairs (PV has 2 DT = KS)
+  static constexpr int NC = NP * NG;                // slots
+  static constexpr int PRE = !SM ? 0 : (NC >= 16 * NG) ? 2 * NG : NG;        // slots that compute the row maxima
+  static constexpr int AHEAD = NG == 2 ? 4 : 6;     // pairs between an operand read and its MFMAs
+  const uint32_t (&vaddr)[Geo<D>::DT];
+  const uint32_t (&kaddr)[Geo<D>::KS];
+  float c2;
+  const bf16x8 (&qf)[2][Geo<D>::KS];
+  f32x16 (&o)[2][Geo<D>::DT];
+  f32x16 (&s_cur)[2];
+  f32x16 (&s_next)[2];
+  u32x4 (&p_cur)[2][2];
+  const u32x4 (&p_prev)[2][2];
+  float (&m_run)[2];
+  float (&l_run)[2];
+  float (&alpha)[2];
+  const int (&lim)[2];           // RAGGED: valid keys of the current sub-tile minus 4 * half, per row group
+  bf16x8 frag[2 * Geo<D>::KS];   // operand fragment of each MFMA pair
+  float mc[2], psum[2];
+};
+
+// pair q: with both products, even q is PV pair q/2 and odd q is QK pair q/2
+template <bool PV, bool QK>
+constexpr bool pair_is_pv(int q) { return PV && (!QK || q % 2 == 0); }
+template <bool PV, bool QK>
+constexpr int pair_index(int q) { return (PV && QK) ? q / 2 : q; }
+
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
+__device__ __forceinline__ void load_frag(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
+  if constexpr (Q < StepCtx<D, GM, PV, QK, SM, RAGGED>::NP) {
+    constexpr int i = pair_index<PV, QK>(Q);
+    if constexpr (pair_is_pv<PV, QK>(Q)) {
+      constexpr int j = i / Geo<D>::DT, dt = i % Geo<D>::DT;
+      c.frag[Q] = lds_read_vt<Geo<D>::ROW>(c.vaddr[dt] + V_OFF + 16 * j * Geo<D>::ROW);
+    } else {
+      c.frag[Q] = lds_read_k(c.kaddr[i] + K_OFF);
+    }
+  }
+}
+
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int Q, int GRP>
+__device__ __forceinline__ void mfma_slot(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
+  constexpr int i = pair_index<PV, QK>(Q);
+  if constexpr (pair_is_pv<PV, QK>(Q)) {
+    constexpr int j = i / Geo<D>::DT, dt = i % Geo<D>::DT;
+    pv_mfma(c.o[GRP][dt], c.frag[Q], as_bf16x8(c.p_prev[GRP][j]));
+  } else {
+    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    c.s_next[GRP] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.frag[Q], c.qf[GRP][i], i == 0 ? zero : c.s_next[GRP], 0, 0, 0);
+  }
+}
+
+// Slice C of the softmax of s_cur: first the row maximum and the reference of each row group, then
+// the 8 probability pairs per group spread evenly over the remaining slices.
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int C>
+__device__ __forceinline__ void valu_slot(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
+  using S = StepCtx<D, GM, PV, QK, SM, RAGGED>;
+  if constexpr (!SM) {
+  } else if constexpr (C < S::PRE) {
+    constexpr int per = S::PRE / S::NG;
+    if constexpr (C % per == per - 1) {
+      constexpr int grp = (C / per == 0) ? S::G0 : 1;
+      if constexpr (RAGGED) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)       // accumulator element v is key 8 (v/4) + 4 half + v%4
+          if (8 * (v / 4) + (v % 4) >= c.lim[grp]) c.s_cur[grp][v] = kMasked;
+      }
+      const float tmax = row_max(c.s_cur[grp]);
+      const float m_new = tmax * c.c2 > c.m_run[grp] * c.c2 + kSlack ? tmax : c.m_run[grp];
+      c.mc[grp] = -m_new * c.c2;
+      c.alpha[grp] = __builtin_amdgcn_exp2f((c.m_run[grp] - m_new) * c.c2);
+      c.m_run[grp] = m_new;
+      c.psum[grp] = 0.0f;
+    }
+  } else {
+    constexpr int lo = (C - S::PRE) * (8 * S::NG) / (S::NC - S::PRE), hi = (C + 1 - S::PRE) * (8 * S::NG) / (S::NC - S::PRE);
+#pragma unroll
+    for (int n = lo; n < hi; ++n) {
+      const int grp = (n / 8 == 0) ? S::G0 : 1, v = 2 * (n % 8);
+      const uint32_t w = prob_pair(c.s_cur[grp][v], c.s_cur[grp][v + 1], c.c2, c.mc[grp], c.psum[grp]);
+      // a use that cannot move: keeps this slice's work in this slot (its results are needed only by the next step)
+      asm volatile("" ::"v"(w), "v"(c.psum[grp]));
+      c.p_cur[grp][v / 8][(v % 8) / 2] = w;
+    }
+    if constexpr (C == S::NC - 1) {
+      if constexpr (GM & 1) c.l_run[0] = c.l_run[0] * c.alpha[0] + c.psum[0];
+      if constexpr (GM & 2) c.l_run[1] = c.l_run[1] * c.alpha[1] + c.psum[1];
+    }
+  }
+}
+
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int I>
+__device__ __forceinline__ void run_slots(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
+  using S = StepCtx<D, GM, PV, QK, SM, RAGGED>;
+  if constexpr (I < S::NC) {
+    constexpr int Q = I / S::NG, k = I % S::NG;
+    if constexpr (k == 0) load_frag<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + S::AHEAD>(c);
+    mfma_slot<D, GM, PV, QK, SM, RAGGED, Q, (k == 0 ? S::G0 : 1)>(c);
+    valu_slot<D, GM, PV, QK, SM, RAGGED, I>(c);
+    __builtin_amdgcn_sched_barrier(0);
+    run_slots<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, I + 1>(c);
+  }
+}
+
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
+__device__ __forceinline__ void preload_frags(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
+  if constexpr (Q < StepCtx<D, GM, PV, QK, SM, RAGGED>::AHEAD) {
+    load_frag<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q>(c);
+    preload_frags<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + 1>(c);
+  }
+}
+
+// K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF>
+__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS], float c2,
+                                     const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
+                                     f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], const u32x4 (&p_prev)[2][2],
+                                     float (&m_run)[2], float (&l_run)[2], float (&alpha)[2], const int (&lim)[2]) {
+  static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
+  StepCtx<D, GM, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, qf, o, s_cur, s_next, p_cur, p_prev, m_run, l_run, alpha, lim,
+                                       {}, {0, 0}, {0, 0}};
+  preload_frags<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
+  __builtin_amdgcn_sched_barrier(0);
+  run_slots<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
+}
+
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
 template <int D, int B>
-__global__ void __launch_bounds__(kThreads) attention_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) attention_kernel(AttnArgs a) {
   constexpr int G = kRowsPerWg / B;        // query blocks per workgroup
   constexpr int SUB = B / kTile;           // 64-key tiles per block
-  constexpr int KS = Geo<D>::KS, DT = Geo<D>::DT, TILE = Geo<D>::TILE_BYTES, NI = Geo<D>::NI;
-  constexpr int DEPTH = 3;                 // a tile's loads are issued this many slots before its first use
-  constexpr int RING = DEPTH + 1;          // ring entries per operand (power of two)
-  constexpr int LPS = 2 * NI;              // global_load_lds instructions per wave per slot (K + V)
-  constexpr int XROWS = DT * 16 + 2;       // exchange rows per wave pair: O, running max, partial sum
-  constexpr int SMEM = 2 * RING * TILE;
-  static_assert((RING & (RING - 1)) == 0, "ring size must be a power of two");
-  static_assert(4 * XROWS * 256 <= SMEM && PBSA_MAX_N_LOC * 4 <= SMEM, "scratch aliases must fit");
+  constexpr int KS = Geo<D>::KS, DT = Geo<D>::DT, TILE = Geo<D>::TILE_BYTES, ROW = Geo<D>::ROW;
+  constexpr int SUB1 = Geo<D>::SUB_BYTES;
+  constexpr int CH = D / 8, RPI = 64 / CH;          // 16-byte chunks per row, rows per wave instruction
+  constexpr int NIW = (kTile / RPI) / 2;            // global_load_lds instructions per wave per tile
+  constexpr int SMEM = 4 * TILE;                    // K ring (2 tiles), V ring (2 tiles)
+  static_assert((3 * PBSA_MAX_N_LOC + PBSA_MAX_C + 1) * 4 <= SMEM, "setup scratch must fit");
 
-  __shared__ __align__(1024) unsigned char smem[SMEM];   // K ring, then V ring
+  __shared__ __align__(1024) unsigned char smem[SMEM];
   __shared__ int t_src[kMaxTiles];         // bit 31: local, bits 0..: (slot * SUB + sub)
-  __shared__ int t_meta[kMaxTiles];        // valid keys (bits 0..7) | which of the G query blocks attend (bits 8..)
-  __shared__ int n_tiles_s;
-  unsigned char* const kring = smem;
-  unsigned char* const vring = smem + RING * TILE;
+  __shared__ int t_meta[kMaxTiles];        // valid keys (bits 0..7) | row groups that attend (bits 8, 9)
+  __shared__ int n_tiles_s, cls_end_s[4];  // list length; end of each class's range
   int* lflag = reinterpret_cast<int*>(smem);        // setup scratch, dead before the first tile is staged
 
   // XCD-aware mapping: consecutive workgroup ids go round-robin to the 8 XCDs, so give XCD x the
@@ -231,32 +349,38 @@ __global__ void __launch_bounds__(kThreads) attention_kernel(AttnArgs a) {
   const int logical = (blockIdx.x % 8) * per + blockIdx.x / 8;
   if (logical >= n_wg) return;
   const int h = logical / n_qt;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int set = wave >> 2, w4 = wave & 3;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = tid >> 6;
   const int T0 = (logical % n_qt) * kRowsPerWg;
   const int i0 = T0 / B;
-  const int my_g = (w4 * 32) / B;
-
-  // ---- Q fragments (B operand of S^T = K Q^T): query row = lane % 32, dims 16*ks + 8*(lane/32) ..+8.
-  // Issued first so the loads fly while the tile list is built.
   const int qn = lane & 31, half = lane >> 5;
-  const int tok = T0 + w4 * 32 + qn;
-  const int tok_c = min(tok, a.Nq - 1);
-  bf16x8 qf[KS];
-  {
+
+  // ---- Q fragments (B operand of S^T = K Q^T): row group g, query row lane % 32, dims 16 ks + 8 (lane/32) ..+8.
+  // Issued first so the loads fly while the tile list is built.
+  const int tok0 = T0 + wave * 32 + qn;                 // row group g holds token tok0 + 64 g
+  bf16x8 qf[2][KS];
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    const int tok_c = min(tok0 + 64 * g, a.Nq - 1);
     const bf16_t* qrow = a.Q + (size_t)h * a.q_stride_h + (size_t)tok_c * a.q_stride_t + 8 * half;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks);
+    for (int ks = 0; ks < KS; ++ks) qf[g][ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks);
   }
+  // The Q fragments are only ever MFMA operands, which may come from the accumulator half of the
+  // register file: define them there, leaving the architectural half to the softmax and the outputs.
+#pragma unroll
+  for (int g = 0; g < 2; ++g)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[g][ks]));
 
   // ---- tile list --------------------------------------------------------------------------------
   // Everything the list needs is fetched from global memory in one parallel round into LDS scratch:
   // per local block the set of query blocks that selected it, its length and its physical slot;
-  // per persistent slot its length.  Wave 0 then compacts both into the list with ballots.
+  // per persistent slot its length.  Wave 0 then compacts both into the list with ballots, one pass
+  // per class: full tiles of both row groups, of group 0 only, of group 1 only, then ragged tiles.
   int* llen_s = lflag + PBSA_MAX_N_LOC;
   int* lmap_s = llen_s + PBSA_MAX_N_LOC;
   int* plen_s = lmap_s + PBSA_MAX_N_LOC;
-  static_assert((3 * PBSA_MAX_N_LOC + PBSA_MAX_C + 1) * 4 <= SMEM, "setup scratch must fit");
   for (int l = tid; l < a.n_loc; l += kThreads) {
     lflag[l] = 0;
     llen_s[l] = a.l_len[l];
@@ -268,192 +392,243 @@ __global__ void __launch_bounds__(kThreads) attention_kernel(AttnArgs a) {
     const int g = idx / a.k, j = idx % a.k;
     if (i0 + g < a.nqb) {
       const int l = a.sel[((size_t)h * a.nqb + i0 + g) * a.k + j];
-      if (l >= 0 && l < a.n_loc) atomicOr(&lflag[l], 1 << g);
+      // with one query block per workgroup both row groups belong to it
+      if (l >= 0 && l < a.n_loc) atomicOr(&lflag[l], G == 1 ? 3 : 1 << g);
     }
   }
   __syncthreads();
   if (wave == 0) {
     int n = 0;
-    // a block yields ceil(len / 64) tiles (0, 1 or 2); positions by a wave prefix count
-    for (int c0 = 0; c0 <= a.C; c0 += 64) {
-      const int c = c0 + lane;
-      const int len = c <= a.C ? min(max(plen_s[c], 0), B) : 0;
-      const int nt = (len + kTile - 1) / kTile;
-      const unsigned long long m1 = __ballot(nt >= 1), m2 = __ballot(nt >= 2);
-      const int pos = n + lanes_below(m1) + lanes_below(m2);
-      for (int s = 0; s < nt; ++s) {
-        t_src[pos + s] = c * SUB + s;
-        t_meta[pos + s] = min(kTile, len - s * kTile) | (((1 << G) - 1) << 8);
+    for (int cls = 0; cls < 4; ++cls) {
+      for (int s = 0; s < SUB; ++s) {
+        if (cls == 0 || cls == 3) {
+          for (int c0 = 0; c0 <= a.C; c0 += 64) {
+            const int c = c0 + lane;
+            const int len = c <= a.C ? min(max(plen_s[c], 0), B) : 0;
+            const int tl = min(max(len - s * kTile, 0), kTile);
+            const bool take = tl > 0 && (tl == kTile ? cls == 0 : cls == 3);
+            const unsigned long long m = __ballot(take);
+            if (take) {
+              const int pos = n + lanes_below(m);
+              t_src[pos] = c * SUB + s;
+              t_meta[pos] = tl | (3 << 8);
+            }
+            n += __popcll(m);
+          }
+        }
+        for (int l0 = 0; l0 < a.n_loc; l0 += 64) {
+          const int l = l0 + lane;
+          const int f = l < a.n_loc ? lflag[l] : 0;
+          int len = 0, slot = 0;
+          if (f) {
+            len = min(max(llen_s[l], 0), B);
+            slot = lmap_s[l];
+            if (slot < 0 || slot >= a.n_loc_cap) len = 0;
+          }
+          const int tl = min(max(len - s * kTile, 0), kTile);
+          const int my_cls = tl < kTile ? 3 : f == 3 ? 0 : f;      // f is 1 or 2 otherwise
+          const bool take = f != 0 && tl > 0 && my_cls == cls;
+          const unsigned long long m = __ballot(take);
+          if (take) {
+            const int pos = n + lanes_below(m);
+            t_src[pos] = (int)(0x80000000u | (uint32_t)(slot * SUB + s));
+            t_meta[pos] = tl | (f << 8);
+          }
+          n += __popcll(m);
+        }
       }
-      n += __popcll(m1) + __popcll(m2);
-    }
-    for (int l0 = 0; l0 < a.n_loc; l0 += 64) {
-      const int l = l0 + lane;
-      const int f = l < a.n_loc ? lflag[l] : 0;
-      int len = 0, slot = 0;
-      if (f) {
-        len = min(max(llen_s[l], 0), B);
-        slot = lmap_s[l];
-        if (slot < 0 || slot >= a.n_loc_cap) len = 0;
-      }
-      const int nt = f ? (len + kTile - 1) / kTile : 0;
-      const unsigned long long m1 = __ballot(nt >= 1), m2 = __ballot(nt >= 2);
-      const int pos = n + lanes_below(m1) + lanes_below(m2);
-      for (int s = 0; s < nt; ++s) {
-        t_src[pos + s] = (int)(0x80000000u | (uint32_t)(slot * SUB + s));
-        t_meta[pos + s] = min(kTile, len - s * kTile) | (f << 8);
-      }
-      n += __popcll(m1) + __popcll(m2);
+      if (lane == 0) cls_end_s[cls] = n;
     }
     if (lane == 0) n_tiles_s = n;
   }
   __syncthreads();
   const int n_tiles = n_tiles_s;
 
-  f32x16 o[DT];
+  f32x16 o[2][DT];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+  for (int g = 0; g < 2; ++g)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) o[dt][v] = 0.0f;
-  f32x16 s0, s1;
+    for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
-  for (int v = 0; v < 16; ++v) { s0[v] = 0.0f; s1[v] = 0.0f; }
-  bf16x8 pf[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) pf[j][e] = (__bf16)0.0f;
-  float m_run = kNegBig, l_run = 0.0f;
+      for (int v = 0; v < 16; ++v) o[g][dt][v] = 0.0f;
+      asm volatile("" : "+a"(o[g][dt]));
+    }
+  f32x16 sA[2], sB[2];                     // S^T of even / odd sub-tiles
+  u32x4 pA[2][2], pB[2][2];                // P^T of even / odd sub-tiles (bf16 pairs)
+  float m_run[2] = {kInitMax, kInitMax}, l_run[2] = {0.0f, 0.0f}, alpha[2] = {1.0f, 1.0f};
   const float c2 = a.scale * 1.4426950408889634f;
 
-  // ---- staging --------------------------------------------------------------------------------
-  // Wave w fills LDS KiB (NI w + n), n < NI, of a tile: rows (64 / (D/8)) (NI w + n) + lane / (D/8),
-  // physical chunk lane % (D/8), i.e. the logical chunk (lane % (D/8)) ^ f(row) of that row.
+  // ---- operand addresses ------------------------------------------------------------------------
+  // this lane's fragment addresses inside ring entry 0, sub-tile 0 (LDS byte addresses)
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  constexpr int CH = D / 8, RPI = 64 / CH;          // chunks per row, rows per wave instruction
-  // A ragged V tile must not bring rows past its valid length into LDS (they meet p = 0 in the
-  // MFMA, and 0 x NaN-or-Inf pattern is NaN): the lanes of such rows fetch the last valid row instead.
-  int koff[NI], vrow[NI], vchk[NI];                 // this lane's byte offset / row / chunk offset in a tile
+  uint32_t ka0[KS], va0[DT];
+  {
+    const int kb = qn * ROW + ((half ^ k_swz<D>(qn)) << 4);        // chunk (2 ks + half) ^ f = (half ^ f) ^ 2 ks
 #pragma unroll
-  for (int n = 0; n < NI; ++n) {
-    const int r = RPI * (NI * wave + n) + lane / CH, c = lane % CH;
-    koff[n] = r * (D * 2) + ((c ^ k_swz<D>(r)) << 4);
-    vrow[n] = r;
-    vchk[n] = (c ^ v_swz<D>(r)) << 4;
+    for (int ks = 0; ks < KS; ++ks) ka0[ks] = smem_lds + (uint32_t)(kb ^ (ks << 5));
+    const int s16 = lane & 15, q16 = (lane >> 4) & 1;
+    const int v_row0 = 4 * half + (s16 >> 2);                      // address row within 16 keys
+    const int v_sub = 2 * q16 + ((s16 & 3) >> 1), v_lo = (s16 & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      va0[dt] = smem_lds + 2 * TILE + (uint32_t)(v_row0 * ROW + (((4 * dt + v_sub) ^ v_swz<D>(v_row0)) << 4) + v_lo);
   }
-  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_lds + NI * wave * 1024);
-  // Byte offset of a tile from the K (or V) base of its cache: descriptor bit 31 picks the cache.
+
+  // ---- staging --------------------------------------------------------------------------------
+  // A wave instruction fills one KiB of a tile: RPI consecutive rows, lane i -> row i / CH, physical
+  // chunk i % CH, i.e. the logical chunk (i % CH) ^ f(row) of that row.  The tile has 2 NIW such
+  // pieces; piece m covers rows RPI m ...  Since f has period 16 in the row (K) or depends on the row
+  // within the piece only (V), the per-lane source offsets of all pieces a wave issues come from a few
+  // patterns plus a multiple of the piece size, which goes into the scalar base: wave w issues the
+  // pieces m = PS (w + 2 q) + e, e < PS, q < NIW / PS, where PS pieces make 16 rows, and pieces with
+  // equal e share a pattern.  A ragged V tile must not bring rows past its valid length into LDS (they
+  // meet p = 0 in the MFMA, and 0 x NaN-or-Inf pattern is NaN): the lanes of such rows fetch the last
+  // valid row instead.
+  constexpr int PS = 8 / RPI > 0 ? 8 / RPI : 1;     // patterns per wave
+  constexpr int NQ = NIW / PS;
+  int koff[PS], voff_w, vrow_w, vchk;
+  {
+    const int rl = lane / CH, c = lane % CH;
+#pragma unroll
+    for (int e = 0; e < PS; ++e) {
+      const int r = RPI * (PS * wave + e) + rl;
+      koff[e] = r * ROW + ((c ^ k_swz<D>(r)) << 4);
+    }
+    vrow_w = RPI * PS * wave + rl;                    // V: f(row) = f(row within the piece), one pattern
+    vchk = (c ^ v_swz<D>(rl)) << 4;
+    voff_w = vrow_w * ROW + vchk;
+  }
+  const uint32_t wave_piece = __builtin_amdgcn_readfirstlane(smem_lds + PS * wave * 1024);
   const size_t head_l = (size_t)h * a.n_loc_cap * B * D * 2, head_p = (size_t)h * (a.C + 1) * B * D * 2;
 #define PBSA_TILE_PTR(SRC, BASE_L, BASE_P)                                                              \
   ((SRC) < 0 ? reinterpret_cast<const unsigned char*>(BASE_L) + head_l + (size_t)((SRC) & 0x7FFFFFFF) * (kTile * D * 2) \
              : reinterpret_cast<const unsigned char*>(BASE_P) + head_p + (size_t)(SRC) * (kTile * D * 2))
-  // slot S_ issues K(S_ + DEPTH) and V(S_ + DEPTH - 2) given their descriptors.  Indices outside the
-  // list are clamped by the caller (the load count per slot stays constant, which the vmcnt
-  // arithmetic below relies on; the ring entry such a load lands in is never read).
-#define PBSA_ISSUE(S_, SRC_K, SRC_V, LEN_V)                                                             \
-  {                                                                                                     \
-    const unsigned char* kp_ = PBSA_TILE_PTR(SRC_K, a.Kl, a.Kp);                                        \
-    const unsigned char* vp_ = PBSA_TILE_PTR(SRC_V, a.Vl, a.Vp);                                        \
-    const uint32_t kl_ = wave_lds + (uint32_t)((((S_) + DEPTH) & (RING - 1)) * TILE);                   \
-    const uint32_t vl_ = wave_lds + (uint32_t)((RING + (((S_) + DEPTH - 2) & (RING - 1))) * TILE);      \
-    _Pragma("unroll") for (int n_ = 0; n_ < NI; ++n_) dma16(kp_ + koff[n_], kl_ + n_ * 1024);           \
-    _Pragma("unroll") for (int n_ = 0; n_ < NI; ++n_)                                                   \
-        dma16(vp_ + (min(vrow[n_], (LEN_V) - 1) * (D * 2) + vchk[n_]), vl_ + n_ * 1024);                \
+  // piece m of the tile: K source rows RPI m.., pattern koff[e] holds rows RPI (PS wave + e)..
+#define PBSA_ISSUE_K(T_, ENTRY)                                                                         \
+  if ((T_) < n_tiles) {                                                                                 \
+    const int src_ = __builtin_amdgcn_readfirstlane(t_src[T_]);                                         \
+    const unsigned char* kp_ = PBSA_TILE_PTR(src_, a.Kl, a.Kp);                                         \
+    _Pragma("unroll") for (int q_ = 0; q_ < NQ; ++q_)                                                   \
+      _Pragma("unroll") for (int e_ = 0; e_ < PS; ++e_)                                                 \
+        dma16(kp_ + q_ * (2 * PS * RPI * ROW), koff[e_],                                                \
+              wave_piece + (ENTRY) * TILE + (q_ * 2 * PS + e_) * 1024);                                 \
   }
-#define PBSA_SRC(IT) __builtin_amdgcn_readfirstlane(t_src[min(max((IT), 0), n_tiles - 1)])
-#define PBSA_META(IT) ((IT) >= 0 && (IT) < n_tiles ? __builtin_amdgcn_readfirstlane(t_meta[IT]) : kTile)
-  // everything but the loads of the last DEPTH-1 slots has landed
-#define PBSA_WAIT_TILES() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS * (DEPTH - 1)) : "memory")
+#define PBSA_ISSUE_V(T_, ENTRY)                                                                         \
+  if ((T_) < n_tiles) {                                                                                 \
+    const int src_ = __builtin_amdgcn_readfirstlane(t_src[T_]);                                         \
+    const int len_ = __builtin_amdgcn_readfirstlane(t_meta[T_]) & 0xFF;                                 \
+    const unsigned char* vp_ = PBSA_TILE_PTR(src_, a.Vl, a.Vp);                                         \
+    if (len_ == kTile) {                                                                                \
+      _Pragma("unroll") for (int q_ = 0; q_ < NQ; ++q_)                                                 \
+        _Pragma("unroll") for (int e_ = 0; e_ < PS; ++e_)                                               \
+          dma16(vp_ + (q_ * 2 * PS + e_) * (RPI * ROW), voff_w,                                         \
+                wave_piece + (2 + (ENTRY)) * TILE + (q_ * 2 * PS + e_) * 1024);                         \
+    } else {                                                                                            \
+      _Pragma("unroll") for (int q_ = 0; q_ < NQ; ++q_)                                                 \
+        _Pragma("unroll") for (int e_ = 0; e_ < PS; ++e_) {                                             \
+          dma16(vp_, min(RPI * (q_ * 2 * PS + e_) + vrow_w, len_ - 1) * ROW + vchk,                     \
+                wave_piece + (2 + (ENTRY)) * TILE + (q_ * 2 * PS + e_) * 1024);                         \
+        }                                                                                               \
+    }                                                                                                   \
+  }
 
-  // per-lane pieces of the V^T operand address: 16-lane group s -> row s/4, chunk pair 2q + (s%4)/2
-  const int s16 = lane & 15, q16 = (lane >> 4) & 1;
-  const int v_row0 = 4 * half + (s16 >> 2);
-  const int v_sub = 2 * q16 + ((s16 & 3) >> 1);
-  const int v_lo = (s16 & 1) * 8;
+  // One class of the list, tiles [TB, TE), as one pipelined run.  Tile t is sub-tiles 2t (buffers A)
+  // and 2t+1 (buffers B):
+  //   before   : QK(TB,0)
+  //   step 2t  : softmax(t,0)  with  PV(t-1,1) (not for t = TB)  and  QK(t,1)
+  //   step 2t+1: softmax(t,1)  with  PV(t,0)                     and  QK(t+1,0) (not for t = TE-1)
+  //   after    : PV(TE-1,1)
+  // Between the two steps of a tile the tiles K(t) and V(t-1) are dead: their ring entries are refilled
+  // with K(t+2) and V(t+1), which have until the same point of the next tile to arrive.  Steps 2t+1 and
+  // 2t+2 read the same two ring entries (V of t, K of t+1), so the loop body is that pair and takes one
+  // set of addresses.  A ragged class runs both row groups and masks, per tile, the keys that do not
+  // exist and the group that does not attend.
+#define PBSA_ADDR_K(T_)                                                                                 \
+  _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) kx[ks] = ka0[ks] + ((T_) & 1) * TILE;
+#define PBSA_ADDR_V(T_)                                                                                 \
+  _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) vx[dt] = va0[dt] + ((T_) & 1) * TILE;
+#define PBSA_LIMITS(T_, RAGGED)                                                                         \
+  if (RAGGED) {                                                                                         \
+    const int meta_ = __builtin_amdgcn_readfirstlane(t_meta[T_]);                                       \
+    const int len_ = meta_ & 0xFF;                                                                      \
+    _Pragma("unroll") for (int g = 0; g < 2; ++g) {                                                     \
+      const bool on_ = (meta_ >> (8 + g)) & 1;                                                          \
+      lim0[g] = (on_ ? min(len_, 32) : 0) - 4 * half;                                                   \
+      lim1[g] = (on_ ? max(len_ - 32, 0) : 0) - 4 * half;                                               \
+    }                                                                                                   \
+  }
+#define PBSA_TURNOVER(T_)                                                                               \
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K(T_+1), V(T_) have landed */                     \
+  __syncthreads();                                                                                      \
+  PBSA_ISSUE_K((T_) + 2, (T_) & 1)                                                                      \
+  PBSA_ISSUE_V((T_) + 1, ((T_) + 1) & 1)
+#define PBSA_RUN_CLASS(GM, RAGGED, TB, TE)                                                              \
+  if ((TB) < (TE)) {                                                                                    \
+    uint32_t kx[KS], vx[DT];                                                                            \
+    int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
+    PBSA_ADDR_K(TB)                                                                                     \
+    PBSA_ADDR_V(TB)                                                                                     \
+    step<D, GM, false, true, false, false, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0); \
+    PBSA_LIMITS(TB, RAGGED)                                                                             \
+    step<D, GM, false, true, true, RAGGED, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0); \
+    rescale<DT>(o, alpha, GM);                                                                          \
+    PBSA_TURNOVER(TB)                                                                                   \
+    for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
+      PBSA_ADDR_V(t)                                                                                    \
+      PBSA_ADDR_K(t + 1)                                                                                \
+      step<D, GM, true, true, true, RAGGED, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1); \
+      rescale<DT>(o, alpha, GM);                                                                        \
+      PBSA_LIMITS(t + 1, RAGGED)                                                                        \
+      step<D, GM, true, true, true, RAGGED, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0); \
+      rescale<DT>(o, alpha, GM);                                                                        \
+      PBSA_TURNOVER(t + 1)                                                                              \
+    }                                                                                                   \
+    PBSA_ADDR_V((TE) - 1)                                                                               \
+    step<D, GM, true, false, true, RAGGED, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1); \
+    rescale<DT>(o, alpha, GM);                                                                          \
+    step<D, GM, true, false, false, false, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0); \
+  }
 
   if (n_tiles > 0) {
-    __syncthreads();                       // lflag (aliasing the K ring) is dead
-    for (int s = -DEPTH; s < 0; ++s)
-      PBSA_ISSUE(s, PBSA_SRC(s + DEPTH), PBSA_SRC(s + DEPTH - 2), PBSA_META(min(max(s + DEPTH - 2, 0), n_tiles - 1)) & 0xFF)
-    // Tile descriptors travel in scalar registers and are fetched from LDS one slot before they are
-    // needed: src_a/b/c describe tiles s+3, s+2, s+1 (K of s+3 and V of s+1 are issued in slot s);
-    // meta_n/0/1/2 are the length/attendance words of tiles s+1, s, s-1, s-2 (a word outside the list
-    // has no attendance bit set).
-    int src_a = PBSA_SRC(DEPTH), src_b = PBSA_SRC(DEPTH - 1), src_c = PBSA_SRC(DEPTH - 2);
-    int meta_n = PBSA_META(1), meta_0 = PBSA_META(0), meta_1 = kTile, meta_2 = kTile;
-    PBSA_WAIT_TILES();
+    __syncthreads();                       // the setup scratch (aliasing the rings) is dead
+    PBSA_ISSUE_K(0, 0)
+    PBSA_ISSUE_K(1, 1)
+    PBSA_ISSUE_V(0, 0)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    // Slot s: the set whose turn it is multiplies (V(s-2) from its ring entry, then K(s)); the other
-    // set runs the softmax of tile s-1.
-    for (int s = 0; s < n_tiles + 2; ++s) {
-      const int nxt_src_v = t_src[min(s + 1 + DEPTH, n_tiles - 1)];       // consumed at the end of the slot
-      const int nxt_meta_v = t_meta[min(s + 2, n_tiles - 1)];
-      PBSA_ISSUE(s, src_a, src_c, meta_n & 0xFF)
-      if (((s + set) & 1) == 0) {
-        {
-          // the S^T accumulators are dead here (tile s-2 went through its softmax, tile s is about to be
-          // written from zero): say so, or they stay allocated across the whole matrix phase
-          f32x16 dead0, dead1;
-          s0 = dead0;
-          s1 = dead1;
-        }
-        if ((meta_2 >> (8 + my_g)) & 1) pv_tile<D>(vring + ((s - 2) & (RING - 1)) * TILE, pf, o, v_row0, v_sub, v_lo);
-        if ((meta_0 >> (8 + my_g)) & 1) qk_tile<D>(kring + (s & (RING - 1)) * TILE, qf, qn, half, s0, s1);
-      } else {
-        if ((meta_1 >> (8 + my_g)) & 1) softmax_tile<DT>(s0, s1, meta_1 & 0xFF, half, c2, m_run, l_run, o, pf);
-      }
-      src_c = src_b; src_b = src_a; src_a = __builtin_amdgcn_readfirstlane(nxt_src_v);
-      meta_2 = meta_1; meta_1 = meta_0; meta_0 = meta_n;
-      meta_n = s + 2 < n_tiles ? __builtin_amdgcn_readfirstlane(nxt_meta_v) : kTile;
-      PBSA_WAIT_TILES();
-      __syncthreads();
+    const int e0 = cls_end_s[0], e1 = cls_end_s[1], e2 = cls_end_s[2];
+    PBSA_RUN_CLASS(3, false, 0, e0)
+    if (G > 1) {
+      PBSA_RUN_CLASS(1, false, e0, e1)
+      PBSA_RUN_CLASS(2, false, e1, e2)
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // stray clamped loads must not land in the exchange area
+    PBSA_RUN_CLASS(3, true, e2, n_tiles)
   }
-  __syncthreads();
 
-  // ---- merge the two sets (same rows, disjoint tiles) and write out ---------------------------
-  // exchange layout: per wave pair w4, XROWS rows of 64 floats ([value index][lane]): conflict-free
-  float* xch = reinterpret_cast<float*>(smem) + (size_t)w4 * XROWS * 64 + lane;
-  if (set == 1) {
+  // ---- epilogue ---------------------------------------------------------------------------------
+  acc_settle<DT>(o[0]);
+  acc_settle<DT>(o[1]);
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+  for (int g = 0; g < 2; ++g) {
+    const float l_tot = l_run[g] + __shfl_xor(l_run[g], 32, 64);
+    const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    const int tok = tok0 + 64 * g;
+    if (tok < a.Nq) {
+      bf16_t* orow = a.O + (size_t)h * a.o_stride_h + (size_t)tok * a.o_stride_t;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) xch[(dt * 16 + v) * 64] = o[dt][v];
-    xch[(DT * 16) * 64] = m_run;
-    xch[(DT * 16 + 1) * 64] = l_run;
-  }
-  __syncthreads();
-  if (set == 1) return;
-  {
-    const float m_b = xch[(DT * 16) * 64], l_b = xch[(DT * 16 + 1) * 64];
-    const float m = fmaxf(m_run, m_b);
-    const float fa = __builtin_amdgcn_exp2f((m_run - m) * c2), fb = __builtin_amdgcn_exp2f((m_b - m) * c2);
+      for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int q4 = 0; q4 < 4; ++q4) {
+          bf16x4 w;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o[dt][v] = o[dt][v] * fa + xch[(dt * 16 + v) * 64] * fb;
-    l_run = l_run * fa + l_b * fb;
-    m_run = m;
-  }
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-  if (tok < a.Nq) {
-    bf16_t* orow = a.O + (size_t)h * a.o_stride_h + (size_t)tok * a.o_stride_t;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 w;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[dt][4 * q4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * q4 + 4 * half) = w;
-      }
-    if (a.lse && half == 0)
-      a.lse[(size_t)h * a.Nq + tok] = l_tot > 0.0f ? m_run * a.scale + __logf(l_tot) : -INFINITY;
+          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[g][dt][4 * q4 + e] * inv);
+          *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * q4 + 4 * half) = w;
+        }
+      if (a.lse && half == 0)
+        a.lse[(size_t)h * a.Nq + tok] = l_tot > 0.0f ? m_run[g] * a.scale + __logf(l_tot) : -INFINITY;
+    }
   }
 }
-
 #pragma clang diagnostic pop
 
 }  // namespace

@@ -18,6 +18,10 @@ from paper_2604_21221_amd import synth  # noqa: E402
 pytestmark = pytest.mark.gpu
 
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+# lse: the kernel's normaliser is the sum of the bf16-rounded probabilities (the numbers its second product
+# uses), each within 2^-9 relative of the exact one, so |lse - exact| <= -log(1 - 2^-9) = 1.96e-3 plus the
+# fp32 exp2 / accumulation error of a few 1e-4
+LSE_ABS = 4e-3
 DEV = "cuda:0"
 
 
@@ -89,7 +93,7 @@ def run_both(gpu, c, st, Q, K, V, g, rows, what, lse_check=True):
         if lse_check:
             fin = np.isfinite(lref)
             assert np.array_equal(np.isfinite(lg), fin)
-            assert np.abs(lg[fin] - lref[fin]).max() < 2e-3, what
+            assert np.abs(lg[fin] - lref[fin]).max() < LSE_ABS, what
     ne = st.n_evict_now()
     sc_ref, src_ref = st.update()
     assert c.update() == ne
