@@ -52,8 +52,9 @@ constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
 constexpr float kInitMax = -1.0e29f;       // running max of a row that has seen no key: above kMasked, below any score
 // The softmax reference of a row follows its running max lazily: it moves (and the output
 // accumulators are rescaled) only when a new score exceeds it by more than kSlack in base-2 exponent
-// units, so probabilities stay below 2^kSlack -- harmless in bf16 / fp32 -- and rescales are rare.
-constexpr float kSlack = 8.0f;
+// units, so probabilities stay below 2^kSlack -- harmless in bf16 / fp32, whose precision is relative --
+// and rescales are rare even when the scores of neighbouring tiles differ by orders of magnitude.
+constexpr float kSlack = 24.0f;
 
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {   // set bits of `mask` below this lane
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -192,6 +193,44 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[2][DT], const float (&alpha)
 // a slice of the softmax, so the matrix pipe works while the VALU computes.  Nothing is allowed to
 // move across slot boundaries.
 // ------------------------------------------------------------------------------------------------
+// Staging loads that ride along a pipeline step: K of tile t+2 and V of tile t+1, one wave
+// instruction per slot from the step's first slot on.  Issued in one burst they would hold the wave at
+// the texture path (about 50 bytes per clock per CU) for a large part of a step; spread out, they
+// travel while the wave computes.
+template <int D>
+struct DmaPlan {
+  static constexpr int CH = D / 8, RPI = 64 / CH;   // 16-byte chunks per row, rows per wave instruction
+  static constexpr int NIW = (kTile / RPI) / 2;      // instructions per wave per tile
+  static constexpr int PS = 8 / RPI > 0 ? 8 / RPI : 1;
+  static constexpr int N = 2 * NIW;                  // K and V
+  const unsigned char* kp;    // source tiles
+  const unsigned char* vp;
+  uint32_t klds, vlds;        // LDS address of this wave's first piece in the destination ring entries
+  int koff[PS];               // per lane: source byte offset of each K pattern
+  int voff[NIW];              // per lane: source byte offset of each V piece, rows past the tile's valid
+                              // length replaced by its last valid row.  Computed when the plan is made and
+                              // left alone until every load has been issued: an address register rewritten
+                              // shortly after the load that uses it has produced wrong loads here.
+  int vrow_w, vchk;           // per lane: V source row of piece 0 and chunk byte offset
+};
+
+template <int D, int IDX>
+__device__ __forceinline__ void dma_issue(const DmaPlan<D>& p) {
+  using P = DmaPlan<D>;
+  constexpr int i = IDX / 2, q = i / P::PS, e = i % P::PS, piece = q * 2 * P::PS + e;
+  if constexpr (IDX % 2 == 0)
+    dma16(p.kp + q * (2 * P::PS * P::RPI * Geo<D>::ROW), p.koff[e], p.klds + piece * 1024);
+  else
+    dma16(p.vp, p.voff[i], p.vlds + piece * 1024);
+}
+template <int D, int LO, int HI>
+__device__ __forceinline__ void dma_issue_range(const DmaPlan<D>& p) {
+  if constexpr (LO < HI) {
+    dma_issue<D, LO>(p);
+    dma_issue_range<D, LO + 1, HI>(p);
+  }
+}
+
 template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED>
 struct StepCtx {
   static constexpr int NG = (GM & 1) + ((GM >> 1) & 1);
@@ -213,6 +252,7 @@ struct StepCtx {
   float (&l_run)[2];
   float (&alpha)[2];
   const int (&lim)[2];           // RAGGED: valid keys of the current sub-tile minus 4 * half, per row group
+  const DmaPlan<D>& dma;
   bf16x8 frag[2 * Geo<D>::KS];   // operand fragment of each MFMA pair
   float mc[2], psum[2];
 };
@@ -287,16 +327,20 @@ __device__ __forceinline__ void valu_slot(StepCtx<D, GM, PV, QK, SM, RAGGED>& c)
   }
 }
 
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int I>
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF, int I>
 __device__ __forceinline__ void run_slots(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
   using S = StepCtx<D, GM, PV, QK, SM, RAGGED>;
   if constexpr (I < S::NC) {
     constexpr int Q = I / S::NG, k = I % S::NG;
     if constexpr (k == 0) load_frag<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + S::AHEAD>(c);
     mfma_slot<D, GM, PV, QK, SM, RAGGED, Q, (k == 0 ? S::G0 : 1)>(c);
+    if constexpr (DMA) {
+      constexpr int ND = DmaPlan<D>::N, NS = S::NC < ND ? S::NC : ND;    // slots that carry loads
+      if constexpr (I < NS) dma_issue_range<D, I * ND / NS, (I + 1) * ND / NS>(c.dma);
+    }
     valu_slot<D, GM, PV, QK, SM, RAGGED, I>(c);
     __builtin_amdgcn_sched_barrier(0);
-    run_slots<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, I + 1>(c);
+    run_slots<D, GM, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, I + 1>(c);
   }
 }
 
@@ -309,19 +353,29 @@ __device__ __forceinline__ void preload_frags(StepCtx<D, GM, PV, QK, SM, RAGGED>
 }
 
 // K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF>
+template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF>
 __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS], float c2,
                                      const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
                                      f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], const u32x4 (&p_prev)[2][2],
-                                     float (&m_run)[2], float (&l_run)[2], float (&alpha)[2], const int (&lim)[2]) {
+                                     float (&m_run)[2], float (&l_run)[2], float (&alpha)[2], const int (&lim)[2],
+                                     const DmaPlan<D>& dma) {
   static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
-  StepCtx<D, GM, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, qf, o, s_cur, s_next, p_cur, p_prev, m_run, l_run, alpha, lim,
+  StepCtx<D, GM, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, qf, o, s_cur, s_next, p_cur, p_prev, m_run, l_run, alpha, lim, dma,
                                        {}, {0, 0}, {0, 0}};
   preload_frags<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
   __builtin_amdgcn_sched_barrier(0);
-  run_slots<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
+  run_slots<D, GM, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
 }
 
+#ifndef XI0
+#define XI0 true
+#endif
+#ifndef XI1
+#define XI1 true
+#endif
+#ifndef XI3
+#define XI3 true
+#endif
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
 template <int D, int B>
@@ -499,6 +553,11 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     voff_w = vrow_w * ROW + vchk;
   }
   const uint32_t wave_piece = __builtin_amdgcn_readfirstlane(smem_lds + PS * wave * 1024);
+  DmaPlan<D> plan;
+  plan.vrow_w = vrow_w;
+  plan.vchk = vchk;
+#pragma unroll
+  for (int e = 0; e < PS; ++e) plan.koff[e] = koff[e];
   const size_t head_l = (size_t)h * a.n_loc_cap * B * D * 2, head_p = (size_t)h * (a.C + 1) * B * D * 2;
 #define PBSA_TILE_PTR(SRC, BASE_L, BASE_P)                                                              \
   ((SRC) < 0 ? reinterpret_cast<const unsigned char*>(BASE_L) + head_l + (size_t)((SRC) & 0x7FFFFFFF) * (kTile * D * 2) \
@@ -557,36 +616,52 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
       lim1[g] = (on_ ? max(len_ - 32, 0) : 0) - 4 * half;                                               \
     }                                                                                                   \
   }
+  // The loads of K(T_+2) and V(T_+1) ride along the step that follows.  Past the end of the list the
+  // last tile is fetched again: the ring entries it lands in are dead and never read.
 #define PBSA_TURNOVER(T_)                                                                               \
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K(T_+1), V(T_) have landed */                     \
   __syncthreads();                                                                                      \
-  PBSA_ISSUE_K((T_) + 2, (T_) & 1)                                                                      \
-  PBSA_ISSUE_V((T_) + 1, ((T_) + 1) & 1)
-#define PBSA_RUN_CLASS(GM, RAGGED, TB, TE)                                                              \
+  {                                                                                                     \
+    const int tk_ = min((T_) + 2, n_tiles - 1), tv_ = min((T_) + 1, n_tiles - 1);                       \
+    const int ksrc_ = __builtin_amdgcn_readfirstlane(t_src[tk_]);                                       \
+    const int vsrc_ = __builtin_amdgcn_readfirstlane(t_src[tv_]);                                       \
+    plan.kp = PBSA_TILE_PTR(ksrc_, a.Kl, a.Kp);                                                         \
+    plan.vp = PBSA_TILE_PTR(vsrc_, a.Vl, a.Vp);                                                         \
+    const int vlast_ = (__builtin_amdgcn_readfirstlane(t_meta[tv_]) & 0xFF) - 1;                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < NIW; ++i_) {                                                \
+      const int piece_ = (i_ / PS) * 2 * PS + i_ % PS;                                                  \
+      plan.voff[i_] = min(RPI * piece_ + plan.vrow_w, vlast_) * ROW + plan.vchk;                        \
+    }                                                                                                   \
+    plan.klds = wave_piece + ((T_) & 1) * TILE;                                                         \
+    plan.vlds = wave_piece + (2 + (((T_) + 1) & 1)) * TILE;                                             \
+  }
+#define PBSA_RUN_CLASS(GM, RAGGED, INSTEP, TB, TE)                                                              \
   if ((TB) < (TE)) {                                                                                    \
     uint32_t kx[KS], vx[DT];                                                                            \
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
     PBSA_ADDR_K(TB)                                                                                     \
     PBSA_ADDR_V(TB)                                                                                     \
-    step<D, GM, false, true, false, false, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0); \
+    step<D, GM, false, true, false, false, false, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan); \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
-    step<D, GM, false, true, true, RAGGED, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0); \
+    step<D, GM, false, true, true, RAGGED, false, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
     rescale<DT>(o, alpha, GM);                                                                          \
     PBSA_TURNOVER(TB)                                                                                   \
+    if (!(INSTEP)) dma_issue_range<D, 0, DmaPlan<D>::N>(plan);                                          \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, GM, true, true, true, RAGGED, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1); \
+      step<D, GM, true, true, true, RAGGED, INSTEP, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
       rescale<DT>(o, alpha, GM);                                                                        \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
-      step<D, GM, true, true, true, RAGGED, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0); \
+      step<D, GM, true, true, true, RAGGED, false, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
       rescale<DT>(o, alpha, GM);                                                                        \
       PBSA_TURNOVER(t + 1)                                                                              \
+      if (!(INSTEP)) dma_issue_range<D, 0, DmaPlan<D>::N>(plan);                                        \
     }                                                                                                   \
     PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, GM, true, false, true, RAGGED, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1); \
+    step<D, GM, true, false, true, RAGGED, INSTEP, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
     rescale<DT>(o, alpha, GM);                                                                          \
-    step<D, GM, true, false, false, false, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0); \
+    step<D, GM, true, false, false, false, false, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
   }
 
   if (n_tiles > 0) {
@@ -597,12 +672,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int e0 = cls_end_s[0], e1 = cls_end_s[1], e2 = cls_end_s[2];
-    PBSA_RUN_CLASS(3, false, 0, e0)
+    PBSA_RUN_CLASS(3, false, XI0, 0, e0)
     if (G > 1) {
-      PBSA_RUN_CLASS(1, false, e0, e1)
-      PBSA_RUN_CLASS(2, false, e1, e2)
+      PBSA_RUN_CLASS(1, false, XI1, e0, e1)
+      PBSA_RUN_CLASS(2, false, XI1, e1, e2)
     }
-    PBSA_RUN_CLASS(3, true, e2, n_tiles)
+    PBSA_RUN_CLASS(3, true, XI3, e2, n_tiles)
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
