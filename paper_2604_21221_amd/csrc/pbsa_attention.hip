@@ -367,15 +367,6 @@ __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const 
   run_slots<D, GM, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
 }
 
-#ifndef XI0
-#define XI0 true
-#endif
-#ifndef XI1
-#define XI1 true
-#endif
-#ifndef XI3
-#define XI3 true
-#endif
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
 template <int D, int B>
@@ -635,7 +626,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     plan.klds = wave_piece + ((T_) & 1) * TILE;                                                         \
     plan.vlds = wave_piece + (2 + (((T_) + 1) & 1)) * TILE;                                             \
   }
-#define PBSA_RUN_CLASS(GM, RAGGED, INSTEP, TB, TE)                                                              \
+#define PBSA_RUN_CLASS(GM, RAGGED, TB, TE)                                                                      \
   if ((TB) < (TE)) {                                                                                    \
     uint32_t kx[KS], vx[DT];                                                                            \
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
@@ -646,22 +637,23 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     step<D, GM, false, true, true, RAGGED, false, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
     rescale<DT>(o, alpha, GM);                                                                          \
     PBSA_TURNOVER(TB)                                                                                   \
-    if (!(INSTEP)) dma_issue_range<D, 0, DmaPlan<D>::N>(plan);                                          \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, GM, true, true, true, RAGGED, INSTEP, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
+      step<D, GM, true, true, true, RAGGED, true, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
       rescale<DT>(o, alpha, GM);                                                                        \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
       step<D, GM, true, true, true, RAGGED, false, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
       rescale<DT>(o, alpha, GM);                                                                        \
       PBSA_TURNOVER(t + 1)                                                                              \
-      if (!(INSTEP)) dma_issue_range<D, 0, DmaPlan<D>::N>(plan);                                        \
     }                                                                                                   \
     PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, GM, true, false, true, RAGGED, INSTEP, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
+    step<D, GM, true, false, true, RAGGED, true, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
     rescale<DT>(o, alpha, GM);                                                                          \
     step<D, GM, true, false, false, false, false, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
+    /* between classes the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
+    acc_settle<DT>(o[0]);                                                                               \
+    acc_settle<DT>(o[1]);                                                                               \
   }
 
   if (n_tiles > 0) {
@@ -672,12 +664,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int e0 = cls_end_s[0], e1 = cls_end_s[1], e2 = cls_end_s[2];
-    PBSA_RUN_CLASS(3, false, XI0, 0, e0)
+    PBSA_RUN_CLASS(3, false, 0, e0)
     if (G > 1) {
-      PBSA_RUN_CLASS(1, false, XI1, e0, e1)
-      PBSA_RUN_CLASS(2, false, XI1, e1, e2)
+      PBSA_RUN_CLASS(1, false, e0, e1)
+      PBSA_RUN_CLASS(2, false, e1, e2)
     }
-    PBSA_RUN_CLASS(3, true, XI3, e2, n_tiles)
+    PBSA_RUN_CLASS(3, true, e2, n_tiles)
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
