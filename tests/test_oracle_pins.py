@@ -414,3 +414,25 @@ def test_rollout_summary_counts(oracle):
     assert st.S_cnt[0].max() == folded
     ids = [int(x) for x in st.p_id[0]]
     assert len(set(ids)) == C and all(0 <= x < 5 * nqb for x in ids)
+
+
+def test_cfg1_rollout_matches_the_stored_fixture():
+    """The oracle's results on cfg1 as frozen by tests/golden/make_cfg1_golden.py (which calls only the
+    oracle): block sets, score bit patterns, slot assignments exactly; stored attention rows to 1e-5.
+    Not a pin against the paper (it prints no intermediate values): a guard against silent drift."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_cfg1_golden", os.path.join(here, "golden", "make_cfg1_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.build()
+    with open(os.path.join(here, "golden", "cfg1_rollout.json")) as f:
+        ref = json.load(f)
+    assert len(now["chunks"]) == len(ref["chunks"])
+    for a, b in zip(now["chunks"], ref["chunks"]):
+        for key in ("sel", "scores_bits", "slot_src", "p_id", "p_len", "S_cnt_sum"):
+            assert a[key] == b[key], key
+        assert np.allclose(a["O_rows"], b["O_rows"], atol=1e-5)
+        assert np.allclose(a["lse_rows"], b["lse_rows"], atol=1e-5)
