@@ -146,14 +146,21 @@ __device__ __forceinline__ void acc_settle(f32x16 (&o)[DT]) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o[0]), "+a"(o[1]));
 }
 
-// max over the 16 keys a lane holds of one row, then with the other half-wave's 16
+// max over the 16 keys a lane holds of one row, then with the other half-wave's 16.  The three-input
+// maximum is written as the instruction: fmaxf would first quiet each input (a move per input), and no
+// NaN can be here -- scores of existing keys are finite and the others have been replaced.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 __device__ __forceinline__ float row_max(const f32x16& s) {
-  float t = fmaxf(fmaxf(s[0], s[1]), s[2]);
+  float t = max3(s[0], s[1], s[2]);
 #pragma unroll
-  for (int v = 3; v < 15; v += 2) t = fmaxf(fmaxf(t, s[v]), s[v + 1]);
-  t = fmaxf(t, s[15]);
+  for (int v = 3; v < 15; v += 2) t = max3(t, s[v], s[v + 1]);
+  t = max3(t, s[15], s[15]);
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
 }
 
 // probabilities of two neighbouring keys: exp2, round to bf16, add to the row sum
