@@ -244,15 +244,19 @@ def test_cfg3_layers(gpu):
 
 
 def test_cfg5_rollout(gpu):
-    """Cold start at the 1-minute shape: the window and the persistent set fill during chunks 0-3,
-    eviction and compression start at chunk 3.  Selection and update exact on every chunk; attention
-    rows sampled on a cold, a filling, the first evicting, and steady-state chunks."""
+    """Cold start at the 1-minute shape, all 80 chunks (240 latent frames): the window and the persistent
+    set fill during chunks 0-3, eviction and compression start at chunk 3 and run on every chunk after.
+    Selection and update exact on every chunk; attention rows sampled on a cold, a filling, the first
+    evicting, and steady-state chunks up to the last."""
     w = synth.WORKLOADS["cfg5"]
     st, g0 = state_for_workload(w)
     c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
     rows = sample_rows(w.H, w.Nq, w.B, per_head=32)
-    n_chunks = 12
+    n_chunks = w.n_chunks
+    assert n_chunks == 80
     for g in range(n_chunks):
         Q, K, V = synth.chunk_qkv(w, 0, g)
-        run_both(gpu, c, st, Q, K, V, g, rows if g in (0, 1, 3, 4, 11) else None, "cfg5")
-    assert int(st.S_cnt.max()) > 0 and (st.p_len[:, :w.C] > 0).all()
+        run_both(gpu, c, st, Q, K, V, g, rows if g in (0, 1, 3, 4, 39, 79) else None, "cfg5")
+    assert (st.p_len[:, :w.C] > 0).all()
+    # every block that left the window and was not kept is in the summary: 77 evictions of 74 blocks
+    assert int(st.S_cnt.max()) == 77 * w.nqb - w.C
