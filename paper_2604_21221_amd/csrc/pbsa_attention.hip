@@ -615,23 +615,31 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     }                                                                                                   \
   }
   // The loads of K(T_+2) and V(T_+1) ride along the step that follows.  Past the end of the list the
-  // last tile is fetched again: the ring entries it lands in are dead and never read.
+  // last tile is fetched again: the ring entries it lands in are dead and never read.  The descriptors
+  // of those tiles were read from LDS one tile earlier (d_ksrc, d_vsrc, d_vmeta), so that no LDS latency
+  // sits between the barrier and the first load; the reads for the next turnover are issued here.
+#define PBSA_FETCH_DESC(T_)                                                                             \
+  {                                                                                                     \
+    d_ksrc = t_src[min((T_) + 2, n_tiles - 1)];                                                         \
+    d_vsrc = t_src[min((T_) + 1, n_tiles - 1)];                                                         \
+    d_vmeta = t_meta[min((T_) + 1, n_tiles - 1)];                                                       \
+  }
 #define PBSA_TURNOVER(T_)                                                                               \
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K(T_+1), V(T_) have landed */                     \
   __syncthreads();                                                                                      \
   {                                                                                                     \
-    const int tk_ = min((T_) + 2, n_tiles - 1), tv_ = min((T_) + 1, n_tiles - 1);                       \
-    const int ksrc_ = __builtin_amdgcn_readfirstlane(t_src[tk_]);                                       \
-    const int vsrc_ = __builtin_amdgcn_readfirstlane(t_src[tv_]);                                       \
+    const int ksrc_ = __builtin_amdgcn_readfirstlane(d_ksrc);                                           \
+    const int vsrc_ = __builtin_amdgcn_readfirstlane(d_vsrc);                                           \
+    const int vlast_ = (__builtin_amdgcn_readfirstlane(d_vmeta) & 0xFF) - 1;                            \
     plan.kp = PBSA_TILE_PTR(ksrc_, a.Kl, a.Kp);                                                         \
     plan.vp = PBSA_TILE_PTR(vsrc_, a.Vl, a.Vp);                                                         \
-    const int vlast_ = (__builtin_amdgcn_readfirstlane(t_meta[tv_]) & 0xFF) - 1;                        \
     _Pragma("unroll") for (int i_ = 0; i_ < NIW; ++i_) {                                                \
       const int piece_ = (i_ / PS) * 2 * PS + i_ % PS;                                                  \
       plan.voff[i_] = min(RPI * piece_ + plan.vrow_w, vlast_) * ROW + plan.vchk;                        \
     }                                                                                                   \
     plan.klds = wave_piece + ((T_) & 1) * TILE;                                                         \
     plan.vlds = wave_piece + (2 + (((T_) + 1) & 1)) * TILE;                                             \
+    PBSA_FETCH_DESC((T_) + 1)                                                                           \
   }
 #define PBSA_RUN_CLASS(GM, RAGGED, TB, TE)                                                                      \
   if ((TB) < (TE)) {                                                                                    \
@@ -671,6 +679,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int e0 = cls_end_s[0], e1 = cls_end_s[1], e2 = cls_end_s[2];
+    int d_ksrc, d_vsrc, d_vmeta;
+    PBSA_FETCH_DESC(0)
     PBSA_RUN_CLASS(3, false, 0, e0)
     if (G > 1) {
       PBSA_RUN_CLASS(1, false, e0, e1)
