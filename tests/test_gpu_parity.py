@@ -149,6 +149,23 @@ def test_small_rollout_every_element(gpu, case):
         run_both(gpu, c, st, Q, K, V, g, "all", name)
 
 
+def test_maximum_sizes(gpu):
+    """The limits of the interface at once: 512 local blocks, 64 persistent slots, 128 selected blocks per
+    query block, a ragged last block.  Cold start, so the window, the slots and the summary fill on the
+    way; selection and update exact on every chunk, attention rows sampled once the cache is full."""
+    H, d, B, w, C, k = 1, 128, 64, 3, 64, 128
+    Nq = 128 * B - 17                       # 128 query blocks, the last with 47 tokens
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    assert c.cap == 512
+    rows = sample_rows(H, Nq, B, per_head=64, seed=5)
+    for g in range(w + 3):
+        Q, K, V = rnd(200 + 3 * g, H, Nq, d), rnd(201 + 3 * g, H, Nq, d, scale=1.5), rnd(202 + 3 * g, H, Nq, d)
+        run_both(gpu, c, st, Q, K, V, g, rows if g >= w else None, "max_sizes")
+    assert (st.p_len[:, :C] > 0).all() and int(st.S_cnt.max()) > 0
+
+
 def test_empty_memory_and_no_selection_gives_zero(gpu):
     """No persistent block and k = 0: no key is visible; O = 0 and lse = -inf."""
     H, d, B, Nq = 1, 64, 64, 100
