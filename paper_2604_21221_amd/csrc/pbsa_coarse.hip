@@ -666,7 +666,7 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Fold + promote.  One thread owns 2 dimensions of one position t of K or V of one head: it adds
+// Fold + promote.  One thread owns 4 dimensions of one position t of K or V of one head: it adds
 // the dropped blocks' rows to the running sum in candidate order, rewrites the summary row, then
 // copies row t of every kept newcomer into its slot.  A slot that is both dropped and refilled is
 // read and written by the same thread, in that order.
@@ -685,72 +685,76 @@ struct FoldArgs {
   const int32_t* promo_slot;
 };
 
-constexpr int kFoldBatch = 80;
+constexpr int kFoldBatch = 40;
 
 __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
-  __shared__ int fsrc_s[kMaxCand], flen_s[kMaxCand], promo_s[PBSA_MAX_C];
+  // per dropped candidate: its valid length and the address of its K and of its V block
+  __shared__ const bf16_t* fptr_s[2][kMaxCand];
+  __shared__ int flen_s[kMaxCand], promo_s[PBSA_MAX_C];
   const int h = blockIdx.y;
   const int C = a.C, C1 = a.C + 1, ncand_max = a.C + a.n_evict;
   const int nf = a.fold && a.S_sum ? a.fold_n[h] : 0;
+  const size_t blk = (size_t)a.B * a.d;
   for (int f = threadIdx.x; f < nf; f += kThreads) {
-    fsrc_s[f] = a.fold_src[(size_t)h * ncand_max + f];
+    const int src = a.fold_src[(size_t)h * ncand_max + f];
     flen_s[f] = a.fold_len[(size_t)h * ncand_max + f];
+    fptr_s[0][f] = src < C ? a.Kp + ((size_t)h * C1 + src) * blk : a.Kl + ((size_t)h * a.n_loc_cap + (src - C)) * blk;
+    fptr_s[1][f] = src < C ? a.Vp + ((size_t)h * C1 + src) * blk : a.Vl + ((size_t)h * a.n_loc_cap + (src - C)) * blk;
   }
   for (int c = threadIdx.x; c < C; c += kThreads) promo_s[c] = a.promo_slot[(size_t)h * C + c];
   __syncthreads();
-  const int tpr = a.d / 2;                                     // threads per row: 2 dimensions each
+  const int tpr = a.d / 4;                                     // threads per row: 4 dimensions each
   const int rows_per_wg = kThreads / tpr;
   const int row = blockIdx.x * rows_per_wg + threadIdx.x / tpr; // over [2][B]
-  const int xc = (threadIdx.x % tpr) * 2;
+  const int xc = (threadIdx.x % tpr) * 4;
   if (row >= 2 * a.B) return;
   const int kv = row / a.B, t = row % a.B;
-  const size_t blk = (size_t)a.B * a.d;
   bf16_t* P = kv ? a.Vp : a.Kp;
   const bf16_t* L = kv ? a.Vl : a.Kl;
   const size_t rowoff = (size_t)t * a.d + xc;
-  const bf16_t* Ph = P + (size_t)h * C1 * blk + rowoff;
   const bf16_t* Lh = L + (size_t)h * a.n_loc_cap * blk + rowoff;
   // promoted rows are independent of the fold: fetch them all before it starts
-  uint32_t pv[PBSA_MAX_C];
+  uint2 pv[PBSA_MAX_C];
 #pragma unroll
   for (int u = 0; u < PBSA_MAX_C; ++u) {
     const int ps = u < C ? promo_s[u] : -1;
-    pv[u] = ps >= 0 ? *reinterpret_cast<const uint32_t*>(Lh + (size_t)ps * blk) : 0u;
+    pv[u] = ps >= 0 ? *reinterpret_cast<const uint2*>(Lh + (size_t)ps * blk) : make_uint2(0u, 0u);
   }
   if (nf > 0) {
     float* ssum = a.S_sum + ((size_t)h * 2 + kv) * blk + rowoff;
-    float2 acc = *reinterpret_cast<float2*>(ssum);
+    float4 acc = *reinterpret_cast<float4*>(ssum);
     const int cnt = a.S_cnt[(size_t)h * a.B + t];     // already the new count (retain_kernel)
     // rows are loaded kFoldBatch at a time (row t exists in every block, valid or not) and added in
     // candidate order, the add predicated on t < len
     for (int f0 = 0; f0 < nf; f0 += kFoldBatch) {
-      uint32_t v[kFoldBatch];
+      uint2 v[kFoldBatch];
 #pragma unroll
-      for (int u = 0; u < kFoldBatch; ++u) {
-        const int src = fsrc_s[min(f0 + u, nf - 1)];
-        const bf16_t* blkp = src < C ? Ph + (size_t)src * blk : Lh + (size_t)(src - C) * blk;
-        v[u] = *reinterpret_cast<const uint32_t*>(blkp);
-      }
+      for (int u = 0; u < kFoldBatch; ++u)
+        v[u] = *reinterpret_cast<const uint2*>(fptr_s[kv][min(f0 + u, nf - 1)] + rowoff);
 #pragma unroll
       for (int u = 0; u < kFoldBatch; ++u) {
         if (f0 + u < nf && t < flen_s[f0 + u]) {
-          acc.x = acc.x + bf_lo(v[u]);
-          acc.y = acc.y + bf_hi(v[u]);
+          acc.x = acc.x + bf_lo(v[u].x);
+          acc.y = acc.y + bf_hi(v[u].x);
+          acc.z = acc.z + bf_lo(v[u].y);
+          acc.w = acc.w + bf_hi(v[u].y);
         }
       }
     }
-    *reinterpret_cast<float2*>(ssum) = acc;
+    *reinterpret_cast<float4*>(ssum) = acc;
     if (cnt > 0) {
       const float fc = (float)cnt;
-      *reinterpret_cast<uint32_t*>(P + ((size_t)h * C1 + C) * blk + rowoff) =
-          f2bf_rne(acc.x / fc) | (f2bf_rne(acc.y / fc) << 16);
+      uint2 w;
+      w.x = f2bf_rne(acc.x / fc) | (f2bf_rne(acc.y / fc) << 16);
+      w.y = f2bf_rne(acc.z / fc) | (f2bf_rne(acc.w / fc) << 16);
+      *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + C) * blk + rowoff) = w;
     }
   }
   // promoted rows: stores after the fold's loads (a refilled slot was read above by this thread)
 #pragma unroll
   for (int u = 0; u < PBSA_MAX_C; ++u) {
     const int ps = u < C ? promo_s[u] : -1;
-    if (ps >= 0) *reinterpret_cast<uint32_t*>(P + ((size_t)h * C1 + u) * blk + rowoff) = pv[u];
+    if (ps >= 0) *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + u) * blk + rowoff) = pv[u];
   }
 }
 
@@ -892,7 +896,7 @@ hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_
 
   FoldArgs fa{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, fold, Kp, Vp, Kl, Vl, S_sum, S_cnt, ws.fold_n,
               ws.fold_src, ws.fold_len, ws.promo_slot};
-  const int rows_per_wg = kThreads / (p.d / 2);
+  const int rows_per_wg = kThreads / (p.d / 4);
   hipLaunchKernelGGL(fold_promote_kernel, dim3((2 * p.B + rows_per_wg - 1) / rows_per_wg, p.H), dim3(kThreads), 0,
                      stream, fa);
   return hipGetLastError();
