@@ -69,6 +69,50 @@ def cpu_baseline(w, n_rows=1536):
     return t_sel, t_att, t_upd, len(hh)
 
 
+def sweep_kernel_grid(dev, reps=20):
+    """pbsa_attention_fwd alone (block sets from pbsa_select_blocks on the same synthetic inputs) on the
+    kernel-benchmark shapes of the paper's appendix: N_C = 5376 query tokens (three 1792-token frames),
+    local KV N_L = 2 or 4 N_C, persistent KV N_P = 0.25 or 0.5 N_L, 12 heads of 128 (the paper does not
+    state heads), blocks of 128.  Shapes whose persistent set exceeds 64 blocks are left out.  The dense
+    stand-in is the same kernel with every visible block selected (block-causal within the chunk)."""
+    import numpy as np
+    import torch
+    from paper_2604_21221_amd import synth, workloads
+    rows = []
+    for ratio_l, ratio_p in ((2, 0.25), (2, 0.5), (4, 0.25)):
+        dense_us = None
+        for topk in (1.0, 0.25, 0.125, 0.0625):
+            w = synth.t7_workload(ratio_l, ratio_p, topk)
+            c, g0 = workloads.cache_for_workload(w, device=dev, fold=False)
+            Q, Kc, Vc = synth.chunk_qkv(w, 0, g0)
+            Qd = workloads.bf16_tensor(Q, dev)
+            c.append_chunk(workloads.bf16_tensor(Kc, dev), workloads.bf16_tensor(Vc, dev), g0)
+            c.select(Qd)
+            O = torch.empty_like(Qd)
+            for _ in range(3):
+                c.attention(Qd, O)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for a, b in ev:
+                a.record()
+                c.attention(Qd, O)
+                b.record()
+            torch.cuda.synchronize()
+            us = float(np.median([a.elapsed_time(b) for a, b in ev])) * 1e3
+            lens = torch.from_numpy(np.tile(synth.block_lens(w), w.window_chunks + 1)).to(dev)
+            flops = executed_flops(c.sel, c.p_len, lens, torch.from_numpy(synth.block_lens(w)).to(dev), w.d)
+            if topk >= 1.0:
+                dense_us = us
+            rows.append({"N_C": w.Nq, "N_L": w.n_loc * w.B, "N_P": w.C * w.B, "N_KV": (w.C + w.n_loc) * w.B,
+                         "top_k_pct": 100 * topk, "k_blocks": w.k, "us": round(us, 1),
+                         "tflops_executed": round(flops / us / 1e6, 1),
+                         "speedup_vs_all_blocks": round(dense_us / us, 2)})
+            del c
+            torch.cuda.empty_cache()
+    return {"metric": "pbsa_attention_fwd latency on the paper's kernel-benchmark shapes (forward)", "unit": "us",
+            "config": {"workload": "N_C=5376 (3 x 1792-token frames), H=12, d=128, B=128; synthetic bf16 inputs"},
+            "data": "synthetic", "dtype": "bf16", "n_gpus": 1, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +120,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-kernel-grid", action="store_true",
+                    help="instead of the step benchmark: pbsa_attention_fwd alone on the shapes of the paper's "
+                         "kernel benchmark (forward latency table of its appendix) that fit the interface limits, "
+                         "at top-k 6.25 / 12.5 / 25 % and with every block selected (the dense stand-in)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run three 1 GiB device copies and exit: the known-size kernel that the HBM byte "
                          "counters are scaled by")
@@ -95,6 +143,9 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": b.numel() * 4, "copies": 3}))
+        return
+    if args.sweep_kernel_grid:
+        print(json.dumps(sweep_kernel_grid(dev, reps=max(args.steps, 10))))
         return
     w = synth.WORKLOADS[args.workload]
     K, W = args.steps, args.warmup

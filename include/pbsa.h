@@ -75,7 +75,7 @@ extern "C" {
 
 #define PBSA_MAX_N_LOC 512 /* logical local blocks          */
 #define PBSA_MAX_C      64 /* persistent slots              */
-#define PBSA_MAX_K     128 /* selected blocks per query block */
+#define PBSA_MAX_K     512 /* selected blocks per query block */
 
 typedef struct pbsa_params {
   uint32_t size;            /* sizeof(pbsa_params); guards against ABI drift                        */

@@ -47,7 +47,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kThreads = 128;
 constexpr int kRowsPerWg = 128;
 constexpr int kTile = 64;                 // keys per staged tile
-constexpr int kMaxTiles = 2 * (PBSA_MAX_C + 1) + 2 * PBSA_MAX_K;   // persistent + local 64-key tiles
+constexpr int kMaxTiles = 2 * (PBSA_MAX_C + 1) + 2 * PBSA_MAX_N_LOC;   // persistent + local 64-key tiles
 constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
 constexpr float kInitMax = -1.0e29f;       // running max of a row that has seen no key: above kMasked, below any score
 // The softmax reference of a row follows its running max lazily: it moves (and the output

@@ -69,7 +69,7 @@ def call_update(p, ws=(0x10000, 1 << 30), S_sum=P, S_cnt=P, Qc=P):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(d=96), pbsa.PBSA_ESHAPE), (dict(B=32), pbsa.PBSA_ESHAPE), (dict(k=129), pbsa.PBSA_ESHAPE),
+    (dict(d=96), pbsa.PBSA_ESHAPE), (dict(B=32), pbsa.PBSA_ESHAPE), (dict(k=513), pbsa.PBSA_ESHAPE),
     (dict(C=65), pbsa.PBSA_ESHAPE), (dict(n_loc=513, n_loc_cap=513), pbsa.PBSA_ESHAPE),
     (dict(n_loc=2), pbsa.PBSA_EINVAL),               # fewer local blocks than the chunk itself has
     (dict(n_loc=17), pbsa.PBSA_EINVAL),              # more than the physical capacity

@@ -149,11 +149,13 @@ def test_small_rollout_every_element(gpu, case):
         run_both(gpu, c, st, Q, K, V, g, "all", name)
 
 
-def test_maximum_sizes(gpu):
-    """The limits of the interface at once: 512 local blocks, 64 persistent slots, 128 selected blocks per
-    query block, a ragged last block.  Cold start, so the window, the slots and the summary fill on the
-    way; selection and update exact on every chunk, attention rows sampled once the cache is full."""
-    H, d, B, w, C, k = 1, 128, 64, 3, 64, 128
+@pytest.mark.parametrize("k", [128, 512])
+def test_maximum_sizes(gpu, k):
+    """The limits of the interface at once: 512 local blocks, 64 persistent slots, a ragged last block, and
+    128 selected blocks per query block or all of them (k = 512 = the limit, every visible block).  Cold
+    start, so the window, the slots and the summary fill on the way; selection and update exact on every
+    chunk, attention rows sampled once the cache is full."""
+    H, d, B, w, C = 1, 128, 64, 3, 64
     Nq = 128 * B - 17                       # 128 query blocks, the last with 47 tokens
     scale = np.float32(1.0 / math.sqrt(d))
     st = OracleState(H, d, B, Nq, w, C, k, scale)
@@ -244,6 +246,19 @@ def test_full_size_single_step(gpu, name):
     for g in range(g0, g0 + 2):
         Q, K, V = synth.chunk_qkv(w, 0, g)
         run_both(gpu, c, st, Q, K, V, g, rows, name)
+
+
+@pytest.mark.parametrize("shape", [(2, 0.25, 0.25), (4, 0.25, 0.0625), (2, 0.5, 1.0)],
+                         ids=["L2_P25_top25", "L4_P25_top6", "L2_P50_all"])
+def test_kernel_grid_shapes(gpu, shape):
+    """Shapes of the paper's kernel benchmark (1792-token frames, blocks divide the chunk exactly), as the
+    sweep of bench.py runs them; selection and update exact, attention on sampled rows."""
+    w = synth.t7_workload(*shape)
+    st, g0 = state_for_workload(w)
+    c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
+    rows = sample_rows(w.H, w.Nq, w.B, per_head=16)
+    Q, K, V = synth.chunk_qkv(w, 0, g0)
+    run_both(gpu, c, st, Q, K, V, g0, rows, w.name)
 
 
 def test_cfg3_layers(gpu):
