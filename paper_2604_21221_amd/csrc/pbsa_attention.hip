@@ -1,18 +1,23 @@
 // PBSA fine stage (Eq. 3-5) for gfx950: block-sparse flash attention on bf16 MFMA.
 //
 // One workgroup = 2 waves = 128 consecutive query tokens of one head (one query block when B = 128,
-// two when B = 64).  A wave owns 64 query rows as two row groups of 32: group g of wave w holds rows
-// 64 g + 32 w .. + 31 of the workgroup, so with B = 64 group g of BOTH waves belongs to query block g
-// and the two waves always have the same amount of work.  Two workgroups share a CU, one wave per
-// SIMD, so a wave has the whole 512-entry register file of its SIMD.
+// two when B = 64).  Wave w owns rows 64 w .. 64 w + 63 of the workgroup as two row groups of 32, so
+// with B = 64 a wave is exactly one query block.  Two workgroups share a CU, one wave per SIMD, so a
+// wave has the whole 512-entry register file of its SIMD.
 //
-// The workgroup walks a tile list of 64-key tiles: every non-empty persistent slot (the dense part of
-// the mask, visible to all rows) and the union of the local blocks selected by its query blocks.  The
-// list is sorted by who attends a tile: first the full tiles both row groups attend, then those only
-// group 0 attends, then those only group 1 attends, last the ragged tiles (fewer than 64 valid keys).
-// The order of keys does not matter to an online softmax, and within a class every step runs the same
-// straight-line code.  K/V tiles go from global memory straight into LDS (global_load_lds, no
-// register round trip), two tiles per operand.
+// The workgroup walks a list of 64-key tiles: every non-empty persistent slot (the dense part of the
+// mask, visible to all rows) and the union of the local blocks selected by its query blocks, sorted by
+// who attends a tile:
+//   shared  full tiles both waves attend, then the ragged tiles (fewer than 64 valid keys, masked per
+//           wave).  The waves stage each tile together, two tiles per operand in flight, and meet at a
+//           barrier once per tile.
+//   solo    full tiles only one wave attends (B = 64: a block one query block selected and its
+//           neighbour did not).  After the shared part each wave streams its own tiles through its own
+//           half of the LDS in 32-key halves, with no barrier: both waves run at full width on different
+//           tiles, and since every query block selects the same number of blocks the two waves, and all
+//           workgroups, have the same amount of work however the selections overlap.
+// The order of keys does not matter to an online softmax.  K/V tiles go from global memory straight
+// into LDS (global_load_lds, no register round trip).
 //
 // MFMA arrangement (v_mfma_f32_32x32x16_bf16, wave64):
 //   S^T = K Q^T   A = K tile rows (32 keys x 16 dims), B = Q^T (16 dims x 32 query rows).
@@ -29,10 +34,10 @@
 // stretch of code cut into slots (one MFMA plus a slice of vector work each), the softmax of
 // sub-tile u (exp2, max, conversions; S^T(u) -> P^T(u)) together with the MFMAs that do not depend
 // on it: O^T += V^T P^T of sub-tile u-1 and S^T = K Q^T of sub-tile u+1.  S^T and P^T are double
-// buffered.  Each class of the list is one pipelined run with its own template instance (which row
-// groups take part, whether keys must be masked); the pipeline drains between classes.  Softmax is online, fp32, base 2 (scale and log2 e folded into one fma); row sums are
-// taken over the bf16-rounded probabilities (two per v_dot2c_f32_bf16), the same numbers the second
-// product uses.
+// buffered.  Each part of the list (shared full, shared ragged, solo) is one pipelined run with its
+// own template instance; the pipeline drains between them.  Softmax is online, fp32, base 2 (scale and
+// log2 e folded into one fma); row sums are taken over the bf16-rounded probabilities (two per
+// v_dot2c_f32_bf16), the same numbers the second product uses.
 #include "pbsa_internal.h"
 
 namespace pbsa {
@@ -50,11 +55,15 @@ constexpr int kTile = 64;                 // keys per staged tile
 constexpr int kMaxTiles = 2 * (PBSA_MAX_C + 1) + 2 * PBSA_MAX_N_LOC;   // persistent + local 64-key tiles
 constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
 constexpr float kInitMax = -1.0e29f;       // running max of a row that has seen no key: above kMasked, below any score
-// The softmax reference of a row follows its running max lazily: it moves (and the output
-// accumulators are rescaled) only when a new score exceeds it by more than kSlack in base-2 exponent
-// units, so probabilities stay below 2^kSlack -- harmless in bf16 / fp32, whose precision is relative --
-// and rescales are rare even when the scores of neighbouring tiles differ by orders of magnitude.
-constexpr float kSlack = 24.0f;
+// The softmax reference of a row is not its running max: probabilities only have to stay inside the
+// exponent range of bf16 / fp32, whose precision is relative.  The reference is set kLift base-2
+// exponent units above the row max of the tile that sets it, and moves (and the output accumulators are
+// rescaled: some 200 vector instructions per row group, and a wait for the other wave at the next
+// barrier) only when a score exceeds it by more than kSlack.  Probabilities then lie between 2^-126 and
+// 2^kSlack, their sums and products below about 2^90, and after the first tile of a row a rescale needs
+// scores that rise by a factor of 2^(kLift + kSlack).
+constexpr float kSlack = 60.0f;
+constexpr float kLift = 40.0f;
 
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {   // set bits of `mask` below this lane
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -104,6 +113,15 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint3
                :
                : "s"(lds_off), "v"(lane_off), "s"(base)
                : "memory");
+}
+// The same with a compile-time displacement of the LDS address, so that the loads of one plan share one
+// scalar LDS base instead of one precomputed address each.
+template <int LDS_IMM>
+__device__ __forceinline__ void dma16i(const void* base, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_base), "v"(lane_off), "s"(base), "n"(LDS_IMM)
+               : "memory", "scc");
 }
 
 template <int D>
@@ -176,10 +194,10 @@ __device__ __forceinline__ uint32_t prob_pair(float s0, float s1, float c2, floa
 }
 
 template <int DT>
-__device__ __forceinline__ void rescale(f32x16 (&o)[2][DT], const float (&alpha)[2], int gm) {
+__device__ __forceinline__ void rescale(f32x16 (&o)[2][DT], const float (&alpha)[2]) {
 #pragma unroll
   for (int g = 0; g < 2; ++g) {
-    if (((gm >> g) & 1) && __any(alpha[g] != 1.0f)) {
+    if (__any(alpha[g] != 1.0f)) {
       acc_settle<DT>(o[g]);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
@@ -191,64 +209,76 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[2][DT], const float (&alpha)
 }
 
 // ------------------------------------------------------------------------------------------------
-// One pipeline step: up to three parts on three different sub-tiles, for the row groups GM.
+// One pipeline step: up to three parts on three different sub-tiles, for both row groups of the wave.
 //   SM  softmax of the current sub-tile: s_cur -> p_cur (RAGGED: keys at or beyond lim[g] are masked)
 //   PV  O^T += V^T P^T of the previous sub-tile (p_prev, V fragments at vaddr + V_OFF)
 //   QK  S^T = K Q^T of the next sub-tile (s_next, K fragments at kaddr + K_OFF)
 // The step is a sequence of MFMA pairs, PV and QK alternating when both are present; the MFMAs of a
-// pair (one per row group) share one LDS fragment, read AHEAD pairs earlier.  After every MFMA comes
+// pair (one per row group) share one LDS fragment, read kAhead pairs earlier.  After every MFMA comes
 // a slice of the softmax, so the matrix pipe works while the VALU computes.  Nothing is allowed to
 // move across slot boundaries.
 // ------------------------------------------------------------------------------------------------
-// Staging loads that ride along a pipeline step: K of tile t+2 and V of tile t+1, one wave
-// instruction per slot from the step's first slot on.  Issued in one burst they would hold the wave at
-// the texture path (about 50 bytes per clock per CU) for a large part of a step; spread out, they
-// travel while the wave computes.
+// Staging loads that ride along a pipeline step, one wave instruction per slot from the step's first
+// slot on.  Issued in one burst they would hold the wave at the texture path (about 50 bytes per clock
+// per CU) for a large part of a step; spread out, they travel while the wave computes.
+//   shared part: K of tile t+2 and V of tile t+1, this wave's half of the pieces of each
+//   solo part:   the 32-key halves K(u+2) and V(u), all pieces, into this wave's own ring entries
+constexpr int kDmaNone = 0, kDmaShared = 1, kDmaSolo = 2;
 template <int D>
 struct DmaPlan {
   static constexpr int CH = D / 8, RPI = 64 / CH;   // 16-byte chunks per row, rows per wave instruction
-  static constexpr int NIW = (kTile / RPI) / 2;      // instructions per wave per tile
+  static constexpr int NIW = (kTile / RPI) / 2;      // instructions per wave per tile = per 32-key half
   static constexpr int PS = 8 / RPI > 0 ? 8 / RPI : 1;
+  static constexpr int NPAT = 16 / RPI;              // pieces per 16 rows, the period of the K permutation
   static constexpr int N = 2 * NIW;                  // K and V
-  const unsigned char* kp;    // source tiles
+  const unsigned char* kp;    // sources
   const unsigned char* vp;
-  uint32_t klds, vlds;        // LDS address of this wave's first piece in the destination ring entries
-  int koff[PS];               // per lane: source byte offset of each K pattern
-  int voff[NIW];              // per lane: source byte offset of each V piece, rows past the tile's valid
+  uint32_t klds, vlds;        // LDS address of this wave's first piece at the destination
+  int koff[PS];               // shared, per lane: source byte offset of each K pattern
+  int voff[NIW];              // shared, per lane: source byte offset of each V piece, rows past the tile's valid
                               // length replaced by its last valid row.  Computed when the plan is made and
                               // left alone until every load has been issued: an address register rewritten
                               // shortly after the load that uses it has produced wrong loads here.
-  int vrow_w, vchk;           // per lane: V source row of piece 0 and chunk byte offset
+  int vrow_w, vchk;           // shared, per lane: V source row of piece 0 and chunk byte offset
+  int ksolo[NPAT];            // solo, per lane: source byte offset of K piece e < NPAT (rows RPI e ..)
+  int vsolo;                  // solo, per lane: source byte offset within any V piece
 };
 
-template <int D, int IDX>
+template <int D, int MODE, int IDX>
 __device__ __forceinline__ void dma_issue(const DmaPlan<D>& p) {
   using P = DmaPlan<D>;
-  constexpr int i = IDX / 2, q = i / P::PS, e = i % P::PS, piece = q * 2 * P::PS + e;
-  if constexpr (IDX % 2 == 0)
-    dma16(p.kp + q * (2 * P::PS * P::RPI * Geo<D>::ROW), p.koff[e], p.klds + piece * 1024);
-  else
-    dma16(p.vp, p.voff[i], p.vlds + piece * 1024);
+  constexpr int i = IDX / 2;
+  if constexpr (MODE == kDmaShared) {
+    constexpr int q = i / P::PS, e = i % P::PS, piece = q * 2 * P::PS + e;
+    if constexpr (IDX % 2 == 0)
+      dma16i<piece * 1024>(p.kp + q * (2 * P::PS * P::RPI * Geo<D>::ROW), p.koff[e], p.klds);
+    else
+      dma16i<piece * 1024>(p.vp, p.voff[i], p.vlds);
+  } else {
+    if constexpr (IDX % 2 == 0)
+      dma16i<i * 1024>(p.kp + (i / P::NPAT) * (16 * Geo<D>::ROW), p.ksolo[i % P::NPAT], p.klds);
+    else
+      dma16i<i * 1024>(p.vp + i * (P::RPI * Geo<D>::ROW), p.vsolo, p.vlds);
+  }
 }
-template <int D, int LO, int HI>
+template <int D, int MODE, int LO, int HI>
 __device__ __forceinline__ void dma_issue_range(const DmaPlan<D>& p) {
   if constexpr (LO < HI) {
-    dma_issue<D, LO>(p);
-    dma_issue_range<D, LO + 1, HI>(p);
+    dma_issue<D, MODE, LO>(p);
+    dma_issue_range<D, MODE, LO + 1, HI>(p);
   }
 }
 
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED>
+constexpr int kAhead = 4;     // MFMA pairs between an operand read and its use
+
+template <int D, bool PV, bool QK, bool SM, bool RAGGED>
 struct StepCtx {
-  static constexpr int NG = (GM & 1) + ((GM >> 1) & 1);
-  static constexpr int G0 = (GM & 1) ? 0 : 1;       // first row group taking part
   static constexpr int NP = (PV ? Geo<D>::KS : 0) + (QK ? Geo<D>::KS : 0);   // MFMA pairs (PV has 2 DT = KS)
-  static constexpr int NC = NP * NG;                // slots
-  static constexpr int PRE = !SM ? 0 : (NC >= 16 * NG) ? 2 * NG : NG;        // slots that compute the row maxima
-  static constexpr int AHEAD = NG == 2 ? 4 : 6;     // pairs between an operand read and its MFMAs
+  static constexpr int NC = 2 * NP;                 // slots
+  static constexpr int PRE = !SM ? 0 : (NC >= 32) ? 4 : 2;                   // slots that compute the row maxima
   const uint32_t (&vaddr)[Geo<D>::DT];
   const uint32_t (&kaddr)[Geo<D>::KS];
-  float c2;
+  float c2, lift;                // log2(e) * softmax scale; kLift in units of the raw scores
   const bf16x8 (&qf)[2][Geo<D>::KS];
   f32x16 (&o)[2][Geo<D>::DT];
   f32x16 (&s_cur)[2];
@@ -270,9 +300,9 @@ constexpr bool pair_is_pv(int q) { return PV && (!QK || q % 2 == 0); }
 template <bool PV, bool QK>
 constexpr int pair_index(int q) { return (PV && QK) ? q / 2 : q; }
 
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
-__device__ __forceinline__ void load_frag(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
-  if constexpr (Q < StepCtx<D, GM, PV, QK, SM, RAGGED>::NP) {
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
+__device__ __forceinline__ void load_frag(StepCtx<D, PV, QK, SM, RAGGED>& c) {
+  if constexpr (Q < StepCtx<D, PV, QK, SM, RAGGED>::NP) {
     constexpr int i = pair_index<PV, QK>(Q);
     if constexpr (pair_is_pv<PV, QK>(Q)) {
       constexpr int j = i / Geo<D>::DT, dt = i % Geo<D>::DT;
@@ -283,8 +313,8 @@ __device__ __forceinline__ void load_frag(StepCtx<D, GM, PV, QK, SM, RAGGED>& c)
   }
 }
 
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int Q, int GRP>
-__device__ __forceinline__ void mfma_slot(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, int Q, int GRP>
+__device__ __forceinline__ void mfma_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
   constexpr int i = pair_index<PV, QK>(Q);
   if constexpr (pair_is_pv<PV, QK>(Q)) {
     constexpr int j = i / Geo<D>::DT, dt = i % Geo<D>::DT;
@@ -297,81 +327,81 @@ __device__ __forceinline__ void mfma_slot(StepCtx<D, GM, PV, QK, SM, RAGGED>& c)
 
 // Slice C of the softmax of s_cur: first the row maximum and the reference of each row group, then
 // the 8 probability pairs per group spread evenly over the remaining slices.
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int C>
-__device__ __forceinline__ void valu_slot(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
-  using S = StepCtx<D, GM, PV, QK, SM, RAGGED>;
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, int C>
+__device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
+  using S = StepCtx<D, PV, QK, SM, RAGGED>;
   if constexpr (!SM) {
   } else if constexpr (C < S::PRE) {
-    constexpr int per = S::PRE / S::NG;
+    constexpr int per = S::PRE / 2;
     if constexpr (C % per == per - 1) {
-      constexpr int grp = (C / per == 0) ? S::G0 : 1;
+      constexpr int grp = C / per;
       if constexpr (RAGGED) {
 #pragma unroll
         for (int v = 0; v < 16; ++v)       // accumulator element v is key 8 (v/4) + 4 half + v%4
           if (8 * (v / 4) + (v % 4) >= c.lim[grp]) c.s_cur[grp][v] = kMasked;
       }
       const float tmax = row_max(c.s_cur[grp]);
-      const float m_new = tmax * c.c2 > c.m_run[grp] * c.c2 + kSlack ? tmax : c.m_run[grp];
+      const float m_new = tmax * c.c2 > c.m_run[grp] * c.c2 + kSlack ? tmax + c.lift : c.m_run[grp];
       c.mc[grp] = -m_new * c.c2;
       c.alpha[grp] = __builtin_amdgcn_exp2f((c.m_run[grp] - m_new) * c.c2);
       c.m_run[grp] = m_new;
       c.psum[grp] = 0.0f;
     }
   } else {
-    constexpr int lo = (C - S::PRE) * (8 * S::NG) / (S::NC - S::PRE), hi = (C + 1 - S::PRE) * (8 * S::NG) / (S::NC - S::PRE);
+    constexpr int lo = (C - S::PRE) * 16 / (S::NC - S::PRE), hi = (C + 1 - S::PRE) * 16 / (S::NC - S::PRE);
 #pragma unroll
     for (int n = lo; n < hi; ++n) {
-      const int grp = (n / 8 == 0) ? S::G0 : 1, v = 2 * (n % 8);
+      const int grp = n / 8, v = 2 * (n % 8);
       const uint32_t w = prob_pair(c.s_cur[grp][v], c.s_cur[grp][v + 1], c.c2, c.mc[grp], c.psum[grp]);
       // a use that cannot move: keeps this slice's work in this slot (its results are needed only by the next step)
       asm volatile("" ::"v"(w), "v"(c.psum[grp]));
       c.p_cur[grp][v / 8][(v % 8) / 2] = w;
     }
     if constexpr (C == S::NC - 1) {
-      if constexpr (GM & 1) c.l_run[0] = c.l_run[0] * c.alpha[0] + c.psum[0];
-      if constexpr (GM & 2) c.l_run[1] = c.l_run[1] * c.alpha[1] + c.psum[1];
+      c.l_run[0] = c.l_run[0] * c.alpha[0] + c.psum[0];
+      c.l_run[1] = c.l_run[1] * c.alpha[1] + c.psum[1];
     }
   }
 }
 
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF, int I>
-__device__ __forceinline__ void run_slots(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
-  using S = StepCtx<D, GM, PV, QK, SM, RAGGED>;
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, int DMA, int K_OFF, int V_OFF, int I>
+__device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c) {
+  using S = StepCtx<D, PV, QK, SM, RAGGED>;
   if constexpr (I < S::NC) {
-    constexpr int Q = I / S::NG, k = I % S::NG;
-    if constexpr (k == 0) load_frag<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + S::AHEAD>(c);
-    mfma_slot<D, GM, PV, QK, SM, RAGGED, Q, (k == 0 ? S::G0 : 1)>(c);
-    if constexpr (DMA) {
+    constexpr int Q = I / 2, k = I % 2;
+    if constexpr (k == 0) load_frag<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + kAhead>(c);
+    mfma_slot<D, PV, QK, SM, RAGGED, Q, k>(c);
+    if constexpr (DMA != kDmaNone) {
       constexpr int ND = DmaPlan<D>::N, NS = S::NC < ND ? S::NC : ND;    // slots that carry loads
-      if constexpr (I < NS) dma_issue_range<D, I * ND / NS, (I + 1) * ND / NS>(c.dma);
+      if constexpr (I < NS) dma_issue_range<D, DMA, I * ND / NS, (I + 1) * ND / NS>(c.dma);
     }
-    valu_slot<D, GM, PV, QK, SM, RAGGED, I>(c);
+    valu_slot<D, PV, QK, SM, RAGGED, I>(c);
     __builtin_amdgcn_sched_barrier(0);
-    run_slots<D, GM, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, I + 1>(c);
+    run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, I + 1>(c);
   }
 }
 
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
-__device__ __forceinline__ void preload_frags(StepCtx<D, GM, PV, QK, SM, RAGGED>& c) {
-  if constexpr (Q < StepCtx<D, GM, PV, QK, SM, RAGGED>::AHEAD) {
-    load_frag<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q>(c);
-    preload_frags<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + 1>(c);
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
+__device__ __forceinline__ void preload_frags(StepCtx<D, PV, QK, SM, RAGGED>& c) {
+  if constexpr (Q < kAhead) {
+    load_frag<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q>(c);
+    preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + 1>(c);
   }
 }
 
 // K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
-template <int D, int GM, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF>
-__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS], float c2,
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, int DMA, int K_OFF, int V_OFF>
+__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS], float c2, float lift,
                                      const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
                                      f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], const u32x4 (&p_prev)[2][2],
                                      float (&m_run)[2], float (&l_run)[2], float (&alpha)[2], const int (&lim)[2],
                                      const DmaPlan<D>& dma) {
   static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
-  StepCtx<D, GM, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, qf, o, s_cur, s_next, p_cur, p_prev, m_run, l_run, alpha, lim, dma,
-                                       {}, {0, 0}, {0, 0}};
-  preload_frags<D, GM, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
+  StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, lift, qf, o, s_cur, s_next, p_cur, p_prev, m_run, l_run, alpha, lim, dma,
+                                   {}, {0, 0}, {0, 0}};
+  preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
   __builtin_amdgcn_sched_barrier(0);
-  run_slots<D, GM, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
+  run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
 }
 
 #pragma clang diagnostic push
@@ -389,8 +419,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 
   __shared__ __align__(1024) unsigned char smem[SMEM];
   __shared__ int t_src[kMaxTiles];         // bit 31: local, bits 0..: (slot * SUB + sub)
-  __shared__ int t_meta[kMaxTiles];        // valid keys (bits 0..7) | row groups that attend (bits 8, 9)
-  __shared__ int n_tiles_s, cls_end_s[4];  // list length; end of each class's range
+  __shared__ int t_meta[kMaxTiles];        // valid keys (bits 0..7) | waves that attend (bits 8, 9)
+  __shared__ int cls_end_s[4];             // end of each part of the list
   int* lflag = reinterpret_cast<int*>(smem);        // setup scratch, dead before the first tile is staged
 
   // XCD-aware mapping: consecutive workgroup ids go round-robin to the 8 XCDs, so give XCD x the
@@ -402,18 +432,18 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   if (logical >= n_wg) return;
   const int h = logical / n_qt;
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int T0 = (logical % n_qt) * kRowsPerWg;
   const int i0 = T0 / B;
   const int qn = lane & 31, half = lane >> 5;
 
   // ---- Q fragments (B operand of S^T = K Q^T): row group g, query row lane % 32, dims 16 ks + 8 (lane/32) ..+8.
   // Issued first so the loads fly while the tile list is built.
-  const int tok0 = T0 + wave * 32 + qn;                 // row group g holds token tok0 + 64 g
+  const int tok0 = T0 + wave * 64 + qn;                 // row group g holds token tok0 + 32 g
   bf16x8 qf[2][KS];
 #pragma unroll
   for (int g = 0; g < 2; ++g) {
-    const int tok_c = min(tok0 + 64 * g, a.Nq - 1);
+    const int tok_c = min(tok0 + 32 * g, a.Nq - 1);
     const bf16_t* qrow = a.Q + (size_t)h * a.q_stride_h + (size_t)tok_c * a.q_stride_t + 8 * half;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[g][ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks);
@@ -427,9 +457,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 
   // ---- tile list --------------------------------------------------------------------------------
   // Everything the list needs is fetched from global memory in one parallel round into LDS scratch:
-  // per local block the set of query blocks that selected it, its length and its physical slot;
+  // per local block the set of waves whose query block selected it, its length and its physical slot;
   // per persistent slot its length.  Wave 0 then compacts both into the list with ballots, one pass
-  // per class: full tiles of both row groups, of group 0 only, of group 1 only, then ragged tiles.
+  // per part: full tiles of both waves, ragged tiles, full tiles of wave 0 only, of wave 1 only.
   int* llen_s = lflag + PBSA_MAX_N_LOC;
   int* lmap_s = llen_s + PBSA_MAX_N_LOC;
   int* plen_s = lmap_s + PBSA_MAX_N_LOC;
@@ -444,7 +474,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     const int g = idx / a.k, j = idx % a.k;
     if (i0 + g < a.nqb) {
       const int l = a.sel[((size_t)h * a.nqb + i0 + g) * a.k + j];
-      // with one query block per workgroup both row groups belong to it
+      // with one query block per workgroup both waves belong to it
       if (l >= 0 && l < a.n_loc) atomicOr(&lflag[l], G == 1 ? 3 : 1 << g);
     }
   }
@@ -453,12 +483,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     int n = 0;
     for (int cls = 0; cls < 4; ++cls) {
       for (int s = 0; s < SUB; ++s) {
-        if (cls == 0 || cls == 3) {
+        if (cls < 2) {
           for (int c0 = 0; c0 <= a.C; c0 += 64) {
             const int c = c0 + lane;
             const int len = c <= a.C ? min(max(plen_s[c], 0), B) : 0;
             const int tl = min(max(len - s * kTile, 0), kTile);
-            const bool take = tl > 0 && (tl == kTile ? cls == 0 : cls == 3);
+            const bool take = tl > 0 && (tl == kTile ? cls == 0 : cls == 1);
             const unsigned long long m = __ballot(take);
             if (take) {
               const int pos = n + lanes_below(m);
@@ -478,7 +508,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
             if (slot < 0 || slot >= a.n_loc_cap) len = 0;
           }
           const int tl = min(max(len - s * kTile, 0), kTile);
-          const int my_cls = tl < kTile ? 3 : f == 3 ? 0 : f;      // f is 1 or 2 otherwise
+          const int my_cls = tl < kTile ? 1 : f == 3 ? 0 : f + 1;      // f is 1 or 2 otherwise
           const bool take = f != 0 && tl > 0 && my_cls == cls;
           const unsigned long long m = __ballot(take);
           if (take) {
@@ -491,10 +521,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
       }
       if (lane == 0) cls_end_s[cls] = n;
     }
-    if (lane == 0) n_tiles_s = n;
   }
   __syncthreads();
-  const int n_tiles = n_tiles_s;
+  const int e0 = cls_end_s[0];             // shared full tiles [0, e0)
+  const int n_tiles = cls_end_s[1];        // shared ragged tiles [e0, n_tiles): the end of the shared list
+  const int solo_b = wave == 0 ? n_tiles : cls_end_s[2];       // this wave's solo tiles [solo_b, solo_e)
+  const int solo_e = wave == 0 ? cls_end_s[2] : cls_end_s[3];
 
   f32x16 o[2][DT];
 #pragma unroll
@@ -508,7 +540,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   f32x16 sA[2], sB[2];                     // S^T of even / odd sub-tiles
   u32x4 pA[2][2], pB[2][2];                // P^T of even / odd sub-tiles (bf16 pairs)
   float m_run[2] = {kInitMax, kInitMax}, l_run[2] = {0.0f, 0.0f}, alpha[2] = {1.0f, 1.0f};
-  const float c2 = a.scale * 1.4426950408889634f;
+  const float c2 = a.scale * 1.4426950408889634f, lift = kLift / c2;
 
   // ---- operand addresses ------------------------------------------------------------------------
   // this lane's fragment addresses inside ring entry 0, sub-tile 0 (LDS byte addresses)
@@ -531,12 +563,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   // chunk i % CH, i.e. the logical chunk (i % CH) ^ f(row) of that row.  The tile has 2 NIW such
   // pieces; piece m covers rows RPI m ...  Since f has period 16 in the row (K) or depends on the row
   // within the piece only (V), the per-lane source offsets of all pieces a wave issues come from a few
-  // patterns plus a multiple of the piece size, which goes into the scalar base: wave w issues the
-  // pieces m = PS (w + 2 q) + e, e < PS, q < NIW / PS, where PS pieces make 16 rows, and pieces with
-  // equal e share a pattern.  A ragged V tile must not bring rows past its valid length into LDS (they
-  // meet p = 0 in the MFMA, and 0 x NaN-or-Inf pattern is NaN): the lanes of such rows fetch the last
-  // valid row instead.
-  constexpr int PS = 8 / RPI > 0 ? 8 / RPI : 1;     // patterns per wave
+  // patterns plus a multiple of the piece size, which goes into the scalar base.  Shared tiles: wave w
+  // issues the pieces m = PS (w + 2 q) + e, e < PS, q < NIW / PS, where PS pieces make 16 rows, and
+  // pieces with equal e share a pattern.  A ragged V tile must not bring rows past its valid length
+  // into LDS (they meet p = 0 in the MFMA, and 0 x NaN-or-Inf pattern is NaN): the lanes of such rows
+  // fetch the last valid row instead.  Solo tiles: a wave issues all NIW pieces of a 32-key half.
+  constexpr int PS = DmaPlan<D>::PS, NPAT = DmaPlan<D>::NPAT;
   constexpr int NQ = NIW / PS;
   int koff[PS], voff_w, vrow_w, vchk;
   {
@@ -589,8 +621,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     }                                                                                                   \
   }
 
-  // One class of the list, tiles [TB, TE), as one pipelined run.  Tile t is sub-tiles 2t (buffers A)
-  // and 2t+1 (buffers B):
+  // One part of the shared list, tiles [TB, TE), as one pipelined run.  Tile t is sub-tiles 2t (buffers
+  // A) and 2t+1 (buffers B):
   //   before   : QK(TB,0)
   //   step 2t  : softmax(t,0)  with  PV(t-1,1) (not for t = TB)  and  QK(t,1)
   //   step 2t+1: softmax(t,1)  with  PV(t,0)                     and  QK(t+1,0) (not for t = TE-1)
@@ -598,8 +630,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   // Between the two steps of a tile the tiles K(t) and V(t-1) are dead: their ring entries are refilled
   // with K(t+2) and V(t+1), which have until the same point of the next tile to arrive.  Steps 2t+1 and
   // 2t+2 read the same two ring entries (V of t, K of t+1), so the loop body is that pair and takes one
-  // set of addresses.  A ragged class runs both row groups and masks, per tile, the keys that do not
-  // exist and the group that does not attend.
+  // set of addresses.  The ragged run masks, per tile, the keys that do not exist and the wave that does
+  // not attend.
 #define PBSA_ADDR_K(T_)                                                                                 \
   _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) kx[ks] = ka0[ks] + ((T_) & 1) * TILE;
 #define PBSA_ADDR_V(T_)                                                                                 \
@@ -608,11 +640,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   if (RAGGED) {                                                                                         \
     const int meta_ = __builtin_amdgcn_readfirstlane(t_meta[T_]);                                       \
     const int len_ = meta_ & 0xFF;                                                                      \
-    _Pragma("unroll") for (int g = 0; g < 2; ++g) {                                                     \
-      const bool on_ = (meta_ >> (8 + g)) & 1;                                                          \
-      lim0[g] = (on_ ? min(len_, 32) : 0) - 4 * half;                                                   \
-      lim1[g] = (on_ ? max(len_ - 32, 0) : 0) - 4 * half;                                               \
-    }                                                                                                   \
+    const bool on_ = (meta_ >> (8 + wave)) & 1;                                                         \
+    lim0[0] = lim0[1] = (on_ ? min(len_, 32) : 0) - 4 * half;                                           \
+    lim1[0] = lim1[1] = (on_ ? max(len_ - 32, 0) : 0) - 4 * half;                                       \
   }
   // The loads of K(T_+2) and V(T_+1) ride along the step that follows.  Past the end of the list the
   // last tile is fetched again: the ring entries it lands in are dead and never read.  The descriptors
@@ -641,32 +671,32 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     plan.vlds = wave_piece + (2 + (((T_) + 1) & 1)) * TILE;                                             \
     PBSA_FETCH_DESC((T_) + 1)                                                                           \
   }
-#define PBSA_RUN_CLASS(GM, RAGGED, TB, TE)                                                                      \
+#define PBSA_RUN_SHARED(RAGGED, TB, TE)                                                                 \
   if ((TB) < (TE)) {                                                                                    \
     uint32_t kx[KS], vx[DT];                                                                            \
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
     PBSA_ADDR_K(TB)                                                                                     \
     PBSA_ADDR_V(TB)                                                                                     \
-    step<D, GM, false, true, false, false, false, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan); \
+    step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan); \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
-    step<D, GM, false, true, true, RAGGED, false, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
-    rescale<DT>(o, alpha, GM);                                                                          \
+    step<D, false, true, true, RAGGED, kDmaNone, SUB1, 0>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
+    rescale<DT>(o, alpha);                                                                              \
     PBSA_TURNOVER(TB)                                                                                   \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, GM, true, true, true, RAGGED, true, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
-      rescale<DT>(o, alpha, GM);                                                                        \
+      step<D, true, true, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
+      rescale<DT>(o, alpha);                                                                            \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
-      step<D, GM, true, true, true, RAGGED, false, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
-      rescale<DT>(o, alpha, GM);                                                                        \
+      step<D, true, true, true, RAGGED, kDmaNone, SUB1, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
+      rescale<DT>(o, alpha);                                                                            \
       PBSA_TURNOVER(t + 1)                                                                              \
     }                                                                                                   \
     PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, GM, true, false, true, RAGGED, true, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
-    rescale<DT>(o, alpha, GM);                                                                          \
-    step<D, GM, true, false, false, false, false, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
-    /* between classes the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
+    step<D, true, false, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
+    rescale<DT>(o, alpha);                                                                              \
+    step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
+    /* between runs the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
     acc_settle<DT>(o[0]);                                                                               \
     acc_settle<DT>(o[1]);                                                                               \
   }
@@ -678,15 +708,86 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     PBSA_ISSUE_V(0, 0)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    const int e0 = cls_end_s[0], e1 = cls_end_s[1], e2 = cls_end_s[2];
     int d_ksrc, d_vsrc, d_vmeta;
     PBSA_FETCH_DESC(0)
-    PBSA_RUN_CLASS(3, false, 0, e0)
-    if (G > 1) {
-      PBSA_RUN_CLASS(1, false, e0, e1)
-      PBSA_RUN_CLASS(2, false, e1, e2)
+    PBSA_RUN_SHARED(false, 0, e0)
+    PBSA_RUN_SHARED(true, e0, n_tiles)
+  }
+
+  // ---- solo part ----------------------------------------------------------------------------------
+  // Wave w streams its own full local tiles [solo_b, solo_e) through ring entry w of K and of V, which
+  // it treats as two 32-key halves.  Sub-tile u = 2t + h lives in half h; in step u the wave computes
+  // softmax(u), PV(u-1) from the other V half and QK(u+1) from the other K half, while the halves it
+  // has finished with are refilled with K(u+2) and V(u), which must have landed when the step ends.
+  //   before   : QK(2 TB)
+  //   step 2t  : softmax(2t)    PV(2t-1) (not for t = TB)   QK(2t+1)        loads K(t+1, half 0), V(t, half 0)
+  //   step 2t+1: softmax(2t+1)  PV(2t)                      QK(2t+2) (not for t = TE-1)   K(t+1, half 1), V(t, half 1)
+  //   after    : PV(2 TE - 1)
+  // These are the step instances of the shared loop with another load plan.  Past the end of the list
+  // the last tile's K is fetched again into halves that are never read.
+  if constexpr (G > 1) {
+    // the other wave may still read the rings, and the shared part's trailing loads may still land in them
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (solo_b < solo_e) {
+      {
+        const int rl = lane / CH, c = lane % CH;
+#pragma unroll
+        for (int e = 0; e < NPAT; ++e) {
+          const int r = RPI * e + rl;
+          plan.ksolo[e] = r * ROW + ((c ^ k_swz<D>(r)) << 4);
+        }
+        plan.vsolo = rl * ROW + vchk;
+      }
+      const unsigned char* kl_h = reinterpret_cast<const unsigned char*>(a.Kl) + head_l;
+      const unsigned char* vl_h = reinterpret_cast<const unsigned char*>(a.Vl) + head_l;
+      const uint32_t kring = __builtin_amdgcn_readfirstlane(smem_lds + wave * TILE);
+      const uint32_t vring = __builtin_amdgcn_readfirstlane(smem_lds + (2 + wave) * TILE);
+      uint32_t kx[KS], vx[DT];
+      const int lim0[2] = {0, 0};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kx[ks] = ka0[ks] + wave * TILE;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) vx[dt] = va0[dt] + wave * TILE;
+      int d_cur = t_src[solo_b], d_next = t_src[min(solo_b + 1, solo_e - 1)], d_nn;
+      // sources of the loads of the steps of tile t: K from tile t+1, V from tile t; HALF picks the rows
+#define PBSA_SOLO_PLAN(HALF)                                                                            \
+  plan.kp = kl_h + (size_t)(__builtin_amdgcn_readfirstlane(d_next) & 0x7FFFFFFF) * (kTile * D * 2) + (HALF) * SUB1; \
+  plan.vp = vl_h + (size_t)(__builtin_amdgcn_readfirstlane(d_cur) & 0x7FFFFFFF) * (kTile * D * 2) + (HALF) * SUB1;  \
+  plan.klds = kring + (HALF) * SUB1;                                                                    \
+  plan.vlds = vring + (HALF) * SUB1;
+#define PBSA_SOLO_LANDED asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      {
+        const unsigned char* kp_ = kl_h + (size_t)(__builtin_amdgcn_readfirstlane(d_cur) & 0x7FFFFFFF) * (kTile * D * 2);
+#pragma unroll
+        for (int i = 0; i < 2 * NIW; ++i)
+          dma16(kp_ + (i / NPAT) * (16 * ROW), plan.ksolo[i % NPAT], kring + i * 1024);
+      }
+      PBSA_SOLO_LANDED
+      step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan);
+      PBSA_SOLO_PLAN(0)
+      step<D, false, true, true, false, kDmaSolo, SUB1, 0>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan);
+      rescale<DT>(o, alpha);
+      PBSA_SOLO_LANDED
+      for (int t = solo_b; t < solo_e - 1; ++t) {
+        d_nn = t_src[min(t + 2, solo_e - 1)];
+        PBSA_SOLO_PLAN(1)
+        step<D, true, true, true, false, kDmaSolo, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan);
+        rescale<DT>(o, alpha);
+        PBSA_SOLO_LANDED
+        d_cur = d_next;
+        d_next = d_nn;
+        PBSA_SOLO_PLAN(0)
+        step<D, true, true, true, false, kDmaSolo, SUB1, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan);
+        rescale<DT>(o, alpha);
+        PBSA_SOLO_LANDED
+      }
+      PBSA_SOLO_PLAN(1)
+      step<D, true, false, true, false, kDmaSolo, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan);
+      rescale<DT>(o, alpha);
+      PBSA_SOLO_LANDED
+      step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan);
     }
-    PBSA_RUN_CLASS(3, true, e2, n_tiles)
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
@@ -696,7 +797,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   for (int g = 0; g < 2; ++g) {
     const float l_tot = l_run[g] + __shfl_xor(l_run[g], 32, 64);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-    const int tok = tok0 + 64 * g;
+    const int tok = tok0 + 32 * g;
     if (tok < a.Nq) {
       bf16_t* orow = a.O + (size_t)h * a.o_stride_h + (size_t)tok * a.o_stride_t;
 #pragma unroll
