@@ -57,12 +57,15 @@ constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
 constexpr float kInitMax = -1.0e29f;       // running max of a row that has seen no key: above kMasked, below any score
 // The softmax reference of a row is not its running max: probabilities only have to stay inside the
 // exponent range of bf16 / fp32, whose precision is relative.  The reference is set kLift base-2
-// exponent units above the row max of the tile that sets it, and moves (and the output accumulators are
-// rescaled: some 200 vector instructions per row group, and a wait for the other wave at the next
-// barrier) only when a score exceeds it by more than kSlack.  Probabilities then lie between 2^-126 and
-// 2^kSlack, their sums and products below about 2^90, and after the first tile of a row a rescale needs
-// scores that rise by a factor of 2^(kLift + kSlack).
+// exponent units above the row max of the sub-tile that sets it and is then used as it stands: a step
+// computes no row maximum.  Whether a reference still serves is read off the row sums the step produces
+// anyway: a probability above 2^kSlack (or an overflow) makes its row's partial sum exceed kBig, and only
+// then is the sub-tile's softmax redone with a new reference and the output accumulators rescaled
+// (softmax_settle).  Probabilities thus lie between 2^-126 and 2^kSlack, their sums and products below
+// about 2^90, and after the first sub-tile of a row a new reference needs scores that rise by a factor
+// of 2^(kLift + kSlack).
 constexpr float kSlack = 60.0f;
+constexpr float kBig = 0x1p60f;            // 2^kSlack
 constexpr float kLift = 40.0f;
 
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {   // set bits of `mask` below this lane
@@ -275,23 +278,21 @@ template <int D, bool PV, bool QK, bool SM, bool RAGGED>
 struct StepCtx {
   static constexpr int NP = (PV ? Geo<D>::KS : 0) + (QK ? Geo<D>::KS : 0);   // MFMA pairs (PV has 2 DT = KS)
   static constexpr int NC = 2 * NP;                 // slots
-  static constexpr int PRE = !SM ? 0 : (NC >= 32) ? 4 : 2;                   // slots that compute the row maxima
+  static constexpr int PRE = SM && RAGGED ? 2 : 0;  // slots that mask the keys that do not exist
   const uint32_t (&vaddr)[Geo<D>::DT];
   const uint32_t (&kaddr)[Geo<D>::KS];
-  float c2, lift;                // log2(e) * softmax scale; kLift in units of the raw scores
+  float c2;                      // log2(e) * softmax scale
   const bf16x8 (&qf)[2][Geo<D>::KS];
   f32x16 (&o)[2][Geo<D>::DT];
   f32x16 (&s_cur)[2];
   f32x16 (&s_next)[2];
   u32x4 (&p_cur)[2][2];
   const u32x4 (&p_prev)[2][2];
-  float (&m_run)[2];
-  float (&l_run)[2];
-  float (&alpha)[2];
+  const float (&mc)[2];          // minus the softmax reference of each row group, times c2
+  float (&psum)[2];              // out: this lane's sum of the probabilities of s_cur, per row group
   const int (&lim)[2];           // RAGGED: valid keys of the current sub-tile minus 4 * half, per row group
   const DmaPlan<D>& dma;
   bf16x8 frag[2 * Geo<D>::KS];   // operand fragment of each MFMA pair
-  float mc[2], psum[2];
 };
 
 // pair q: with both products, even q is PV pair q/2 and odd q is QK pair q/2
@@ -325,29 +326,18 @@ __device__ __forceinline__ void mfma_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
   }
 }
 
-// Slice C of the softmax of s_cur: first the row maximum and the reference of each row group, then
-// the 8 probability pairs per group spread evenly over the remaining slices.
+// Slice C of the softmax of s_cur: in a ragged step first the masking of each row group, then the 8
+// probability pairs per group spread evenly over the remaining slices.
 template <int D, bool PV, bool QK, bool SM, bool RAGGED, int C>
 __device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
   using S = StepCtx<D, PV, QK, SM, RAGGED>;
   if constexpr (!SM) {
   } else if constexpr (C < S::PRE) {
-    constexpr int per = S::PRE / 2;
-    if constexpr (C % per == per - 1) {
-      constexpr int grp = C / per;
-      if constexpr (RAGGED) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v)       // accumulator element v is key 8 (v/4) + 4 half + v%4
-          if (8 * (v / 4) + (v % 4) >= c.lim[grp]) c.s_cur[grp][v] = kMasked;
-      }
-      const float tmax = row_max(c.s_cur[grp]);
-      const float m_new = tmax * c.c2 > c.m_run[grp] * c.c2 + kSlack ? tmax + c.lift : c.m_run[grp];
-      c.mc[grp] = -m_new * c.c2;
-      c.alpha[grp] = __builtin_amdgcn_exp2f((c.m_run[grp] - m_new) * c.c2);
-      c.m_run[grp] = m_new;
-      c.psum[grp] = 0.0f;
-    }
+    for (int v = 0; v < 16; ++v)           // accumulator element v is key 8 (v/4) + 4 half + v%4
+      if (8 * (v / 4) + (v % 4) >= c.lim[C]) c.s_cur[C][v] = kMasked;
   } else {
+    if constexpr (C == S::PRE) c.psum[0] = c.psum[1] = 0.0f;
     constexpr int lo = (C - S::PRE) * 16 / (S::NC - S::PRE), hi = (C + 1 - S::PRE) * 16 / (S::NC - S::PRE);
 #pragma unroll
     for (int n = lo; n < hi; ++n) {
@@ -356,10 +346,6 @@ __device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
       // a use that cannot move: keeps this slice's work in this slot (its results are needed only by the next step)
       asm volatile("" ::"v"(w), "v"(c.psum[grp]));
       c.p_cur[grp][v / 8][(v % 8) / 2] = w;
-    }
-    if constexpr (C == S::NC - 1) {
-      c.l_run[0] = c.l_run[0] * c.alpha[0] + c.psum[0];
-      c.l_run[1] = c.l_run[1] * c.alpha[1] + c.psum[1];
     }
   }
 }
@@ -391,17 +377,47 @@ __device__ __forceinline__ void preload_frags(StepCtx<D, PV, QK, SM, RAGGED>& c)
 
 // K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
 template <int D, bool PV, bool QK, bool SM, bool RAGGED, int DMA, int K_OFF, int V_OFF>
-__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS], float c2, float lift,
+__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS], float c2,
                                      const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
                                      f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], const u32x4 (&p_prev)[2][2],
-                                     float (&m_run)[2], float (&l_run)[2], float (&alpha)[2], const int (&lim)[2],
+                                     const float (&mc)[2], float (&psum)[2], const int (&lim)[2],
                                      const DmaPlan<D>& dma) {
   static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
-  StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, lift, qf, o, s_cur, s_next, p_cur, p_prev, m_run, l_run, alpha, lim, dma,
-                                   {}, {0, 0}, {0, 0}};
+  StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, qf, o, s_cur, s_next, p_cur, p_prev, mc, psum, lim, dma, {}};
   preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
   __builtin_amdgcn_sched_barrier(0);
   run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
+}
+
+// After a step with a softmax.  Normally the row sums join the running sums and that is all.  If a sum
+// says that the reference of some row no longer serves (or was never set: a row's first keys), the
+// softmax of the sub-tile is redone here, outside the pipeline, for both row groups: row maxima, new
+// references where a score is more than kSlack above the old one (the other rows keep theirs and get the
+// same probabilities again), probabilities, running sums; the caller then rescales the output
+// accumulators by alpha unless nothing has been added to them yet.  The next step takes p and the new
+// references.  Returns whether the softmax was redone (the same answer in every lane).
+template <int D>
+__device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[2][2], float (&m_ref)[2], float (&mc)[2],
+                                               float (&l_run)[2], const float (&psum)[2], float (&alpha)[2], float c2,
+                                               float lift) {
+  if (__builtin_expect(__any(!(psum[0] <= kBig) || !(psum[1] <= kBig)), 0)) {
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const float tmax = row_max(s[g]);
+      const float m_new = tmax * c2 > m_ref[g] * c2 + kSlack ? tmax + lift : m_ref[g];
+      alpha[g] = __builtin_amdgcn_exp2f((m_ref[g] - m_new) * c2);
+      m_ref[g] = m_new;
+      mc[g] = -m_new * c2;
+      float ps = 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) p[g][v / 8][(v % 8) / 2] = prob_pair(s[g][v], s[g][v + 1], c2, mc[g], ps);
+      l_run[g] = l_run[g] * alpha[g] + ps;
+    }
+    return true;
+  }
+  l_run[0] += psum[0];
+  l_run[1] += psum[1];
+  return false;
 }
 
 #pragma clang diagnostic push
@@ -539,8 +555,9 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     }
   f32x16 sA[2], sB[2];                     // S^T of even / odd sub-tiles
   u32x4 pA[2][2], pB[2][2];                // P^T of even / odd sub-tiles (bf16 pairs)
-  float m_run[2] = {kInitMax, kInitMax}, l_run[2] = {0.0f, 0.0f}, alpha[2] = {1.0f, 1.0f};
   const float c2 = a.scale * 1.4426950408889634f, lift = kLift / c2;
+  float m_ref[2] = {kInitMax, kInitMax}, mc[2] = {-kInitMax * c2, -kInitMax * c2}, l_run[2] = {0.0f, 0.0f}, psum[2], alpha[2];
+  bool o_live = false;                     // something has been added to the output accumulators
 
   // ---- operand addresses ------------------------------------------------------------------------
   // this lane's fragment addresses inside ring entry 0, sub-tile 0 (LDS byte addresses)
@@ -677,25 +694,25 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
     PBSA_ADDR_K(TB)                                                                                     \
     PBSA_ADDR_V(TB)                                                                                     \
-    step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan); \
+    step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan); \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
-    step<D, false, true, true, RAGGED, kDmaNone, SUB1, 0>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
-    rescale<DT>(o, alpha);                                                                              \
+    step<D, false, true, true, RAGGED, kDmaNone, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan); \
+    if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha); o_live = true;                                                                              \
     PBSA_TURNOVER(TB)                                                                                   \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, true, true, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
-      rescale<DT>(o, alpha);                                                                            \
+      step<D, true, true, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim1, plan); \
+      if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);                                                                            \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
-      step<D, true, true, true, RAGGED, kDmaNone, SUB1, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
-      rescale<DT>(o, alpha);                                                                            \
+      step<D, true, true, true, RAGGED, kDmaNone, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan); \
+      if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);                                                                            \
       PBSA_TURNOVER(t + 1)                                                                              \
     }                                                                                                   \
     PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, true, false, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim1, plan); \
-    rescale<DT>(o, alpha);                                                                              \
-    step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan); \
+    step<D, true, false, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim1, plan); \
+    if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);                                                                              \
+    step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan); \
     /* between runs the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
     acc_settle<DT>(o[0]);                                                                               \
     acc_settle<DT>(o[1]);                                                                               \
@@ -764,29 +781,29 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
           dma16(kp_ + (i / NPAT) * (16 * ROW), plan.ksolo[i % NPAT], kring + i * 1024);
       }
       PBSA_SOLO_LANDED
-      step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan);
+      step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan);
       PBSA_SOLO_PLAN(0)
-      step<D, false, true, true, false, kDmaSolo, SUB1, 0>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan);
-      rescale<DT>(o, alpha);
+      step<D, false, true, true, false, kDmaSolo, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan);
+      if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha); o_live = true;
       PBSA_SOLO_LANDED
       for (int t = solo_b; t < solo_e - 1; ++t) {
         d_nn = t_src[min(t + 2, solo_e - 1)];
         PBSA_SOLO_PLAN(1)
-        step<D, true, true, true, false, kDmaSolo, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan);
-        rescale<DT>(o, alpha);
+        step<D, true, true, true, false, kDmaSolo, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan);
+        if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);
         PBSA_SOLO_LANDED
         d_cur = d_next;
         d_next = d_nn;
         PBSA_SOLO_PLAN(0)
-        step<D, true, true, true, false, kDmaSolo, SUB1, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan);
-        rescale<DT>(o, alpha);
+        step<D, true, true, true, false, kDmaSolo, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan);
+        if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);
         PBSA_SOLO_LANDED
       }
       PBSA_SOLO_PLAN(1)
-      step<D, true, false, true, false, kDmaSolo, 0, 0>(vx, kx, c2, lift, qf, o, sB, sA, pB, pA, m_run, l_run, alpha, lim0, plan);
-      rescale<DT>(o, alpha);
+      step<D, true, false, true, false, kDmaSolo, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan);
+      if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);
       PBSA_SOLO_LANDED
-      step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, lift, qf, o, sA, sB, pA, pB, m_run, l_run, alpha, lim0, plan);
+      step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan);
     }
   }
 
@@ -810,7 +827,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
           *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * q4 + 4 * half) = w;
         }
       if (a.lse && half == 0)
-        a.lse[(size_t)h * a.Nq + tok] = l_tot > 0.0f ? m_run[g] * a.scale + __logf(l_tot) : -INFINITY;
+        a.lse[(size_t)h * a.Nq + tok] = l_tot > 0.0f ? m_ref[g] * a.scale + __logf(l_tot) : -INFINITY;
     }
   }
 }
