@@ -118,7 +118,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="cfg3: the shapes of cfg2 on 30 layers, each with its own cache and inputs, visited in turn")
+    ap.add_argument("--denoise-steps", type=int, default=1,
+                    help="T: selection + attention passes per layer-chunk; the cache (persistent set, window, pooled keys "
+                         "of the window) is the same for all of them and the update follows the last one only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--settle-steps", type=int, default=150,
                     help="untimed steps before the warm-up steps, so that the GPU's clocks have settled under load")
@@ -153,15 +157,22 @@ def main():
     K, W = args.steps, args.warmup
 
     # ---- state: reach steady state (full window, full persistent set, non-empty summary) untimed ----
-    c, g0 = workloads.cache_for_workload(w, device=dev)
+    # one cache and one set of inputs per layer; a step visits the layers in turn
+    L, T = w.n_layers, max(1, args.denoise_steps)
     n_ring = w.window_chunks + 1
     n_setup = n_ring + 2 if w.cold_start else n_ring
-    Q_at = {}                  # ring position -> the query chunk that goes with the K/V sitting there
-    for g in range(g0, g0 + n_setup):
-        Q, Kc, Vc = synth.chunk_qkv(w, 0, g)
-        Qd = workloads.bf16_tensor(Q, dev)
-        c.step(Qd, workloads.bf16_tensor(Kc, dev), workloads.bf16_tensor(Vc, dev), g)
-        Q_at[(c.n_appended - 1) % n_ring] = Qd
+    caches, Q_ats = [], []
+    for layer in range(L):
+        cl, g0 = workloads.cache_for_workload(w, layer=layer, device=dev)
+        Q_at = {}              # ring position -> the query chunk that goes with the K/V sitting there
+        for g in range(g0, g0 + n_setup):
+            Q, Kc, Vc = synth.chunk_qkv(w, layer, g)
+            Qd = workloads.bf16_tensor(Q, dev)
+            cl.step(Qd, workloads.bf16_tensor(Kc, dev), workloads.bf16_tensor(Vc, dev), g)
+            Q_at[(cl.n_appended - 1) % n_ring] = Qd
+        caches.append(cl)
+        Q_ats.append(Q_at)
+    c = caches[0]
     g_next = g0 + n_setup
     torch.cuda.synchronize()
 
@@ -181,11 +192,18 @@ def main():
         # the producer has written the next chunk's K/V into the ring position that was just freed
         # (here: the data already there serves as the new chunk); its queries are the matching Q.
         # i is the row of the history buffers this step records into.
-        g = g_next + n_done[0]
+        g = g_next + n_done[0] // L
+        c = caches[n_done[0] % L]
         n_done[0] += 1
         c.adopt_chunk(g)
-        Qd = Q_at[(c.n_appended - 1) % n_ring]
+        Qd = Q_ats[(n_done[0] - 1) % L][(c.n_appended - 1) % n_ring]
         c.sel, c.slot_src = sel_hist[i], src_hist[i]
+        for _ in range(T - 1):
+            # earlier denoising passes of this chunk: the chunk's own K/V (and so its pooled keys) change
+            # from pass to pass, everything else in the cache stays
+            c.select(Qd)
+            c.attention(Qd, O)
+            c.rewrite_chunk()
         if sel_ev is not None:
             sel_ev[0].record(stream)
         c.select(Qd)
@@ -220,14 +238,14 @@ def main():
     torch.cuda.synchronize()
 
     step_s = (t1 - t0) / K
-    attn_ms = sum(a.elapsed_time(b) for a, b in ev) / K
+    attn_ms = sum(a.elapsed_time(b) for a, b in ev) / K                 # the last pass's launch
     rows = torch.from_numpy(synth.block_lens(w)).to(dev)
     # lengths by logical block are the same for every arrangement (each chunk has the same block lens)
     l_len = torch.from_numpy(np.tile(synth.block_lens(w), n_ring)).to(dev)
     flops = [executed_flops(sel_hist[W + i], plen_hist[W + i], l_len, rows, w.d) for i in range(K)]
-    mean_flops = float(np.mean(flops))
+    mean_flops = float(np.mean(flops)) * T
     tflops_step = mean_flops / step_s / 1e12
-    tflops_attn = mean_flops / (attn_ms * 1e-3) / 1e12
+    tflops_attn = mean_flops / T / (attn_ms * 1e-3) / 1e12
 
     # HBM-bound calls: algorithmic bytes over the event-bracketed duration.  Selection reads the chunk's
     # Q and K once and writes sel and the logits; the update reads the logits, reads K and V of every
@@ -254,7 +272,7 @@ def main():
         "pct_bf16_mfma_peak_step": round(100 * tflops_step / PEAK_BF16_TFLOPS, 3),
         "config": {"workload": f"{w.name} steady state: H={w.H} d={w.d} B={w.B} Nq={w.Nq} C={w.C}+summary "
                                f"window={w.window_chunks} chunks ({w.n_win} blocks) k={w.k}",
-                   "executed_gflop_per_step": round(mean_flops / 1e9, 3)},
+                   "layers": L, "denoise_steps": T, "executed_gflop_per_step": round(mean_flops / 1e9, 3)},
         "roofline": {"kernel": "pbsa_attention_fwd", "bound": "mfma", "achieved": round(tflops_attn, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 5),
                      "traffic": HBM_TRAFFIC_BYTES.get(w.name), "traffic_unit": "bytes per launch",
@@ -271,10 +289,10 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import pbsa_oracle as orc
         t_sel, t_att, t_upd, n_rows = cpu_baseline(w)
-        cpu_s = t_sel + t_att + t_upd
+        cpu_s = T * (t_sel + t_att) + t_upd
         out["cpu_baseline"] = {
             "value": round(mean_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(),
-            "kind": "oracle", "seconds_per_layer_chunk": round(cpu_s, 3),
+            "kind": "oracle", "seconds_per_layer_chunk": round(cpu_s, 3),   # all T passes
             "sample": f"full selection ({t_sel:.3f} s) and update ({t_upd:.3f} s) of one {w.name} steady-state chunk; "
                       f"attention on {n_rows} of {w.H * w.Nq} rows, scaled to the chunk ({t_att:.2f} s)"}
     print(json.dumps(out))

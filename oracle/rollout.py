@@ -53,6 +53,14 @@ class OracleState:
         self.n_appended += 1
         self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
 
+    def rewrite_chunk(self, Kb, Vb):
+        """Overwrite the newest chunk's blocks in place (the chunk's K/V change between the denoising passes
+        of one chunk, Sec. 3.1); its pooled keys are recomputed by the next selection, the window's are kept."""
+        pos = self.chunks[-1][0]
+        self.Kl[:, pos * self.nqb:(pos + 1) * self.nqb] = Kb
+        self.Vl[:, pos * self.nqb:(pos + 1) * self.nqb] = Vb
+        self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
+
     def set_persistent(self, Kp, Vp, lens, ids):
         """Seed the first C slots with given blocks ([H][C][B][d]); pooled keys by the oracle's own pooling."""
         C = Kp.shape[1]

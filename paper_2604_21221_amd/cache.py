@@ -120,6 +120,18 @@ class PbsaCache:
         self.n_appended += 1
         self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
 
+    def rewrite_chunk(self, K=None, V=None):
+        """Between the denoising passes of one chunk (Sec. 3.1: each chunk is denoised in T passes over the
+        same cache) only the newest chunk's own K/V change: overwrite them in place ([H][Nq][d] bf16), or
+        with no arguments just note that the producer has.  The next selection then pools the chunk's
+        blocks again; the pooled keys of the window stay cached."""
+        assert self.chunk_pos, "no chunk to rewrite"
+        pos = self.chunk_pos[-1]
+        for dst, src in ((self.Kl, K), (self.Vl, V)):
+            if src is not None:
+                dst[:, pos * self.nqb:(pos + 1) * self.nqb].view(self.H, self.nqb * self.B, self.d)[:, :self.Nq] = src
+        self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
+
     def adopt_chunk(self, chunk_id):
         """Declare the next ring position to hold chunk `chunk_id` whose K/V the producer has already
         written there in block-major layout (zero-copy append)."""

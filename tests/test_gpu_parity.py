@@ -222,6 +222,49 @@ def test_determinism(gpu):
         assert torch.equal(c.attention(Q), O0)
 
 
+def test_denoising_passes_share_the_cache(gpu):
+    """T passes over one chunk (Sec. 3.1): between passes only the chunk's own K/V and the queries change.
+    Every pass must match the oracle on every element, the update follows the last pass, and the pooled
+    keys of the window are taken from the cache, not recomputed: a marker planted in one of them on both
+    sides before the second pass must survive and must steer both selections alike."""
+    H, d, B, Nq, w, C, k = 2, 128, 64, 333, 2, 4, 5
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale, n_sink=1)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, n_sink=1, device=DEV)
+    wl = gpu["wl"]
+    for g in range(w + 1):       # fill the window
+        run_both(gpu, c, st, rnd(300 + 3 * g, H, Nq, d), rnd(301 + 3 * g, H, Nq, d, scale=1.5), rnd(302 + 3 * g, H, Nq, d),
+                 g, None, "denoise fill")
+    g = w + 1
+    lens = np.full(st.nqb, B, np.int32); lens[-1] = Nq - (st.nqb - 1) * B
+    for t in range(3):
+        Q, K, V = rnd(400 + 3 * t, H, Nq, d), rnd(401 + 3 * t, H, Nq, d, scale=1.5), rnd(402 + 3 * t, H, Nq, d)
+        print(f"[case] denoise pass {t}", flush=True)
+        if t == 0:
+            st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * st.nqb + np.arange(st.nqb))
+            c.append_chunk(wl.bf16_tensor(K, DEV), wl.bf16_tensor(V, DEV), g)
+        else:
+            st.rewrite_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B))
+            c.rewrite_chunk(wl.bf16_tensor(K, DEV), wl.bf16_tensor(V, DEV))
+            assert c.stale_from == st.stale_from == st.n_loc - st.nqb
+        if t == 1:               # the marker: window block 1 of head 0 (physical slot via the maps)
+            slot = int(st._maps()[0][1])
+            st.Kc_l[0, slot] = 3.0
+            c.Kc_l[0, slot] = 3.0
+        st.select(Q)
+        Qd = wl.bf16_tensor(Q, DEV)
+        c.select(Qd)
+        compare_select(c, st, f"denoise pass {t}")
+        if t >= 1:
+            assert torch.all(c.Kc_l[0, slot] == 3.0)
+        Oref, _ = st.attention(Q)
+        check_attention(c.attention(Qd).float().cpu().numpy(), Oref, f"denoise pass {t}")
+    ne = st.n_evict_now()
+    sc_ref, src_ref = st.update()
+    assert c.update() == ne
+    compare_update(c, st, wl, sc_ref, src_ref, ne, "denoise update")
+
+
 # ------------------------------------------------------------------------------------------------
 # the five workloads
 # ------------------------------------------------------------------------------------------------
