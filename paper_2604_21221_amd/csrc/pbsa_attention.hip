@@ -36,8 +36,8 @@
 // on it: O^T += V^T P^T of sub-tile u-1 and S^T = K Q^T of sub-tile u+1.  S^T and P^T are double
 // buffered.  Each part of the list (shared full, shared ragged, solo) is one pipelined run with its
 // own template instance; the pipeline drains between them.  Softmax is online, fp32, base 2 (scale and
-// log2 e folded into one fma); row sums are taken over the bf16-rounded probabilities (two per
-// v_dot2c_f32_bf16), the same numbers the second product uses.
+// log2 e folded into one fma); row sums are taken over the bf16-rounded probabilities, the same
+// numbers the second product uses.
 #include "pbsa_internal.h"
 
 namespace pbsa {
@@ -184,16 +184,35 @@ __device__ __forceinline__ float row_max(const f32x16& s) {
   return max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
 }
 
-// probabilities of two neighbouring keys: exp2, round to bf16, add to the row sum
-__device__ __forceinline__ uint32_t prob_pair(float s0, float s1, float c2, float mc, float& psum) {
+// The probabilities of two neighbouring keys: exp2 of each score, then the two rounded to a bf16 pair.
+// The pipeline steps issue the stages in different slots so that none waits for the one before.
+__device__ __forceinline__ float prob_exp(float s, float c2, float mc) { return __builtin_amdgcn_exp2f(__builtin_fmaf(s, c2, mc)); }
+__device__ __forceinline__ uint32_t prob_round(float e0, float e1) {
   bf16x2 pk;
-  pk[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s0, c2, mc));
-  pk[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s1, c2, mc));
+  pk[0] = (__bf16)e0;
+  pk[1] = (__bf16)e1;
+  return __builtin_bit_cast(uint32_t, pk);
+}
+// Row sums are taken over the rounded values, the numbers the second product uses, one
+// v_dot2c_f32_bf16 per pair.  That instruction executes in the matrix pipeline: issued between MFMAs
+// it waits for the one in flight and holds up the next, and the wave, which issues in order, loses the
+// overlap of its vector work with the matrix pipe.  So the sums of a sub-tile are not taken in the step
+// that computes its probabilities but in one burst at the start of the next step, while that step's
+// first operand fragments are on their way from LDS and the matrix pipe has nothing to do.
+__device__ __forceinline__ void prob_sum(uint32_t w, float& psum) {
   bf16x2 one;
   one[0] = (__bf16)1.0f;
   one[1] = (__bf16)1.0f;
-  psum = __builtin_amdgcn_fdot2_f32_bf16(pk, one, psum, false);
-  return __builtin_bit_cast(uint32_t, pk);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), one, psum, false);
+}
+__device__ __forceinline__ void row_sums(const u32x4 (&p)[2][2], float (&psum)[2]) {
+  float ps[4] = {0.0f, 0.0f, 0.0f, 0.0f};    // two chains per row group
+#pragma unroll
+  for (int w = 0; w < 8; ++w)
+#pragma unroll
+    for (int g = 0; g < 2; ++g) prob_sum(p[g][w / 4][w % 4], ps[2 * g + (w & 1)]);
+  psum[0] = ps[0] + ps[1];
+  psum[1] = ps[2] + ps[3];
 }
 
 template <int DT>
@@ -289,10 +308,10 @@ struct StepCtx {
   u32x4 (&p_cur)[2][2];
   const u32x4 (&p_prev)[2][2];
   const float (&mc)[2];          // minus the softmax reference of each row group, times c2
-  float (&psum)[2];              // out: this lane's sum of the probabilities of s_cur, per row group
   const int (&lim)[2];           // RAGGED: valid keys of the current sub-tile minus 4 * half, per row group
   const DmaPlan<D>& dma;
   bf16x8 frag[2 * Geo<D>::KS];   // operand fragment of each MFMA pair
+  float ex[32];                  // exp2 of the scores, row group g element v at 16 g + v, until they are rounded
 };
 
 // pair q: with both products, even q is PV pair q/2 and odd q is QK pair q/2
@@ -326,8 +345,11 @@ __device__ __forceinline__ void mfma_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
   }
 }
 
-// Slice C of the softmax of s_cur: in a ragged step first the masking of each row group, then the 8
-// probability pairs per group spread evenly over the remaining slices.
+// Slice C of the softmax of s_cur.  In a ragged step the first two slices mask the row groups.  The
+// other NS slices share the 32 scores of a lane (score e in slice e NS / 32) and the 16 pairs: the
+// exponential of a score is issued in its slice and a pair is rounded one slice after its second
+// exponential (the last slice takes what would fall behind it), so every slice has about the same few
+// instructions and none of them waits for the previous one.
 template <int D, bool PV, bool QK, bool SM, bool RAGGED, int C>
 __device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
   using S = StepCtx<D, PV, QK, SM, RAGGED>;
@@ -337,15 +359,24 @@ __device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
     for (int v = 0; v < 16; ++v)           // accumulator element v is key 8 (v/4) + 4 half + v%4
       if (8 * (v / 4) + (v % 4) >= c.lim[C]) c.s_cur[C][v] = kMasked;
   } else {
-    if constexpr (C == S::PRE) c.psum[0] = c.psum[1] = 0.0f;
-    constexpr int lo = (C - S::PRE) * 16 / (S::NC - S::PRE), hi = (C + 1 - S::PRE) * 16 / (S::NC - S::PRE);
+    constexpr int NS = S::NC - S::PRE, j = C - S::PRE;
+    constexpr bool last = j == NS - 1;
 #pragma unroll
-    for (int n = lo; n < hi; ++n) {
-      const int grp = n / 8, v = 2 * (n % 8);
-      const uint32_t w = prob_pair(c.s_cur[grp][v], c.s_cur[grp][v + 1], c.c2, c.mc[grp], c.psum[grp]);
-      // a use that cannot move: keeps this slice's work in this slot (its results are needed only by the next step)
-      asm volatile("" ::"v"(w), "v"(c.psum[grp]));
-      c.p_cur[grp][v / 8][(v % 8) / 2] = w;
+    for (int e = 0; e < 32; ++e) {
+      if (e * NS / 32 == j) {
+        c.ex[e] = prob_exp(c.s_cur[e / 16][e % 16], c.c2, c.mc[e / 16]);
+        // a use that cannot move keeps the work of a slice in its slot
+        asm volatile("" ::"v"(c.ex[e]));
+      }
+    }
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {         // pair n: scores 2n, 2n+1 of row group n / 8
+      const int jr = (2 * n + 1) * NS / 32 + 1;
+      if (jr == j || (last && jr > j)) {
+        const uint32_t w = prob_round(c.ex[2 * n], c.ex[2 * n + 1]);
+        asm volatile("" ::"v"(w));
+        c.p_cur[n / 8][(n % 8) / 4][n % 4] = w;
+      }
     }
   }
 }
@@ -357,6 +388,7 @@ __device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c) {
     constexpr int Q = I / 2, k = I % 2;
     if constexpr (k == 0) load_frag<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + kAhead>(c);
     mfma_slot<D, PV, QK, SM, RAGGED, Q, k>(c);
+    __builtin_amdgcn_sched_barrier(0);         // the MFMA first, then the slot's vector work
     if constexpr (DMA != kDmaNone) {
       constexpr int ND = DmaPlan<D>::N, NS = S::NC < ND ? S::NC : ND;    // slots that carry loads
       if constexpr (I < NS) dma_issue_range<D, DMA, I * ND / NS, (I + 1) * ND / NS>(c.dma);
@@ -375,31 +407,27 @@ __device__ __forceinline__ void preload_frags(StepCtx<D, PV, QK, SM, RAGGED>& c)
   }
 }
 
-// K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
-template <int D, bool PV, bool QK, bool SM, bool RAGGED, int DMA, int K_OFF, int V_OFF>
-__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS], float c2,
-                                     const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
-                                     f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], const u32x4 (&p_prev)[2][2],
-                                     const float (&mc)[2], float (&psum)[2], const int (&lim)[2],
-                                     const DmaPlan<D>& dma) {
-  static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
-  StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, c2, qf, o, s_cur, s_next, p_cur, p_prev, mc, psum, lim, dma, {}};
-  preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
-  __builtin_amdgcn_sched_barrier(0);
-  run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
-}
+// Everything a step needs of the running softmax: per row group the reference (m_ref, and mc = -m_ref c2),
+// the running sum, and whether anything has been added to the output accumulators yet.
+struct SoftmaxRun {
+  float m_ref[2], mc[2], l_run[2];
+  float c2, lift;
+  bool o_live;
+};
 
-// After a step with a softmax.  Normally the row sums join the running sums and that is all.  If a sum
-// says that the reference of some row no longer serves (or was never set: a row's first keys), the
-// softmax of the sub-tile is redone here, outside the pipeline, for both row groups: row maxima, new
-// references where a score is more than kSlack above the old one (the other rows keep theirs and get the
-// same probabilities again), probabilities, running sums; the caller then rescales the output
-// accumulators by alpha unless nothing has been added to them yet.  The next step takes p and the new
-// references.  Returns whether the softmax was redone (the same answer in every lane).
+// The softmax of a sub-tile is settled at the start of the step that uses its probabilities (every step
+// with a second product).  Normally its row sums join the running sums and that is all.  If a sum says
+// that the reference of some row no longer serves (or was never set: a row's first keys), the softmax of
+// the sub-tile is redone here, outside the pipeline, for both row groups: row maxima, new references
+// where a score is more than kSlack above the old one (the other rows keep theirs and get the same
+// probabilities again), probabilities, running sums; the caller then rescales the output accumulators by
+// alpha unless nothing has been added to them yet.  Returns whether the softmax was redone (the same
+// answer in every lane).  s is the sub-tile's S^T, which the coming step will overwrite, p its P^T.
 template <int D>
 __device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[2][2], float (&m_ref)[2], float (&mc)[2],
-                                               float (&l_run)[2], const float (&psum)[2], float (&alpha)[2], float c2,
-                                               float lift) {
+                                               float (&l_run)[2], float (&alpha)[2], float c2, float lift) {
+  float psum[2];
+  row_sums(p, psum);
   if (__builtin_expect(__any(!(psum[0] <= kBig) || !(psum[1] <= kBig)), 0)) {
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
@@ -408,16 +436,38 @@ __device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[
       alpha[g] = __builtin_amdgcn_exp2f((m_ref[g] - m_new) * c2);
       m_ref[g] = m_new;
       mc[g] = -m_new * c2;
-      float ps = 0.0f;
 #pragma unroll
-      for (int v = 0; v < 16; v += 2) p[g][v / 8][(v % 8) / 2] = prob_pair(s[g][v], s[g][v + 1], c2, mc[g], ps);
-      l_run[g] = l_run[g] * alpha[g] + ps;
+      for (int v = 0; v < 16; v += 2)
+        p[g][v / 8][(v % 8) / 2] = prob_round(prob_exp(s[g][v], c2, mc[g]), prob_exp(s[g][v + 1], c2, mc[g]));
     }
+    row_sums(p, psum);
+    l_run[0] = l_run[0] * alpha[0] + psum[0];
+    l_run[1] = l_run[1] * alpha[1] + psum[1];
     return true;
   }
   l_run[0] += psum[0];
   l_run[1] += psum[1];
   return false;
+}
+
+// K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, int DMA, int K_OFF, int V_OFF>
+__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS],
+                                     const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
+                                     f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], u32x4 (&p_prev)[2][2], SoftmaxRun& sr,
+                                     const int (&lim)[2], const DmaPlan<D>& dma) {
+  static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
+  StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, sr.c2, qf, o, s_cur, s_next, p_cur, p_prev, sr.mc, lim, dma, {}, {}};
+  preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
+  if constexpr (PV) {
+    // p_prev is the softmax of the sub-tile whose S^T still sits in s_next
+    float alpha[2];
+    if (softmax_settle<D>(s_next, p_prev, sr.m_ref, sr.mc, sr.l_run, alpha, sr.c2, sr.lift) && sr.o_live)
+      rescale<Geo<D>::DT>(o, alpha);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
+  if constexpr (PV) sr.o_live = true;
 }
 
 #pragma clang diagnostic push
@@ -556,8 +606,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   f32x16 sA[2], sB[2];                     // S^T of even / odd sub-tiles
   u32x4 pA[2][2], pB[2][2];                // P^T of even / odd sub-tiles (bf16 pairs)
   const float c2 = a.scale * 1.4426950408889634f, lift = kLift / c2;
-  float m_ref[2] = {kInitMax, kInitMax}, mc[2] = {-kInitMax * c2, -kInitMax * c2}, l_run[2] = {0.0f, 0.0f}, psum[2], alpha[2];
-  bool o_live = false;                     // something has been added to the output accumulators
+  SoftmaxRun sr{{kInitMax, kInitMax}, {-kInitMax * c2, -kInitMax * c2}, {0.0f, 0.0f}, c2, lift, false};
 
   // ---- operand addresses ------------------------------------------------------------------------
   // this lane's fragment addresses inside ring entry 0, sub-tile 0 (LDS byte addresses)
@@ -694,25 +743,21 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
     PBSA_ADDR_K(TB)                                                                                     \
     PBSA_ADDR_V(TB)                                                                                     \
-    step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan); \
+    step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan); \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
-    step<D, false, true, true, RAGGED, kDmaNone, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan); \
-    if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha); o_live = true;                                                                              \
+    step<D, false, true, true, RAGGED, kDmaNone, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
     PBSA_TURNOVER(TB)                                                                                   \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, true, true, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim1, plan); \
-      if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);                                                                            \
+      step<D, true, true, true, RAGGED, kDmaShared, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
-      step<D, true, true, true, RAGGED, kDmaNone, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan); \
-      if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);                                                                            \
+      step<D, true, true, true, RAGGED, kDmaNone, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
       PBSA_TURNOVER(t + 1)                                                                              \
     }                                                                                                   \
     PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, true, false, true, RAGGED, kDmaShared, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim1, plan); \
-    if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);                                                                              \
-    step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan); \
+    step<D, true, false, true, RAGGED, kDmaShared, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
+    step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
     /* between runs the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
     acc_settle<DT>(o[0]);                                                                               \
     acc_settle<DT>(o[1]);                                                                               \
@@ -781,29 +826,25 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
           dma16(kp_ + (i / NPAT) * (16 * ROW), plan.ksolo[i % NPAT], kring + i * 1024);
       }
       PBSA_SOLO_LANDED
-      step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan);
+      step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
       PBSA_SOLO_PLAN(0)
-      step<D, false, true, true, false, kDmaSolo, SUB1, 0>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan);
-      if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha); o_live = true;
+      step<D, false, true, true, false, kDmaSolo, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
       PBSA_SOLO_LANDED
       for (int t = solo_b; t < solo_e - 1; ++t) {
         d_nn = t_src[min(t + 2, solo_e - 1)];
         PBSA_SOLO_PLAN(1)
-        step<D, true, true, true, false, kDmaSolo, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan);
-        if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);
+        step<D, true, true, true, false, kDmaSolo, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
         PBSA_SOLO_LANDED
         d_cur = d_next;
         d_next = d_nn;
         PBSA_SOLO_PLAN(0)
-        step<D, true, true, true, false, kDmaSolo, SUB1, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan);
-        if (softmax_settle<D>(sA, pA, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);
+        step<D, true, true, true, false, kDmaSolo, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
         PBSA_SOLO_LANDED
       }
       PBSA_SOLO_PLAN(1)
-      step<D, true, false, true, false, kDmaSolo, 0, 0>(vx, kx, c2, qf, o, sB, sA, pB, pA, mc, psum, lim0, plan);
-      if (softmax_settle<D>(sB, pB, m_ref, mc, l_run, psum, alpha, c2, lift) && o_live) rescale<DT>(o, alpha);
+      step<D, true, false, true, false, kDmaSolo, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
       PBSA_SOLO_LANDED
-      step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, c2, qf, o, sA, sB, pA, pB, mc, psum, lim0, plan);
+      step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
     }
   }
 
@@ -812,7 +853,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   acc_settle<DT>(o[1]);
 #pragma unroll
   for (int g = 0; g < 2; ++g) {
-    const float l_tot = l_run[g] + __shfl_xor(l_run[g], 32, 64);
+    const float l_tot = sr.l_run[g] + __shfl_xor(sr.l_run[g], 32, 64);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     const int tok = tok0 + 32 * g;
     if (tok < a.Nq) {
@@ -827,7 +868,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
           *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * q4 + 4 * half) = w;
         }
       if (a.lse && half == 0)
-        a.lse[(size_t)h * a.Nq + tok] = l_tot > 0.0f ? m_ref[g] * a.scale + __logf(l_tot) : -INFINITY;
+        a.lse[(size_t)h * a.Nq + tok] = l_tot > 0.0f ? sr.m_ref[g] * a.scale + __logf(l_tot) : -INFINITY;
     }
   }
 }
