@@ -117,13 +117,20 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint3
                : "s"(lds_off), "v"(lane_off), "s"(base)
                : "memory");
 }
-// The same with a compile-time displacement of the LDS address, so that the loads of one plan share one
-// scalar LDS base instead of one precomputed address each.
+// Four such loads of consecutive KiB: the instruction's offset field moves the LDS address and the
+// global address alike, so one setting of M0 and one scalar base serve four loads whose sources are
+// 1 KiB apart like their destinations (lane offsets o0..o3 are relative to those steps).  A load costs
+// the issuing wave about 20 cycles with its own M0 setting and base, which is why they come in fours.
 template <int LDS_IMM>
-__device__ __forceinline__ void dma16i(const void* base, uint32_t lane_off, uint32_t lds_base) {
-  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+__device__ __forceinline__ void dma16x4(const void* base, uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3,
+                                        uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %0, %6\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %1, %5\n\t"
+               "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+               "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+               "global_load_lds_dwordx4 %4, %5 offset:3072"
                :
-               : "s"(lds_base), "v"(lane_off), "s"(base), "n"(LDS_IMM)
+               : "s"(lds_base), "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(base), "n"(LDS_IMM)
                : "memory", "scc");
 }
 
@@ -240,57 +247,57 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[2][DT], const float (&alpha)
 // a slice of the softmax, so the matrix pipe works while the VALU computes.  Nothing is allowed to
 // move across slot boundaries.
 // ------------------------------------------------------------------------------------------------
-// Staging loads that ride along a pipeline step, one wave instruction per slot from the step's first
-// slot on.  Issued in one burst they would hold the wave at the texture path (about 50 bytes per clock
-// per CU) for a large part of a step; spread out, they travel while the wave computes.
-//   shared part: K of tile t+2 and V of tile t+1, this wave's half of the pieces of each
-//   solo part:   the 32-key halves K(u+2) and V(u), all pieces, into this wave's own ring entries
-constexpr int kDmaNone = 0, kDmaShared = 1, kDmaSolo = 2;
+// Staging loads that ride along a pipeline step, in bursts of four wave instructions (4 KiB: 16 rows at
+// D = 128) at a few slots of the step's first half; spread out like this they travel while the wave
+// computes.  A plan names what one wave loads during one step, always 32 tile rows per operand:
+//   shared part: this wave's half (rows 32 w ..) of K of tile t+2 and of V of tile t+1
+//   solo part:   the 32-key halves K(u+2) and V(u) of its own tiles, into its own ring entries
 template <int D>
 struct DmaPlan {
   static constexpr int CH = D / 8, RPI = 64 / CH;   // 16-byte chunks per row, rows per wave instruction
-  static constexpr int NIW = (kTile / RPI) / 2;      // instructions per wave per tile = per 32-key half
-  static constexpr int PS = 8 / RPI > 0 ? 8 / RPI : 1;
-  static constexpr int NPAT = 16 / RPI;              // pieces per 16 rows, the period of the K permutation
-  static constexpr int N = 2 * NIW;                  // K and V
-  const unsigned char* kp;    // sources
+  static constexpr int NIW = 32 / RPI;               // wave instructions (1 KiB pieces) per 32 rows
+  static constexpr int NW = NIW / 4;                 // bursts per operand
+  static constexpr int NB = 2 * NW;                  // bursts per step: K and V of each 4 KiB window
+  const unsigned char* kp;    // source of the first of the 32 rows
   const unsigned char* vp;
-  uint32_t klds, vlds;        // LDS address of this wave's first piece at the destination
-  int koff[PS];               // shared, per lane: source byte offset of each K pattern
-  int voff[NIW];              // shared, per lane: source byte offset of each V piece, rows past the tile's valid
-                              // length replaced by its last valid row.  Computed when the plan is made and
-                              // left alone until every load has been issued: an address register rewritten
+  const unsigned char* vtile; // ragged V tile: its first row
+  uint32_t klds, vlds;        // LDS address the first row goes to
+  int kpat[4];                // per lane: source byte offset within piece k of a window (the K permutation has
+                              // a period of 16 rows, at most the window)
+  int vpat;                   // per lane: source byte offset within any V piece
+  bool vragged;               // the V tile has fewer than 64 valid rows: rows past them must not reach LDS
+  int voff[NIW];              // then, per lane: source byte offset from vtile of each piece, rows past the
+                              // valid length replaced by the last valid row.  Computed when the plan is made
+                              // and left alone until every load has been issued: an address register rewritten
                               // shortly after the load that uses it has produced wrong loads here.
-  int vrow_w, vchk;           // shared, per lane: V source row of piece 0 and chunk byte offset
-  int ksolo[NPAT];            // solo, per lane: source byte offset of K piece e < NPAT (rows RPI e ..)
-  int vsolo;                  // solo, per lane: source byte offset within any V piece
 };
 
-template <int D, int MODE, int IDX>
-__device__ __forceinline__ void dma_issue(const DmaPlan<D>& p) {
-  using P = DmaPlan<D>;
-  constexpr int i = IDX / 2;
-  if constexpr (MODE == kDmaShared) {
-    constexpr int q = i / P::PS, e = i % P::PS, piece = q * 2 * P::PS + e;
-    if constexpr (IDX % 2 == 0)
-      dma16i<piece * 1024>(p.kp + q * (2 * P::PS * P::RPI * Geo<D>::ROW), p.koff[e], p.klds);
-    else
-      dma16i<piece * 1024>(p.vp, p.voff[i], p.vlds);
+template <int D, int B>
+__device__ __forceinline__ void dma_burst(const DmaPlan<D>& p) {
+  constexpr int win = B / 2;
+  if constexpr (B % 2 == 0) {
+    dma16x4<win * 4096>(p.kp + win * 4096, p.kpat[0], p.kpat[1], p.kpat[2], p.kpat[3], p.klds);
   } else {
-    if constexpr (IDX % 2 == 0)
-      dma16i<i * 1024>(p.kp + (i / P::NPAT) * (16 * Geo<D>::ROW), p.ksolo[i % P::NPAT], p.klds);
-    else
-      dma16i<i * 1024>(p.vp + i * (P::RPI * Geo<D>::ROW), p.vsolo, p.vlds);
+    if (__builtin_expect(p.vragged, 0)) {
+      dma16(p.vtile, p.voff[4 * win + 0], p.vlds + (4 * win + 0) * 1024);
+      dma16(p.vtile, p.voff[4 * win + 1], p.vlds + (4 * win + 1) * 1024);
+      dma16(p.vtile, p.voff[4 * win + 2], p.vlds + (4 * win + 2) * 1024);
+      dma16(p.vtile, p.voff[4 * win + 3], p.vlds + (4 * win + 3) * 1024);
+    } else {
+      dma16x4<win * 4096>(p.vp + win * 4096, p.vpat, p.vpat, p.vpat, p.vpat, p.vlds);
+    }
   }
 }
-template <int D, int MODE, int LO, int HI>
-__device__ __forceinline__ void dma_issue_range(const DmaPlan<D>& p) {
-  if constexpr (LO < HI) {
-    dma_issue<D, MODE, LO>(p);
-    dma_issue_range<D, MODE, LO + 1, HI>(p);
+// all of a plan at once (before a pipelined run starts)
+template <int D, int B = 0>
+__device__ __forceinline__ void dma_all(const DmaPlan<D>& p, bool k_too, bool v_too) {
+  if constexpr (B < DmaPlan<D>::NB) {
+    if (B % 2 == 0 ? k_too : v_too) dma_burst<D, B>(p);
+    dma_all<D, B + 1>(p, k_too, v_too);
   }
 }
 
+constexpr int kDmaNone = 0, kDmaShared = 1, kDmaSolo = 1;   // a step carries a plan's loads or not
 constexpr int kAhead = 4;     // MFMA pairs between an operand read and its use
 
 template <int D, bool PV, bool QK, bool SM, bool RAGGED>
@@ -390,8 +397,9 @@ __device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c) {
     mfma_slot<D, PV, QK, SM, RAGGED, Q, k>(c);
     __builtin_amdgcn_sched_barrier(0);         // the MFMA first, then the slot's vector work
     if constexpr (DMA != kDmaNone) {
-      constexpr int ND = DmaPlan<D>::N, NS = S::NC < ND ? S::NC : ND;    // slots that carry loads
-      if constexpr (I < NS) dma_issue_range<D, DMA, I * ND / NS, (I + 1) * ND / NS>(c.dma);
+      constexpr int every = (S::NC < 16 ? S::NC : 16) / DmaPlan<D>::NB;     // a burst every few slots of the first 16
+      static_assert(every >= 1, "a slot for every burst");
+      if constexpr (I % every == 0 && I / every < DmaPlan<D>::NB) dma_burst<D, I / every>(c.dma);
     }
     valu_slot<D, PV, QK, SM, RAGGED, I>(c);
     __builtin_amdgcn_sched_barrier(0);
@@ -626,64 +634,41 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 
   // ---- staging --------------------------------------------------------------------------------
   // A wave instruction fills one KiB of a tile: RPI consecutive rows, lane i -> row i / CH, physical
-  // chunk i % CH, i.e. the logical chunk (i % CH) ^ f(row) of that row.  The tile has 2 NIW such
-  // pieces; piece m covers rows RPI m ...  Since f has period 16 in the row (K) or depends on the row
-  // within the piece only (V), the per-lane source offsets of all pieces a wave issues come from a few
-  // patterns plus a multiple of the piece size, which goes into the scalar base.  Shared tiles: wave w
-  // issues the pieces m = PS (w + 2 q) + e, e < PS, q < NIW / PS, where PS pieces make 16 rows, and
-  // pieces with equal e share a pattern.  A ragged V tile must not bring rows past its valid length
-  // into LDS (they meet p = 0 in the MFMA, and 0 x NaN-or-Inf pattern is NaN): the lanes of such rows
-  // fetch the last valid row instead.  Solo tiles: a wave issues all NIW pieces of a 32-key half.
-  constexpr int PS = DmaPlan<D>::PS, NPAT = DmaPlan<D>::NPAT;
-  constexpr int NQ = NIW / PS;
-  int koff[PS], voff_w, vrow_w, vchk;
-  {
-    const int rl = lane / CH, c = lane % CH;
-#pragma unroll
-    for (int e = 0; e < PS; ++e) {
-      const int r = RPI * (PS * wave + e) + rl;
-      koff[e] = r * ROW + ((c ^ k_swz<D>(r)) << 4);
-    }
-    vrow_w = RPI * PS * wave + rl;                    // V: f(row) = f(row within the piece), one pattern
-    vchk = (c ^ v_swz<D>(rl)) << 4;
-    voff_w = vrow_w * ROW + vchk;
-  }
-  const uint32_t wave_piece = __builtin_amdgcn_readfirstlane(smem_lds + PS * wave * 1024);
+  // chunk i % CH, i.e. the logical chunk (i % CH) ^ f(row) of that row.  Since f has period 16 in the row
+  // (K) or depends on the row within the piece only (V), the per-lane source offsets within a piece are
+  // four patterns for K (the pieces of 16 rows) and one for V, whatever rows a load brings.  In the
+  // shared part wave w brings rows 32 w .. 32 w + 31 of every tile.  A ragged V tile must not bring rows
+  // past its valid length into LDS (they meet p = 0 in the MFMA, and 0 x NaN-or-Inf pattern is NaN): the
+  // lanes of such rows fetch the last valid row instead.
+  const int rl = lane / CH, vchk = ((lane % CH) ^ v_swz<D>(rl)) << 4;
   DmaPlan<D> plan;
-  plan.vrow_w = vrow_w;
-  plan.vchk = vchk;
 #pragma unroll
-  for (int e = 0; e < PS; ++e) plan.koff[e] = koff[e];
+  for (int k = 0; k < 4; ++k) plan.kpat[k] = rl * ROW + (((lane % CH) ^ k_swz<D>(RPI * k + rl)) << 4);
+  plan.vpat = rl * ROW + vchk;
+  plan.vragged = false;
+#pragma unroll
+  for (int i = 0; i < NIW; ++i) plan.voff[i] = 0;
+  const uint32_t smem_s = __builtin_amdgcn_readfirstlane(smem_lds);
   const size_t head_l = (size_t)h * a.n_loc_cap * B * D * 2, head_p = (size_t)h * (a.C + 1) * B * D * 2;
 #define PBSA_TILE_PTR(SRC, BASE_L, BASE_P)                                                              \
   ((SRC) < 0 ? reinterpret_cast<const unsigned char*>(BASE_L) + head_l + (size_t)((SRC) & 0x7FFFFFFF) * (kTile * D * 2) \
              : reinterpret_cast<const unsigned char*>(BASE_P) + head_p + (size_t)(SRC) * (kTile * D * 2))
-  // piece m of the tile: K source rows RPI m.., pattern koff[e] holds rows RPI (PS wave + e)..
-#define PBSA_ISSUE_K(T_, ENTRY)                                                                         \
-  if ((T_) < n_tiles) {                                                                                 \
-    const int src_ = __builtin_amdgcn_readfirstlane(t_src[T_]);                                         \
-    const unsigned char* kp_ = PBSA_TILE_PTR(src_, a.Kl, a.Kp);                                         \
-    _Pragma("unroll") for (int q_ = 0; q_ < NQ; ++q_)                                                   \
-      _Pragma("unroll") for (int e_ = 0; e_ < PS; ++e_)                                                 \
-        dma16(kp_ + q_ * (2 * PS * RPI * ROW), koff[e_],                                                \
-              wave_piece + (ENTRY) * TILE + (q_ * 2 * PS + e_) * 1024);                                 \
-  }
-#define PBSA_ISSUE_V(T_, ENTRY)                                                                         \
-  if ((T_) < n_tiles) {                                                                                 \
-    const int src_ = __builtin_amdgcn_readfirstlane(t_src[T_]);                                         \
-    const int len_ = __builtin_amdgcn_readfirstlane(t_meta[T_]) & 0xFF;                                 \
-    const unsigned char* vp_ = PBSA_TILE_PTR(src_, a.Vl, a.Vp);                                         \
-    if (len_ == kTile) {                                                                                \
-      _Pragma("unroll") for (int q_ = 0; q_ < NQ; ++q_)                                                 \
-        _Pragma("unroll") for (int e_ = 0; e_ < PS; ++e_)                                               \
-          dma16(vp_ + (q_ * 2 * PS + e_) * (RPI * ROW), voff_w,                                         \
-                wave_piece + (2 + (ENTRY)) * TILE + (q_ * 2 * PS + e_) * 1024);                         \
-    } else {                                                                                            \
-      _Pragma("unroll") for (int q_ = 0; q_ < NQ; ++q_)                                                 \
-        _Pragma("unroll") for (int e_ = 0; e_ < PS; ++e_) {                                             \
-          dma16(vp_, min(RPI * (q_ * 2 * PS + e_) + vrow_w, len_ - 1) * ROW + vchk,                     \
-                wave_piece + (2 + (ENTRY)) * TILE + (q_ * 2 * PS + e_) * 1024);                         \
-        }                                                                                               \
+  // the plan that brings this wave's half of K tile KSRC into K ring entry KENTRY and of V tile VSRC
+  // (descriptor words of the list) into V ring entry VENTRY
+#define PBSA_PLAN_SHARED(KSRC, VSRC, VMETA, KENTRY, VENTRY)                                             \
+  {                                                                                                     \
+    const int ksrc_ = __builtin_amdgcn_readfirstlane(KSRC);                                             \
+    const int vsrc_ = __builtin_amdgcn_readfirstlane(VSRC);                                             \
+    const int vlast_ = (__builtin_amdgcn_readfirstlane(VMETA) & 0xFF) - 1;                              \
+    plan.kp = PBSA_TILE_PTR(ksrc_, a.Kl, a.Kp) + wave * (TILE / 2);                                     \
+    plan.vtile = PBSA_TILE_PTR(vsrc_, a.Vl, a.Vp);                                                      \
+    plan.vp = plan.vtile + wave * (TILE / 2);                                                           \
+    plan.klds = smem_s + (KENTRY) * TILE + wave * (TILE / 2);                                           \
+    plan.vlds = smem_s + (2 + (VENTRY)) * TILE + wave * (TILE / 2);                                     \
+    plan.vragged = vlast_ < kTile - 1;                                                                  \
+    if (plan.vragged) {                                                                                 \
+      _Pragma("unroll") for (int i_ = 0; i_ < NIW; ++i_)                                                \
+        plan.voff[i_] = min(32 * wave + RPI * i_ + rl, vlast_) * ROW + vchk;                            \
     }                                                                                                   \
   }
 
@@ -723,20 +708,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 #define PBSA_TURNOVER(T_)                                                                               \
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K(T_+1), V(T_) have landed */                     \
   __syncthreads();                                                                                      \
-  {                                                                                                     \
-    const int ksrc_ = __builtin_amdgcn_readfirstlane(d_ksrc);                                           \
-    const int vsrc_ = __builtin_amdgcn_readfirstlane(d_vsrc);                                           \
-    const int vlast_ = (__builtin_amdgcn_readfirstlane(d_vmeta) & 0xFF) - 1;                            \
-    plan.kp = PBSA_TILE_PTR(ksrc_, a.Kl, a.Kp);                                                         \
-    plan.vp = PBSA_TILE_PTR(vsrc_, a.Vl, a.Vp);                                                         \
-    _Pragma("unroll") for (int i_ = 0; i_ < NIW; ++i_) {                                                \
-      const int piece_ = (i_ / PS) * 2 * PS + i_ % PS;                                                  \
-      plan.voff[i_] = min(RPI * piece_ + plan.vrow_w, vlast_) * ROW + plan.vchk;                        \
-    }                                                                                                   \
-    plan.klds = wave_piece + ((T_) & 1) * TILE;                                                         \
-    plan.vlds = wave_piece + (2 + (((T_) + 1) & 1)) * TILE;                                             \
-    PBSA_FETCH_DESC((T_) + 1)                                                                           \
-  }
+  PBSA_PLAN_SHARED(d_ksrc, d_vsrc, d_vmeta, (T_) & 1, ((T_) + 1) & 1)                                   \
+  PBSA_FETCH_DESC((T_) + 1)
 #define PBSA_RUN_SHARED(RAGGED, TB, TE)                                                                 \
   if ((TB) < (TE)) {                                                                                    \
     uint32_t kx[KS], vx[DT];                                                                            \
@@ -765,9 +738,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 
   if (n_tiles > 0) {
     __syncthreads();                       // the setup scratch (aliasing the rings) is dead
-    PBSA_ISSUE_K(0, 0)
-    PBSA_ISSUE_K(1, 1)
-    PBSA_ISSUE_V(0, 0)
+    PBSA_PLAN_SHARED(t_src[0], t_src[0], t_meta[0], 0, 0)
+    dma_all<D>(plan, true, true);
+    if (n_tiles > 1) {
+      PBSA_PLAN_SHARED(t_src[1], t_src[0], t_meta[0], 1, 0)
+      dma_all<D>(plan, true, false);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     int d_ksrc, d_vsrc, d_vmeta;
@@ -792,26 +768,17 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (solo_b < solo_e) {
-      {
-        const int rl = lane / CH, c = lane % CH;
-#pragma unroll
-        for (int e = 0; e < NPAT; ++e) {
-          const int r = RPI * e + rl;
-          plan.ksolo[e] = r * ROW + ((c ^ k_swz<D>(r)) << 4);
-        }
-        plan.vsolo = rl * ROW + vchk;
-      }
       const unsigned char* kl_h = reinterpret_cast<const unsigned char*>(a.Kl) + head_l;
       const unsigned char* vl_h = reinterpret_cast<const unsigned char*>(a.Vl) + head_l;
-      const uint32_t kring = __builtin_amdgcn_readfirstlane(smem_lds + wave * TILE);
-      const uint32_t vring = __builtin_amdgcn_readfirstlane(smem_lds + (2 + wave) * TILE);
+      const uint32_t kring = smem_s + wave * TILE, vring = smem_s + (2 + wave) * TILE;
+      plan.vragged = false;
       uint32_t kx[KS], vx[DT];
       const int lim0[2] = {0, 0};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) kx[ks] = ka0[ks] + wave * TILE;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) vx[dt] = va0[dt] + wave * TILE;
-      int d_cur = t_src[solo_b], d_next = t_src[min(solo_b + 1, solo_e - 1)], d_nn;
+      int d_cur = t_src[solo_b], d_next, d_nn;
       // sources of the loads of the steps of tile t: K from tile t+1, V from tile t; HALF picks the rows
 #define PBSA_SOLO_PLAN(HALF)                                                                            \
   plan.kp = kl_h + (size_t)(__builtin_amdgcn_readfirstlane(d_next) & 0x7FFFFFFF) * (kTile * D * 2) + (HALF) * SUB1; \
@@ -819,12 +786,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   plan.klds = kring + (HALF) * SUB1;                                                                    \
   plan.vlds = vring + (HALF) * SUB1;
 #define PBSA_SOLO_LANDED asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      {
-        const unsigned char* kp_ = kl_h + (size_t)(__builtin_amdgcn_readfirstlane(d_cur) & 0x7FFFFFFF) * (kTile * D * 2);
-#pragma unroll
-        for (int i = 0; i < 2 * NIW; ++i)
-          dma16(kp_ + (i / NPAT) * (16 * ROW), plan.ksolo[i % NPAT], kring + i * 1024);
-      }
+      d_next = d_cur;                     // the whole K tile of the first solo tile, half by half
+      PBSA_SOLO_PLAN(0)
+      dma_all<D>(plan, true, false);
+      PBSA_SOLO_PLAN(1)
+      dma_all<D>(plan, true, false);
+      d_next = t_src[min(solo_b + 1, solo_e - 1)];
       PBSA_SOLO_LANDED
       step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
       PBSA_SOLO_PLAN(0)
