@@ -113,6 +113,55 @@ def sweep_kernel_grid(dev, reps=20):
             "data": "synthetic", "dtype": "bf16", "n_gpus": 1, "rows": rows}
 
 
+def bench_blockify(dev, reps=50):
+    """pbsa_blockify on a chunk of the paper's kernel-benchmark geometry (3 frames of 56 x 32 patches =
+    5376 tokens, 12 heads of 128): Q, K and V rearranged in one launch, K and V straight into a ring
+    position of a cache; then pbsa_unblockify of an output.  A permutation: algorithmic bytes = every
+    byte read once and written once."""
+    import numpy as np
+    import torch
+    from paper_2604_21221_amd import pbsa
+    from oracle import blockify as ob
+    T, Hs, Ws, H, d, B = 3, 56, 32, 12, 128, 64
+    rows = []
+    for Bt, Bh, Bw in ((1, 8, 8), (3, 4, 4)):
+        g = pbsa.make_grid(T, Hs, Ws, Bt, Bh, Bw, H, d, B)
+        nb = (T // Bt) * (Hs // Bh) * (Ws // Bw)
+        X = [torch.randn(T, Hs, Ws, H, d, device=dev).to(torch.bfloat16) for _ in range(3)]
+        cap = 4 * nb
+        Kl = torch.zeros(H, cap, B, d, dtype=torch.bfloat16, device=dev)
+        Vl = torch.zeros_like(Kl)
+        Qb = torch.zeros(H, nb, B, d, dtype=torch.bfloat16, device=dev)
+        O = torch.empty(T, Hs, Ws, H, d, dtype=torch.bfloat16, device=dev)
+        fwd = lambda: pbsa.pbsa_blockify(g, X, [Qb, Kl[:, nb:], Vl[:, nb:]], [nb * B * d, cap * B * d, cap * B * d])
+        inv = lambda: pbsa.pbsa_unblockify(g, Qb, nb * B * d, O)
+        out = {}
+        for name, fn, n_t in (("pbsa_blockify", fwd, 3), ("pbsa_unblockify", inv, 1)):
+            for _ in range(100):
+                fn()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for a, b in ev:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            us = float(np.median([a.elapsed_time(b) for a, b in ev])) * 1e3
+            nbytes = 2 * n_t * T * Hs * Ws * H * d * 2
+            out[name] = {"us": round(us, 2), "algorithmic_bytes": nbytes, "achieved": round(nbytes / us / 1e3, 1),
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4)}
+        assert torch.equal(O, X[0]), "rearrange and its inverse do not give the input back"
+        xh = X[1].cpu().view(torch.int16).numpy()
+        t0 = time.perf_counter()
+        ref = ob.blockify(xh, Bt, Bh, Bw)
+        t_cpu = time.perf_counter() - t0
+        assert np.array_equal(Kl[:, nb:2 * nb, :Bt * Bh * Bw].cpu().view(torch.int16).numpy(), ref)
+        out["cpu_oracle_us_per_tensor"] = round(t_cpu * 1e6, 1)
+        rows.append({"block": [Bt, Bh, Bw], "n_blocks": nb, **out})
+    return {"metric": "pbsa_blockify / pbsa_unblockify achieved HBM GB/s (bytes read + written)", "unit": "GB/s",
+            "config": {"workload": "chunk of 3 x 56 x 32 tokens, H=12, d=128, block slots of 64 rows; Q, K, V in one launch"},
+            "data": "synthetic", "dtype": "bf16", "n_gpus": 1, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -130,6 +179,8 @@ def main():
                     help="instead of the step benchmark: pbsa_attention_fwd alone on the shapes of the paper's "
                          "kernel benchmark (forward latency table of its appendix) that fit the interface limits, "
                          "at top-k 6.25 / 12.5 / 25 % and with every block selected (the dense stand-in)")
+    ap.add_argument("--blockify", action="store_true",
+                    help="instead of the step benchmark: the block rearrange of a chunk's Q, K, V and its inverse")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run three 1 GiB device copies and exit: the known-size kernel that the HBM byte "
                          "counters are scaled by")
@@ -149,6 +200,9 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": b.numel() * 4, "copies": 3}))
+        return
+    if args.blockify:
+        print(json.dumps(bench_blockify(dev)))
         return
     if args.sweep_kernel_grid:
         print(json.dumps(sweep_kernel_grid(dev, reps=max(args.steps, 10))))

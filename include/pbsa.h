@@ -150,6 +150,31 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
                        const int64_t* l_id, float* scores, int32_t* slot_src, void* ws, size_t ws_bytes,
                        void* hip_stream);
 
+/* Locality-preserving block rearrange (App. "Rearrange for Locality Preserving", Alg. 3): the tokens of a
+ * chunk come from the model in (frame, patch row, patch column) order, T x Hs x Ws of them, each a row of
+ * H heads x d; a block is a Bt x Bh x Bw box of the grid, blocks are numbered (t_b, h_b, w_b) row-major and
+ * the tokens of a block (dt, dh, dw) row-major, which is the block-major layout every other call here works
+ * on.  Alg. 3 assumes that the block shape divides the grid; so does this call (PBSA_ESHAPE otherwise). */
+typedef struct pbsa_grid {
+  uint32_t size;            /* sizeof(pbsa_grid)                                                    */
+  int32_t T, Hs, Ws;        /* latent grid of the chunk: frames, patch rows, patch columns          */
+  int32_t Bt, Bh, Bw;       /* block shape                                                          */
+  int32_t H, d;             /* heads, head dim (a multiple of 8)                                    */
+  int32_t B;                /* token rows per block slot on the block-major side, >= Bt * Bh * Bw   */
+} pbsa_grid;
+
+/* Rearranges n tensors (1 <= n <= 4: say Q, K and V of a chunk) in one launch.  X[i] is token-major,
+ * [T][Hs][Ws][H][d] bf16.  On the block-major side head h of tensor i starts blk_stride_h[i] * h elements
+ * after Xblk[i], block b of it b * B * d elements further, token row r of the block r * d further; rows
+ * Bt*Bh*Bw .. B-1 of a slot are left as they are (their block's valid length is Bt*Bh*Bw).  With Xblk[i]
+ * pointing at the first slot of a ring position of Kl / Vl and blk_stride_h[i] = n_loc_cap * B * d this is
+ * the cache append.  X, Xblk and blk_stride_h are HOST arrays of n entries; the pointers in X and Xblk are
+ * device pointers, 16-byte aligned; strides are multiples of 8 elements. */
+int pbsa_blockify(const pbsa_grid* g, int32_t n, const void* const* X, void* const* Xblk, const int64_t* blk_stride_h,
+                  void* hip_stream);
+/* The inverse for one tensor (the attention output): block-major Xblk -> token-major X. */
+int pbsa_unblockify(const pbsa_grid* g, const void* Xblk, int64_t blk_stride_h, void* X, void* hip_stream);
+
 const char* pbsa_strerror(int code);
 int pbsa_version(void);
 

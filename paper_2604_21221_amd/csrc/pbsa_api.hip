@@ -143,5 +143,51 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
+namespace {
+int check_grid(const pbsa_grid* g) {
+  if (!g || g->size != sizeof(pbsa_grid)) return PBSA_EINVAL;
+  if (g->T < 1 || g->Hs < 1 || g->Ws < 1 || g->Bt < 1 || g->Bh < 1 || g->Bw < 1 || g->H < 1 || g->d < 8 || g->B < 1)
+    return PBSA_EINVAL;
+  if (g->d % 8 != 0) return PBSA_ESHAPE;
+  if (g->T % g->Bt != 0 || g->Hs % g->Bh != 0 || g->Ws % g->Bw != 0) return PBSA_ESHAPE;
+  if ((int64_t)g->Bt * g->Bh * g->Bw > g->B) return PBSA_ESHAPE;
+  if ((int64_t)g->T * g->Hs * g->Ws * g->H * g->d >= ((int64_t)1 << 40)) return PBSA_ESHAPE;
+  if ((int64_t)g->H * 4 > 65535) return PBSA_ESHAPE;
+  return PBSA_OK;
+}
+}  // namespace
+
+int pbsa_blockify(const pbsa_grid* g, int32_t n, const void* const* X, void* const* Xblk, const int64_t* blk_stride_h,
+                  void* hip_stream) {
+  int rc = check_grid(g);
+  if (rc) return rc;
+  if (n < 1 || n > 4 || !X || !Xblk || !blk_stride_h) return PBSA_EINVAL;
+  pbsa::LayoutTensors t{};
+  t.n = n;
+  for (int i = 0; i < n; ++i) {
+    if (!X[i] || !Xblk[i] || blk_stride_h[i] < 0) return PBSA_EINVAL;
+    if (!aligned16(X[i]) || !aligned16(Xblk[i]) || blk_stride_h[i] % 8 != 0) return PBSA_EALIGN;
+    t.tok[i] = static_cast<const pbsa::bf16_t*>(X[i]);
+    t.blk[i] = static_cast<pbsa::bf16_t*>(Xblk[i]);
+    t.blk_stride_h[i] = blk_stride_h[i];
+  }
+  hipError_t e = pbsa::launch_blockify(*g, t, true, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_unblockify(const pbsa_grid* g, const void* Xblk, int64_t blk_stride_h, void* X, void* hip_stream) {
+  int rc = check_grid(g);
+  if (rc) return rc;
+  if (!X || !Xblk || blk_stride_h < 0) return PBSA_EINVAL;
+  if (!aligned16(X) || !aligned16(Xblk) || blk_stride_h % 8 != 0) return PBSA_EALIGN;
+  pbsa::LayoutTensors t{};
+  t.n = 1;
+  t.tok[0] = static_cast<const pbsa::bf16_t*>(X);
+  t.blk[0] = static_cast<pbsa::bf16_t*>(const_cast<void*>(Xblk));
+  t.blk_stride_h[0] = blk_stride_h;
+  hipError_t e = pbsa::launch_blockify(*g, t, false, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -37,4 +37,13 @@ hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_
                          const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
                          hipStream_t stream);
 
+// blockify: to_blocks = true moves token-major -> block-major, false the other way
+struct LayoutTensors {
+  int n;
+  const bf16_t* tok[4];     // token-major side (read when to_blocks, written otherwise)
+  bf16_t* blk[4];           // block-major side
+  long blk_stride_h[4];
+};
+hipError_t launch_blockify(const pbsa_grid& g, const LayoutTensors& t, bool to_blocks, hipStream_t stream);
+
 }  // namespace pbsa

@@ -16,7 +16,7 @@ PBSA_OK, PBSA_EINVAL, PBSA_ESHAPE, PBSA_EALIGN, PBSA_EWS, PBSA_EHIP = 0, -1, -2,
 PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_K = 512, 64, 512
 
 EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
-           "pbsa_memory_update", "pbsa_strerror", "pbsa_version")
+           "pbsa_memory_update", "pbsa_blockify", "pbsa_unblockify", "pbsa_strerror", "pbsa_version")
 
 
 class pbsa_params(ctypes.Structure):
@@ -35,6 +35,16 @@ def make_params(H, d, B, Nq, n_loc, n_loc_cap, C, k, scale, n_sink=0, causal=1, 
     os_ = o_strides or (Nq * d, d)
     return pbsa_params(ctypes.sizeof(pbsa_params), H, d, B, Nq, -(-Nq // B), n_loc, n_loc_cap, C, n_sink, k, causal,
                        n_evict, pool_from, scale, qs[0], qs[1], os_[0], os_[1])
+
+
+class pbsa_grid(ctypes.Structure):
+    _fields_ = [("size", ctypes.c_uint32), ("T", ctypes.c_int32), ("Hs", ctypes.c_int32), ("Ws", ctypes.c_int32),
+                ("Bt", ctypes.c_int32), ("Bh", ctypes.c_int32), ("Bw", ctypes.c_int32), ("H", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("B", ctypes.c_int32)]
+
+
+def make_grid(T, Hs, Ws, Bt, Bh, Bw, H, d, B) -> pbsa_grid:
+    return pbsa_grid(ctypes.sizeof(pbsa_grid), T, Hs, Ws, Bt, Bh, Bw, H, d, B)
 
 
 class PbsaError(RuntimeError):
@@ -65,8 +75,11 @@ def lib() -> ctypes.CDLL:
         L.pbsa_select_blocks.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.pbsa_attention_fwd.argtypes = [pp] + [vp] * 12 + [sz, vp]
         L.pbsa_memory_update.argtypes = [pp] + [vp] * 18 + [sz, vp]
+        pg = ctypes.POINTER(pbsa_grid)
+        L.pbsa_blockify.argtypes = [pg, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_int64), vp]
+        L.pbsa_unblockify.argtypes = [pg, vp, ctypes.c_int64, vp, vp]
         for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
-                     "pbsa_memory_update"):
+                     "pbsa_memory_update", "pbsa_blockify", "pbsa_unblockify"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -144,3 +157,16 @@ def pbsa_memory_update(p, Qc, Kc_l, Zl, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt,
                                     _ptr(p_len), _ptr(p_id), _ptr(S_sum), _ptr(S_cnt), _ptr(Kl), _ptr(Vl),
                                     _ptr(l_len), _ptr(l_map), _ptr(l_id), _ptr(scores), _ptr(slot_src), w, wb,
                                     _stream(stream)))
+
+
+def pbsa_blockify(g, X, Xblk, blk_stride_h, stream=None):
+    """X, Xblk: sequences of tensors (or device addresses), blk_stride_h: sequence of ints, one per tensor."""
+    n = len(X)
+    xs = (ctypes.c_void_p * n)(*[_ptr(x) for x in X])
+    bs = (ctypes.c_void_p * n)(*[_ptr(x) for x in Xblk])
+    st = (ctypes.c_int64 * n)(*[int(v) for v in blk_stride_h])
+    _check(lib().pbsa_blockify(ctypes.byref(g), n, xs, bs, st, _stream(stream)))
+
+
+def pbsa_unblockify(g, Xblk, blk_stride_h, X, stream=None):
+    _check(lib().pbsa_unblockify(ctypes.byref(g), _ptr(Xblk), int(blk_stride_h), _ptr(X), _stream(stream)))

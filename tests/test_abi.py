@@ -137,3 +137,36 @@ def test_binding_refuses_host_tensors(L):
     import torch
     with pytest.raises(TypeError):
         pbsa.pbsa_select_blocks(good(), torch.zeros(4), P, P, P, P, P, P, None, None, stream=0)
+
+
+def test_blockify_argument_checks(L):
+    """Grid and pointer validation of the rearrange calls; no GPU needed (validation precedes any HIP call)."""
+    import ctypes
+    vp = ctypes.c_void_p
+    good = dict(T=3, Hs=8, Ws=8, Bt=1, Bh=8, Bw=8, H=2, d=128, B=64)
+    X = (vp * 1)(0x1000)
+    Y = (vp * 1)(0x2000)
+    st = (ctypes.c_int64 * 1)(64 * 128 * 3)
+
+    def call(**kw):
+        g = pbsa.make_grid(**{**good, **kw})
+        return L.pbsa_blockify(ctypes.byref(g), 1, X, Y, st, None)
+
+    assert call(Bh=3) == pbsa.PBSA_ESHAPE            # block shape must divide the grid
+    assert call(Bt=2) == pbsa.PBSA_ESHAPE
+    assert call(B=63) == pbsa.PBSA_ESHAPE            # a slot must hold a block
+    assert call(d=12) == pbsa.PBSA_ESHAPE
+    assert call(T=0) == pbsa.PBSA_EINVAL
+    g = pbsa.make_grid(**good)
+    assert L.pbsa_blockify(ctypes.byref(g), 0, X, Y, st, None) == pbsa.PBSA_EINVAL
+    assert L.pbsa_blockify(ctypes.byref(g), 5, X, Y, st, None) == pbsa.PBSA_EINVAL
+    assert L.pbsa_blockify(ctypes.byref(g), 1, None, Y, st, None) == pbsa.PBSA_EINVAL
+    bad = (vp * 1)(0x1004)
+    assert L.pbsa_blockify(ctypes.byref(g), 1, bad, Y, st, None) == pbsa.PBSA_EALIGN
+    st_bad = (ctypes.c_int64 * 1)(7)
+    assert L.pbsa_blockify(ctypes.byref(g), 1, X, Y, st_bad, None) == pbsa.PBSA_EALIGN
+    g.size = 4
+    assert L.pbsa_blockify(ctypes.byref(g), 1, X, Y, st, None) == pbsa.PBSA_EINVAL
+    g = pbsa.make_grid(**good)
+    assert L.pbsa_unblockify(ctypes.byref(g), None, 0, vp(0x1000), None) == pbsa.PBSA_EINVAL
+    assert L.pbsa_unblockify(ctypes.byref(g), vp(0x1008), 0, vp(0x1000), None) == pbsa.PBSA_EALIGN

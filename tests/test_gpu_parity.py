@@ -266,6 +266,85 @@ def test_denoising_passes_share_the_cache(gpu):
 
 
 # ------------------------------------------------------------------------------------------------
+# block rearrange (Alg. 3): a permutation, compared bit for bit
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(3, 56, 32, 1, 8, 8, 12, 128, 64), (3, 56, 32, 3, 4, 4, 12, 128, 64),
+                                   (2, 6, 10, 1, 3, 5, 3, 64, 64), (1, 8, 8, 1, 8, 8, 1, 8, 128)],
+                         ids=["frames_1x8x8", "frames_3x4x4_in_64_slots", "odd_small", "one_block"])
+def test_blockify_matches_the_oracle(gpu, shape):
+    """Three tensors in one launch, each into its own strided destination (one of them a ring position
+    of a larger cache); rows of a slot beyond the block's tokens keep what they held; the inverse call
+    restores the token-major tensor."""
+    from oracle import blockify as ob
+    T, Hs, Ws, Bt, Bh, Bw, H, d, B = shape
+    pbsa = gpu["pbsa"]
+    g = pbsa.make_grid(T, Hs, Ws, Bt, Bh, Bw, H, d, B)
+    nb, rows = (T // Bt) * (Hs // Bh) * (Ws // Bw), Bt * Bh * Bw
+    print(f"[case] blockify {shape}", flush=True)
+    Xs = [rnd(500 + i, T, Hs, Ws, H, d) for i in range(3)]
+    Xd = [torch.from_numpy(x.view(np.int16)).to(DEV) for x in Xs]
+    cap = nb + 5                                           # tensor 0 goes to slots 3.. of a cache of `cap` slots per head
+    dst = [torch.full((H, cap, B, d), 0x1234, dtype=torch.int16, device=DEV),
+           torch.full((H, nb, B, d), 0x1234, dtype=torch.int16, device=DEV),
+           torch.full((H, nb, B, d), 0x1234, dtype=torch.int16, device=DEV)]
+    pbsa.pbsa_blockify(g, Xd, [dst[0][:, 3:], dst[1], dst[2]], [cap * B * d, nb * B * d, nb * B * d])
+    for i in range(3):
+        ref = ob.blockify(Xs[i], Bt, Bh, Bw).view(np.int16)
+        got = dst[i].cpu().numpy()
+        blk = got[:, 3:3 + nb] if i == 0 else got
+        assert np.array_equal(blk[:, :, :rows], ref), f"tensor {i}"
+        assert np.all(blk[:, :, rows:] == 0x1234), "rows beyond the block were touched"
+        if i == 0:
+            assert np.all(got[:, :3] == 0x1234) and np.all(got[:, 3 + nb:] == 0x1234), "slots outside the target were touched"
+    back = torch.full((T, Hs, Ws, H, d), 0x4321, dtype=torch.int16, device=DEV)
+    pbsa.pbsa_unblockify(g, dst[1], nb * B * d, back)
+    assert np.array_equal(back.cpu().numpy(), Xs[1].view(np.int16))
+
+
+def test_blockified_chunk_through_the_whole_step(gpu):
+    """Model-side tensors in, model-side output out: Q, K, V of a chunk arrive token-major on a T x Hs x Ws
+    grid, pbsa_blockify appends K/V to the cache and lays Q out, the three calls run, pbsa_unblockify
+    returns O.  The oracle does the same with its own rearrange."""
+    from oracle import blockify as ob
+    T, Hs, Ws, Bt, Bh, Bw, H, d, B = 2, 8, 16, 1, 8, 8, 2, 128, 64
+    Nq = T * Hs * Ws
+    w, C, k = 1, 2, 2
+    scale = np.float32(1.0 / math.sqrt(d))
+    pbsa, wl = gpu["pbsa"], gpu["wl"]
+    g = pbsa.make_grid(T, Hs, Ws, Bt, Bh, Bw, H, d, B)
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    lens = np.full(st.nqb, B, np.int32)
+    for gidx in range(3):
+        print(f"[case] blockified step chunk {gidx}", flush=True)
+        Xq, Xk, Xv = (rnd(600 + 3 * gidx + j, T, Hs, Ws, H, d, scale=(1.5 if j == 1 else 1.0)) for j in range(3))
+        # oracle side: rearrange, then the block-major path
+        Qb, Kb, Vb = (ob.blockify(x, Bt, Bh, Bw) for x in (Xq, Xk, Xv))          # [H][nqb][B][d]
+        st.append_chunk(Kb, Vb, lens, gidx * st.nqb + np.arange(st.nqb))
+        Qo = Qb.reshape(H, Nq, d)
+        st.select(Qo)
+        Oref, _ = st.attention(Qo)
+        Oref_tok = ob.unblockify(Oref.reshape(H, st.nqb, B, d), T, Hs, Ws, Bt, Bh, Bw)
+        # library side
+        pos = c.n_appended % (w + 1)
+        Qd = torch.empty(H, Nq, d, dtype=torch.bfloat16, device=DEV)
+        src = [torch.from_numpy(x.view(np.int16)).to(DEV) for x in (Xq, Xk, Xv)]
+        pbsa.pbsa_blockify(g, src, [Qd, c.Kl[:, pos * c.nqb:], c.Vl[:, pos * c.nqb:]],
+                           [Nq * d, c.Kl.stride(0), c.Vl.stride(0)])
+        c.adopt_chunk(gidx)
+        c.select(Qd)
+        compare_select(c, st, "blockified")
+        O = c.attention(Qd)
+        Otok = torch.empty(T, Hs, Ws, H, d, dtype=torch.bfloat16, device=DEV)
+        pbsa.pbsa_unblockify(g, O, Nq * d, Otok)
+        check_attention(Otok.float().cpu().numpy(), Oref_tok, "blockified")
+        ne = st.n_evict_now()
+        sc_ref, src_ref = st.update()
+        assert c.update() == ne
+        compare_update(c, st, wl, sc_ref, src_ref, ne, "blockified")
+
+
+# ------------------------------------------------------------------------------------------------
 # the five workloads
 # ------------------------------------------------------------------------------------------------
 def test_cfg1_every_element(gpu):

@@ -436,3 +436,44 @@ def test_cfg1_rollout_matches_the_stored_fixture():
             assert a[key] == b[key], key
         assert np.allclose(a["O_rows"], b["O_rows"], atol=1e-5)
         assert np.allclose(a["lse_rows"], b["lse_rows"], atol=1e-5)
+
+
+# ------------------------------------------------------------------------------------------------
+# block rearrange (Alg. 3): pinned by a brute-force index walk and by what the layout promises
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(3, 8, 12, 1, 4, 4), (3, 8, 8, 3, 4, 4), (2, 16, 8, 1, 8, 8), (4, 4, 6, 2, 2, 3)])
+def test_blockify_is_the_box_walk(shape):
+    from oracle import blockify as ob
+    T, Hs, Ws, Bt, Bh, Bw = shape
+    H, d = 2, 3
+    X = np.arange(T * Hs * Ws * H * d, dtype=np.int64).reshape(T, Hs, Ws, H, d)
+    Y = ob.blockify(X, Bt, Bh, Bw)
+    Nt, Nh, Nw = T // Bt, Hs // Bh, Ws // Bw
+    assert Y.shape == (H, Nt * Nh * Nw, Bt * Bh * Bw, d)
+    # every block is one box of the grid, blocks and the tokens inside them in row-major order
+    for tb in range(Nt):
+        for hb in range(Nh):
+            for wb in range(Nw):
+                b = (tb * Nh + hb) * Nw + wb
+                r = 0
+                for dt in range(Bt):
+                    for dh in range(Bh):
+                        for dw in range(Bw):
+                            for h in range(H):
+                                assert np.array_equal(Y[h, b, r], X[tb * Bt + dt, hb * Bh + dh, wb * Bw + dw, h])
+                            r += 1
+    # a permutation (nothing lost, nothing doubled) and its inverse
+    assert np.array_equal(np.sort(Y.ravel()), X.ravel())
+    assert np.array_equal(ob.unblockify(Y, T, Hs, Ws, Bt, Bh, Bw), X)
+
+
+def test_blockify_degenerate_shapes():
+    from oracle import blockify as ob
+    X = np.arange(2 * 4 * 6 * 1 * 2).reshape(2, 4, 6, 1, 2)
+    # one block = the whole grid: token order unchanged; blocks of one token: token order unchanged too
+    assert np.array_equal(ob.blockify(X, 2, 4, 6)[0, 0], X.reshape(-1, 2))
+    assert np.array_equal(ob.blockify(X, 1, 1, 1)[0, :, 0], X.reshape(-1, 2))
+    # blocks that are whole rows keep raster order
+    assert np.array_equal(ob.blockify(X, 1, 1, 6)[0].reshape(-1, 2), X.reshape(-1, 2))
+    with pytest.raises(AssertionError):
+        ob.blockify(X, 1, 3, 6)
