@@ -426,9 +426,8 @@ struct SoftmaxRun {
 // The softmax of a sub-tile is settled at the start of the step that uses its probabilities (every step
 // with a second product).  Normally its row sums join the running sums and that is all.  If a sum says
 // that the reference of some row no longer serves (or was never set: a row's first keys), the softmax of
-// the sub-tile is redone here, outside the pipeline, for both row groups: row maxima, new references
-// where a score is more than kSlack above the old one (the other rows keep theirs and get the same
-// probabilities again), probabilities, running sums; the caller then rescales the output accumulators by
+// the sub-tile is redone here, outside the pipeline, for both row groups: row maxima, references raised
+// to kLift above them where that is higher than the old reference, probabilities, running sums; the caller then rescales the output accumulators by
 // alpha unless nothing has been added to them yet.  Returns whether the softmax was redone (the same
 // answer in every lane).  s is the sub-tile's S^T, which the coming step will overwrite, p its P^T.
 template <int D>
@@ -440,7 +439,9 @@ __device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const float tmax = row_max(s[g]);
-      const float m_new = tmax * c2 > m_ref[g] * c2 + kSlack ? tmax + lift : m_ref[g];
+      // every row takes the occasion to move its reference up to kLift above what it sees now: the redo and the
+      // rescale cost the same, and a row that was drifting towards its own limit will not ask for another
+      const float m_new = tmax + lift > m_ref[g] ? tmax + lift : m_ref[g];
       alpha[g] = __builtin_amdgcn_exp2f((m_ref[g] - m_new) * c2);
       m_ref[g] = m_new;
       mc[g] = -m_new * c2;
