@@ -496,6 +496,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   __shared__ int t_src[kMaxTiles];         // bit 31: local, bits 0..: (slot * SUB + sub)
   __shared__ int t_meta[kMaxTiles];        // valid keys (bits 0..7) | waves that attend (bits 8, 9)
   __shared__ int cls_end_s[4];             // end of each part of the list
+  constexpr int kMaxRounds = (kMaxTiles + kThreads - 1) / kThreads;
+  __shared__ int cnt_s[kMaxRounds * 2 * 4], off_s[kMaxRounds * 2 * 4];   // per round, wave and class: tiles, first place
   int* lflag = reinterpret_cast<int*>(smem);        // setup scratch, dead before the first tile is staged
 
   // XCD-aware mapping: consecutive workgroup ids go round-robin to the 8 XCDs, so give XCD x the
@@ -533,8 +535,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   // ---- tile list --------------------------------------------------------------------------------
   // Everything the list needs is fetched from global memory in one parallel round into LDS scratch:
   // per local block the set of waves whose query block selected it, its length and its physical slot;
-  // per persistent slot its length.  Wave 0 then compacts both into the list with ballots, one pass
-  // per part: full tiles of both waves, ragged tiles, full tiles of wave 0 only, of wave 1 only.
+  // per persistent slot its length.  The candidates -- the 64-key tiles of the persistent slots, then
+  // of the local blocks, in ascending order -- are then classified by all threads, candidate i by thread
+  // i mod 128 in round i / 128: full tiles of both waves, ragged tiles, full tiles of wave 0 only, of
+  // wave 1 only.  A first pass counts each class per round and wave (ballots), one thread per class
+  // turns the counts into offsets, a second pass classifies again and writes each tile to its place:
+  // every part of the list is in ascending candidate order.
   int* llen_s = lflag + PBSA_MAX_N_LOC;
   int* lmap_s = llen_s + PBSA_MAX_N_LOC;
   int* plen_s = lmap_s + PBSA_MAX_N_LOC;
@@ -554,47 +560,58 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     }
   }
   __syncthreads();
-  if (wave == 0) {
+  const int n_pers = (a.C + 1) * SUB, n_cand = n_pers + a.n_loc * SUB;
+  // candidate i -> its class (-1: no tile) and its list entry
+  auto classify = [&](int i, int& src, int& meta) -> int {
+    if (i >= n_cand) return -1;
+    if (i < n_pers) {
+      const int c = i / SUB, sub = i % SUB;
+      const int tl = min(max(min(max(plen_s[c], 0), B) - sub * kTile, 0), kTile);
+      src = i;
+      meta = tl | (3 << 8);
+      return tl == 0 ? -1 : tl == kTile ? 0 : 1;
+    }
+    const int l = (i - n_pers) / SUB, sub = (i - n_pers) % SUB;
+    const int f = lflag[l], slot = lmap_s[l];
+    if (f == 0 || slot < 0 || slot >= a.n_loc_cap) return -1;
+    const int tl = min(max(min(max(llen_s[l], 0), B) - sub * kTile, 0), kTile);
+    src = (int)(0x80000000u | (uint32_t)(slot * SUB + sub));
+    meta = tl | (f << 8);
+    return tl == 0 ? -1 : tl < kTile ? 1 : f == 3 ? 0 : f + 1;      // f is 1 or 2 otherwise
+  };
+  const int n_rounds = (n_cand + kThreads - 1) / kThreads;
+  for (int r = 0; r < n_rounds; ++r) {
+    int src, meta;
+    const int cls = classify(r * kThreads + tid, src, meta);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const unsigned long long m = __ballot(cls == c);
+      if (lane == 0) cnt_s[(r * 2 + wave) * 4 + c] = __popcll(m);
+    }
+  }
+  __syncthreads();
+  if (tid < 4) {                           // class tid: its range in the list, and where each round and wave writes
     int n = 0;
-    for (int cls = 0; cls < 4; ++cls) {
-      for (int s = 0; s < SUB; ++s) {
-        if (cls < 2) {
-          for (int c0 = 0; c0 <= a.C; c0 += 64) {
-            const int c = c0 + lane;
-            const int len = c <= a.C ? min(max(plen_s[c], 0), B) : 0;
-            const int tl = min(max(len - s * kTile, 0), kTile);
-            const bool take = tl > 0 && (tl == kTile ? cls == 0 : cls == 1);
-            const unsigned long long m = __ballot(take);
-            if (take) {
-              const int pos = n + lanes_below(m);
-              t_src[pos] = c * SUB + s;
-              t_meta[pos] = tl | (3 << 8);
-            }
-            n += __popcll(m);
-          }
-        }
-        for (int l0 = 0; l0 < a.n_loc; l0 += 64) {
-          const int l = l0 + lane;
-          const int f = l < a.n_loc ? lflag[l] : 0;
-          int len = 0, slot = 0;
-          if (f) {
-            len = min(max(llen_s[l], 0), B);
-            slot = lmap_s[l];
-            if (slot < 0 || slot >= a.n_loc_cap) len = 0;
-          }
-          const int tl = min(max(len - s * kTile, 0), kTile);
-          const int my_cls = tl < kTile ? 1 : f == 3 ? 0 : f + 1;      // f is 1 or 2 otherwise
-          const bool take = f != 0 && tl > 0 && my_cls == cls;
-          const unsigned long long m = __ballot(take);
-          if (take) {
-            const int pos = n + lanes_below(m);
-            t_src[pos] = (int)(0x80000000u | (uint32_t)(slot * SUB + s));
-            t_meta[pos] = tl | (f << 8);
-          }
-          n += __popcll(m);
-        }
+    for (int c = 0; c < tid; ++c)
+      for (int q = 0; q < 2 * n_rounds; ++q) n += cnt_s[q * 4 + c];
+    for (int q = 0; q < 2 * n_rounds; ++q) {
+      off_s[q * 4 + tid] = n;
+      n += cnt_s[q * 4 + tid];
+    }
+    cls_end_s[tid] = n;
+  }
+  __syncthreads();
+  for (int r = 0; r < n_rounds; ++r) {
+    int src = 0, meta = 0;
+    const int cls = classify(r * kThreads + tid, src, meta);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const unsigned long long m = __ballot(cls == c);
+      if (cls == c) {
+        const int pos = off_s[(r * 2 + wave) * 4 + c] + lanes_below(m);
+        t_src[pos] = src;
+        t_meta[pos] = meta;
       }
-      if (lane == 0) cls_end_s[cls] = n;
     }
   }
   __syncthreads();
