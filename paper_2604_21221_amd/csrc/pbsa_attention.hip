@@ -514,24 +514,6 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   const int i0 = T0 / B;
   const int qn = lane & 31, half = lane >> 5;
 
-  // ---- Q fragments (B operand of S^T = K Q^T): row group g, query row lane % 32, dims 16 ks + 8 (lane/32) ..+8.
-  // Issued first so the loads fly while the tile list is built.
-  const int tok0 = T0 + wave * 64 + qn;                 // row group g holds token tok0 + 32 g
-  bf16x8 qf[2][KS];
-#pragma unroll
-  for (int g = 0; g < 2; ++g) {
-    const int tok_c = min(tok0 + 32 * g, a.Nq - 1);
-    const bf16_t* qrow = a.Q + (size_t)h * a.q_stride_h + (size_t)tok_c * a.q_stride_t + 8 * half;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[g][ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks);
-  }
-  // The Q fragments are only ever MFMA operands, which may come from the accumulator half of the
-  // register file: define them there, leaving the architectural half to the softmax and the outputs.
-#pragma unroll
-  for (int g = 0; g < 2; ++g)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[g][ks]));
-
   // ---- tile list --------------------------------------------------------------------------------
   // Everything the list needs is fetched from global memory in one parallel round into LDS scratch:
   // per local block the set of waves whose query block selected it, its length and its physical slot;
@@ -550,14 +532,35 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     lmap_s[l] = a.l_map[l];
   }
   for (int c = tid; c <= a.C; c += kThreads) plen_s[c] = a.p_len[(size_t)h * (a.C + 1) + c];
+  // the selections of this workgroup's query blocks, fetched now (loads return in order: anything asked
+  // for after the queries would wait for them) and turned into flags once the flags are zeroed
+  constexpr int kSelPer = (2 * PBSA_MAX_K + kThreads - 1) / kThreads;
+  int selv[kSelPer];
+#pragma unroll
+  for (int u = 0; u < kSelPer; ++u) {
+    const int idx = tid + u * kThreads;
+    const int g = idx / max(a.k, 1), j = idx % max(a.k, 1);
+    selv[u] = idx < G * a.k && i0 + g < a.nqb ? a.sel[((size_t)h * a.nqb + i0 + g) * a.k + j] : -1;
+  }
+
+  // ---- Q fragments (B operand of S^T = K Q^T): row group g, query row lane % 32, dims 16 ks + 8 (lane/32) ..+8.
+  // Issued after the few loads the tile list waits for and not touched until the list is built: the
+  // chunk's queries come from HBM while every workgroup of the launch asks for its own at the same time.
+  const int tok0 = T0 + wave * 64 + qn;                 // row group g holds token tok0 + 32 g
+  bf16x8 qf[2][KS];
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    const int tok_c = min(tok0 + 32 * g, a.Nq - 1);
+    const bf16_t* qrow = a.Q + (size_t)h * a.q_stride_h + (size_t)tok_c * a.q_stride_t + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[g][ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks);
+  }
   __syncthreads();
-  for (int idx = tid; idx < G * a.k; idx += kThreads) {
-    const int g = idx / a.k, j = idx % a.k;
-    if (i0 + g < a.nqb) {
-      const int l = a.sel[((size_t)h * a.nqb + i0 + g) * a.k + j];
-      // with one query block per workgroup both waves belong to it
-      if (l >= 0 && l < a.n_loc) atomicOr(&lflag[l], G == 1 ? 3 : 1 << g);
-    }
+#pragma unroll
+  for (int u = 0; u < kSelPer; ++u) {
+    const int l = selv[u], g = (tid + u * kThreads) / max(a.k, 1);
+    // with one query block per workgroup both waves belong to it
+    if (l >= 0 && l < a.n_loc) atomicOr(&lflag[l], G == 1 ? 3 : 1 << g);
   }
   __syncthreads();
   const int n_pers = (a.C + 1) * SUB, n_cand = n_pers + a.n_loc * SUB;
@@ -615,6 +618,13 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     }
   }
   __syncthreads();
+  // The Q fragments are only ever MFMA operands, which may come from the accumulator half of the
+  // register file: define them there, leaving the architectural half to the softmax and the outputs.
+#pragma unroll
+  for (int g = 0; g < 2; ++g)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[g][ks]));
+
   const int e0 = cls_end_s[0];             // shared full tiles [0, e0)
   const int n_tiles = cls_end_s[1];        // shared ragged tiles [e0, n_tiles): the end of the shared list
   const int solo_b = wave == 0 ? n_tiles : cls_end_s[2];       // this wave's solo tiles [solo_b, solo_e)
