@@ -149,6 +149,24 @@ def test_small_rollout_every_element(gpu, case):
         run_both(gpu, c, st, Q, K, V, g, "all", name)
 
 
+def test_disjoint_selections_without_memory(gpu):
+    """No persistent blocks, and the two query blocks of a workgroup select different key blocks: the
+    kernel's tile list then has no tile both waves attend, only tiles each wave walks alone."""
+    H, d, B, Nq, w, C, k = 2, 128, 64, 128, 1, 0, 1
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale, causal=0)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, causal=0, device=DEV)
+    for g in range(3):
+        Q = synth.bf16_bits_to_f32(rnd(700 + 3 * g, H, Nq, d))
+        K = synth.bf16_bits_to_f32(rnd(701 + 3 * g, H, Nq, d))
+        # query block i looks along axis i, key block i of the chunk lies along axis i: block i selects block i
+        for i in range(2):
+            Q[:, i * B:(i + 1) * B, i] += 8.0
+            K[:, i * B:(i + 1) * B, i] += 8.0
+        run_both(gpu, c, st, synth.to_bf16_bits(Q), synth.to_bf16_bits(K), rnd(702 + 3 * g, H, Nq, d), g, "all", "disjoint")
+        assert not np.intersect1d(st.sel[0, 0], st.sel[0, 1]).size, "the case must keep the selections apart"
+
+
 @pytest.mark.parametrize("k", [128, 512])
 def test_maximum_sizes(gpu, k):
     """The limits of the interface at once: 512 local blocks, 64 persistent slots, a ragged last block, and
