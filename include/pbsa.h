@@ -74,7 +74,9 @@ extern "C" {
 #define PBSA_EHIP   (-5) /* a HIP call or kernel launch failed                                   */
 
 #define PBSA_MAX_N_LOC 512 /* logical local blocks          */
-#define PBSA_MAX_C      64 /* persistent slots              */
+#define PBSA_MAX_C      64 /* persistent slots that pbsa_memory_update can maintain */
+#define PBSA_MAX_C_ATTEND 192 /* persistent slots that pbsa_attention_fwd can attend (pbsa_select_blocks does not
+                               * look at them); above PBSA_MAX_C the caller maintains the set itself */
 #define PBSA_MAX_K     512 /* selected blocks per query block */
 
 typedef struct pbsa_params {
@@ -99,7 +101,8 @@ typedef struct pbsa_params {
 } pbsa_params;
 
 /* Bytes of scratch that any call with these parameters may need (device memory, 256-byte aligned,
- * passed as `ws`).  Contents need not be preserved between calls. */
+ * passed as `ws`).  Contents need not be preserved between calls.  Only pbsa_memory_update needs any, so
+ * C is held to PBSA_MAX_C here as there. */
 int pbsa_workspace_bytes(const pbsa_params* p, size_t* out);
 
 /* Block representatives by average pooling (Eq. 6; pooling operator of Sec. 4.1):

@@ -37,7 +37,9 @@ class PbsaCache:
         self.slot_src = torch.full((H, max(C, 1)), -1, dtype=torch.int32, device=self.dev)
         self.scores = z(H, C + self.nqb, dt=torch.float32)
         full = pbsa.make_params(H, d, B, Nq, self.cap, self.cap, C, k, self.scale, n_sink, causal, n_evict=self.nqb)
-        self.ws = torch.empty(max(pbsa.pbsa_workspace_bytes(full), 256), dtype=torch.uint8, device=self.dev)
+        # with more slots than pbsa_memory_update maintains the cache can only be selected from and attended
+        n_ws = pbsa.pbsa_workspace_bytes(full) if C <= pbsa.PBSA_MAX_C else 0
+        self.ws = torch.empty(max(n_ws, 256), dtype=torch.uint8, device=self.dev)
         self.chunk_pos = []          # ring position of each chunk in the local region, oldest first
         self.chunk_ids = []          # global chunk index of each
         self.n_appended = 0

@@ -15,8 +15,8 @@ int hip_fail(hipError_t e) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Checks that do not depend on which call is made.
-int check_common(const pbsa_params* p) {
+// Checks that do not depend on which call is made, but for the number of persistent slots it can handle.
+int check_common(const pbsa_params* p, int max_c = PBSA_MAX_C) {
   if (!p) return PBSA_EINVAL;
   if (p->size != sizeof(pbsa_params)) return PBSA_EINVAL;
   if (p->H < 1 || p->Nq < 1 || p->n_loc < 0 || p->C < 0 || p->k < 0 || p->n_sink < 0 || p->n_evict < 0 ||
@@ -29,7 +29,7 @@ int check_common(const pbsa_params* p) {
   if (p->n_sink > p->C || p->n_evict > p->n_loc || p->pool_from > p->n_loc) return PBSA_EINVAL;
   if (p->causal != 0 && p->causal != 1) return PBSA_EINVAL;
   if (!(p->scale > 0.0f) || !(p->scale < 1e30f)) return PBSA_EINVAL;
-  if (p->n_loc > PBSA_MAX_N_LOC || p->C > PBSA_MAX_C || p->k > PBSA_MAX_K) return PBSA_ESHAPE;
+  if (p->n_loc > PBSA_MAX_N_LOC || p->C > max_c || p->k > PBSA_MAX_K) return PBSA_ESHAPE;
   if ((int64_t)p->H * p->n_loc_cap * p->B * p->d >= ((int64_t)1 << 40)) return PBSA_ESHAPE;
   return PBSA_OK;
 }
@@ -53,7 +53,7 @@ const char* pbsa_strerror(int code) {
   switch (code) {
     case PBSA_OK: return "ok";
     case PBSA_EINVAL: return "invalid argument (NULL pointer, wrong params.size, or inconsistent counts)";
-    case PBSA_ESHAPE: return "unsupported shape (d and B must be 64 or 128; n_loc, C, k within PBSA_MAX_*)";
+    case PBSA_ESHAPE: return "unsupported shape (d and B must be 64 or 128; n_loc, C, k within PBSA_MAX_*; a block shape must divide its grid)";
     case PBSA_EALIGN: return "misaligned pointer (16 bytes) or stride (multiple of 8 elements)";
     case PBSA_EWS: return "workspace missing or too small (see pbsa_workspace_bytes)";
     case PBSA_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP call failed";
@@ -86,7 +86,7 @@ int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, cons
                        const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl, void* ws,
                        size_t ws_bytes, void* hip_stream) {
   (void)ws; (void)ws_bytes;
-  int rc = check_common(p);
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
   if (rc) return rc;
   if (!Q || !Kl || !l_len || !l_map || !Kc_l || !Qc) return PBSA_EINVAL;
   if (p->k > 0 && !sel) return PBSA_EINVAL;
@@ -102,7 +102,7 @@ int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, cons
                        const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
                        const int32_t* sel, void* O, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
   (void)ws; (void)ws_bytes;
-  int rc = check_common(p);
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
   if (rc) return rc;
   if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O) return PBSA_EINVAL;
   if (p->k > 0 && !sel) return PBSA_EINVAL;

@@ -52,7 +52,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kThreads = 128;
 constexpr int kRowsPerWg = 128;
 constexpr int kTile = 64;                 // keys per staged tile
-constexpr int kMaxTiles = 2 * (PBSA_MAX_C + 1) + 2 * PBSA_MAX_N_LOC;   // persistent + local 64-key tiles
+constexpr int kMaxTiles = 2 * (PBSA_MAX_C_ATTEND + 1) + 2 * PBSA_MAX_N_LOC;   // persistent + local 64-key tiles
 constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
 constexpr float kInitMax = -1.0e29f;       // running max of a row that has seen no key: above kMasked, below any score
 // The softmax reference of a row is not its running max: probabilities only have to stay inside the
@@ -490,7 +490,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   constexpr int CH = D / 8, RPI = 64 / CH;          // 16-byte chunks per row, rows per wave instruction
   constexpr int NIW = (kTile / RPI) / 2;            // global_load_lds instructions per wave per tile
   constexpr int SMEM = 4 * TILE;                    // K ring (2 tiles), V ring (2 tiles)
-  static_assert((3 * PBSA_MAX_N_LOC + PBSA_MAX_C + 1) * 4 <= SMEM, "setup scratch must fit");
+  static_assert((3 * PBSA_MAX_N_LOC + PBSA_MAX_C_ATTEND + 1) * 4 <= SMEM, "setup scratch must fit");
 
   __shared__ __align__(1024) unsigned char smem[SMEM];
   __shared__ int t_src[kMaxTiles];         // bit 31: local, bits 0..: (slot * SUB + sub)

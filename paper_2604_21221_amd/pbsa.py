@@ -13,7 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libpbsa.so")
 
 PBSA_OK, PBSA_EINVAL, PBSA_ESHAPE, PBSA_EALIGN, PBSA_EWS, PBSA_EHIP = 0, -1, -2, -3, -4, -5
-PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_K = 512, 64, 512
+PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 512, 64, 192, 512
 
 EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
            "pbsa_memory_update", "pbsa_blockify", "pbsa_unblockify", "pbsa_strerror", "pbsa_version")

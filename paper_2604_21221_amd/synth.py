@@ -188,18 +188,18 @@ WORKLOADS = {
 }
 
 
-def t7_workload(ratio_l: int, ratio_p: float, topk: float, B: int = 128) -> Workload:
+def t7_workload(ratio_l: int, ratio_p: float, topk: float, B: int = 128, frames: int = 3) -> Workload:
     """A shape of the paper's kernel benchmark (App. kernel-level analysis, the forward columns of the
-    latency table): 1792-token frames, query chunk N_C = 3 frames = 5376 tokens (blocks divide it
-    exactly), local KV N_L = ratio_l * N_C (the chunk included), persistent KV N_P = ratio_p * N_L,
+    latency table): 1792-token frames, query chunk N_C = 3 frames = 5376 tokens or 12 frames = 21504
+    (blocks divide it exactly), local KV N_L = ratio_l * N_C (the chunk included), persistent KV N_P = ratio_p * N_L,
     top-k = topk * (number of local blocks); topk = 1 selects every block (the dense stand-in).
     Heads and head dim are not stated there: 12 x 128 as in the other workloads."""
-    F, frames = 1792, 3
+    F = 1792
     nqb = F * frames // B
     n_loc = ratio_l * nqb
     C = int(round(ratio_p * n_loc))
     k = n_loc if topk >= 1.0 else max(1, int(round(topk * n_loc)))
-    name = f"t7_L{ratio_l}_P{int(round(ratio_p * 100))}_K{int(round(topk * 10000))}_B{B}"
+    name = f"t7_C{frames}_L{ratio_l}_P{int(round(ratio_p * 100))}_K{int(round(topk * 10000))}_B{B}"
     return Workload(name, H=12, d=128, F=F, B=B, chunk_frames=frames, window_chunks=ratio_l - 1, C=C, k=k,
                     seed=7, bias_rank=4, bias_scale=2.0)
 

@@ -39,7 +39,7 @@ def test_exports_match_header(L):
 
 def test_header_constants_match_binding():
     text = open(os.path.join(ROOT, "include", "pbsa.h")).read()
-    for name in ("PBSA_MAX_N_LOC", "PBSA_MAX_C", "PBSA_MAX_K"):
+    for name in ("PBSA_MAX_N_LOC", "PBSA_MAX_C", "PBSA_MAX_C_ATTEND", "PBSA_MAX_K"):
         assert int(re.search(rf"#define {name}\s+(\d+)", text).group(1)) == getattr(pbsa, name)
     for name in ("PBSA_EINVAL", "PBSA_ESHAPE", "PBSA_EALIGN", "PBSA_EWS", "PBSA_EHIP"):
         assert int(re.search(rf"#define {name}\s+\((-\d+)\)", text).group(1)) == getattr(pbsa, name)
@@ -70,7 +70,7 @@ def call_update(p, ws=(0x10000, 1 << 30), S_sum=P, S_cnt=P, Qc=P):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(d=96), pbsa.PBSA_ESHAPE), (dict(B=32), pbsa.PBSA_ESHAPE), (dict(k=513), pbsa.PBSA_ESHAPE),
-    (dict(C=65), pbsa.PBSA_ESHAPE), (dict(n_loc=513, n_loc_cap=513), pbsa.PBSA_ESHAPE),
+    (dict(C=193), pbsa.PBSA_ESHAPE), (dict(n_loc=513, n_loc_cap=513), pbsa.PBSA_ESHAPE),
     (dict(n_loc=2), pbsa.PBSA_EINVAL),               # fewer local blocks than the chunk itself has
     (dict(n_loc=17), pbsa.PBSA_EINVAL),              # more than the physical capacity
     (dict(n_sink=5), pbsa.PBSA_EINVAL), (dict(n_evict=17), pbsa.PBSA_EINVAL), (dict(causal=2), pbsa.PBSA_EINVAL),
@@ -87,6 +87,18 @@ def test_bad_params_rejected_by_every_call(L, kw, code):
         with pytest.raises(pbsa.PbsaError) as e:
             call_update(p)
         assert e.value.code == code
+
+
+def test_update_maintains_fewer_slots_than_attention_attends(L):
+    """65..192 persistent slots: the update and its workspace refuse them (that selection and attention accept
+    them is a GPU test: with valid parameters those calls launch)."""
+    p = good(C=65)
+    with pytest.raises(pbsa.PbsaError) as e:
+        call_update(p)
+    assert e.value.code == pbsa.PBSA_ESHAPE
+    with pytest.raises(pbsa.PbsaError) as e:
+        pbsa.pbsa_workspace_bytes(p)
+    assert e.value.code == pbsa.PBSA_ESHAPE
 
 
 def test_wrong_struct_size_and_nqb(L):

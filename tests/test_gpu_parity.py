@@ -149,6 +149,35 @@ def test_small_rollout_every_element(gpu, case):
         run_both(gpu, c, st, Q, K, V, g, "all", name)
 
 
+def test_more_persistent_slots_than_the_update_maintains(gpu):
+    """Selection and attention with 100 persistent slots (the update stops at 64): lengths from empty to
+    full, compared with the oracle on every element."""
+    H, d, B, Nq, w, C, k = 1, 64, 64, 150, 1, 100, 2
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    Kp, Vp = rnd(801, H, C, B, d), rnd(802, H, C, B, d)
+    pl = np.tile((np.arange(C, dtype=np.int32) * 7) % (B + 1), (H, 1))          # 0 .. 64 valid rows
+    ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+    st.set_persistent(Kp, Vp, pl, ids)
+    c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                     torch.from_numpy(ids))
+    lens = np.full(st.nqb, B, np.int32); lens[-1] = Nq - (st.nqb - 1) * B
+    for g in range(2):
+        print(f"[case] 100 slots chunk {g}", flush=True)
+        Q, K, V = rnd(810 + 3 * g, H, Nq, d), rnd(811 + 3 * g, H, Nq, d), rnd(812 + 3 * g, H, Nq, d)
+        st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * st.nqb + np.arange(st.nqb))
+        Qd = gpu["wl"].bf16_tensor(Q, DEV)
+        c.append_chunk(gpu["wl"].bf16_tensor(K, DEV), gpu["wl"].bf16_tensor(V, DEV), g)
+        st.select(Q)
+        c.select(Qd)
+        compare_select(c, st, "100 slots")
+        Oref, _ = st.attention(Q)
+        check_attention(c.attention(Qd).float().cpu().numpy(), Oref, "100 slots")
+    with pytest.raises(gpu["pbsa"].PbsaError):
+        c.update()
+
+
 def test_disjoint_selections_without_memory(gpu):
     """No persistent blocks, and the two query blocks of a workgroup select different key blocks: the
     kernel's tile list then has no tile both waves attend, only tiles each wave walks alone."""
