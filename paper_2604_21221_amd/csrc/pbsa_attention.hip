@@ -32,12 +32,13 @@
 //
 // Software pipeline.  The unit is a sub-tile of 32 keys.  In step u a wave runs, as one straight
 // stretch of code cut into slots (one MFMA plus a slice of vector work each), the softmax of
-// sub-tile u (exp2, max, conversions; S^T(u) -> P^T(u)) together with the MFMAs that do not depend
-// on it: O^T += V^T P^T of sub-tile u-1 and S^T = K Q^T of sub-tile u+1.  S^T and P^T are double
-// buffered.  Each part of the list (shared full, shared ragged, solo) is one pipelined run with its
-// own template instance; the pipeline drains between them.  Softmax is online, fp32, base 2 (scale and
-// log2 e folded into one fma); row sums are taken over the bf16-rounded probabilities, the same
-// numbers the second product uses.
+// sub-tile u (one fma and one exp2 per score, one conversion per pair; S^T(u) -> P^T(u)) together with
+// the MFMAs that do not depend on it: O^T += V^T P^T of sub-tile u-1 and S^T = K Q^T of sub-tile u+1.
+// S^T and P^T are double buffered.  Each part of the list (shared full, shared ragged, solo) is one
+// pipelined run with its own template instance; the pipeline drains between them.  Softmax is online,
+// fp32, base 2 (scale and log2 e folded into one fma), against a reference that a step takes as given;
+// the row sums (over the bf16-rounded probabilities, the numbers the second product uses) and the check
+// that the reference still serves come at the start of the next step (softmax_settle).
 #include "pbsa_internal.h"
 
 namespace pbsa {
@@ -54,11 +55,11 @@ constexpr int kRowsPerWg = 128;
 constexpr int kTile = 64;                 // keys per staged tile
 constexpr int kMaxTiles = 2 * (PBSA_MAX_C_ATTEND + 1) + 2 * PBSA_MAX_N_LOC;   // persistent + local 64-key tiles
 constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
-constexpr float kInitMax = -1.0e29f;       // running max of a row that has seen no key: above kMasked, below any score
+constexpr float kInitMax = -1.0e29f;       // reference of a row that has seen no key: above kMasked, below any score
 // The softmax reference of a row is not its running max: probabilities only have to stay inside the
 // exponent range of bf16 / fp32, whose precision is relative.  The reference is set kLift base-2
 // exponent units above the row max of the sub-tile that sets it and is then used as it stands: a step
-// computes no row maximum.  Whether a reference still serves is read off the row sums the step produces
+// computes no row maximum.  Whether a reference still serves is read off the row sums, which are needed
 // anyway: a probability above 2^kSlack (or an overflow) makes its row's partial sum exceed kBig, and only
 // then is the sub-tile's softmax redone with a new reference and the output accumulators rescaled
 // (softmax_settle).  Probabilities thus lie between 2^-126 and 2^kSlack, their sums and products below
@@ -297,7 +298,7 @@ __device__ __forceinline__ void dma_all(const DmaPlan<D>& p, bool k_too, bool v_
   }
 }
 
-constexpr int kDmaNone = 0, kDmaShared = 1, kDmaSolo = 1;   // a step carries a plan's loads or not
+constexpr bool kLoads = true, kNoLoads = false;   // whether a step carries its plan's loads
 constexpr int kAhead = 4;     // MFMA pairs between an operand read and its use
 
 template <int D, bool PV, bool QK, bool SM, bool RAGGED>
@@ -388,7 +389,7 @@ __device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
   }
 }
 
-template <int D, bool PV, bool QK, bool SM, bool RAGGED, int DMA, int K_OFF, int V_OFF, int I>
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF, int I>
 __device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c) {
   using S = StepCtx<D, PV, QK, SM, RAGGED>;
   if constexpr (I < S::NC) {
@@ -396,7 +397,7 @@ __device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c) {
     if constexpr (k == 0) load_frag<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + kAhead>(c);
     mfma_slot<D, PV, QK, SM, RAGGED, Q, k>(c);
     __builtin_amdgcn_sched_barrier(0);         // the MFMA first, then the slot's vector work
-    if constexpr (DMA != kDmaNone) {
+    if constexpr (DMA) {
       constexpr int every = (S::NC < 16 ? S::NC : 16) / DmaPlan<D>::NB;     // a burst every few slots of the first 16
       static_assert(every >= 1, "a slot for every burst");
       if constexpr (I % every == 0 && I / every < DmaPlan<D>::NB) dma_burst<D, I / every>(c.dma);
@@ -460,7 +461,7 @@ __device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[
 }
 
 // K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
-template <int D, bool PV, bool QK, bool SM, bool RAGGED, int DMA, int K_OFF, int V_OFF>
+template <int D, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF>
 __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS],
                                      const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
                                      f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], u32x4 (&p_prev)[2][2], SoftmaxRun& sr,
@@ -744,21 +745,21 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
     PBSA_ADDR_K(TB)                                                                                     \
     PBSA_ADDR_V(TB)                                                                                     \
-    step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan); \
+    step<D, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan); \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
-    step<D, false, true, true, RAGGED, kDmaNone, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
+    step<D, false, true, true, RAGGED, kNoLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
     PBSA_TURNOVER(TB)                                                                                   \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, true, true, true, RAGGED, kDmaShared, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
+      step<D, true, true, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
-      step<D, true, true, true, RAGGED, kDmaNone, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
+      step<D, true, true, true, RAGGED, kNoLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
       PBSA_TURNOVER(t + 1)                                                                              \
     }                                                                                                   \
     PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, true, false, true, RAGGED, kDmaShared, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
-    step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
+    step<D, true, false, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
+    step<D, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
     /* between runs the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
     acc_settle<DT>(o[0]);                                                                               \
     acc_settle<DT>(o[1]);                                                                               \
@@ -821,25 +822,25 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
       dma_all<D>(plan, true, false);
       d_next = t_src[min(solo_b + 1, solo_e - 1)];
       PBSA_SOLO_LANDED
-      step<D, false, true, false, false, kDmaNone, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
+      step<D, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
       PBSA_SOLO_PLAN(0)
-      step<D, false, true, true, false, kDmaSolo, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
+      step<D, false, true, true, false, kLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
       PBSA_SOLO_LANDED
       for (int t = solo_b; t < solo_e - 1; ++t) {
         d_nn = t_src[min(t + 2, solo_e - 1)];
         PBSA_SOLO_PLAN(1)
-        step<D, true, true, true, false, kDmaSolo, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
+        step<D, true, true, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
         PBSA_SOLO_LANDED
         d_cur = d_next;
         d_next = d_nn;
         PBSA_SOLO_PLAN(0)
-        step<D, true, true, true, false, kDmaSolo, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
+        step<D, true, true, true, false, kLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
         PBSA_SOLO_LANDED
       }
       PBSA_SOLO_PLAN(1)
-      step<D, true, false, true, false, kDmaSolo, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
+      step<D, true, false, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
       PBSA_SOLO_LANDED
-      step<D, true, false, false, false, kDmaNone, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
+      step<D, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
     }
   }
 
