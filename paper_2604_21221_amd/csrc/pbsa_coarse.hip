@@ -510,11 +510,14 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   __shared__ float s[kMaxCand];           // mean column score of slot / evicted-block columns, U order
   __shared__ int cand[kMaxCand];          // < C: slot, else C + local block
   __shared__ unsigned char win[kMaxCand];
+  __shared__ int rank_s[kMaxCand];
+  __shared__ unsigned char vac_s[PBSA_MAX_C];   // slot whose occupant is dropped
   __shared__ int old_len[PBSA_MAX_C + 1];
   __shared__ int src_s[PBSA_MAX_C];
   __shared__ int flen[kMaxCand];          // valid tokens of each dropped candidate
   __shared__ int e_len[PBSA_MAX_N_LOC];   // valid tokens / physical slot of the evicted blocks
   __shared__ int e_map[PBSA_MAX_N_LOC];
+  __shared__ long long e_id[PBSA_MAX_N_LOC];   // global ids of the evicted blocks
   __shared__ int nf_s, npos_s;
   const int h = blockIdx.x, C = a.C, C1 = a.C + 1;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -523,7 +526,11 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   for (int e = threadIdx.x; e < a.n_evict; e += kThreads) {
     e_len[e] = max(0, min(a.l_len[e], a.B));
     e_map[e] = min(max(a.l_map[e], 0), a.n_loc_cap - 1);
+    e_id[e] = a.l_id[e];
   }
+  // the summary's counts are needed at the very end: ask for them now, not after everything else
+  static_assert(kThreads >= 128, "one thread per position of a block");
+  const int cnt_mine = a.fold && threadIdx.x < a.B ? a.S_cnt[(size_t)h * a.B + threadIdx.x] : 0;
   if (threadIdx.x == 0) npos_s = 0;
   __syncthreads();
   // occupied slots: U position of slot c = number of occupied slots below it (C <= 64: one ballot)
@@ -572,25 +579,39 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
     cs[ncP + e] = s[nP + e];
   }
   __syncthreads();
-  for (int x = threadIdx.x; x < nc; x += kThreads) {
-    int rank = 0;
-    const float mine = cs[x];
+  // rank of a candidate = how many beat it (higher score, or equal score and lower index).  All threads
+  // take part: with P = kThreads / nc threads per candidate each counts over its share of the others
+  // (several 16-byte reads in flight), and the shares meet in an integer counter.
+  for (int x = threadIdx.x; x < nc; x += kThreads) rank_s[x] = 0;
+  __syncthreads();
+  {
+    const int P = max(1, kThreads / max(nc, 1)), n4 = (nc + 3) / 4, per = (n4 + P - 1) / P;
     const float4* c4 = reinterpret_cast<const float4*>(cs);
-    for (int y = 0; y < nc; y += 4) {
-      const float4 v = c4[y >> 2];
-      rank += (y + 0 < nc && (v.x > mine || (v.x == mine && y + 0 < x))) ? 1 : 0;
-      rank += (y + 1 < nc && (v.y > mine || (v.y == mine && y + 1 < x))) ? 1 : 0;
-      rank += (y + 2 < nc && (v.z > mine || (v.z == mine && y + 2 < x))) ? 1 : 0;
-      rank += (y + 3 < nc && (v.w > mine || (v.w == mine && y + 3 < x))) ? 1 : 0;
+    for (int idx = threadIdx.x; idx < nc * P; idx += kThreads) {
+      const int x = idx % nc, part = idx / nc;
+      const float mine = cs[x];
+      int rank = 0;
+      const int q_end = min(n4, (part + 1) * per);
+#pragma unroll 4
+      for (int q = part * per; q < q_end; ++q) {
+        const float4 v = c4[q];
+        const int y = 4 * q;
+        rank += (y + 0 < nc && (v.x > mine || (v.x == mine && y + 0 < x))) ? 1 : 0;
+        rank += (y + 1 < nc && (v.y > mine || (v.y == mine && y + 1 < x))) ? 1 : 0;
+        rank += (y + 2 < nc && (v.z > mine || (v.z == mine && y + 2 < x))) ? 1 : 0;
+        rank += (y + 3 < nc && (v.w > mine || (v.w == mine && y + 3 < x))) ? 1 : 0;
+      }
+      if (rank) atomicAdd(&rank_s[x], rank);
     }
-    win[x] = rank < places;
   }
+  __syncthreads();
+  for (int x = threadIdx.x; x < nc; x += kThreads) win[x] = rank_s[x] < places;
+  for (int c = threadIdx.x; c < C; c += kThreads) vac_s[c] = 0;
   __syncthreads();
   // wave 0: dropped candidates, in candidate order, go to the fold list; then kept newcomers, in
   // ascending block order, take the vacated and empty slots in ascending slot order
   if (wave == 0) {
     int nf = 0;
-    uint64_t vacated = 0;                      // slots whose occupant was dropped
     for (int x0 = 0; x0 < nc; x0 += 64) {
       const int x = x0 + lane;
       const bool lose = x < nc && !win[x];
@@ -602,19 +623,18 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
         a.fold_src[(size_t)h * ncand_max + f] = slot_cand ? cand[x] : C + e_map[cand[x] - C];
         a.fold_len[(size_t)h * ncand_max + f] = len;
         flen[f] = len;
+        if (slot_cand) vac_s[cand[x]] = 1;
       }
-      const uint64_t vm = __ballot(lose && cand[min(x, nc - 1)] < C);
-      // bit positions of vm are candidate indices; turn them into slot numbers
-      for (uint64_t m = vm; m; m &= m - 1) vacated |= 1ull << cand[x0 + __ffsll((unsigned long long)m) - 1];
       nf += __popcll(lm);
     }
     if (lane == 0) { a.fold_n[h] = nf; nf_s = nf; }
-    // free slots = (empty or vacated) and >= n_sink
-    const bool is_free = lane < C && lane >= a.n_sink && (old_len[lane] <= 0 || ((vacated >> lane) & 1));
+    // free slots = (empty or vacated) and >= n_sink (vac_s: written above by this wave, LDS keeps a wave's order)
+    const bool vacated = lane < C && vac_s[lane];
+    const bool is_free = lane < C && lane >= a.n_sink && (old_len[lane] <= 0 || vacated);
     const uint64_t free_mask = __ballot(is_free);
     if (lane < C) {
       src_s[lane] = -1;
-      if ((vacated >> lane) & 1) old_len[lane] = 0;
+      if (vacated) old_len[lane] = 0;
     }
     int taken = 0;
     for (int x0 = ncP; x0 < nc; x0 += 64) {
@@ -636,8 +656,10 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   __syncthreads();
   // per-position counts of the summary: every dropped block adds one to each position it has
   if (a.fold && nf_s > 0) {
-    for (int t = threadIdx.x; t < a.B; t += kThreads) {
-      int cnt = a.S_cnt[(size_t)h * a.B + t];
+    if (threadIdx.x < a.B) {
+      const int t = threadIdx.x;
+      int cnt = cnt_mine;
+#pragma unroll 8
       for (int f = 0; f < nf_s; ++f) cnt += t < flen[f] ? 1 : 0;
       a.S_cnt[(size_t)h * a.B + t] = cnt;
       if (cnt > 0) atomicAdd(&npos_s, 1);
@@ -651,7 +673,7 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
     const int e = src_s[c];
     a.slot_src[(size_t)h * C + c] = e;
     a.promo_slot[(size_t)h * C + c] = e >= 0 ? e_map[e] : -1;
-    if (e >= 0) a.p_id[(size_t)h * C + c] = a.l_id[e];
+    if (e >= 0) a.p_id[(size_t)h * C + c] = e_id[e];
     else if (c >= a.n_sink && old_len[c] == 0) a.p_id[(size_t)h * C + c] = -1;
   }
   // pooled keys move with the promoted blocks: independent float4 copies
