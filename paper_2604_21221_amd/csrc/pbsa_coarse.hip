@@ -596,10 +596,11 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
       for (int q = part * per; q < q_end; ++q) {
         const float4 v = c4[q];
         const int y = 4 * q;
-        rank += (y + 0 < nc && (v.x > mine || (v.x == mine && y + 0 < x))) ? 1 : 0;
-        rank += (y + 1 < nc && (v.y > mine || (v.y == mine && y + 1 < x))) ? 1 : 0;
-        rank += (y + 2 < nc && (v.z > mine || (v.z == mine && y + 2 < x))) ? 1 : 0;
-        rank += (y + 3 < nc && (v.w > mine || (v.w == mine && y + 3 < x))) ? 1 : 0;
+        // without branches: (in range) and (higher, or equal and earlier)
+        rank += (int)(y + 0 < nc) & ((int)(v.x > mine) | ((int)(v.x == mine) & (int)(y + 0 < x)));
+        rank += (int)(y + 1 < nc) & ((int)(v.y > mine) | ((int)(v.y == mine) & (int)(y + 1 < x)));
+        rank += (int)(y + 2 < nc) & ((int)(v.z > mine) | ((int)(v.z == mine) & (int)(y + 2 < x)));
+        rank += (int)(y + 3 < nc) & ((int)(v.w > mine) | ((int)(v.w == mine) & (int)(y + 3 < x)));
       }
       if (rank) atomicAdd(&rank_s[x], rank);
     }
@@ -660,7 +661,7 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
       const int t = threadIdx.x;
       int cnt = cnt_mine;
 #pragma unroll 8
-      for (int f = 0; f < nf_s; ++f) cnt += t < flen[f] ? 1 : 0;
+      for (int f = 0; f < nf_s; ++f) cnt += (int)(t < flen[f]);
       a.S_cnt[(size_t)h * a.B + t] = cnt;
       if (cnt > 0) atomicAdd(&npos_s, 1);
     }
