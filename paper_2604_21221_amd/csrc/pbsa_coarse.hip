@@ -709,11 +709,13 @@ struct FoldArgs {
 };
 
 constexpr int kFoldBatch = 40;
+constexpr int kPromoBatch = 8;
 
 __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   // per dropped candidate: its valid length and the address of its K and of its V block
   __shared__ const bf16_t* fptr_s[2][kMaxCand];
-  __shared__ int flen_s[kMaxCand], promo_s[PBSA_MAX_C];
+  __shared__ int flen_s[kMaxCand];
+  __shared__ int promo_dst[PBSA_MAX_C], promo_src[PBSA_MAX_C], n_promo_s;   // refilled slots, compacted
   const int h = blockIdx.y;
   const int C = a.C, C1 = a.C + 1, ncand_max = a.C + a.n_evict;
   const int nf = a.fold && a.S_sum ? a.fold_n[h] : 0;
@@ -724,8 +726,23 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
     fptr_s[0][f] = src < C ? a.Kp + ((size_t)h * C1 + src) * blk : a.Kl + ((size_t)h * a.n_loc_cap + (src - C)) * blk;
     fptr_s[1][f] = src < C ? a.Vp + ((size_t)h * C1 + src) * blk : a.Vl + ((size_t)h * a.n_loc_cap + (src - C)) * blk;
   }
-  for (int c = threadIdx.x; c < C; c += kThreads) promo_s[c] = a.promo_slot[(size_t)h * C + c];
+  if (threadIdx.x < 64) {                  // wave 0 compacts the slots that are refilled (usually few or none)
+    int n = 0;
+    for (int c0 = 0; c0 < C; c0 += 64) {
+      const int c = c0 + (int)threadIdx.x;
+      const int ps = c < C ? a.promo_slot[(size_t)h * C + c] : -1;
+      const uint64_t m = __ballot(ps >= 0);
+      if (ps >= 0) {
+        const int pos = n + lanes_below(m);
+        promo_dst[pos] = c;
+        promo_src[pos] = ps;
+      }
+      n += __popcll(m);
+    }
+    if (threadIdx.x == 0) n_promo_s = n;
+  }
   __syncthreads();
+  const int n_promo = n_promo_s;
   const int tpr = a.d / 4;                                     // threads per row: 4 dimensions each
   const int rows_per_wg = kThreads / tpr;
   const int row = blockIdx.x * rows_per_wg + threadIdx.x / tpr; // over [2][B]
@@ -736,13 +753,11 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   const bf16_t* L = kv ? a.Vl : a.Kl;
   const size_t rowoff = (size_t)t * a.d + xc;
   const bf16_t* Lh = L + (size_t)h * a.n_loc_cap * blk + rowoff;
-  // promoted rows are independent of the fold: fetch them all before it starts
-  uint2 pv[PBSA_MAX_C];
+  // promoted rows are independent of the fold: the first few are fetched before it starts
+  uint2 pv[kPromoBatch];
 #pragma unroll
-  for (int u = 0; u < PBSA_MAX_C; ++u) {
-    const int ps = u < C ? promo_s[u] : -1;
-    pv[u] = ps >= 0 ? *reinterpret_cast<const uint2*>(Lh + (size_t)ps * blk) : make_uint2(0u, 0u);
-  }
+  for (int u = 0; u < kPromoBatch; ++u)
+    pv[u] = u < n_promo ? *reinterpret_cast<const uint2*>(Lh + (size_t)promo_src[u] * blk) : make_uint2(0u, 0u);
   if (nf > 0) {
     float* ssum = a.S_sum + ((size_t)h * 2 + kv) * blk + rowoff;
     float4 acc = *reinterpret_cast<float4*>(ssum);
@@ -775,9 +790,15 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   }
   // promoted rows: stores after the fold's loads (a refilled slot was read above by this thread)
 #pragma unroll
-  for (int u = 0; u < PBSA_MAX_C; ++u) {
-    const int ps = u < C ? promo_s[u] : -1;
-    if (ps >= 0) *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + u) * blk + rowoff) = pv[u];
+  for (int u = 0; u < kPromoBatch; ++u)
+    if (u < n_promo) *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + promo_dst[u]) * blk + rowoff) = pv[u];
+  for (int u0 = kPromoBatch; u0 < n_promo; u0 += kPromoBatch) {     // more than a few: the rest, batch by batch
+#pragma unroll
+    for (int u = 0; u < kPromoBatch; ++u)
+      pv[u] = u0 + u < n_promo ? *reinterpret_cast<const uint2*>(Lh + (size_t)promo_src[u0 + u] * blk) : make_uint2(0u, 0u);
+#pragma unroll
+    for (int u = 0; u < kPromoBatch; ++u)
+      if (u0 + u < n_promo) *reinterpret_cast<uint2*>(P + ((size_t)h * C1 + promo_dst[u0 + u]) * blk + rowoff) = pv[u];
   }
 }
 
