@@ -280,29 +280,29 @@ int orc_scores(const orc_cfg* c, const float* Qc, const float* Kc_l, const int32
   return 0;
 }
 
-/* Persistent-memory update (Eq. 9 and its footnote, plus the compressed-history block):
+/* Retention, slot assignment and fold, given the scores (Eq. 9 and its footnote, plus the
+ * compressed-history block):
  *  - candidates = occupants of slots n_sink..C-1 (slot order) then the n_evict leading local
  *    blocks (block order); the top C-n_sink by (score desc, candidate index asc) are kept;
  *  - a kept occupant stays in its slot; kept newcomers, in ascending block order, fill the vacated
  *    and empty slots in ascending slot order (K, V, pooled key, len and id move with the block);
  *  - every dropped candidate is folded, position by position, into the running mean kept as
  *    S_sum / S_cnt, whose bf16 view becomes slot C (skipped when S_sum is NULL).
+ * s_p [H][C]: score of each slot (ignored for empty ones); s_l [H][n_loc]: of each local block
+ * (only the first n_evict are read).
  * scores [H][C+n_evict] (optional): score of slot 0..C-1 (0 if empty) then of each evicted block.
  * slot_src [H][C]: -1 = slot unchanged, e >= 0 = filled from local block e. */
-int orc_memory_update(const orc_cfg* c, const float* Qc, const float* Kc_l, uint16_t* Kp, uint16_t* Vp,
-                      float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
-                      const uint16_t* Kl, const uint16_t* Vl, const int32_t* l_len, const int32_t* l_map,
-                      const int64_t* l_id, float* scores, int32_t* slot_src) {
+static int retain_and_fold(const orc_cfg* c, const float* s_p, const float* s_l, const float* Kc_l, uint16_t* Kp,
+                           uint16_t* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                           const uint16_t* Kl, const uint16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                           const int64_t* l_id, float* scores, int32_t* slot_src) {
   const int d = c->d, B = c->B, C = c->C, C1 = c->C + 1;
   const size_t blk = (size_t)B * d;
-  float* s_p = (float*)malloc(sizeof(float) * (size_t)(c->H * C + 1));
-  float* s_l = (float*)malloc(sizeof(float) * (size_t)(c->H * c->n_loc + 1));
   const int ncand_max = C + c->n_evict;
   int* cand = (int*)malloc(sizeof(int) * (size_t)(ncand_max + 1));   /* <C: slot, else C+e */
   float* cs = (float*)malloc(sizeof(float) * (size_t)(ncand_max + 1));
   char* win = (char*)malloc((size_t)(ncand_max + 1));
-  if (!s_p || !s_l || !cand || !cs || !win) return -1;
-  if (orc_scores(c, Qc, Kc_l, l_map, Kc_p, p_len, s_p, s_l)) return -1;
+  if (!cand || !cs || !win) return -1;
   for (int h = 0; h < c->H; ++h) {
     int32_t* plen = p_len + (size_t)h * C1;
     if (scores) {
@@ -384,6 +384,125 @@ int orc_memory_update(const orc_cfg* c, const float* Qc, const float* Kc_l, uint
     for (int q = c->n_sink; q < C; ++q)
       if (plen[q] == 0) p_id[(size_t)h * C + q] = -1;
   }
-  free(s_p); free(s_l); free(cand); free(cs); free(win);
+  free(cand); free(cs); free(win);
   return 0;
+}
+
+/* Persistent-memory update with the coarse persistence scores of Eq. 7-8 (orc_scores), then the
+ * retention and fold above. */
+int orc_memory_update(const orc_cfg* c, const float* Qc, const float* Kc_l, uint16_t* Kp, uint16_t* Vp,
+                      float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                      const uint16_t* Kl, const uint16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                      const int64_t* l_id, float* scores, int32_t* slot_src) {
+  float* s_p = (float*)malloc(sizeof(float) * (size_t)(c->H * c->C + 1));
+  float* s_l = (float*)malloc(sizeof(float) * (size_t)(c->H * c->n_loc + 1));
+  if (!s_p || !s_l) return -1;
+  if (orc_scores(c, Qc, Kc_l, l_map, Kc_p, p_len, s_p, s_l)) return -1;
+  const int rc = retain_and_fold(c, s_p, s_l, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map,
+                                 l_id, scores, slot_src);
+  free(s_p); free(s_l);
+  return rc;
+}
+
+/* Attention mass that the fine stage (Eq. 3-5) puts on each key block: the variant of the
+ * persistence score that accumulates the token-level attention actually paid, mask included,
+ * in place of the block-level softmax of Eq. 7.  For each requested query block (head qb_h[n],
+ * block qb_i[n]) and each key block u -- persistent slot u for u <= C (the summary is u = C),
+ * local block u - C - 1 beyond --
+ *     mass[n][u] = sum over the rows q of the query block and the valid tokens j of block u of
+ *                  P[q][j],  P = the row softmax of Eq. 3-5 over what row q attends,
+ * and 0 for a block the query block does not attend (an empty slot, a local block outside its
+ * row of sel).  fp64; every row adds exactly 1 in total.  mass [n_qb][C+1+n_loc]. */
+int orc_attention_mass(const orc_cfg* c, const uint16_t* Q, const uint16_t* Kp, const int32_t* p_len,
+                       const uint16_t* Kl, const int32_t* l_len, const int32_t* l_map, const int32_t* sel,
+                       int64_t n_qb, const int32_t* qb_h, const int32_t* qb_i, double* mass) {
+  const int d = c->d, B = c->B, nu = c->C + 1 + c->n_loc;
+  const size_t max_keys = (size_t)(c->C + 1 + c->k) * B + 1;
+  int fail = 0;
+#pragma omp parallel
+  {
+    double* z = (double*)malloc(sizeof(double) * max_keys);
+    int* unit = (int*)malloc(sizeof(int) * max_keys);
+    double* q = (double*)malloc(sizeof(double) * (size_t)d);
+    if (!z || !unit || !q) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int64_t n = 0; n < n_qb; ++n) {
+        const int h = qb_h[n], i = qb_i[n];
+        double* out = mass + (size_t)n * nu;
+        for (int u = 0; u < nu; ++u) out[u] = 0.0;
+        const int32_t* row_sel = sel + ((size_t)h * c->nqb + i) * c->k;
+        for (int t = i * B; t < i * B + q_block_len(c, i); ++t) {
+          const uint16_t* qrow = Q + ((size_t)h * c->Nq + t) * d;
+          for (int x = 0; x < d; ++x) q[x] = (double)bf2f(qrow[x]);
+          size_t nk = 0;
+          for (int s = 0; s <= c->C; ++s) {
+            const int len = p_len[(size_t)h * (c->C + 1) + s];
+            const size_t base = ((size_t)h * (c->C + 1) + s) * B * d;
+            for (int j = 0; j < len; ++j) {
+              double acc = 0.0;
+              for (int x = 0; x < d; ++x) acc += q[x] * (double)bf2f(Kp[base + (size_t)j * d + x]);
+              z[nk] = acc * (double)c->scale;
+              unit[nk++] = s;
+            }
+          }
+          for (int jj = 0; jj < c->k; ++jj) {
+            const int l = row_sel[jj];
+            if (l < 0) continue;
+            const size_t base = ((size_t)h * c->n_loc_cap + l_map[l]) * B * d;
+            for (int j = 0; j < l_len[l]; ++j) {
+              double acc = 0.0;
+              for (int x = 0; x < d; ++x) acc += q[x] * (double)bf2f(Kl[base + (size_t)j * d + x]);
+              z[nk] = acc * (double)c->scale;
+              unit[nk++] = c->C + 1 + l;
+            }
+          }
+          if (nk == 0) continue;
+          double m = z[0];
+          for (size_t j = 1; j < nk; ++j) m = z[j] > m ? z[j] : m;
+          double sum = 0.0;
+          for (size_t j = 0; j < nk; ++j) {
+            z[j] = exp(z[j] - m);
+            sum += z[j];
+          }
+          for (size_t j = 0; j < nk; ++j) out[unit[j]] += z[j] / sum;
+        }
+      }
+    }
+    free(z);
+    free(unit);
+    free(q);
+  }
+  return fail ? -1 : 0;
+}
+
+/* Persistent-memory update ranked by accumulated fine attention mass.  Mt [H][C+1+n_loc][nqb]
+ * fp32: mass of key block u (numbered as in orc_attention_mass) from query block i.  The score
+ * of a block is its mass per query token, in fp32 in a fixed order because it decides the slots:
+ *   acc = acc + Mt[h][u][i] over i ascending from 0.0f, then acc / (float)Nq   (0 for an empty slot);
+ * retention, slot assignment and fold are those of the coarse update (Eq. 9). */
+int orc_memory_update_fine(const orc_cfg* c, const float* Mt, const float* Kc_l, uint16_t* Kp, uint16_t* Vp,
+                           float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                           const uint16_t* Kl, const uint16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                           const int64_t* l_id, float* scores, int32_t* slot_src) {
+  const int nu = c->C + 1 + c->n_loc;
+  float* s_p = (float*)malloc(sizeof(float) * (size_t)(c->H * c->C + 1));
+  float* s_l = (float*)malloc(sizeof(float) * (size_t)(c->H * c->n_loc + 1));
+  if (!s_p || !s_l) return -1;
+  for (int h = 0; h < c->H; ++h) {
+    for (int u = 0; u < nu; ++u) {
+      if (u == c->C) continue;                        /* the summary is never a candidate */
+      float acc = 0.0f;
+      for (int i = 0; i < c->nqb; ++i) acc = acc + Mt[((size_t)h * nu + u) * c->nqb + i];
+      const float s = acc / (float)c->Nq;
+      if (u < c->C) s_p[(size_t)h * c->C + u] = p_len[(size_t)h * (c->C + 1) + u] > 0 ? s : 0.0f;
+      else s_l[(size_t)h * c->n_loc + (u - c->C - 1)] = s;
+    }
+  }
+  const int rc = retain_and_fold(c, s_p, s_l, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map,
+                                 l_id, scores, slot_src);
+  free(s_p); free(s_l);
+  return rc;
 }

@@ -176,3 +176,48 @@ def memory_update(cfg: Cfg, Qc, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, K
     if rc:
         raise RuntimeError(f"orc_memory_update failed: {rc}")
     return sc, src
+
+
+def attention_mass(cfg: Cfg, Q, Kp, p_len, Kl, l_len, l_map, sel, qb_h=None, qb_i=None):
+    """fp64 attention mass of every key block from the requested query blocks: [n][C+1+n_loc]
+    (all H * nqb query blocks, head-major, when no list is given)."""
+    H, d, B = cfg.H, cfg.d, cfg.B
+    if qb_h is None:
+        hh, ii = np.meshgrid(np.arange(H, dtype=np.int32), np.arange(cfg.nqb, dtype=np.int32), indexing="ij")
+        qb_h, qb_i = hh.ravel(), ii.ravel()
+    qb_h = np.ascontiguousarray(qb_h, np.int32)
+    qb_i = np.ascontiguousarray(qb_i, np.int32)
+    n = qb_h.shape[0]
+    mass = np.zeros((n, cfg.C + 1 + cfg.n_loc), np.float64)
+    c = cfg.c()
+    rc = lib().orc_attention_mass(
+        ctypes.byref(c), _p(Q, np.uint16, (H, cfg.Nq, d)), _p(Kp, np.uint16, (H, cfg.C + 1, B, d)),
+        _p(p_len, np.int32, (H, cfg.C + 1)), _p(Kl, np.uint16, (H, cfg.n_loc_cap, B, d)),
+        _p(l_len, np.int32, (cfg.n_loc,)), _p(l_map, np.int32, (cfg.n_loc,)),
+        _p(sel, np.int32, (H, cfg.nqb, cfg.k)), ctypes.c_int64(n), _p(qb_h, np.int32), _p(qb_i, np.int32),
+        _p(mass, np.float64))
+    if rc:
+        raise RuntimeError(f"orc_attention_mass failed: {rc}")
+    return mass
+
+
+def memory_update_fine(cfg: Cfg, Mt, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id):
+    """Update ranked by fine attention mass Mt [H][C+1+n_loc][nqb] fp32; in place like memory_update;
+    returns (scores, slot_src)."""
+    H, d, B, C = cfg.H, cfg.d, cfg.B, cfg.C
+    sc = np.zeros((H, C + cfg.n_evict), np.float32)
+    src = np.full((H, C), -1, np.int32)
+    c = cfg.c()
+    rc = lib().orc_memory_update_fine(
+        ctypes.byref(c), _p(Mt, np.float32, (H, C + 1 + cfg.n_loc, cfg.nqb)),
+        _p(Kc_l, np.float32, (H, cfg.n_loc_cap, d)),
+        _p(Kp, np.uint16, (H, C + 1, B, d)), _p(Vp, np.uint16, (H, C + 1, B, d)),
+        _p(Kc_p, np.float32, (H, C, d)), _p(p_len, np.int32, (H, C + 1)), _p(p_id, np.int64, (H, C)),
+        _p(S_sum, np.float32, (H, 2, B, d)) if S_sum is not None else None,
+        _p(S_cnt, np.int32, (H, B)) if S_sum is not None else None,
+        _p(Kl, np.uint16, (H, cfg.n_loc_cap, B, d)), _p(Vl, np.uint16, (H, cfg.n_loc_cap, B, d)),
+        _p(l_len, np.int32, (cfg.n_loc,)), _p(l_map, np.int32, (cfg.n_loc,)), _p(l_id, np.int64, (cfg.n_loc,)),
+        _p(sc, np.float32), _p(src, np.int32))
+    if rc:
+        raise RuntimeError(f"orc_memory_update_fine failed: {rc}")
+    return sc, src

@@ -108,6 +108,11 @@ class OracleState:
         l_map, l_len, _ = self._maps()
         return orc.attention(self.cfg(), Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map, self.sel)
 
+    def attention_mass(self, Q, qb_h=None, qb_i=None):
+        """fp64 mass of every key block (slots 0..C, then the local blocks) from the given query blocks."""
+        l_map, l_len, _ = self._maps()
+        return orc.attention_mass(self.cfg(), Q, self.Kp, self.p_len, self.Kl, l_len, l_map, self.sel, qb_h, qb_i)
+
     def n_evict_now(self):
         return self.nqb if len(self.chunks) == self.w + 1 else 0
 
@@ -118,6 +123,18 @@ class OracleState:
         sc, src = orc.memory_update(self.cfg(n_evict=ne), self.Qc, self.Kc_l, self.Kp, self.Vp, self.Kc_p,
                                     self.p_len, self.p_id, self.S_sum, self.S_cnt, self.Kl, self.Vl, l_len, l_map,
                                     l_id)
+        if ne:
+            self.chunks.pop(0)
+            self.stale_from = self.n_loc
+        return sc, src
+
+    def update_fine(self, Mt):
+        """The same update ranked by fine attention mass Mt [H][C+1+n_loc][nqb] fp32; then slide the window."""
+        l_map, l_len, l_id = self._maps()
+        ne = self.n_evict_now()
+        sc, src = orc.memory_update_fine(self.cfg(n_evict=ne), np.ascontiguousarray(Mt, np.float32), self.Kc_l,
+                                         self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id, self.S_sum, self.S_cnt,
+                                         self.Kl, self.Vl, l_len, l_map, l_id)
         if ne:
             self.chunks.pop(0)
             self.stale_from = self.n_loc

@@ -392,6 +392,156 @@ def test_fold_of_constant_blocks_is_exact_and_drop_mode(oracle):
     assert st3.p_len[0, 1] == 0
 
 
+# ------------------------------------------------------------------------------------------------
+# fine attention mass and the update ranked by it
+# ------------------------------------------------------------------------------------------------
+def ref_block_mass(st, Q, sel):
+    """Per (head, query block, key block) sums of the explicit masked softmax matrix (fp64), written
+    independently of the oracle: the dense P of Eq. 3-5 first, then plain slicing by block owner."""
+    l_map, l_len, _ = st._maps()
+    nu = st.C + 1 + st.n_loc
+    out = np.zeros((st.H, st.nqb, nu))
+    for h in range(st.H):
+        keys, owner = [], []
+        for s in range(st.C + 1):
+            n = st.p_len[h, s]
+            keys.append(f32(st.Kp[h, s, :n])); owner += [s] * n
+        for l in range(st.n_loc):
+            n = l_len[l]
+            keys.append(f32(st.Kl[h, l_map[l], :n])); owner += [st.C + 1 + l] * n
+        Kc = np.concatenate(keys).astype(np.float64)
+        owner = np.array(owner)
+        M = np.full((st.Nq, len(owner)), -np.inf)
+        for t in range(st.Nq):
+            vis = [st.C + 1 + int(x) for x in sel[h, t // st.B] if x >= 0]
+            M[t, (owner <= st.C) | np.isin(owner, vis)] = 0.0
+        S = f32(Q[h]).astype(np.float64) @ Kc.T * st.scale + M
+        P = np.exp(S - S.max(1, keepdims=True))
+        P /= P.sum(1, keepdims=True)
+        for i in range(st.nqb):
+            rows = P[i * st.B:min((i + 1) * st.B, st.Nq)]
+            for u in range(nu):
+                out[h, i, u] = rows[:, owner == u].sum()
+    return out
+
+
+def test_attention_mass_is_the_block_sum_of_the_softmax_matrix(oracle):
+    st, Q = make_state(20, H=2, d=16, B=8, Nq=20, w=2, C=3, k=3, p_lens=[[8, 0, 5], [8, 8, 8]])
+    st.set_summary(np.abs(rnd(201, 2, 2, 8, 16)).astype(np.float32), np.tile(np.array([2, 2, 1, 1, 0, 0, 0, 0], np.int32), (2, 1)))
+    sel, _ = st.select(Q)
+    mass = st.attention_mass(Q).reshape(st.H, st.nqb, -1)
+    np.testing.assert_allclose(mass, ref_block_mass(st, Q, sel), rtol=0, atol=1e-12)
+    # every row of a softmax matrix adds 1: a query block's masses add up to its number of rows
+    rows = np.array([8, 8, 4], np.float64)
+    np.testing.assert_allclose(mass.sum(2), np.tile(rows, (st.H, 1)), rtol=0, atol=1e-12)
+    # no mass where nothing is attended: the empty slot, the local blocks outside the row of sel
+    assert np.all(mass[0, :, 1] == 0.0)
+    for h in range(st.H):
+        for i in range(st.nqb):
+            off = sorted(set(range(st.n_loc)) - set(int(x) for x in sel[h, i] if x >= 0))
+            assert np.all(mass[h, i, st.C + 1 + np.array(off)] == 0.0)
+            on = [int(x) for x in sel[h, i] if x >= 0]
+            assert np.all(mass[h, i, st.C + 1 + np.array(on)] > 0.0)
+    assert np.all(mass[:, :, st.C] > 0.0)                    # the summary block is attended by every row
+    # a list of query blocks gives the same numbers as the full run
+    part = st.attention_mass(Q, np.array([1, 0], np.int32), np.array([2, 1], np.int32))
+    assert np.array_equal(part[0], mass[1, 2]) and np.array_equal(part[1], mass[0, 1])
+
+
+def test_attention_mass_closed_forms(oracle):
+    # one persistent block and nothing else: all the mass of every row lands on it
+    st, Q = make_state(21, H=1, d=16, B=8, Nq=12, w=0, C=1, k=0, p_lens=[[6]])
+    st.select(Q)
+    mass = st.attention_mass(Q).reshape(1, st.nqb, -1)
+    np.testing.assert_allclose(mass[0, :, 0], [8.0, 4.0], rtol=1e-14)
+    assert np.all(mass[0, :, 1:] == 0.0)
+    # identical keys everywhere: the mass of a block is proportional to its valid tokens
+    st, Q = make_state(22, H=1, d=16, B=8, Nq=16, w=1, C=2, k=4, causal=0, p_lens=[[8, 3]])
+    l_map, l_len, _ = st._maps()
+    row = bf(rnd(221, 1, 16))
+    st.Kp[...] = row
+    st.Kl[...] = row
+    sel, _ = st.select(Q)
+    st.sel = np.tile(np.arange(4, dtype=np.int32), (1, st.nqb, 1))       # everything attended, whatever the ties chose
+    mass = st.attention_mass(Q).reshape(st.nqb, -1)
+    tokens = np.array([8, 3, 0] + [8] * 4, np.float64)
+    np.testing.assert_allclose(mass, np.tile(8.0 * tokens / tokens.sum(), (st.nqb, 1)), rtol=1e-12)
+    # garbage in the padding rows of a ragged block carries no mass
+    st.Kp[0, 1, 3:] = bf(np.full((5, 16), 40.0))
+    np.testing.assert_array_equal(st.attention_mass(Q).reshape(st.nqb, -1), mass)
+
+
+def fine_inputs(st, seed, ties=False):
+    """A made-up mass matrix [H][C+1+n_loc][nqb] (the update only ranks it)."""
+    nu = st.C + 1 + st.n_loc
+    Mt = np.abs(rnd(seed, st.H, nu, st.nqb)).astype(np.float32)
+    if ties:
+        Mt = np.round(Mt).astype(np.float32)                           # few distinct sums: many equal scores
+    return Mt
+
+
+@pytest.mark.parametrize("seed,n_sink,ties", [(30, 0, False), (31, 1, False), (32, 0, True), (33, 2, True)])
+def test_fine_retention_is_bruteforce_topc_of_the_column_sums(oracle, seed, n_sink, ties):
+    st, Q = make_state(seed, H=3, d=16, B=8, Nq=28, w=2, C=4, k=2, n_sink=n_sink,
+                       p_lens=[[8, 8, 5, 8], [8, 0, 8, 8], [8, 8, 8, 0]])
+    st.select(Q)
+    Mt = fine_inputs(st, seed, ties)
+    b = dict(p_len=st.p_len.copy(), p_id=st.p_id.copy(), Kp=st.Kp.copy(), Kl=st.Kl.copy(), maps=st._maps())
+    ne, C = st.n_evict_now(), st.C
+    sc, src = st.update_fine(Mt)
+    l_map, l_len, l_id = b["maps"]
+    # the score is the mass per query token, summed over query blocks in ascending order in fp32
+    want = np.zeros((st.H, C + 1 + len(l_map)), np.float32)
+    for i in range(st.nqb):
+        want = want + Mt[:, :, i]
+    want = want / np.float32(st.Nq)
+    n_tied = 0
+    for h in range(st.H):
+        occ = b["p_len"][h, :C] > 0
+        assert sc[h, :C].tolist() == np.where(occ, want[h, :C], np.float32(0)).tolist()
+        assert sc[h, C:].tolist() == want[h, C + 1:C + 1 + ne].tolist()
+        cands = [("p", s) for s in range(n_sink, C) if occ[s]] + [("e", e) for e in range(ne)]
+        val = [float(want[h, s]) if kind == "p" else float(want[h, C + 1 + s]) for kind, s in cands]
+        order = sorted(range(len(cands)), key=lambda a: (-val[a], a))
+        winners = set(order[:C - n_sink])
+        n_tied += len(val) - len(set(val))
+        free = [s for s in range(n_sink, C) if not occ[s]]
+        free += [cands[a][1] for a in range(len(cands)) if cands[a][0] == "p" and a not in winners]
+        free.sort()
+        new = sorted(cands[a][1] for a in winners if cands[a][0] == "e")
+        want_src = np.full(C, -1)
+        for s, e in zip(free, new):
+            want_src[s] = e
+        assert src[h].tolist() == want_src.tolist()
+        for s in range(C):
+            if want_src[s] >= 0:
+                e = want_src[s]
+                assert np.array_equal(st.Kp[h, s], b["Kl"][h, l_map[e]]) and st.p_id[h, s] == l_id[e]
+            elif occ[s] and s not in free:
+                assert np.array_equal(st.Kp[h, s], b["Kp"][h, s]) and st.p_id[h, s] == b["p_id"][h, s]
+        n_lost = len(cands) - len(winners)
+        assert st.S_cnt[h].max() == n_lost or n_lost == 0
+    assert (n_tied > 0) == ties
+
+
+def test_fine_and_coarse_updates_share_everything_but_the_score(oracle):
+    """Fed the coarse column scores as a one-query-block mass matrix, the fine update must do exactly what the
+    coarse one does: retention, slots and fold are one piece of arithmetic with two sources of scores."""
+    a, Q = make_state(34, H=2, d=16, B=8, Nq=8, w=2, C=3, k=2, p_lens=[[8, 8, 6], [8, 0, 8]])
+    b2, _ = make_state(34, H=2, d=16, B=8, Nq=8, w=2, C=3, k=2, p_lens=[[8, 8, 6], [8, 0, 8]])
+    a.select(Q); b2.select(Q)
+    l_map, _, _ = a._maps()
+    s_p, s_l = oracle.scores(a.cfg(), a.Qc, a.Kc_l, l_map, a.Kc_p, a.p_len)
+    Mt = np.zeros((a.H, a.C + 1 + a.n_loc, 1), np.float32)
+    Mt[:, :a.C, 0] = s_p * np.float32(a.Nq)                 # Nq = 8: scaling by a power of two and back is exact
+    Mt[:, a.C + 1:, 0] = s_l * np.float32(a.Nq)
+    sc_a, src_a = a.update()
+    sc_b, src_b = b2.update_fine(Mt)
+    assert np.array_equal(sc_a, sc_b) and np.array_equal(src_a, src_b)
+    for name in ("Kp", "Vp", "p_len", "p_id", "Kc_p", "S_sum", "S_cnt"):
+        assert np.array_equal(getattr(a, name), getattr(b2, name))
+
+
 def test_rollout_summary_counts(oracle):
     """Cold start over several chunks: window fills, then every update evicts one chunk; counts add up."""
     H, d, B, Nq, w, C = 1, 16, 8, 20, 2, 2
