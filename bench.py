@@ -197,6 +197,10 @@ def main():
                          "at top-k 6.25 / 12.5 / 25 % and with every block selected (the dense stand-in)")
     ap.add_argument("--blockify", action="store_true",
                     help="instead of the step benchmark: the block rearrange of a chunk's Q, K, V and its inverse")
+    ap.add_argument("--fine-mass", action="store_true",
+                    help="the step with the persistent set ranked by the attention actually paid: after the attention "
+                         "call pbsa_attention_mass sums the probabilities per key block and pbsa_memory_update_fine "
+                         "ranks by them (select + attention + mass + update per step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run three 1 GiB device copies and exit: the known-size kernel that the HBM byte "
                          "counters are scaled by")
@@ -253,12 +257,13 @@ def main():
     src_hist = torch.full((n_total,) + tuple(c.slot_src.shape), -1, dtype=torch.int32, device=dev)
     plen_hist = torch.zeros((n_total,) + tuple(c.p_len.shape), dtype=torch.int32, device=dev)
     new_ev = lambda n: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-    ev, ev_sel, ev_upd = new_ev(K), new_ev(K2), new_ev(K2)
+    ev, ev_sel, ev_upd, ev_mass = new_ev(K), new_ev(K2), new_ev(K2), new_ev(K2)
+    lse = torch.empty(w.H, w.Nq, dtype=torch.float32, device=dev) if args.fine_mass else None
     stream = torch.cuda.current_stream()
 
     n_done = [0]
 
-    def one_step(i, attn_ev=None, sel_ev=None, upd_ev=None):
+    def one_step(i, attn_ev=None, sel_ev=None, upd_ev=None, mass_ev=None):
         # the producer has written the next chunk's K/V into the ring position that was just freed
         # (here: the data already there serves as the new chunk); its queries are the matching Q.
         # i is the row of the history buffers this step records into.
@@ -282,12 +287,21 @@ def main():
         plen_hist[i].copy_(c.p_len, non_blocking=True)
         if attn_ev is not None:
             attn_ev[0].record(stream)
-        c.attention(Qd, O)
+        c.attention(Qd, O, lse)
         if attn_ev is not None:
             attn_ev[1].record(stream)
+        if args.fine_mass:
+            if mass_ev is not None:
+                mass_ev[0].record(stream)
+            Mt = c.attention_mass(Qd, lse)
+            if mass_ev is not None:
+                mass_ev[1].record(stream)
         if upd_ev is not None:
             upd_ev[0].record(stream)
-        c.update()
+        if args.fine_mass:
+            c.update_fine(Mt)
+        else:
+            c.update()
         if upd_ev is not None:
             upd_ev[1].record(stream)
 
@@ -304,7 +318,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for i in range(K2):
-        one_step(W + K + i, sel_ev=ev_sel[i], upd_ev=ev_upd[i])
+        one_step(W + K + i, sel_ev=ev_sel[i], upd_ev=ev_upd[i], mass_ev=ev_mass[i])
     torch.cuda.synchronize()
 
     step_s = (t1 - t0) / K
@@ -330,7 +344,9 @@ def main():
         occupied = int((plen_hist[i][:, :w.C] > 0).sum().item())
         promoted = int((src_hist[i] >= 0).sum().item())
         folded = occupied + w.H * w.nqb - min(w.H * w.C, occupied + w.H * w.nqb)
-        upd_bytes.append(w.H * w.nqb * n_loc * 4 + folded * 2 * blk + promoted * 4 * blk
+        # what the ranking reads: the coarse logits, or the candidates' rows of the mass matrix
+        ranked = w.H * (w.C + w.nqb) * ((w.nqb + 3) & ~3) * 4 if args.fine_mass else w.H * w.nqb * n_loc * 4
+        upd_bytes.append(ranked + folded * 2 * blk + promoted * 4 * blk
                          + w.H * (2 * 2 * w.B * w.d * 4 + 2 * blk))
     upd_b = float(np.mean(upd_bytes))
 
@@ -356,6 +372,15 @@ def main():
                                    "unit": "GB/s", "frac": round(upd_b / upd_us / 1e3 / PEAK_HBM_GBS, 4)},
             "note": f"{K2} steps after the timed region, HIP events around each call"},
     }
+    if args.fine_mass:
+        mass_us = sum(a.elapsed_time(b) for a, b in ev_mass) / K2 * 1e3
+        qk_flops = mean_flops / T / 2          # the first product of the attention only
+        out["metric"] = out["metric"].replace("select+attention+update", "select+attention+mass+update")
+        out["hbm_bound_calls"]["pbsa_memory_update_fine"] = out["hbm_bound_calls"].pop("pbsa_memory_update")
+        out["fine_mass"] = {"pbsa_attention_mass": {
+            "us_per_call": round(mass_us, 2), "executed_gflop": round(qk_flops / 1e9, 3),
+            "achieved": round(qk_flops / mass_us / 1e6, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(qk_flops / mass_us / 1e6 / PEAK_BF16_TFLOPS, 5), "bound": "mfma"}}
     if not args.no_cpu_baseline:
         from oracle import pbsa_oracle as orc
         t_sel, t_att, t_upd, n_rows = cpu_baseline(w)

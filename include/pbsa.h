@@ -8,6 +8,9 @@
  *
  *     pbsa_select_blocks  ->  pbsa_attention_fwd  ->  pbsa_memory_update
  *
+ * (or, ranking the persistent set by the attention actually paid:  ... -> pbsa_attention_fwd ->
+ * pbsa_attention_mass -> pbsa_memory_update_fine).
+ *
  * Conventions
  *  - Every tensor pointer is a DEVICE pointer owned by the caller; `const pbsa_params*` and the
  *    `size_t*` result of pbsa_workspace_bytes are HOST pointers.  The library never allocates,
@@ -152,6 +155,31 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
                        const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
                        const int64_t* l_id, float* scores, int32_t* slot_src, void* ws, size_t ws_bytes,
                        void* hip_stream);
+
+/* Attention mass per key block (the fine-grained counterpart of Eq. 7: the attention of Eq. 3-5 as it was
+ * actually paid, mask included, summed block by block).  Key blocks are numbered u = slot for the persistent
+ * slots 0..C (the summary is u = C) and u = C + 1 + l for local block l.
+ *   Mt[h][u][i] = sum over the tokens q of query block i and the valid tokens j of key block u of
+ *                 exp(scale * dot(Q[q], K[j]) - lse[h][q]),
+ * 0 where query block i does not attend block u (an empty slot, a local block outside its row of sel).
+ * lse [H][Nq] fp32 is the output of pbsa_attention_fwd for the same arguments, so the masses of a query
+ * block add up to its number of tokens (within 5e-3 relative: lse carries the rounding of the bf16
+ * probabilities).  Mt [H][C+1+n_loc][nqb_pad] fp32 out, nqb_pad = nqb rounded up to a multiple of 4; the
+ * padding columns are not written.  bf16 MFMA for the scores, fp32 sums in a fixed order. */
+int pbsa_attention_mass(const pbsa_params* p, const void* Q, const void* Kp, const int32_t* p_len, const void* Kl,
+                        const int32_t* l_len, const int32_t* l_map, const int32_t* sel, const float* lse, float* Mt,
+                        void* hip_stream);
+
+/* pbsa_memory_update with the persistence score taken from the attention mass instead of Eq. 7-8's
+ * block-level softmax: the score of key block u is its mass per query token,
+ *   (...((0 + Mt[h][u][0]) + Mt[h][u][1]) ... + Mt[h][u][nqb-1]) / (float)Nq      (binary32, this order),
+ * 0 for an empty slot.  Candidates, ranking (Eq. 9), slot assignment, fold and every output are those of
+ * pbsa_memory_update; Kc_l is only read to move the pooled keys of promoted blocks.  Mt is laid out as
+ * pbsa_attention_mass writes it (any matrix of that shape is ranked the same way). */
+int pbsa_memory_update_fine(const pbsa_params* p, const float* Mt, const float* Kc_l, void* Kp, void* Vp, float* Kc_p,
+                            int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt, const void* Kl,
+                            const void* Vl, const int32_t* l_len, const int32_t* l_map, const int64_t* l_id,
+                            float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* Locality-preserving block rearrange (App. "Rearrange for Locality Preserving", Alg. 3): the tokens of a
  * chunk come from the model in (frame, patch row, patch column) order, T x Hs x Ws of them, each a row of

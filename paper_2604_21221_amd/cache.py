@@ -174,6 +174,43 @@ class PbsaCache:
             self.stale_from = self.n_loc
         return ne
 
+    # -- the variant that ranks the persistent set by the attention actually paid --------------------
+    def attention_mass(self, Q, lse, Mt=None):
+        """Mass of every key block (slots 0..C, then the local blocks) from every query block:
+        [H][C+1+n_loc][nqb rounded up to 4] fp32, from the log-sum-exp that attention() wrote."""
+        n_u, pad = self.C + 1 + self.n_loc, (self.nqb + 3) & ~3
+        if Mt is None:
+            if getattr(self, "_Mt", None) is None:
+                self._Mt = torch.zeros(self.H * (self.C + 1 + self.cap) * pad, dtype=torch.float32, device=self.dev)
+            Mt = self._Mt[:self.H * n_u * pad].view(self.H, n_u, pad)
+        l_map, l_len, _ = self._device_maps()
+        pbsa.pbsa_attention_mass(self.params(Q=Q), Q, self.Kp, self.p_len, self.Kl, l_len, l_map, self.sel, lse, Mt)
+        return Mt
+
+    def update_fine(self, Mt):
+        l_map, l_len, l_id = self._device_maps(want_ids=True)
+        ne = self.n_evict_now()
+        pbsa.pbsa_memory_update_fine(self.params(n_evict=ne), Mt, self.Kc_l, self.Kp, self.Vp, self.Kc_p, self.p_len,
+                                     self.p_id, self.S_sum, self.S_cnt, self.Kl, self.Vl, l_len, l_map, l_id,
+                                     self.scores, self.slot_src, self.ws)
+        if ne:
+            self.chunk_pos.pop(0)
+            self.chunk_ids.pop(0)
+            self.stale_from = self.n_loc
+        return ne
+
+    def step_fine(self, Q, K, V, chunk_id, O=None, lse=None):
+        """The step with the fine-mass score: append, select, attend, mass, update."""
+        if lse is None:
+            if getattr(self, "_lse", None) is None:
+                self._lse = torch.empty(self.H, self.Nq, dtype=torch.float32, device=self.dev)
+            lse = self._lse
+        self.append_chunk(K, V, chunk_id)
+        self.select(Q)
+        O = self.attention(Q, O, lse)
+        self.update_fine(self.attention_mass(Q, lse))
+        return O
+
     def step(self, Q, K, V, chunk_id, O=None, lse=None):
         """One layer-chunk step: append the chunk, select, attend, update (all enqueued, no sync)."""
         self.append_chunk(K, V, chunk_id)

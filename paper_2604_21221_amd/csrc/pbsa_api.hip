@@ -143,6 +143,44 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
+int pbsa_attention_mass(const pbsa_params* p, const void* Q, const void* Kp, const int32_t* p_len, const void* Kl,
+                        const int32_t* l_len, const int32_t* l_map, const int32_t* sel, const float* lse, float* Mt,
+                        void* hip_stream) {
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  if (rc) return rc;
+  if (!Q || !Kp || !p_len || !Kl || !l_len || !l_map || !lse || !Mt) return PBSA_EINVAL;
+  if (p->k > 0 && !sel) return PBSA_EINVAL;
+  rc = check_strides(p->q_stride_h, p->q_stride_t, p);
+  if (rc) return rc;
+  if (!aligned16(Q) || !aligned16(Kp) || !aligned16(Kl) || !aligned16(Mt)) return PBSA_EALIGN;
+  hipError_t e = pbsa::launch_attention_mass(*p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kp),
+                                             p_len, static_cast<const pbsa::bf16_t*>(Kl), l_len, l_map, sel, lse, Mt,
+                                             static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_memory_update_fine(const pbsa_params* p, const float* Mt, const float* Kc_l, void* Kp, void* Vp, float* Kc_p,
+                            int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt, const void* Kl,
+                            const void* Vl, const int32_t* l_len, const int32_t* l_map, const int64_t* l_id,
+                            float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Mt || !Kc_l || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !l_id) return PBSA_EINVAL;
+  if (p->C > 0 && (!Kc_p || !p_id || !slot_src)) return PBSA_EINVAL;
+  if ((S_sum == nullptr) != (S_cnt == nullptr)) return PBSA_EINVAL;
+  if (!aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(Kc_l) ||
+      !aligned16(Kc_p) || !aligned16(Mt) || !aligned16(S_sum))
+    return PBSA_EALIGN;
+  if (!ws || ws_bytes < workspace_bytes(*p)) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  const pbsa::UpdateWs w = pbsa::carve_update_ws(*p, ws);
+  hipError_t e = pbsa::launch_update_fine(*p, Mt, Kc_l, static_cast<pbsa::bf16_t*>(Kp), static_cast<pbsa::bf16_t*>(Vp),
+                                          Kc_p, p_len, p_id, S_sum, S_cnt, static_cast<const pbsa::bf16_t*>(Kl),
+                                          static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, l_id, scores, slot_src, w,
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
 namespace {
 int check_grid(const pbsa_grid* g) {
   if (!g || g->size != sizeof(pbsa_grid)) return PBSA_EINVAL;

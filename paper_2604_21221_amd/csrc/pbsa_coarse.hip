@@ -482,6 +482,8 @@ constexpr int kMaxCand = PBSA_MAX_C + PBSA_MAX_N_LOC;
 
 struct RetainArgs {
   int H, nqb, nqb_pad, n_loc, n_loc_cap, C, n_sink, n_evict, nU_max, d, B, fold;
+  int fine, Nq;             // fine: A is the attention-mass matrix [H][C+1+n_loc][nqb_pad], one row per key block
+                            // (slots 0..C, then the local blocks), and a score is its row sum over Nq
   const float* A;           // A^T [H][nU_max][nqb_pad]
   const float* Kc_l;
   float* Kc_p;
@@ -543,7 +545,10 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   // A column is contiguous in A^T: its rows are fetched 64 at a time and added in ascending order.
   for (int j = threadIdx.x; j < n_need; j += kThreads) {
     float acc = 0.0f;
-    const float4* col = reinterpret_cast<const float4*>(a.A + ((size_t)h * a.nU_max + j) * a.nqb_pad);
+    // where column j of U sits: the coarse matrix is in U order (occupied slots, then local blocks); the mass
+    // matrix has a row for every slot, the summary included
+    const int at = !a.fine ? j : j < nP ? nth_set_bit(occ_mask, j) : C + 1 + (j - nP);
+    const float4* col = reinterpret_cast<const float4*>(a.A + ((size_t)h * a.nU_max + at) * a.nqb_pad);
     for (int i0 = 0; i0 < a.nqb; i0 += 64) {
       float4 v[16];
 #pragma unroll
@@ -557,7 +562,7 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
         if (i + 3 < a.nqb) acc = acc + v[u].w;
       }
     }
-    s[j] = acc / (float)a.nqb;
+    s[j] = acc / (float)(a.fine ? a.Nq : a.nqb);
   }
   __syncthreads();
   // candidates: occupants of slots >= n_sink in slot order, then the evicted blocks
@@ -902,6 +907,12 @@ static hipError_t launch_rows_z_t(const ScoreArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+static hipError_t launch_retain_fold(const pbsa_params& p, const float* A, int n_rows, int fine, const float* Kc_l,
+                                     bf16_t* Kp, bf16_t* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum,
+                                     int32_t* S_cnt, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
+                                     const int32_t* l_map, const int64_t* l_id, float* scores, int32_t* slot_src,
+                                     const UpdateWs& ws, hipStream_t stream);
+
 hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, bf16_t* Kp,
                          bf16_t* Vp,
                          float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
@@ -930,12 +941,23 @@ hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_
   }
   if (e != hipSuccess) return e;
 
+  return launch_retain_fold(p, ws.A, nU_max, 0, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id,
+                            scores, slot_src, ws, stream);
+}
+
+// Retention and fold given the matrix whose row sums are the scores
+static hipError_t launch_retain_fold(const pbsa_params& p, const float* A, int n_rows, int fine, const float* Kc_l, bf16_t* Kp,
+                              bf16_t* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                              const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                              const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
+                              hipStream_t stream) {
+  const int nqb_pad = (p.nqb + 3) & ~3;
   const int fold = S_sum != nullptr;
-  RetainArgs ra{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, p.n_sink, p.n_evict, nU_max, p.d, p.B, fold, ws.A,
-                Kc_l, Kc_p, p_len, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n, ws.fold_src,
+  RetainArgs ra{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, p.n_sink, p.n_evict, n_rows, p.d, p.B, fold, fine, p.Nq,
+                A, Kc_l, Kc_p, p_len, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n, ws.fold_src,
                 ws.fold_len, ws.promo_slot};
   hipLaunchKernelGGL(retain_kernel, dim3(p.H), dim3(kThreads), 0, stream, ra);
-  e = hipGetLastError();
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
   FoldArgs fa{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, fold, Kp, Vp, Kl, Vl, S_sum, S_cnt, ws.fold_n,
@@ -944,6 +966,15 @@ hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_
   hipLaunchKernelGGL(fold_promote_kernel, dim3((2 * p.B + rows_per_wg - 1) / rows_per_wg, p.H), dim3(kThreads), 0,
                      stream, fa);
   return hipGetLastError();
+}
+
+hipError_t launch_update_fine(const pbsa_params& p, const float* Mt, const float* Kc_l, bf16_t* Kp, bf16_t* Vp,
+                              float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                              const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                              const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
+                              hipStream_t stream) {
+  return launch_retain_fold(p, Mt, p.C + 1 + p.n_loc, 1, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len,
+                            l_map, l_id, scores, slot_src, ws, stream);
 }
 
 }  // namespace pbsa

@@ -37,6 +37,16 @@ hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_
                          const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
                          hipStream_t stream);
 
+// fine attention mass Mt [H][C+1+n_loc][nqb rounded up to 4] and the update ranked by it (Mt given: Qc / Zl unused)
+hipError_t launch_attention_mass(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const int32_t* p_len,
+                                 const bf16_t* Kl, const int32_t* l_len, const int32_t* l_map, const int32_t* sel,
+                                 const float* lse, float* Mt, hipStream_t stream);
+hipError_t launch_update_fine(const pbsa_params& p, const float* Mt, const float* Kc_l, bf16_t* Kp, bf16_t* Vp,
+                              float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                              const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                              const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
+                              hipStream_t stream);
+
 // blockify: to_blocks = true moves token-major -> block-major, false the other way
 struct LayoutTensors {
   int n;

@@ -145,6 +145,29 @@ def test_workspace_checks(L):
     assert e.value.code == pbsa.PBSA_EALIGN
 
 
+def test_fine_mass_argument_checks(L):
+    """pbsa_attention_mass and pbsa_memory_update_fine validate like the calls they sit beside."""
+    p = good(n_evict=4)
+    need = pbsa.pbsa_workspace_bytes(p)
+
+    def mass(p=p, Q=P, lse=P, Mt=P):
+        pbsa.pbsa_attention_mass(p, Q, P, P, P, P, P, P, lse, Mt, stream=0)
+
+    def fine(p=p, Mt=P, ws=(0x10000, 1 << 30), S_cnt=P):
+        pbsa.pbsa_memory_update_fine(p, Mt, P, P, P, P, P, P, P, S_cnt, P, P, P, P, P, None, P, ws, stream=0)
+
+    for call, kw, code in [(mass, dict(lse=None), pbsa.PBSA_EINVAL), (mass, dict(Mt=None), pbsa.PBSA_EINVAL),
+                           (mass, dict(Mt=P + 4), pbsa.PBSA_EALIGN), (mass, dict(Q=P + 2), pbsa.PBSA_EALIGN),
+                           (mass, dict(p=good(d=96)), pbsa.PBSA_ESHAPE), (mass, dict(p=good(C=193)), pbsa.PBSA_ESHAPE),
+                           (fine, dict(Mt=None), pbsa.PBSA_EINVAL), (fine, dict(S_cnt=None), pbsa.PBSA_EINVAL),
+                           (fine, dict(Mt=P + 8), pbsa.PBSA_EALIGN), (fine, dict(ws=None), pbsa.PBSA_EWS),
+                           (fine, dict(ws=(0x10000, need - 1)), pbsa.PBSA_EWS),
+                           (fine, dict(p=good(C=65)), pbsa.PBSA_ESHAPE), (fine, dict(p=good(n_evict=17)), pbsa.PBSA_EINVAL)]:
+        with pytest.raises(pbsa.PbsaError) as e:
+            call(**kw)
+        assert e.value.code == code, (call.__name__, kw)
+
+
 def test_binding_refuses_host_tensors(L):
     import torch
     with pytest.raises(TypeError):
