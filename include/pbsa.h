@@ -8,8 +8,8 @@
  *
  *     pbsa_select_blocks  ->  pbsa_attention_fwd  ->  pbsa_memory_update
  *
- * (or, ranking the persistent set by the attention actually paid:  ... -> pbsa_attention_fwd ->
- * pbsa_attention_mass -> pbsa_memory_update_fine).
+ * (or, ranking the persistent set by the attention actually paid:
+ *     pbsa_select_blocks  ->  pbsa_attention_fwd_mass  ->  pbsa_memory_update_fine).
  *
  * Conventions
  *  - Every tensor pointer is a DEVICE pointer owned by the caller; `const pbsa_params*` and the
@@ -169,6 +169,19 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
 int pbsa_attention_mass(const pbsa_params* p, const void* Q, const void* Kp, const int32_t* p_len, const void* Kl,
                         const int32_t* l_len, const int32_t* l_map, const int32_t* sel, const float* lse, float* Mt,
                         void* hip_stream);
+
+/* pbsa_attention_fwd and the attention mass in one call: the attention kernel also records, per sub-tile of
+ * keys and per query row, the logarithm of the row's probability sum over that sub-tile (numbers its softmax
+ * has anyway), and a short second kernel turns the records into Mt, laid out as above.  Costs a few per cent
+ * over pbsa_attention_fwd where pbsa_attention_mass repeats the whole first product.  O, lse (required here)
+ * and every argument before them are those of pbsa_attention_fwd; the masses are those of the bf16-rounded
+ * probabilities the second product used, so a query block's masses add up to its number of tokens to fp32
+ * rounding.  ws: pbsa_mass_workspace_bytes(p) bytes of device scratch, 256-byte aligned, contents not kept. */
+int pbsa_mass_workspace_bytes(const pbsa_params* p, size_t* out);
+int pbsa_attention_fwd_mass(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                            const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                            const int32_t* sel, void* O, float* lse, float* Mt, void* ws, size_t ws_bytes,
+                            void* hip_stream);
 
 /* pbsa_memory_update with the persistence score taken from the attention mass instead of Eq. 7-8's
  * block-level softmax: the score of key block u is its mass per query token,

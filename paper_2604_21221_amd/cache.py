@@ -178,14 +178,36 @@ class PbsaCache:
     def attention_mass(self, Q, lse, Mt=None):
         """Mass of every key block (slots 0..C, then the local blocks) from every query block:
         [H][C+1+n_loc][nqb rounded up to 4] fp32, from the log-sum-exp that attention() wrote."""
-        n_u, pad = self.C + 1 + self.n_loc, (self.nqb + 3) & ~3
         if Mt is None:
-            if getattr(self, "_Mt", None) is None:
-                self._Mt = torch.zeros(self.H * (self.C + 1 + self.cap) * pad, dtype=torch.float32, device=self.dev)
-            Mt = self._Mt[:self.H * n_u * pad].view(self.H, n_u, pad)
+            Mt = self._mass_buffer()
         l_map, l_len, _ = self._device_maps()
         pbsa.pbsa_attention_mass(self.params(Q=Q), Q, self.Kp, self.p_len, self.Kl, l_len, l_map, self.sel, lse, Mt)
         return Mt
+
+    def _mass_buffer(self):
+        n_u, pad = self.C + 1 + self.n_loc, (self.nqb + 3) & ~3
+        if getattr(self, "_Mt", None) is None:
+            self._Mt = torch.zeros(self.H * (self.C + 1 + self.cap) * pad, dtype=torch.float32, device=self.dev)
+        return self._Mt[:self.H * n_u * pad].view(self.H, n_u, pad)
+
+    def attention_with_mass(self, Q, O=None, lse=None):
+        """Attention and the mass matrix in one call (the attention kernel records what the mass needs).
+        Returns (O, Mt)."""
+        if O is None:
+            O = torch.empty_like(Q)
+        if lse is None:
+            if getattr(self, "_lse", None) is None:
+                self._lse = torch.empty(self.H, self.Nq, dtype=torch.float32, device=self.dev)
+            lse = self._lse
+        if getattr(self, "_mass_ws", None) is None:
+            full = pbsa.make_params(self.H, self.d, self.B, self.Nq, self.cap, self.cap, self.C, self.k, self.scale)
+            self._mass_ws = torch.empty(pbsa.pbsa_mass_workspace_bytes(full), dtype=torch.uint8, device=self.dev)
+        Mt = self._mass_buffer()
+        l_map, l_len, _ = self._device_maps()
+        p = self.params(Q=Q, O=O)
+        pbsa.pbsa_attention_fwd_mass(p, Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map, self.sel, O,
+                                     lse, Mt, self._mass_ws)
+        return O, Mt
 
     def update_fine(self, Mt):
         l_map, l_len, l_id = self._device_maps(want_ids=True)
@@ -200,15 +222,11 @@ class PbsaCache:
         return ne
 
     def step_fine(self, Q, K, V, chunk_id, O=None, lse=None):
-        """The step with the fine-mass score: append, select, attend, mass, update."""
-        if lse is None:
-            if getattr(self, "_lse", None) is None:
-                self._lse = torch.empty(self.H, self.Nq, dtype=torch.float32, device=self.dev)
-            lse = self._lse
+        """The step with the fine-mass score: append, select, attend (recording the mass), update."""
         self.append_chunk(K, V, chunk_id)
         self.select(Q)
-        O = self.attention(Q, O, lse)
-        self.update_fine(self.attention_mass(Q, lse))
+        O, Mt = self.attention_with_mass(Q, O, lse)
+        self.update_fine(Mt)
         return O
 
     def step(self, Q, K, V, chunk_id, O=None, lse=None):

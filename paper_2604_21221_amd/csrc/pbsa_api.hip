@@ -115,8 +115,44 @@ int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, cons
   hipError_t e = pbsa::launch_attention(
       *p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kp),
       static_cast<const pbsa::bf16_t*>(Vp), p_len, static_cast<const pbsa::bf16_t*>(Kl),
-      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, sel, static_cast<pbsa::bf16_t*>(O), lse,
+      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, sel, static_cast<pbsa::bf16_t*>(O), lse, nullptr,
       static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_mass_workspace_bytes(const pbsa_params* p, size_t* out) {
+  if (!out) return PBSA_EINVAL;
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  if (rc) return rc;
+  *out = pbsa::carve_mass_ws(*p, nullptr).bytes;
+  return PBSA_OK;
+}
+
+int pbsa_attention_fwd_mass(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                            const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                            const int32_t* sel, void* O, float* lse, float* Mt, void* ws, size_t ws_bytes,
+                            void* hip_stream) {
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  if (rc) return rc;
+  if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O || !lse || !Mt) return PBSA_EINVAL;
+  if (p->k > 0 && !sel) return PBSA_EINVAL;
+  rc = check_strides(p->q_stride_h, p->q_stride_t, p);
+  if (rc) return rc;
+  rc = check_strides(p->o_stride_h, p->o_stride_t, p);
+  if (rc) return rc;
+  if (!aligned16(Q) || !aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(O) ||
+      !aligned16(Mt))
+    return PBSA_EALIGN;
+  if (!ws || ws_bytes < pbsa::carve_mass_ws(*p, nullptr).bytes) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  const pbsa::MassRows rows = pbsa::carve_mass_ws(*p, ws);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = pbsa::launch_attention(
+      *p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kp),
+      static_cast<const pbsa::bf16_t*>(Vp), p_len, static_cast<const pbsa::bf16_t*>(Kl),
+      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, sel, static_cast<pbsa::bf16_t*>(O), lse, &rows, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = pbsa::launch_mass_reduce(*p, rows, lse, Mt, stream);
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 

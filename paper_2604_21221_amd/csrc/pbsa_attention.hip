@@ -88,6 +88,10 @@ struct AttnArgs {
   const int32_t* sel;
   bf16_t* O;
   float* lse;
+  // mass variant only: per workgroup the tile list, per wave and sub-tile the row sums (see MassOut)
+  float* R;
+  int32_t* Rlist;
+  int r_slots, list_cap;
 };
 
 // LDS layout of a 64-key tile: unpadded rows of D bf16 whose 16-byte chunks are permuted within the
@@ -433,8 +437,8 @@ struct SoftmaxRun {
 // answer in every lane).  s is the sub-tile's S^T, which the coming step will overwrite, p its P^T.
 template <int D>
 __device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[2][2], float (&m_ref)[2], float (&mc)[2],
-                                               float (&l_run)[2], float (&alpha)[2], float c2, float lift) {
-  float psum[2];
+                                               float (&l_run)[2], float (&alpha)[2], float c2, float lift,
+                                               float (&psum)[2]) {
   row_sums(p, psum);
   if (__builtin_expect(__any(!(psum[0] <= kBig) || !(psum[1] <= kBig)), 0)) {
 #pragma unroll
@@ -460,20 +464,40 @@ __device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[
   return false;
 }
 
+// The mass variant of the kernel also leaves, for every sub-tile a wave settles and every one of its 64 rows,
+// the base-2 logarithm of the row's share of the softmax normaliser that falls on that sub-tile, in absolute
+// units (independent of the reference in force at the time): log2(sum of the sub-tile's probabilities) plus
+// the reference.  A later pass turns them into attention mass per key block: 2^(that - log2 normaliser),
+// summed over rows.  One 256-byte store per settle: lanes 0..31 hold rows 0..31, lanes 32..63 rows 32..63.
+struct MassOut {
+  float* rp;        // where this wave's next 64 values go (uniform)
+  int lane;
+  bool hi;          // lane >= 32
+};
+
 // K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
-template <int D, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF>
+template <int D, bool MASS, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF>
 __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS],
                                      const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
                                      f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], u32x4 (&p_prev)[2][2], SoftmaxRun& sr,
-                                     const int (&lim)[2], const DmaPlan<D>& dma) {
+                                     const int (&lim)[2], const DmaPlan<D>& dma, MassOut& mo) {
   static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
   StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, sr.c2, qf, o, s_cur, s_next, p_cur, p_prev, sr.mc, lim, dma, {}, {}};
   preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
   if constexpr (PV) {
     // p_prev is the softmax of the sub-tile whose S^T still sits in s_next
-    float alpha[2];
-    if (softmax_settle<D>(s_next, p_prev, sr.m_ref, sr.mc, sr.l_run, alpha, sr.c2, sr.lift) && sr.o_live)
+    float alpha[2], psum[2];
+    if (softmax_settle<D>(s_next, p_prev, sr.m_ref, sr.mc, sr.l_run, alpha, sr.c2, sr.lift, psum) && sr.o_live)
       rescale<Geo<D>::DT>(o, alpha);
+    if constexpr (MASS) {
+      // psum[g] is this lane's half of the row sum of row group g (its 16 of the 32 keys).  Swapping the upper
+      // half of psum[0] with the lower half of psum[1] and adding gives lanes 0..31 the whole sum of group 0 and
+      // lanes 32..63 that of group 1: row 32 g + lane % 32 = lane.
+      const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(psum[0]), __float_as_uint(psum[1]), false, false);
+      const float tot = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+      mo.rp[mo.lane] = __builtin_amdgcn_logf(tot) - (mo.hi ? sr.mc[1] : sr.mc[0]);
+      mo.rp += 64;
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
   run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
@@ -482,7 +506,7 @@ __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const 
 
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
-template <int D, int B>
+template <int D, int B, bool MASS>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) attention_kernel(AttnArgs a) {
   constexpr int G = kRowsPerWg / B;        // query blocks per workgroup
   constexpr int SUB = B / kTile;           // 64-key tiles per block
@@ -573,6 +597,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
       const int tl = min(max(min(max(plen_s[c], 0), B) - sub * kTile, 0), kTile);
       src = i;
       meta = tl | (3 << 8);
+      if constexpr (MASS) meta |= (c << 10) | (sub << 20);       // the key block the tile belongs to, and which tile of it
       return tl == 0 ? -1 : tl == kTile ? 0 : 1;
     }
     const int l = (i - n_pers) / SUB, sub = (i - n_pers) % SUB;
@@ -581,6 +606,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     const int tl = min(max(min(max(llen_s[l], 0), B) - sub * kTile, 0), kTile);
     src = (int)(0x80000000u | (uint32_t)(slot * SUB + sub));
     meta = tl | (f << 8);
+    if constexpr (MASS) meta |= ((a.C + 1 + l) << 10) | (sub << 20);
     return tl == 0 ? -1 : tl < kTile ? 1 : f == 3 ? 0 : f + 1;      // f is 1 or 2 otherwise
   };
   const int n_rounds = (n_cand + kThreads - 1) / kThreads;
@@ -626,6 +652,14 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[g][ks]));
 
+  MassOut mo{nullptr, lane, lane >= 32};
+  if constexpr (MASS) {
+    // the later pass walks the same list: the ends of its four parts, then a descriptor per tile
+    int32_t* out = a.Rlist + (size_t)logical * a.list_cap;
+    if (tid < 4) out[tid] = cls_end_s[tid];
+    for (int i = tid; i < cls_end_s[3] && i < a.list_cap - 4; i += kThreads) out[4 + i] = t_meta[i];
+    mo.rp = a.R + ((size_t)logical * 2 + wave) * a.r_slots * 64;
+  }
   const int e0 = cls_end_s[0];             // shared full tiles [0, e0)
   const int n_tiles = cls_end_s[1];        // shared ragged tiles [e0, n_tiles): the end of the shared list
   const int solo_b = wave == 0 ? n_tiles : cls_end_s[2];       // this wave's solo tiles [solo_b, solo_e)
@@ -745,21 +779,21 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
     PBSA_ADDR_K(TB)                                                                                     \
     PBSA_ADDR_V(TB)                                                                                     \
-    step<D, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan); \
+    step<D, MASS, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo); \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
-    step<D, false, true, true, RAGGED, kNoLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
+    step<D, MASS, false, true, true, RAGGED, kNoLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
     PBSA_TURNOVER(TB)                                                                                   \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, true, true, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
+      step<D, MASS, true, true, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo); \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
-      step<D, true, true, true, RAGGED, kNoLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
+      step<D, MASS, true, true, true, RAGGED, kNoLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
       PBSA_TURNOVER(t + 1)                                                                              \
     }                                                                                                   \
     PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, true, false, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan); \
-    step<D, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan); \
+    step<D, MASS, true, false, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo); \
+    step<D, MASS, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
     /* between runs the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
     acc_settle<DT>(o[0]);                                                                               \
     acc_settle<DT>(o[1]);                                                                               \
@@ -822,25 +856,25 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
       dma_all<D>(plan, true, false);
       d_next = t_src[min(solo_b + 1, solo_e - 1)];
       PBSA_SOLO_LANDED
-      step<D, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
+      step<D, MASS, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo);
       PBSA_SOLO_PLAN(0)
-      step<D, false, true, true, false, kLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
+      step<D, MASS, false, true, true, false, kLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo);
       PBSA_SOLO_LANDED
       for (int t = solo_b; t < solo_e - 1; ++t) {
         d_nn = t_src[min(t + 2, solo_e - 1)];
         PBSA_SOLO_PLAN(1)
-        step<D, true, true, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
+        step<D, MASS, true, true, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo);
         PBSA_SOLO_LANDED
         d_cur = d_next;
         d_next = d_nn;
         PBSA_SOLO_PLAN(0)
-        step<D, true, true, true, false, kLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
+        step<D, MASS, true, true, true, false, kLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo);
         PBSA_SOLO_LANDED
       }
       PBSA_SOLO_PLAN(1)
-      step<D, true, false, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan);
+      step<D, MASS, true, false, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo);
       PBSA_SOLO_LANDED
-      step<D, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan);
+      step<D, MASS, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo);
     }
   }
 
@@ -872,17 +906,27 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 
 }  // namespace
 
+template <bool MASS>
+static void launch_attention_t(const pbsa_params& p, const AttnArgs& a, dim3 grid, hipStream_t stream) {
+  const dim3 block(kThreads);
+  if (p.d == 128 && p.B == 128) hipLaunchKernelGGL((attention_kernel<128, 128, MASS>), grid, block, 0, stream, a);
+  else if (p.d == 128 && p.B == 64) hipLaunchKernelGGL((attention_kernel<128, 64, MASS>), grid, block, 0, stream, a);
+  else if (p.d == 64 && p.B == 128) hipLaunchKernelGGL((attention_kernel<64, 128, MASS>), grid, block, 0, stream, a);
+  else hipLaunchKernelGGL((attention_kernel<64, 64, MASS>), grid, block, 0, stream, a);
+}
+
 hipError_t launch_attention(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
                             const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
-                            const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, hipStream_t stream) {
+                            const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, const MassRows* rows,
+                            hipStream_t stream) {
   AttnArgs a{p.H, p.Nq, p.nqb, p.n_loc, p.n_loc_cap, p.C, p.k, p.scale, p.q_stride_h, p.q_stride_t,
-             p.o_stride_h, p.o_stride_t, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse};
+             p.o_stride_h, p.o_stride_t, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse,
+             rows ? rows->R : nullptr, rows ? rows->list : nullptr, rows ? rows->r_slots : 0,
+             rows ? rows->list_cap : 0};
   const int n_wg = p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
-  const dim3 grid(8 * ((n_wg + 7) / 8)), block(kThreads);
-  if (p.d == 128 && p.B == 128) hipLaunchKernelGGL((attention_kernel<128, 128>), grid, block, 0, stream, a);
-  else if (p.d == 128 && p.B == 64) hipLaunchKernelGGL((attention_kernel<128, 64>), grid, block, 0, stream, a);
-  else if (p.d == 64 && p.B == 128) hipLaunchKernelGGL((attention_kernel<64, 128>), grid, block, 0, stream, a);
-  else hipLaunchKernelGGL((attention_kernel<64, 64>), grid, block, 0, stream, a);
+  const dim3 grid(8 * ((n_wg + 7) / 8));
+  if (rows) launch_attention_t<true>(p, a, grid, stream);
+  else launch_attention_t<false>(p, a, grid, stream);
   return hipGetLastError();
 }
 

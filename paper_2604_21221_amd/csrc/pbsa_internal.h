@@ -27,9 +27,25 @@ hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32
 hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
                          const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
                          hipStream_t stream);
+// Scratch of the attention call that also produces the attention mass: what the attention kernel leaves for
+// the pass that follows it.  Per workgroup (128 query rows of a head) a tile list of list_cap ints: the ends of
+// the list's four parts, then a descriptor per tile; per wave r_slots records of 64 floats, one per sub-tile
+// in the order the wave settles them (log2 of each row's share of its normaliser, absolute).
+struct MassRows {
+  float* R;
+  int32_t* list;
+  int r_slots, list_cap;
+  size_t bytes;
+};
+MassRows carve_mass_ws(const pbsa_params& p, void* base);
+
+// rows == nullptr: the plain attention kernel
 hipError_t launch_attention(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
                             const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
-                            const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, hipStream_t stream);
+                            const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, const MassRows* rows,
+                            hipStream_t stream);
+hipError_t launch_mass_reduce(const pbsa_params& p, const MassRows& rows, const float* lse, float* Mt,
+                              hipStream_t stream);
 hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, bf16_t* Kp,
                          bf16_t* Vp,
                          float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,

@@ -151,6 +151,18 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
     const float l = a.lse[(size_t)h * a.Nq + tok_c];
     nl[g] = tok < a.Nq && l > -INFINITY ? -l * 1.4426950408889634f : -INFINITY;
   }
+  // B = 64: a tile that only the other query block of the workgroup attends is shared out among all four waves,
+  // this wave taking that block's row group rh: its fragments and normaliser
+  bf16x8 qo[KS];
+  float nlo = -INFINITY;
+  if constexpr (G == 2) {
+    const int tok = T0 + (1 - rh) * 64 + rh * 32 + qn, tok_c = min(tok, a.Nq - 1);
+    const bf16_t* qrow = a.Q + (size_t)h * a.q_stride_h + (size_t)tok_c * a.q_stride_t + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qo[ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks);
+    const float l = a.lse[(size_t)h * a.Nq + tok_c];
+    nlo = tok < a.Nq && l > -INFINITY ? -l * 1.4426950408889634f : -INFINITY;
+  }
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < kSelPer; ++u) {
@@ -210,6 +222,11 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[g][ks]));
     asm volatile("" : "+v"(nl[g]));
   }
+  if constexpr (G == 2) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qo[ks]));
+    asm volatile("" : "+v"(nlo));
+  }
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
   const uint32_t ring_s = __builtin_amdgcn_readfirstlane(smem_lds);
   // K fragment of this lane inside a ring entry: key row 32 kh + lane % 32, logical chunk 2 ks + lane / 32 at
@@ -249,16 +266,23 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
       const int meta = __builtin_amdgcn_readfirstlane(t_meta[t]);
       const int len = meta & 0xFF;
       float total = 0.0f;
-      if ((meta >> (8 + rh)) & 1) {
-        const uint32_t off = (uint32_t)((t % RING) * TILE);
+      const uint32_t off = (uint32_t)((t % RING) * TILE);
+      const int att = (meta >> 8) & 3;     // row halves that attend: both, or (B = 64) one query block alone
+      // accumulator element v is key 8 (v / 4) + 4 half + v % 4 of the wave's 32; keys past the valid length hold
+      // anything at all and are left out by selection, not by a product
+      const int lim = len - 32 * kh - 4 * half;
+      if (att == 3) {
         f32x16 s[2];
+        bf16x8 kf[KS];                     // all operand reads first: their latency is paid once, not per k-step
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kf[ks] = lds_read_k(ka[ks] + off);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 kf = lds_read_k(ka[ks] + off);
           const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
           for (int g = 0; g < 2; ++g)
-            s[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[g][ks], ks == 0 ? zero : s[g], 0, 0, 0);
+            s[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[g][ks], ks == 0 ? zero : s[g], 0, 0, 0);
         }
         float acc[2] = {0.0f, 0.0f};
         if (len == kTile) {
@@ -267,9 +291,6 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[g] += __builtin_amdgcn_exp2f(__builtin_fmaf(s[g][v], c2, nl[g]));
         } else {
-          // accumulator element v is key 8 (v / 4) + 4 half + v % 4 of the wave's 32; rows past the valid length
-          // hold anything at all and are left out by selection, not by a product
-          const int lim = len - 32 * kh - 4 * half;
 #pragma unroll
           for (int g = 0; g < 2; ++g)
 #pragma unroll
@@ -279,6 +300,32 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
             }
         }
         total = wave_sum(acc[0] + acc[1]);
+      } else if (G == 2) {
+        // one query block alone: its 64 rows x 64 keys are four 32 x 32 products, one per wave
+        const bool mine = att == 1 << rh;  // the block is this wave's own: row group rh of it is qf[rh]
+        f32x16 s1;
+        bf16x8 kf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kf[ks] = lds_read_k(ka[ks] + off);
+        __builtin_amdgcn_sched_barrier(0);
+        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        auto product = [&](const bf16x8 (&q)[KS]) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], q[ks], ks == 0 ? zero : s1, 0, 0, 0);
+        };
+        // three uniform branches rather than a choice of operands, which would copy the fragments
+        if (!mine) product(qo);
+        else if (rh == 0) product(qf[0]);
+        else product(qf[1]);
+        const float nsel = !mine ? nlo : rh == 0 ? nl[0] : nl[1];
+        float acc = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[v], c2, nsel));
+          acc += 8 * (v / 4) + (v % 4) < lim ? e : 0.0f;
+        }
+        total = wave_sum(acc);
       }
       if (lane == 0) part[4 * t + wave] = total;
     }
@@ -298,8 +345,14 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
         const int p = p0 + sub;
         if (p < n_tiles && (t_meta[p] >> 10) == u) {
           if constexpr (G == 2) {
-            v = v + part[4 * p + 2 * g];
-            v = v + part[4 * p + 2 * g + 1];
+            const int att = (t_meta[p] >> 8) & 3;
+            if (att == 3) {                // each row half's two waves hold the two key halves of its query block
+              v = v + part[4 * p + 2 * g];
+              v = v + part[4 * p + 2 * g + 1];
+            } else if (att == 1 << g) {    // this query block alone: all four waves worked for it
+#pragma unroll
+              for (int w = 0; w < 4; ++w) v = v + part[4 * p + w];
+            }
           } else {
 #pragma unroll
             for (int w = 0; w < 4; ++w) v = v + part[4 * p + w];
@@ -308,6 +361,93 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
       }
     }
     a.Mt[((size_t)h * n_u + u) * a.nqb_pad + i0 + g] = v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The pass behind the mass variant of the attention kernel.  That kernel has left, per workgroup, its tile list
+// and, per wave and sub-tile, log2 of every row's unnormalised probability sum over the sub-tile; with the rows'
+// log-sum-exp the share of a row is 2^(that - log2 normaliser).  One workgroup here per workgroup there: every
+// (tile, wave) pair is summed over the wave's 64 rows and its two sub-tiles by one wave (lane = row), then the
+// numbers of a key block and query block are added in a fixed order.
+// ------------------------------------------------------------------------------------------------
+struct ReduceArgs {
+  int H, Nq, nqb, nqb_pad, n_u, r_slots, list_cap;
+  const float* R;
+  const int32_t* list;
+  const float* lse;
+  float* Mt;
+};
+
+template <int B>
+__global__ void __launch_bounds__(kThreads) mass_reduce_kernel(ReduceArgs a) {
+  constexpr int G = kRowsPerWg / B, SUB = B / kTile;
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* part = reinterpret_cast<float*>(smem);            // [tile][wave of the attention kernel]
+  int* meta_s = reinterpret_cast<int*>(part + 2 * a.list_cap);
+  int* pos_s = meta_s + a.list_cap;                        // [key block][tile of the block] -> list position or -1
+  __shared__ int ends[4];
+  const int n_qt = (a.Nq + kRowsPerWg - 1) / kRowsPerWg;
+  const int logical = blockIdx.x, h = logical / n_qt, T0 = (logical % n_qt) * kRowsPerWg, i0 = T0 / B;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t* list = a.list + (size_t)logical * a.list_cap;
+  if (tid < 4) ends[tid] = list[tid];
+  for (int i = tid; i < a.n_u * SUB; i += kThreads) pos_s[i] = -1;
+  __syncthreads();
+  const int n_shared = min(ends[1], a.list_cap - 4), n_list = min(ends[3], a.list_cap - 4);
+  const int solo1 = min(ends[2], n_list);                  // wave 0 alone: [n_shared, solo1), wave 1: [solo1, n_list)
+  for (int i = tid; i < n_list; i += kThreads) {
+    const int m = list[4 + i];
+    meta_s[i] = m;
+    const int u = (m >> 10) & 1023, sub = (m >> 20) & 1;
+    if (u < a.n_u && sub < SUB) pos_s[u * SUB + sub] = i;
+  }
+  // minus log2 of the normaliser of the rows this lane stands for, one per wave of the attention kernel; a row
+  // that does not exist or attended nothing takes no part
+  float nl[2];
+  bool live[2];
+#pragma unroll
+  for (int aw = 0; aw < 2; ++aw) {
+    const int tok = T0 + 64 * aw + lane;
+    const float l = a.lse[(size_t)h * a.Nq + min(tok, a.Nq - 1)];
+    live[aw] = tok < a.Nq && l > -INFINITY;
+    nl[aw] = live[aw] ? -l * 1.4426950408889634f : 0.0f;
+  }
+  for (int q = wave; q < 2 * n_list; q += kThreads / 64) {
+    const int p = q >> 1, aw = q & 1;
+    // the wave's record of the tile's first sub-tile: shared tiles come first, two records each, then its own
+    int slot = -1;
+    if (p < n_shared) slot = 2 * p;
+    else if (aw == 0 && p < solo1) slot = 2 * n_shared + 2 * (p - n_shared);
+    else if (aw == 1 && p >= solo1) slot = 2 * n_shared + 2 * (p - solo1);
+    float total = 0.0f;
+    if (slot >= 0 && slot + 1 < a.r_slots) {
+      const float* r = a.R + (((size_t)logical * 2 + aw) * a.r_slots + slot) * 64 + lane;
+      const float x0 = r[0], x1 = r[64];
+      const float n = aw ? nl[1] : nl[0];
+      const float e = __builtin_amdgcn_exp2f(x0 + n) + __builtin_amdgcn_exp2f(x1 + n);
+      total = wave_sum((aw ? live[1] : live[0]) ? e : 0.0f);
+    }
+    if (lane == 0) part[q] = total;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < a.n_u * G; idx += kThreads) {
+    const int u = idx / G, g = idx % G;
+    if (i0 + g >= a.nqb) continue;
+    float v = 0.0f;
+#pragma unroll
+    for (int sub = 0; sub < SUB; ++sub) {
+      const int p = pos_s[u * SUB + sub];
+      if (p >= 0) {
+        if constexpr (G == 2) {
+          v = v + part[2 * p + g];           // wave g of the attention kernel is query block g
+        } else {
+          v = v + part[2 * p];
+          v = v + part[2 * p + 1];
+        }
+      }
+    }
+    a.Mt[((size_t)h * a.n_u + u) * a.nqb_pad + i0 + g] = v;
   }
 }
 
@@ -326,6 +466,32 @@ hipError_t launch_mass_t(const MassArgs& a, size_t lds, dim3 grid, hipStream_t s
 }
 
 }  // namespace
+
+MassRows carve_mass_ws(const pbsa_params& p, void* base) {
+  MassRows m;
+  const int sub = p.B / kTile, g = kRowsPerWg / p.B;
+  const int tiles = (p.C + 1) * sub + (g * p.k < p.n_loc ? g * p.k : p.n_loc) * sub;    // most a workgroup can list
+  const size_t n_wg = (size_t)p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
+  m.r_slots = 2 * tiles;
+  m.list_cap = 4 + tiles;
+  char* b = static_cast<char*>(base);
+  const size_t r_bytes = (n_wg * 2 * m.r_slots * 64 * 4 + 255) & ~(size_t)255;
+  m.R = reinterpret_cast<float*>(b);
+  m.list = reinterpret_cast<int32_t*>(b + r_bytes);
+  m.bytes = r_bytes + ((n_wg * m.list_cap * 4 + 255) & ~(size_t)255);
+  return m;
+}
+
+hipError_t launch_mass_reduce(const pbsa_params& p, const MassRows& rows, const float* lse, float* Mt,
+                              hipStream_t stream) {
+  const int n_u = p.C + 1 + p.n_loc, sub = p.B / kTile;
+  ReduceArgs a{p.H, p.Nq, p.nqb, (p.nqb + 3) & ~3, n_u, rows.r_slots, rows.list_cap, rows.R, rows.list, lse, Mt};
+  const int n_wg = p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
+  const size_t lds = (size_t)rows.list_cap * 12 + (size_t)n_u * sub * 4;
+  if (p.B == 128) hipLaunchKernelGGL(mass_reduce_kernel<128>, dim3(n_wg), dim3(kThreads), lds, stream, a);
+  else hipLaunchKernelGGL(mass_reduce_kernel<64>, dim3(n_wg), dim3(kThreads), lds, stream, a);
+  return hipGetLastError();
+}
 
 hipError_t launch_attention_mass(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const int32_t* p_len,
                                  const bf16_t* Kl, const int32_t* l_len, const int32_t* l_map, const int32_t* sel,

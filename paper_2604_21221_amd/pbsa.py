@@ -16,8 +16,8 @@ PBSA_OK, PBSA_EINVAL, PBSA_ESHAPE, PBSA_EALIGN, PBSA_EWS, PBSA_EHIP = 0, -1, -2,
 PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 512, 64, 192, 512
 
 EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
-           "pbsa_memory_update", "pbsa_attention_mass", "pbsa_memory_update_fine", "pbsa_blockify", "pbsa_unblockify",
-           "pbsa_strerror", "pbsa_version")
+           "pbsa_memory_update", "pbsa_attention_mass", "pbsa_mass_workspace_bytes", "pbsa_attention_fwd_mass",
+           "pbsa_memory_update_fine", "pbsa_blockify", "pbsa_unblockify", "pbsa_strerror", "pbsa_version")
 
 
 class pbsa_params(ctypes.Structure):
@@ -77,13 +77,15 @@ def lib() -> ctypes.CDLL:
         L.pbsa_attention_fwd.argtypes = [pp] + [vp] * 12 + [sz, vp]
         L.pbsa_memory_update.argtypes = [pp] + [vp] * 18 + [sz, vp]
         L.pbsa_attention_mass.argtypes = [pp] + [vp] * 10
+        L.pbsa_mass_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+        L.pbsa_attention_fwd_mass.argtypes = [pp] + [vp] * 13 + [sz, vp]
         L.pbsa_memory_update_fine.argtypes = [pp] + [vp] * 17 + [sz, vp]
         pg = ctypes.POINTER(pbsa_grid)
         L.pbsa_blockify.argtypes = [pg, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_int64), vp]
         L.pbsa_unblockify.argtypes = [pg, vp, ctypes.c_int64, vp, vp]
         for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
-                     "pbsa_memory_update", "pbsa_attention_mass", "pbsa_memory_update_fine", "pbsa_blockify",
-                     "pbsa_unblockify"):
+                     "pbsa_memory_update", "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
+                     "pbsa_attention_fwd_mass", "pbsa_memory_update_fine", "pbsa_blockify", "pbsa_unblockify"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -166,6 +168,19 @@ def pbsa_memory_update(p, Qc, Kc_l, Zl, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt,
 def pbsa_attention_mass(p, Q, Kp, p_len, Kl, l_len, l_map, sel, lse, Mt, stream=None):
     _check(lib().pbsa_attention_mass(ctypes.byref(p), _ptr(Q), _ptr(Kp), _ptr(p_len), _ptr(Kl), _ptr(l_len),
                                      _ptr(l_map), _ptr(sel), _ptr(lse), _ptr(Mt), _stream(stream)))
+
+
+def pbsa_mass_workspace_bytes(p: pbsa_params) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().pbsa_mass_workspace_bytes(ctypes.byref(p), ctypes.byref(out)))
+    return out.value
+
+
+def pbsa_attention_fwd_mass(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse, Mt, ws, stream=None):
+    w, wb = _ws(ws)
+    _check(lib().pbsa_attention_fwd_mass(ctypes.byref(p), _ptr(Q), _ptr(Kp), _ptr(Vp), _ptr(p_len), _ptr(Kl), _ptr(Vl),
+                                         _ptr(l_len), _ptr(l_map), _ptr(sel), _ptr(O), _ptr(lse), _ptr(Mt), w, wb,
+                                         _stream(stream)))
 
 
 def pbsa_memory_update_fine(p, Mt, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id, scores,

@@ -156,7 +156,20 @@ def test_fine_mass_argument_checks(L):
     def fine(p=p, Mt=P, ws=(0x10000, 1 << 30), S_cnt=P):
         pbsa.pbsa_memory_update_fine(p, Mt, P, P, P, P, P, P, P, S_cnt, P, P, P, P, P, None, P, ws, stream=0)
 
-    for call, kw, code in [(mass, dict(lse=None), pbsa.PBSA_EINVAL), (mass, dict(Mt=None), pbsa.PBSA_EINVAL),
+    def fused(p=p, lse=P, Mt=P, ws=(0x10000, 1 << 40)):
+        pbsa.pbsa_attention_fwd_mass(p, P, P, P, P, P, P, P, P, P, P, lse, Mt, ws, stream=0)
+
+    need_m = pbsa.pbsa_mass_workspace_bytes(p)
+    # per 128 query rows: two waves x 2 (C + 1 + min(2k, n_loc)) records of 256 bytes, and the tile list
+    assert need_m >= 2 * 2 * 2 * 2 * (5 + 6) * 256 and need_m % 256 == 0
+    with pytest.raises(pbsa.PbsaError) as e:
+        pbsa.pbsa_mass_workspace_bytes(good(B=32))
+    assert e.value.code == pbsa.PBSA_ESHAPE
+    for call, kw, code in [(fused, dict(lse=None), pbsa.PBSA_EINVAL), (fused, dict(Mt=None), pbsa.PBSA_EINVAL),
+                           (fused, dict(ws=None), pbsa.PBSA_EWS), (fused, dict(ws=(0x10000, need_m - 1)), pbsa.PBSA_EWS),
+                           (fused, dict(ws=(0x10010, need_m)), pbsa.PBSA_EALIGN), (fused, dict(Mt=P + 4), pbsa.PBSA_EALIGN),
+                           (fused, dict(p=good(C=193)), pbsa.PBSA_ESHAPE),
+                           (mass, dict(lse=None), pbsa.PBSA_EINVAL), (mass, dict(Mt=None), pbsa.PBSA_EINVAL),
                            (mass, dict(Mt=P + 4), pbsa.PBSA_EALIGN), (mass, dict(Q=P + 2), pbsa.PBSA_EALIGN),
                            (mass, dict(p=good(d=96)), pbsa.PBSA_ESHAPE), (mass, dict(p=good(C=193)), pbsa.PBSA_ESHAPE),
                            (fine, dict(Mt=None), pbsa.PBSA_EINVAL), (fine, dict(S_cnt=None), pbsa.PBSA_EINVAL),
