@@ -464,15 +464,17 @@ __device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[
   return false;
 }
 
-// The mass variant of the kernel also leaves, for every sub-tile a wave settles and every one of its 64 rows,
-// the base-2 logarithm of the row's share of the softmax normaliser that falls on that sub-tile, in absolute
-// units (independent of the reference in force at the time): log2(sum of the sub-tile's probabilities) plus
-// the reference.  A later pass turns them into attention mass per key block: 2^(that - log2 normaliser),
-// summed over rows.  One 256-byte store per settle: lanes 0..31 hold rows 0..31, lanes 32..63 rows 32..63.
+// The mass variant of the kernel also leaves, for every 64-key tile a wave walks and every one of its 64 rows,
+// the base-2 logarithm of the row's share of the softmax normaliser that falls on that tile, in absolute units
+// (independent of the reference in force at the time): log2(sum of the tile's probabilities) minus mc.  A later
+// pass turns them into attention mass per key block: 2^(that - log2 normaliser), summed over rows.  The sum of
+// a tile's first sub-tile is held until the second is settled; one 256-byte store per tile: lanes 0..31 hold
+// rows 0..31, lanes 32..63 rows 32..63.
 struct MassOut {
   float* rp;        // where this wave's next 64 values go (uniform)
   int lane;
   bool hi;          // lane >= 32
+  float hold, hold_mc;   // the first sub-tile's row sum and the mc it is relative to
 };
 
 // K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
@@ -495,8 +497,16 @@ __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const 
       // lanes 32..63 that of group 1: row 32 g + lane % 32 = lane.
       const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(psum[0]), __float_as_uint(psum[1]), false, false);
       const float tot = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-      mo.rp[mo.lane] = __builtin_amdgcn_logf(tot) - (mo.hi ? sr.mc[1] : sr.mc[0]);
-      mo.rp += 64;
+      const float mc_now = mo.hi ? sr.mc[1] : sr.mc[0];
+      if constexpr (V_OFF == 0) {          // the sub-tile settled is the one whose V the step multiplies: a tile's first
+        mo.hold = tot;
+        mo.hold_mc = mc_now;
+      } else {
+        // the held sum in today's units (the factor is 1 unless the reference moved in between)
+        const float both = __builtin_fmaf(mo.hold, __builtin_amdgcn_exp2f(mc_now - mo.hold_mc), tot);
+        mo.rp[mo.lane] = __builtin_amdgcn_logf(both) - mc_now;
+        mo.rp += 64;
+      }
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -652,7 +662,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[g][ks]));
 
-  MassOut mo{nullptr, lane, lane >= 32};
+  MassOut mo{nullptr, lane, lane >= 32, 0.0f, 0.0f};
   if constexpr (MASS) {
     // the later pass walks the same list: the ends of its four parts, then a descriptor per tile
     int32_t* out = a.Rlist + (size_t)logical * a.list_cap;

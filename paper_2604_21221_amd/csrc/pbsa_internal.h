@@ -29,8 +29,8 @@ hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl
                          hipStream_t stream);
 // Scratch of the attention call that also produces the attention mass: what the attention kernel leaves for
 // the pass that follows it.  Per workgroup (128 query rows of a head) a tile list of list_cap ints: the ends of
-// the list's four parts, then a descriptor per tile; per wave r_slots records of 64 floats, one per sub-tile
-// in the order the wave settles them (log2 of each row's share of its normaliser, absolute).
+// the list's four parts, then a descriptor per tile; per wave r_slots records of 64 floats, one per tile in
+// the order the wave walks them (log2 of each row's share of its normaliser, absolute).
 struct MassRows {
   float* R;
   int32_t* list;

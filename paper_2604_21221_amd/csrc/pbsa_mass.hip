@@ -366,9 +366,9 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 // The pass behind the mass variant of the attention kernel.  That kernel has left, per workgroup, its tile list
-// and, per wave and sub-tile, log2 of every row's unnormalised probability sum over the sub-tile; with the rows'
+// and, per wave and tile, log2 of every row's unnormalised probability sum over the tile; with the rows'
 // log-sum-exp the share of a row is 2^(that - log2 normaliser).  One workgroup here per workgroup there: every
-// (tile, wave) pair is summed over the wave's 64 rows and its two sub-tiles by one wave (lane = row), then the
+// (tile, wave) pair is summed over the wave's 64 rows by one wave (lane = row), then the
 // numbers of a key block and query block are added in a fixed order.
 // ------------------------------------------------------------------------------------------------
 struct ReduceArgs {
@@ -379,8 +379,12 @@ struct ReduceArgs {
   float* Mt;
 };
 
+// 16 waves: a workgroup's hundred or two (tile, wave) pairs are a batch or two per wave, so the loads of the whole
+// workgroup are in flight together
+constexpr int kReduceThreads = 1024;
+
 template <int B>
-__global__ void __launch_bounds__(kThreads) mass_reduce_kernel(ReduceArgs a) {
+__global__ void __launch_bounds__(kReduceThreads) mass_reduce_kernel(ReduceArgs a) {
   constexpr int G = kRowsPerWg / B, SUB = B / kTile;
   extern __shared__ __align__(16) unsigned char smem[];
   float* part = reinterpret_cast<float*>(smem);            // [tile][wave of the attention kernel]
@@ -392,11 +396,11 @@ __global__ void __launch_bounds__(kThreads) mass_reduce_kernel(ReduceArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t* list = a.list + (size_t)logical * a.list_cap;
   if (tid < 4) ends[tid] = list[tid];
-  for (int i = tid; i < a.n_u * SUB; i += kThreads) pos_s[i] = -1;
+  for (int i = tid; i < a.n_u * SUB; i += kReduceThreads) pos_s[i] = -1;
   __syncthreads();
   const int n_shared = min(ends[1], a.list_cap - 4), n_list = min(ends[3], a.list_cap - 4);
   const int solo1 = min(ends[2], n_list);                  // wave 0 alone: [n_shared, solo1), wave 1: [solo1, n_list)
-  for (int i = tid; i < n_list; i += kThreads) {
+  for (int i = tid; i < n_list; i += kReduceThreads) {
     const int m = list[4 + i];
     meta_s[i] = m;
     const int u = (m >> 10) & 1023, sub = (m >> 20) & 1;
@@ -413,25 +417,36 @@ __global__ void __launch_bounds__(kThreads) mass_reduce_kernel(ReduceArgs a) {
     live[aw] = tok < a.Nq && l > -INFINITY;
     nl[aw] = live[aw] ? -l * 1.4426950408889634f : 0.0f;
   }
-  for (int q = wave; q < 2 * n_list; q += kThreads / 64) {
-    const int p = q >> 1, aw = q & 1;
-    // the wave's record of the tile's first sub-tile: shared tiles come first, two records each, then its own
-    int slot = -1;
-    if (p < n_shared) slot = 2 * p;
-    else if (aw == 0 && p < solo1) slot = 2 * n_shared + 2 * (p - n_shared);
-    else if (aw == 1 && p >= solo1) slot = 2 * n_shared + 2 * (p - solo1);
-    float total = 0.0f;
-    if (slot >= 0 && slot + 1 < a.r_slots) {
-      const float* r = a.R + (((size_t)logical * 2 + aw) * a.r_slots + slot) * 64 + lane;
-      const float x0 = r[0], x1 = r[64];
-      const float n = aw ? nl[1] : nl[0];
-      const float e = __builtin_amdgcn_exp2f(x0 + n) + __builtin_amdgcn_exp2f(x1 + n);
-      total = wave_sum((aw ? live[1] : live[0]) ? e : 0.0f);
+  // (tile, wave) pairs in batches: all the records of a batch are asked for before any is used, and the cross-lane
+  // sums of a batch interleave -- one pair at a time the loop is a chain of memory and reduction latencies
+  constexpr int kBatch = 8;
+  for (int q0 = wave * kBatch; q0 < 2 * n_list; q0 += (kReduceThreads / 64) * kBatch) {
+    float x[kBatch];
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const int q = q0 + j, p = q >> 1, aw = q & 1;
+      // the wave's record of the tile: shared tiles come first, then its own
+      int slot = -1;
+      if (q < 2 * n_list) {
+        if (p < n_shared) slot = p;
+        else if (aw == 0 && p < solo1) slot = p;
+        else if (aw == 1 && p >= solo1) slot = n_shared + (p - solo1);
+      }
+      x[j] = slot >= 0 && slot < a.r_slots ? a.R[(((size_t)logical * 2 + aw) * a.r_slots + slot) * 64 + lane] : -INFINITY;
     }
-    if (lane == 0) part[q] = total;
+    float tot[kBatch];
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const int aw = (q0 + j) & 1;
+      const float e = __builtin_amdgcn_exp2f(x[j] + (aw ? nl[1] : nl[0]));
+      tot[j] = wave_sum((aw ? live[1] : live[0]) ? e : 0.0f);
+    }
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+      if (lane == 0 && q0 + j < 2 * n_list) part[q0 + j] = tot[j];
   }
   __syncthreads();
-  for (int idx = tid; idx < a.n_u * G; idx += kThreads) {
+  for (int idx = tid; idx < a.n_u * G; idx += kReduceThreads) {
     const int u = idx / G, g = idx % G;
     if (i0 + g >= a.nqb) continue;
     float v = 0.0f;
@@ -472,7 +487,7 @@ MassRows carve_mass_ws(const pbsa_params& p, void* base) {
   const int sub = p.B / kTile, g = kRowsPerWg / p.B;
   const int tiles = (p.C + 1) * sub + (g * p.k < p.n_loc ? g * p.k : p.n_loc) * sub;    // most a workgroup can list
   const size_t n_wg = (size_t)p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
-  m.r_slots = 2 * tiles;
+  m.r_slots = tiles;
   m.list_cap = 4 + tiles;
   char* b = static_cast<char*>(base);
   const size_t r_bytes = (n_wg * 2 * m.r_slots * 64 * 4 + 255) & ~(size_t)255;
@@ -488,8 +503,8 @@ hipError_t launch_mass_reduce(const pbsa_params& p, const MassRows& rows, const 
   ReduceArgs a{p.H, p.Nq, p.nqb, (p.nqb + 3) & ~3, n_u, rows.r_slots, rows.list_cap, rows.R, rows.list, lse, Mt};
   const int n_wg = p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
   const size_t lds = (size_t)rows.list_cap * 12 + (size_t)n_u * sub * 4;
-  if (p.B == 128) hipLaunchKernelGGL(mass_reduce_kernel<128>, dim3(n_wg), dim3(kThreads), lds, stream, a);
-  else hipLaunchKernelGGL(mass_reduce_kernel<64>, dim3(n_wg), dim3(kThreads), lds, stream, a);
+  if (p.B == 128) hipLaunchKernelGGL(mass_reduce_kernel<128>, dim3(n_wg), dim3(kReduceThreads), lds, stream, a);
+  else hipLaunchKernelGGL(mass_reduce_kernel<64>, dim3(n_wg), dim3(kReduceThreads), lds, stream, a);
   return hipGetLastError();
 }
 

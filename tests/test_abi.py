@@ -160,8 +160,8 @@ def test_fine_mass_argument_checks(L):
         pbsa.pbsa_attention_fwd_mass(p, P, P, P, P, P, P, P, P, P, P, lse, Mt, ws, stream=0)
 
     need_m = pbsa.pbsa_mass_workspace_bytes(p)
-    # per 128 query rows: two waves x 2 (C + 1 + min(2k, n_loc)) records of 256 bytes, and the tile list
-    assert need_m >= 2 * 2 * 2 * 2 * (5 + 6) * 256 and need_m % 256 == 0
+    # per 128 query rows: two waves x (C + 1 + min(2k, n_loc)) records of 256 bytes, and the tile list
+    assert need_m >= 2 * 2 * 2 * (5 + 6) * 256 and need_m % 256 == 0
     with pytest.raises(pbsa.PbsaError) as e:
         pbsa.pbsa_mass_workspace_bytes(good(B=32))
     assert e.value.code == pbsa.PBSA_ESHAPE
