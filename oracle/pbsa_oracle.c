@@ -506,3 +506,103 @@ int orc_memory_update_fine(const orc_cfg* c, const float* Mt, const float* Kc_l,
   free(s_p); free(s_l);
   return rc;
 }
+
+/* Backward of the PBSA fine stage (the gradient of Eq. 3-5; the paper's training kernel): given dO, the
+ * gradient of a scalar loss with respect to the output O = P V, with P the masked row softmax of
+ * Z = scale * Q K^T over what each row attends,
+ *     dV_j  = sum_q P[q][j] dO[q]                      dP[q][j] = dO[q] . V_j
+ *     dZ    = P o (dP - D),  D[q] = sum_j P[q][j] dP[q][j]  ( = dO[q] . O[q] )
+ *     dQ_q  = scale * sum_j dZ[q][j] K_j               dK_j  = scale * sum_q dZ[q][j] Q_q
+ * (the chain rule through a row softmax, written out).  Everything in fp64 from the bf16 inputs; O is
+ * recomputed here, not taken from anybody.  Q, dO [H][Nq][d] bf16 bits.  Outputs fp64, each either NULL
+ * or zero-filled by the caller: dQ [H][Nq][d], dKp/dVp [H][C+1][B][d], dKl/dVl [H][n_loc_cap][B][d]
+ * (physical slots, like Kl).  A key that no row attends, and rows past a block's length, get nothing.
+ * row_mask (optional, [H][Nq] bytes): only rows with a non-zero byte take part, so that the cost of a
+ * check at full size can be bounded; their dQ is exact, dK/dV are then the sums over those rows only. */
+int orc_attention_bwd(const orc_cfg* c, const uint16_t* Q, const uint16_t* Kp, const uint16_t* Vp,
+                      const int32_t* p_len, const uint16_t* Kl, const uint16_t* Vl, const int32_t* l_len,
+                      const int32_t* l_map, const int32_t* sel, const uint16_t* dO, const uint8_t* row_mask,
+                      double* dQ, double* dKp, double* dVp, double* dKl, double* dVl) {
+  const int d = c->d, B = c->B;
+  const size_t max_keys = (size_t)(c->C + 1 + c->k) * B + 1;
+  int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int h = 0; h < c->H; ++h) {          /* a head's keys belong to that head alone: no two threads share an output */
+    double* z = (double*)malloc(sizeof(double) * max_keys);
+    const uint16_t** krow = (const uint16_t**)malloc(sizeof(void*) * max_keys);
+    const uint16_t** vrow = (const uint16_t**)malloc(sizeof(void*) * max_keys);
+    double** dk = (double**)malloc(sizeof(void*) * max_keys);
+    double** dv = (double**)malloc(sizeof(void*) * max_keys);
+    double* q = (double*)malloc(sizeof(double) * (size_t)d);
+    double* g = (double*)malloc(sizeof(double) * (size_t)d);
+    double* o = (double*)malloc(sizeof(double) * (size_t)d);
+    if (!z || !krow || !vrow || !dk || !dv || !q || !g || !o) {
+#pragma omp atomic write
+      fail = 1;
+    } else {
+      for (int t = 0; t < c->Nq; ++t) {
+        if (row_mask && !row_mask[(size_t)h * c->Nq + t]) continue;
+        const int i = t / B;
+        for (int x = 0; x < d; ++x) {
+          q[x] = (double)bf2f(Q[((size_t)h * c->Nq + t) * d + x]);
+          g[x] = (double)bf2f(dO[((size_t)h * c->Nq + t) * d + x]);
+        }
+        size_t n = 0;
+        for (int s = 0; s <= c->C; ++s) {
+          const size_t base = ((size_t)h * (c->C + 1) + s) * B * d;
+          for (int u = 0; u < p_len[(size_t)h * (c->C + 1) + s]; ++u, ++n) {
+            krow[n] = Kp + base + (size_t)u * d;
+            vrow[n] = Vp + base + (size_t)u * d;
+            dk[n] = dKp ? dKp + base + (size_t)u * d : NULL;
+            dv[n] = dVp ? dVp + base + (size_t)u * d : NULL;
+          }
+        }
+        const int32_t* row_sel = sel + ((size_t)h * c->nqb + i) * c->k;
+        for (int j = 0; j < c->k; ++j) {
+          const int l = row_sel[j];
+          if (l < 0) continue;
+          const size_t base = ((size_t)h * c->n_loc_cap + l_map[l]) * B * d;
+          for (int u = 0; u < l_len[l]; ++u, ++n) {
+            krow[n] = Kl + base + (size_t)u * d;
+            vrow[n] = Vl + base + (size_t)u * d;
+            dk[n] = dKl ? dKl + base + (size_t)u * d : NULL;
+            dv[n] = dVl ? dVl + base + (size_t)u * d : NULL;
+          }
+        }
+        if (n == 0) continue;
+        double m = -INFINITY;
+        for (size_t j = 0; j < n; ++j) {
+          double acc = 0.0;
+          for (int x = 0; x < d; ++x) acc += q[x] * (double)bf2f(krow[j][x]);
+          z[j] = acc * (double)c->scale;
+          m = z[j] > m ? z[j] : m;
+        }
+        double sum = 0.0;
+        for (size_t j = 0; j < n; ++j) {
+          z[j] = exp(z[j] - m);
+          sum += z[j];
+        }
+        for (int x = 0; x < d; ++x) o[x] = 0.0;
+        for (size_t j = 0; j < n; ++j) {
+          z[j] /= sum;                                      /* P[q][j] */
+          for (int x = 0; x < d; ++x) o[x] += z[j] * (double)bf2f(vrow[j][x]);
+        }
+        double D = 0.0;
+        for (int x = 0; x < d; ++x) D += g[x] * o[x];
+        for (size_t j = 0; j < n; ++j) {
+          double dp = 0.0;
+          for (int x = 0; x < d; ++x) dp += g[x] * (double)bf2f(vrow[j][x]);
+          const double dz = z[j] * (dp - D) * (double)c->scale;
+          if (dQ)
+            for (int x = 0; x < d; ++x) dQ[((size_t)h * c->Nq + t) * d + x] += dz * (double)bf2f(krow[j][x]);
+          if (dk[j])
+            for (int x = 0; x < d; ++x) dk[j][x] += dz * q[x];
+          if (dv[j])
+            for (int x = 0; x < d; ++x) dv[j][x] += z[j] * g[x];
+        }
+      }
+    }
+    free(z); free(krow); free(vrow); free(dk); free(dv); free(q); free(g); free(o);
+  }
+  return fail ? -1 : 0;
+}

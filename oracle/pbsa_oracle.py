@@ -221,3 +221,25 @@ def memory_update_fine(cfg: Cfg, Mt, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_c
     if rc:
         raise RuntimeError(f"orc_memory_update_fine failed: {rc}")
     return sc, src
+
+
+def attention_bwd(cfg: Cfg, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, dO, row_mask=None, want_kv=True):
+    """fp64 gradients of the fine stage: (dQ [H][Nq][d], dKp, dVp [H][C+1][B][d], dKl, dVl [H][cap][B][d]);
+    with row_mask ([H][Nq] bool) only those rows take part."""
+    H, d, B = cfg.H, cfg.d, cfg.B
+    dQ = np.zeros((H, cfg.Nq, d), np.float64)
+    outs = [np.zeros((H, cfg.C + 1, B, d), np.float64), np.zeros((H, cfg.C + 1, B, d), np.float64),
+            np.zeros((H, cfg.n_loc_cap, B, d), np.float64), np.zeros((H, cfg.n_loc_cap, B, d), np.float64)] if want_kv else [None] * 4
+    mask = None if row_mask is None else np.ascontiguousarray(row_mask, np.uint8)
+    c = cfg.c()
+    rc = lib().orc_attention_bwd(
+        ctypes.byref(c), _p(Q, np.uint16, (H, cfg.Nq, d)), _p(Kp, np.uint16, (H, cfg.C + 1, B, d)),
+        _p(Vp, np.uint16, (H, cfg.C + 1, B, d)), _p(p_len, np.int32, (H, cfg.C + 1)),
+        _p(Kl, np.uint16, (H, cfg.n_loc_cap, B, d)), _p(Vl, np.uint16, (H, cfg.n_loc_cap, B, d)),
+        _p(l_len, np.int32, (cfg.n_loc,)), _p(l_map, np.int32, (cfg.n_loc,)),
+        _p(sel, np.int32, (H, cfg.nqb, cfg.k)), _p(dO, np.uint16, (H, cfg.Nq, d)),
+        _p(mask, np.uint8, (H, cfg.Nq)) if mask is not None else None,
+        _p(dQ, np.float64), *[_p(a, np.float64) if a is not None else None for a in outs])
+    if rc:
+        raise RuntimeError(f"orc_attention_bwd failed: {rc}")
+    return (dQ, *outs)

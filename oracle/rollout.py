@@ -113,6 +113,12 @@ class OracleState:
         l_map, l_len, _ = self._maps()
         return orc.attention_mass(self.cfg(), Q, self.Kp, self.p_len, self.Kl, l_len, l_map, self.sel, qb_h, qb_i)
 
+    def attention_bwd(self, Q, dO, row_mask=None, want_kv=True):
+        """fp64 gradients (dQ, dKp, dVp, dKl, dVl) of the fine stage for the output gradient dO."""
+        l_map, l_len, _ = self._maps()
+        return orc.attention_bwd(self.cfg(), Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map,
+                                 self.sel, dO, row_mask, want_kv)
+
     def n_evict_now(self):
         return self.nqb if len(self.chunks) == self.w + 1 else 0
 

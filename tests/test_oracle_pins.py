@@ -542,6 +542,103 @@ def test_fine_and_coarse_updates_share_everything_but_the_score(oracle):
         assert np.array_equal(getattr(a, name), getattr(b2, name))
 
 
+# ------------------------------------------------------------------------------------------------
+# backward of the fine stage
+# ------------------------------------------------------------------------------------------------
+def gathered(st, h, sel):
+    """Keys and values of head h as fp64 matrices, where each key lives (('p', slot, token) / ('l', physical
+    slot, token)), and the visibility mask [Nq][n_keys] of Eq. 5."""
+    l_map, l_len, _ = st._maps()
+    keys, vals, where, owner = [], [], [], []
+    for s in range(st.C + 1):
+        for u in range(st.p_len[h, s]):
+            keys.append(f32(st.Kp[h, s, u])); vals.append(f32(st.Vp[h, s, u])); where.append(("p", s, u)); owner.append(-1)
+    for l in range(st.n_loc):
+        for u in range(l_len[l]):
+            keys.append(f32(st.Kl[h, l_map[l], u])); vals.append(f32(st.Vl[h, l_map[l], u]))
+            where.append(("l", int(l_map[l]), u)); owner.append(l)
+    owner = np.array(owner)
+    M = np.full((st.Nq, len(owner)), -np.inf)
+    for t in range(st.Nq):
+        vis = [int(x) for x in sel[h, t // st.B] if x >= 0]
+        M[t, (owner < 0) | np.isin(owner, vis)] = 0.0
+    return np.array(keys, np.float64), np.array(vals, np.float64), where, M
+
+
+def loss_of(Qh, K, V, M, G, scale):
+    """sum(O * G) with O = softmax(Q K^T scale + M) V: the scalar whose gradient the backward pass is."""
+    S = Qh @ K.T * scale + M
+    P = np.exp(S - S.max(1, keepdims=True))
+    P /= P.sum(1, keepdims=True)
+    return float(((P @ V) * G).sum())
+
+
+def test_backward_matches_finite_differences_of_the_forward(oracle):
+    st, Q = make_state(40, H=2, d=16, B=8, Nq=20, w=2, C=3, k=2, p_lens=[[8, 0, 5], [8, 8, 8]])
+    st.set_summary(np.abs(rnd(401, 2, 2, 8, 16)).astype(np.float32), np.tile(np.array([2, 2, 1, 0, 0, 0, 0, 0], np.int32), (2, 1)))
+    sel, _ = st.select(Q)
+    dO = bf(rnd(402, st.H, st.Nq, st.d))
+    dQ, dKp, dVp, dKl, dVl = st.attention_bwd(Q, dO)
+    eps = 1e-5
+    for h in range(st.H):
+        K, V, where, M = gathered(st, h, sel)
+        Qh, G = f32(Q[h]).astype(np.float64), f32(dO[h]).astype(np.float64)
+
+        def num(arr, idx):
+            old = arr[idx]
+            arr[idx] = old + eps; up = loss_of(Qh, K, V, M, G, st.scale)
+            arr[idx] = old - eps; dn = loss_of(Qh, K, V, M, G, st.scale)
+            arr[idx] = old
+            return (up - dn) / (2 * eps)
+
+        pick = (rnd(403 + h, 24) * 1e6).astype(np.int64)
+        for n in range(8):
+            t, x = abs(pick[n]) % st.Nq, abs(pick[n + 8]) % st.d
+            np.testing.assert_allclose(dQ[h, t, x], num(Qh, (t, x)), rtol=1e-6, atol=1e-9)
+        for n in range(12):                      # keys of every kind: persistent, summary, selected by some, by none
+            j, x = abs(pick[n]) % len(where) if n > 3 else [0, len(where) - 1, st.p_len[h, :st.C].sum(), len(where) // 2][n], abs(pick[n + 12]) % st.d
+            kind, slot, u = where[j]
+            dK, dV = (dKp, dVp) if kind == "p" else (dKl, dVl)
+            np.testing.assert_allclose(dK[h, slot, u, x], num(K, (j, x)), rtol=1e-6, atol=1e-9)
+            np.testing.assert_allclose(dV[h, slot, u, x], num(V, (j, x)), rtol=1e-6, atol=1e-9)
+
+
+def test_backward_invariants_and_special_cases(oracle):
+    st, Q = make_state(41, H=2, d=16, B=8, Nq=28, w=2, C=2, k=2, p_lens=[[8, 6], [8, 8]])
+    sel, _ = st.select(Q)
+    dO = bf(rnd(412, st.H, st.Nq, st.d))
+    dQ, dKp, dVp, dKl, dVl = st.attention_bwd(Q, dO)
+    G = f32(dO).astype(np.float64)
+    for h in range(st.H):
+        # every row's probabilities add up to 1: the value gradients add up to the output gradients
+        np.testing.assert_allclose(dVp[h].sum((0, 1)) + dVl[h].sum((0, 1)), G[h].sum(0), rtol=1e-12, atol=1e-12)
+        # a softmax does not see a vector added to all its keys: the key gradients of a head add up to zero
+        np.testing.assert_allclose(dKp[h].sum((0, 1)) + dKl[h].sum((0, 1)), 0.0, atol=1e-12)
+    l_map, l_len, _ = st._maps()
+    # nothing for keys that nobody attends: the padding of ragged blocks, the blocks in no row of sel
+    assert np.all(dKp[0, 1, 6:] == 0) and np.all(dVp[0, 1, 6:] == 0)
+    assert np.all(dKl[:, l_map[-1], l_len[-1]:] == 0)
+    for h in range(st.H):
+        unused = sorted(set(range(st.n_loc)) - set(int(x) for x in sel[h].ravel() if x >= 0))
+        assert unused
+        assert np.all(dKl[h, l_map[unused]] == 0) and np.all(dVl[h, l_map[unused]] == 0)
+        used = sorted(set(int(x) for x in sel[h].ravel() if x >= 0))
+        assert all(np.abs(dVl[h, l_map[l], :l_len[l]]).min() > 0 for l in used)
+    # a subset of the rows: their dQ is that of the full run, the others get none; dK/dV are sums over rows
+    mask = np.zeros((st.H, st.Nq), bool); mask[0, ::3] = True; mask[1, 5] = True
+    dQ2, dKp2, dVp2, dKl2, dVl2 = st.attention_bwd(Q, dO, row_mask=mask)
+    assert np.array_equal(dQ2[mask], dQ[mask]) and np.all(dQ2[~mask] == 0)
+    dQ3, dKp3, dVp3, dKl3, dVl3 = st.attention_bwd(Q, dO, row_mask=~mask)
+    np.testing.assert_allclose(dKp2 + dKp3, dKp, atol=1e-13); np.testing.assert_allclose(dVl2 + dVl3, dVl, atol=1e-13)
+    # one key and nothing else: P = 1 whatever Q is, so dQ = dK = 0 and the key's value takes all of dO
+    st1, Q1 = make_state(42, H=1, d=16, B=8, Nq=12, w=0, C=1, k=0, p_lens=[[1]])
+    st1.select(Q1)
+    dO1 = bf(rnd(421, 1, 12, 16))
+    dQ1, dKp1, dVp1, _, _ = st1.attention_bwd(Q1, dO1)
+    assert np.all(dQ1 == 0) and np.all(dKp1 == 0)
+    np.testing.assert_allclose(dVp1[0, 0, 0], f32(dO1[0]).astype(np.float64).sum(0), rtol=1e-14)
+
+
 def test_rollout_summary_counts(oracle):
     """Cold start over several chunks: window fills, then every update evicts one chunk; counts add up."""
     H, d, B, Nq, w, C = 1, 16, 8, 20, 2, 2
