@@ -194,6 +194,22 @@ int pbsa_memory_update_fine(const pbsa_params* p, const float* Mt, const float* 
                             const void* Vl, const int32_t* l_len, const int32_t* l_map, const int64_t* l_id,
                             float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Backward of pbsa_attention_fwd (the paper's training kernel: gradients through the block-sparse attention).
+ * With P the masked row softmax of Eq. 3-5 and dO the gradient of a scalar loss with respect to O = P V:
+ *   dV = P^T dO,  dZ = P o (dO V^T - D) with D[q] = dO[q] . O[q],  dQ = scale dZ K,  dK = scale dZ^T Q.
+ * Inputs: everything pbsa_attention_fwd took, its outputs O (bf16) and lse (fp32, required), and dO, bf16 with
+ * O's strides.  P is recomputed as exp(scale q.k - lse) on bf16 MFMA; P and dZ are rounded to bf16 for the second
+ * products, sums are fp32.  Outputs, fp32, every element written exactly once (deterministic, no atomics):
+ *   dQ [H][Nq][d] dense;  dKp, dVp [H][C+1][B][d] (the summary slot C included);  dKl, dVl [H][n_loc_cap][B][d] by
+ *   physical slot: the slots of the n_loc logical blocks are written in full -- zeros for rows past a block's
+ *   length and for blocks no query block selected -- other slots are left alone.
+ * ws: pbsa_bwd_workspace_bytes(p) bytes of device scratch (the D vector), 256-byte aligned. */
+int pbsa_bwd_workspace_bytes(const pbsa_params* p, size_t* out);
+int pbsa_attention_bwd(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                       const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map, const int32_t* sel,
+                       const void* O, const void* dO, const float* lse, float* dQ, float* dKp, float* dVp, float* dKl,
+                       float* dVl, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Locality-preserving block rearrange (App. "Rearrange for Locality Preserving", Alg. 3): the tokens of a
  * chunk come from the model in (frame, patch row, patch column) order, T x Hs x Ws of them, each a row of
  * H heads x d; a block is a Bt x Bh x Bw box of the grid, blocks are numbered (t_b, h_b, w_b) row-major and

@@ -229,6 +229,22 @@ class PbsaCache:
         self.update_fine(Mt)
         return O
 
+    def attention_bwd(self, Q, O, dO, lse, grads=None):
+        """Gradients of attention(Q) for the output gradient dO (bf16, O's strides): returns the dict of fp32
+        tensors dQ [H][Nq][d], dKp, dVp [H][C+1][B][d], dKl, dVl [H][cap][B][d] (allocated unless given)."""
+        if grads is None:
+            z = lambda *s: torch.zeros(*s, dtype=torch.float32, device=self.dev)
+            grads = dict(dQ=z(self.H, self.Nq, self.d), dKp=z(self.H, self.C + 1, self.B, self.d),
+                         dVp=z(self.H, self.C + 1, self.B, self.d), dKl=z(self.H, self.cap, self.B, self.d),
+                         dVl=z(self.H, self.cap, self.B, self.d))
+        p = self.params(Q=Q, O=O)
+        if getattr(self, "_bwd_ws", None) is None:
+            self._bwd_ws = torch.empty(pbsa.pbsa_bwd_workspace_bytes(p), dtype=torch.uint8, device=self.dev)
+        l_map, l_len, _ = self._device_maps()
+        pbsa.pbsa_attention_bwd(p, Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map, self.sel, O, dO, lse,
+                                grads["dQ"], grads["dKp"], grads["dVp"], grads["dKl"], grads["dVl"], self._bwd_ws)
+        return grads
+
     def step(self, Q, K, V, chunk_id, O=None, lse=None):
         """One layer-chunk step: append the chunk, select, attend, update (all enqueued, no sync)."""
         self.append_chunk(K, V, chunk_id)

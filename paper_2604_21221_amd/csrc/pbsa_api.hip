@@ -217,6 +217,44 @@ int pbsa_memory_update_fine(const pbsa_params* p, const float* Mt, const float* 
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
+int pbsa_bwd_workspace_bytes(const pbsa_params* p, size_t* out) {
+  if (!out) return PBSA_EINVAL;
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  if (rc) return rc;
+  *out = pbsa::bwd_workspace_bytes(*p);
+  return PBSA_OK;
+}
+
+int pbsa_attention_bwd(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                       const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map, const int32_t* sel,
+                       const void* O, const void* dO, const float* lse, float* dQ, float* dKp, float* dVp, float* dKl,
+                       float* dVl, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  if (rc) return rc;
+  if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O || !dO || !lse || !dQ || !dKp || !dVp ||
+      !dKl || !dVl)
+    return PBSA_EINVAL;
+  if (p->k > 0 && !sel) return PBSA_EINVAL;
+  rc = check_strides(p->q_stride_h, p->q_stride_t, p);
+  if (rc) return rc;
+  rc = check_strides(p->o_stride_h, p->o_stride_t, p);
+  if (rc) return rc;
+  // a tile's lane offsets are 32-bit: 64 rows of the widest stride must fit
+  if (p->q_stride_t >= ((int64_t)1 << 24) || p->o_stride_t >= ((int64_t)1 << 24)) return PBSA_ESHAPE;
+  if (!aligned16(Q) || !aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(O) ||
+      !aligned16(dO) || !aligned16(dQ) || !aligned16(dKp) || !aligned16(dVp) || !aligned16(dKl) || !aligned16(dVl))
+    return PBSA_EALIGN;
+  if (!ws || ws_bytes < pbsa::bwd_workspace_bytes(*p)) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  hipError_t e = pbsa::launch_attention_bwd(
+      *p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kp),
+      static_cast<const pbsa::bf16_t*>(Vp), p_len, static_cast<const pbsa::bf16_t*>(Kl),
+      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, sel, static_cast<const pbsa::bf16_t*>(O),
+      static_cast<const pbsa::bf16_t*>(dO), lse, dQ, dKp, dVp, dKl, dVl, static_cast<float*>(ws),
+      static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
 namespace {
 int check_grid(const pbsa_grid* g) {
   if (!g || g->size != sizeof(pbsa_grid)) return PBSA_EINVAL;

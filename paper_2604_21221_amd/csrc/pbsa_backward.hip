@@ -1,0 +1,479 @@
+// Backward of the PBSA fine stage for gfx950 (the gradient of Eq. 3-5; the paper's training kernel is
+// the block-sparse attention backward).  With P the masked row softmax of Z = scale Q K^T and dO given:
+//     dV = P^T dO        dP = dO V^T        dZ = P o (dP - D),  D[q] = dO[q] . O[q]
+//     dQ = scale dZ K    dK = scale dZ^T Q
+// P is recomputed from the forward's log-sum-exp: exp2(z c2 - lse log2 e); nothing of the forward's
+// probabilities is stored.  Three kernels, no atomics, every output element written by exactly one lane:
+//   prep   D[h][q] = sum_x dO[q][x] O[q][x]                                      (fp32, from the bf16 tensors)
+//   dq     one workgroup per 64 query rows: their Q and dO fragments stay in registers, the 64-key tiles they
+//          attend (persistent slots, then the blocks of their row of sel) stream through LDS
+//   dkv    one workgroup per 64-key tile: its K and V fragments stay in registers, the 64-row tiles of the query
+//          blocks that attend it (all of them for a persistent slot; those whose row of sel names the block
+//          otherwise, found by scanning sel) stream through LDS
+// dq and dkv are one template: a fixed side in registers (B operands), a streamed side in LDS (A operands):
+//   A1 = T1 F1^T, A2 = T2 F2^T   32 streamed rows x 32 fixed rows per MFMA chain (v_mfma_f32_32x32x16_bf16)
+//          dq:  T1 = K, T2 = V, F1 = Q, F2 = dO   ->  A1 = Z^T / scale, A2 = dP^T     (keys x queries)
+//          dkv: T1 = Q, T2 = dO, F1 = K, F2 = V   ->  A1 = Z / scale,   A2 = dP       (queries x keys)
+//   P and dZ, elementwise from A1, A2 and the per-query lse and D, rounded to bf16, are B operands as the
+//   accumulators hold them (the contraction index enumerated in accumulator order), and the A operands of the
+//   second products are transposing LDS reads of the streamed tiles with the same enumeration:
+//          dq:  dQ^T += K^T dZ^T          dkv: dK^T += Q^T dZ,  dV^T += dO^T P
+// A workgroup is two waves; wave w owns fixed rows 32 w .. 32 w + 31.  Tiles go from global memory straight to
+// LDS (global_load_lds) into a ring of two, the next tile in flight while one is used; the 16-byte chunks of
+// a row are permuted by the row number so that the row-wise operand reads are free of bank conflicts (the
+// transposing reads then see two-way conflicts).  Rows past a tile's valid length are never loaded: their
+// lanes fetch the last valid row, and the elementwise stage zeroes what belongs to them.
+#include "pbsa_internal.h"
+
+namespace pbsa {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kThreads = 128;
+constexpr int kTile = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct BwdArgs {
+  int H, Nq, nqb, n_loc, n_loc_cap, C, k, B;
+  float scale;
+  long q_stride_h, q_stride_t, o_stride_h, o_stride_t;
+  const bf16_t* Q;
+  const bf16_t* Kp;
+  const bf16_t* Vp;
+  const int32_t* p_len;
+  const bf16_t* Kl;
+  const bf16_t* Vl;
+  const int32_t* l_len;
+  const int32_t* l_map;
+  const int32_t* sel;
+  const bf16_t* O;
+  const bf16_t* dO;
+  const float* lse;
+  float* Dr;          // [H][Nq] rowsum(dO o O)
+  float* dQ;
+  float* dKp;
+  float* dVp;
+  float* dKl;
+  float* dVl;
+};
+
+__device__ __forceinline__ int lanes_below(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// One wave-wide global -> LDS load of 16 bytes per lane: LDS bytes [lds_off, lds_off + 1024) receive lane i's
+// 16 bytes at lds_off + 16 i.  Completion is tracked by the issuing wave's vmcnt.
+__device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_off), "v"(lane_off), "s"(base)
+               : "memory");
+}
+
+typedef __attribute__((address_space(3))) const bf16x8* lds_b128_t;
+typedef __attribute__((address_space(3))) bf16x4* lds_tr_t;
+__device__ __forceinline__ bf16x8 lds_read_row(uint32_t addr) { return *(lds_b128_t)(uintptr_t)addr; }
+// transposed fragment of 16 streamed rows: two transposing reads, rows r and r + 8 of the 16.  HI_XOR: what the
+// row permutation does to the byte address when the row goes up by 8.
+// off: this lane's byte offset inside the tile (the permutation acts on it), base: LDS address of the tile plus a
+// whole number of 16-row groups.
+template <int ROW, int HI_XOR>
+__device__ __forceinline__ bf16x8 lds_read_tr(uint32_t base, uint32_t off) {
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_tr_t)(uintptr_t)(base + off));
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_tr_t)(uintptr_t)(base + (off ^ HI_XOR) + 8 * ROW));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  bf16x2 pk;
+  pk[0] = (__bf16)a;
+  pk[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, pk);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& w) { return __builtin_bit_cast(bf16x8, w); }
+
+// ------------------------------------------------------------------------------------------------
+// D[h][q] = dO[q] . O[q]: 16 lanes per row, 8 elements each (d = 128) or 8 lanes (d = 64)
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) bwd_prep_kernel(BwdArgs a) {
+  constexpr int LPR = D / 8;               // lanes per row
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  const long row = idx / LPR;
+  const int part = (int)(idx % LPR);
+  float acc = 0.0f;
+  const bool ok = row < (long)a.H * a.Nq;
+  if (ok) {
+    const int h = (int)(row / a.Nq), t = (int)(row % a.Nq);
+    const size_t off = (size_t)h * a.o_stride_h + (size_t)t * a.o_stride_t + 8 * part;
+    const bf16x8 o = *reinterpret_cast<const bf16x8*>(a.O + off);
+    const bf16x8 g = *reinterpret_cast<const bf16x8*>(a.dO + off);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc = __builtin_fmaf((float)o[x], (float)g[x], acc);
+  }
+#pragma unroll
+  for (int s = 1; s < LPR; s <<= 1) acc += __shfl_xor(acc, s, 64);
+  if (ok && part == 0) a.Dr[row] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// dq (KV = false) and dkv (KV = true)
+// ------------------------------------------------------------------------------------------------
+template <int D, bool KV>
+__global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, ROW = D * 2, TILE = kTile * ROW;
+  constexpr int CH = D / 8, RPI = 64 / CH;          // 16-byte chunks per row, rows per load instruction
+  constexpr int NI = 32 / RPI;                      // load instructions per wave per tile (its 32 rows)
+  constexpr int HI_XOR = CH == 16 ? 128 : 0;        // row + 8 flips bit 3 of the chunk permutation when it has 4 bits
+  extern __shared__ __align__(1024) unsigned char smem[];
+  __shared__ int cnt_s[2 * 12];
+  __shared__ __align__(16) float nl_s[2][kTile], d_s[2][kTile];   // dkv: per ring entry, -lse log2 e and D of the tile's rows
+  // ring: entry e holds T1 at e * 2 TILE and T2 behind it
+  int* lst_a = reinterpret_cast<int*>(smem + 4 * TILE);   // per streamed tile: where it is
+  const int SUB = a.B / kTile;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int qn = lane & 31, half = lane >> 5;
+  const int h = blockIdx.y;
+  const float c2 = a.scale * kLog2e;
+
+  // ---- what this workgroup is, and the list of streamed tiles ------------------------------------
+  int n_cand;
+  int* lst_b;                              // per streamed tile: its valid rows
+  int* flag_s;                             // dkv: query blocks that attend the key block
+  // dq: 64 query rows; dkv: one 64-key tile, persistent (slot c) or local (logical block l)
+  const int r_tile = blockIdx.x;           // dq: row tile; dkv: key tile index
+  int i_blk = 0, fixed_len = 0, kv_slot_tile = 0;
+  bool kv_local = false;
+  if constexpr (!KV) {
+    i_blk = r_tile * kTile / a.B;
+    n_cand = (a.C + 1) * SUB + a.k * SUB;
+    lst_b = lst_a + n_cand;
+    flag_s = lst_b + n_cand;
+    fixed_len = min(kTile, a.Nq - r_tile * kTile);
+  } else {
+    n_cand = a.nqb * SUB;
+    lst_b = lst_a + n_cand;
+    flag_s = lst_b + n_cand;
+    const int n_pers = (a.C + 1) * SUB;
+    kv_local = r_tile >= n_pers;
+    if (!kv_local) {
+      const int c = r_tile / SUB, sub = r_tile % SUB;
+      fixed_len = min(max(min(max(a.p_len[(size_t)h * (a.C + 1) + c], 0), a.B) - sub * kTile, 0), kTile);
+      kv_slot_tile = r_tile;
+    } else {
+      const int l = (r_tile - n_pers) / SUB, sub = (r_tile - n_pers) % SUB;
+      const int slot = a.l_map[l];
+      const bool ok = slot >= 0 && slot < a.n_loc_cap;
+      fixed_len = ok ? min(max(min(max(a.l_len[l], 0), a.B) - sub * kTile, 0), kTile) : 0;
+      kv_slot_tile = (ok ? slot : 0) * SUB + sub;
+      for (int i = tid; i < a.nqb; i += kThreads) flag_s[i] = 0;
+      __syncthreads();
+      for (int e = tid; e < a.nqb * a.k; e += kThreads)
+        if (a.sel[(size_t)h * a.nqb * a.k + e] == l) flag_s[e / a.k] = 1;
+      if (!ok) fixed_len = -1;             // a block that is nowhere: nothing to write either
+    }
+    __syncthreads();
+  }
+  if (KV && fixed_len < 0) return;
+  auto classify = [&](int i, int& where, int& rows) -> bool {
+    if (i >= n_cand) return false;
+    if constexpr (!KV) {
+      const int n_pers = (a.C + 1) * SUB;
+      if (i < n_pers) {
+        const int c = i / SUB, sub = i % SUB;
+        rows = min(max(min(max(a.p_len[(size_t)h * (a.C + 1) + c], 0), a.B) - sub * kTile, 0), kTile);
+        where = i;
+        return rows > 0;
+      }
+      const int jj = (i - n_pers) / SUB, sub = (i - n_pers) % SUB;
+      const int l = a.sel[((size_t)h * a.nqb + i_blk) * a.k + jj];
+      if (l < 0 || l >= a.n_loc) return false;
+      const int slot = a.l_map[l];
+      if (slot < 0 || slot >= a.n_loc_cap) return false;
+      rows = min(max(min(max(a.l_len[l], 0), a.B) - sub * kTile, 0), kTile);
+      where = (int)(0x80000000u | (uint32_t)(slot * SUB + sub));
+      return rows > 0;
+    } else {
+      const int ib = i / SUB;
+      if (fixed_len <= 0 || (kv_local && !flag_s[ib])) return false;
+      rows = min(kTile, a.Nq - i * kTile);            // row tile i covers tokens 64 i ..
+      where = i;
+      return rows > 0;
+    }
+  };
+  const int n_rounds = (n_cand + kThreads - 1) / kThreads;     // at most 12 (host-checked)
+  for (int r = 0; r < n_rounds; ++r) {
+    int where, rows;
+    const unsigned long long m = __ballot(classify(r * kThreads + tid, where, rows));
+    if (lane == 0) cnt_s[r * 2 + wave] = __popcll(m);
+  }
+  __syncthreads();
+  int n_tiles = 0;
+  for (int q = 0; q < 2 * n_rounds; ++q) n_tiles += cnt_s[q];
+  for (int r = 0; r < n_rounds; ++r) {
+    int where = 0, rows = 0;
+    const bool on = classify(r * kThreads + tid, where, rows);
+    const unsigned long long m = __ballot(on);
+    if (on) {
+      int pos = lanes_below(m);
+      for (int q = 0; q < r * 2 + wave; ++q) pos += cnt_s[q];
+      lst_a[pos] = where;
+      lst_b[pos] = rows;
+    }
+  }
+  __syncthreads();
+
+  // ---- fixed fragments (B operands): fixed row 32 w + lane % 32, dims 16 ks + 8 (lane / 32) .. + 8 ----
+  bf16x8 f1[KS], f2[KS];
+  float nl_fix = -INFINITY, d_fix = 0.0f;  // dq: this lane's query row
+  {
+    const int row = min(32 * wave + qn, max(fixed_len, 1) - 1);
+    const bf16_t *p1, *p2;
+    if constexpr (!KV) {
+      const int tok = r_tile * kTile + row;
+      p1 = a.Q + (size_t)h * a.q_stride_h + (size_t)tok * a.q_stride_t;
+      p2 = a.dO + (size_t)h * a.o_stride_h + (size_t)tok * a.o_stride_t;
+      const float l = a.lse[(size_t)h * a.Nq + tok];
+      if (32 * wave + qn < fixed_len && l > -INFINITY) nl_fix = -l * kLog2e;
+      d_fix = a.Dr[(size_t)h * a.Nq + tok];
+    } else {
+      const size_t base = kv_local ? ((size_t)h * a.n_loc_cap * a.B + (size_t)kv_slot_tile * kTile) * D
+                                   : ((size_t)h * (a.C + 1) * a.B + (size_t)kv_slot_tile * kTile) * D;
+      p1 = (kv_local ? a.Kl : a.Kp) + base + (size_t)row * D;
+      p2 = (kv_local ? a.Vl : a.Vp) + base + (size_t)row * D;
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      f1[ks] = *reinterpret_cast<const bf16x8*>(p1 + 16 * ks + 8 * half);
+      f2[ks] = *reinterpret_cast<const bf16x8*>(p2 + 16 * ks + 8 * half);
+    }
+  }
+  // they have arrived before the walk starts: no wait for them inside it, where one would also wait for the tiles
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(f1[ks]), "+v"(f2[ks]));
+  asm volatile("" : "+v"(nl_fix), "+v"(d_fix));
+
+  f32x16 out1[DT], out2[DT];               // dq: dQ^T; dkv: dK^T and dV^T   (32 dims x 32 fixed rows each)
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) out1[dt][v] = out2[dt][v] = 0.0f;
+
+  // ---- LDS addresses of this lane's operand reads inside ring entry 0 -------------------------------
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const uint32_t ring_s = __builtin_amdgcn_readfirstlane(smem_lds);
+  uint32_t ra[KS], ta[DT];
+  {
+    const int kb = qn * ROW + ((half ^ (qn & (CH - 1))) << 4);           // row lane % 32, logical chunk 2 ks + half
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ra[ks] = smem_lds + (uint32_t)(kb ^ (ks << 5));
+    const int s16 = lane & 15, q16 = (lane >> 4) & 1;
+    const int row0 = 4 * half + (s16 >> 2);                              // address row within 16 streamed rows
+    const int sub = 2 * q16 + ((s16 & 3) >> 1), lo = (s16 & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) ta[dt] = (uint32_t)(row0 * ROW + (((4 * dt + sub) ^ (row0 & (CH - 1))) << 4) + lo);
+  }
+
+  // ---- staging -------------------------------------------------------------------------------------
+  const int rl = lane / CH;
+  auto stage = [&](int t, int entry) {
+    const int where = __builtin_amdgcn_readfirstlane(lst_a[t]);
+    const int last = __builtin_amdgcn_readfirstlane(lst_b[t]) - 1;
+    const unsigned char *s1, *s2;
+    long st1, st2;                         // row strides in bytes
+    if constexpr (!KV) {
+      const size_t off = where < 0 ? ((size_t)h * a.n_loc_cap * a.B + (size_t)(where & 0x7FFFFFFF) * kTile) * D * 2
+                                   : ((size_t)h * (a.C + 1) * a.B + (size_t)where * kTile) * D * 2;
+      s1 = reinterpret_cast<const unsigned char*>(where < 0 ? a.Kl : a.Kp) + off;
+      s2 = reinterpret_cast<const unsigned char*>(where < 0 ? a.Vl : a.Vp) + off;
+      st1 = st2 = ROW;
+    } else {
+      s1 = reinterpret_cast<const unsigned char*>(a.Q + (size_t)h * a.q_stride_h + (size_t)where * kTile * a.q_stride_t);
+      s2 = reinterpret_cast<const unsigned char*>(a.dO + (size_t)h * a.o_stride_h + (size_t)where * kTile * a.o_stride_t);
+      st1 = a.q_stride_t * 2;
+      st2 = a.o_stride_t * 2;
+    }
+    const uint32_t dst = ring_s + (uint32_t)(entry * 2 * TILE + wave * (TILE / 2));
+#pragma unroll
+    for (int k = 0; k < NI; ++k) {
+      const int row = 32 * wave + RPI * k + rl, src_row = min(row, last);
+      const uint32_t chunk = (uint32_t)(((lane % CH) ^ (row & (CH - 1))) << 4);
+      dma16(s1, (uint32_t)(src_row * st1) + chunk, dst + k * 1024);
+      dma16(s2, (uint32_t)(src_row * st2) + chunk, dst + TILE + k * 1024);
+    }
+  };
+
+  float nl_r = 0.0f, d_r = 0.0f;           // dkv: the coming tile's row scalars, one row per thread of wave 0
+  auto fetch_rows = [&](int t) {
+    if constexpr (KV) {
+      if (tid < kTile) {
+        const int tok = lst_a[t] * kTile + tid, tok_c = min(tok, a.Nq - 1);
+        const float l = a.lse[(size_t)h * a.Nq + tok_c];
+        nl_r = tok < a.Nq && l > -INFINITY ? -l * kLog2e : -INFINITY;
+        d_r = a.Dr[(size_t)h * a.Nq + tok_c];
+      }
+    }
+  };
+
+  if (n_tiles > 0) {
+    stage(0, 0);
+    fetch_rows(0);
+  }
+  for (int t = 0; t < n_tiles; ++t) {
+    const int e = t & 1;
+    if constexpr (KV) {
+      if (tid < kTile) {
+        nl_s[e][tid] = nl_r;
+        d_s[e][tid] = d_r;
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // this wave's rows of tile t are in
+    __syncthreads();                                        // everybody's are, and tile t-1 has been used by all
+    if (t + 1 < n_tiles) {
+      stage(t + 1, e ^ 1);
+      fetch_rows(t + 1);
+    }
+    const int rows = __builtin_amdgcn_readfirstlane(lst_b[t]);
+    const uint32_t off1 = (uint32_t)(e * 2 * TILE), off2 = off1 + TILE;
+#pragma unroll
+    for (int mg = 0; mg < 2; ++mg) {
+      f32x16 a1, a2;
+      {
+        bf16x8 x1[KS], x2[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          x1[ks] = lds_read_row(ra[ks] + off1 + mg * 32 * ROW);
+          x2[ks] = lds_read_row(ra[ks] + off2 + mg * 32 * ROW);
+        }
+        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[ks], f1[ks], ks == 0 ? zero : a1, 0, 0, 0);
+          a2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[ks], ks == 0 ? zero : a2, 0, 0, 0);
+        }
+      }
+      // accumulator element v: streamed row 32 mg + 8 (v / 4) + 4 half + v % 4, fixed row 32 w + lane % 32
+      u32x4 eP[2], eZ[2];
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        float nlv[4], dv[4];
+        if constexpr (KV) {
+          const float4 n4 = *reinterpret_cast<const float4*>(&nl_s[e][32 * mg + 8 * v4 + 4 * half]);
+          const float4 d4 = *reinterpret_cast<const float4*>(&d_s[e][32 * mg + 8 * v4 + 4 * half]);
+          nlv[0] = n4.x; nlv[1] = n4.y; nlv[2] = n4.z; nlv[3] = n4.w;
+          dv[0] = d4.x; dv[1] = d4.y; dv[2] = d4.z; dv[3] = d4.w;
+        }
+        float pz[4], zz[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const int v = 4 * v4 + x;
+          const int srow = 32 * mg + 8 * v4 + 4 * half + x;              // streamed row of this element
+          const float nl = KV ? nlv[x] : nl_fix, dd = KV ? dv[x] : d_fix;
+          // what does not exist takes no part: streamed rows past the tile's length, fixed rows past theirs
+          const bool live = srow < rows && 32 * wave + qn < fixed_len;
+          const float p = live ? __builtin_amdgcn_exp2f(__builtin_fmaf(a1[v], c2, nl)) : 0.0f;
+          pz[x] = p;
+          zz[x] = live ? p * (a2[v] - dd) : 0.0f;
+        }
+        eP[v4 / 2][(v4 % 2) * 2 + 0] = pack2(pz[0], pz[1]);
+        eP[v4 / 2][(v4 % 2) * 2 + 1] = pack2(pz[2], pz[3]);
+        eZ[v4 / 2][(v4 % 2) * 2 + 0] = pack2(zz[0], zz[1]);
+        eZ[v4 / 2][(v4 % 2) * 2 + 1] = pack2(zz[2], zz[3]);
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const uint32_t radd = smem_lds + (uint32_t)((32 * mg + 16 * j) * ROW);
+          const bf16x8 t1 = lds_read_tr<ROW, HI_XOR>(radd + off1, ta[dt]);
+          out1[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, as_bf16x8(eZ[j]), out1[dt], 0, 0, 0);
+          if constexpr (KV) {
+            const bf16x8 t2 = lds_read_tr<ROW, HI_XOR>(radd + off2, ta[dt]);
+            out2[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, as_bf16x8(eP[j]), out2[dt], 0, 0, 0);
+          }
+        }
+    }
+  }
+
+  // ---- outputs: element v of tile dt is dim 32 dt + 8 (v / 4) + 4 half + v % 4 of fixed row 32 w + lane % 32 ----
+  const int frow = 32 * wave + qn;
+  if constexpr (!KV) {
+    if (frow < fixed_len) {
+      float* o = a.dQ + ((size_t)h * a.Nq + (size_t)r_tile * kTile + frow) * D;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4)
+          *reinterpret_cast<float4*>(o + 32 * dt + 8 * v4 + 4 * half) =
+              make_float4(out1[dt][4 * v4] * a.scale, out1[dt][4 * v4 + 1] * a.scale, out1[dt][4 * v4 + 2] * a.scale,
+                          out1[dt][4 * v4 + 3] * a.scale);
+    }
+  } else {
+    // every row of the tile's slot is written: zeros past the valid length and for a block nobody attends
+    const size_t base = kv_local ? ((size_t)h * a.n_loc_cap * a.B + (size_t)kv_slot_tile * kTile) * D
+                                 : ((size_t)h * (a.C + 1) * a.B + (size_t)kv_slot_tile * kTile) * D;
+    float* ok_ = (kv_local ? a.dKl : a.dKp) + base + (size_t)frow * D;
+    float* ov_ = (kv_local ? a.dVl : a.dVp) + base + (size_t)frow * D;
+    const float sc = frow < fixed_len ? a.scale : 0.0f, one = frow < fixed_len ? 1.0f : 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        *reinterpret_cast<float4*>(ok_ + 32 * dt + 8 * v4 + 4 * half) =
+            make_float4(out1[dt][4 * v4] * sc, out1[dt][4 * v4 + 1] * sc, out1[dt][4 * v4 + 2] * sc, out1[dt][4 * v4 + 3] * sc);
+        *reinterpret_cast<float4*>(ov_ + 32 * dt + 8 * v4 + 4 * half) =
+            make_float4(out2[dt][4 * v4] * one, out2[dt][4 * v4 + 1] * one, out2[dt][4 * v4 + 2] * one, out2[dt][4 * v4 + 3] * one);
+      }
+  }
+}
+
+template <int D, bool KV>
+hipError_t launch_bwd_t(const BwdArgs& a, dim3 grid, size_t lds, hipStream_t stream) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kernel<D, KV>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((bwd_kernel<D, KV>), grid, dim3(kThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t bwd_workspace_bytes(const pbsa_params& p) { return (((size_t)p.H * p.Nq * 4) + 255) & ~(size_t)255; }
+
+hipError_t launch_attention_bwd(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
+                                const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
+                                const int32_t* l_map, const int32_t* sel, const bf16_t* O, const bf16_t* dO,
+                                const float* lse, float* dQ, float* dKp, float* dVp, float* dKl, float* dVl, float* Dr,
+                                hipStream_t stream) {
+  BwdArgs a{p.H, p.Nq, p.nqb, p.n_loc, p.n_loc_cap, p.C, p.k, p.B, p.scale, p.q_stride_h, p.q_stride_t, p.o_stride_h,
+            p.o_stride_t, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, dO, lse, Dr, dQ, dKp, dVp, dKl, dVl};
+  const int sub = p.B / kTile;
+  const long n_lanes = (long)p.H * p.Nq * (p.d / 8);
+  const dim3 pgrid((unsigned)((n_lanes + 255) / 256));
+  if (p.d == 128) hipLaunchKernelGGL(bwd_prep_kernel<128>, pgrid, dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(bwd_prep_kernel<64>, pgrid, dim3(256), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t ring = (size_t)4 * kTile * p.d * 2;
+  {
+    const size_t n_cand = (size_t)(p.C + 1 + p.k) * sub;
+    const dim3 grid((p.Nq + kTile - 1) / kTile, p.H);
+    const size_t lds = ring + n_cand * 8 + 16;
+    e = p.d == 128 ? launch_bwd_t<128, false>(a, grid, lds, stream) : launch_bwd_t<64, false>(a, grid, lds, stream);
+    if (e != hipSuccess) return e;
+  }
+  {
+    const size_t n_cand = (size_t)p.nqb * sub;
+    const dim3 grid((p.C + 1 + p.n_loc) * sub, p.H);
+    const size_t lds = ring + n_cand * 8 + (size_t)p.nqb * 4 + 16;
+    e = p.d == 128 ? launch_bwd_t<128, true>(a, grid, lds, stream) : launch_bwd_t<64, true>(a, grid, lds, stream);
+  }
+  return e;
+}
+
+}  // namespace pbsa

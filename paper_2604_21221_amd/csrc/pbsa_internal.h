@@ -63,6 +63,14 @@ hipError_t launch_update_fine(const pbsa_params& p, const float* Mt, const float
                               const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
                               hipStream_t stream);
 
+// backward of the fine stage; Dr: [H][Nq] floats of scratch (bwd_workspace_bytes)
+size_t bwd_workspace_bytes(const pbsa_params& p);
+hipError_t launch_attention_bwd(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
+                                const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
+                                const int32_t* l_map, const int32_t* sel, const bf16_t* O, const bf16_t* dO,
+                                const float* lse, float* dQ, float* dKp, float* dVp, float* dKl, float* dVl, float* Dr,
+                                hipStream_t stream);
+
 // blockify: to_blocks = true moves token-major -> block-major, false the other way
 struct LayoutTensors {
   int n;

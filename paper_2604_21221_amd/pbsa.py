@@ -17,7 +17,8 @@ PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 512, 64, 192, 512
 
 EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
            "pbsa_memory_update", "pbsa_attention_mass", "pbsa_mass_workspace_bytes", "pbsa_attention_fwd_mass",
-           "pbsa_memory_update_fine", "pbsa_blockify", "pbsa_unblockify", "pbsa_strerror", "pbsa_version")
+           "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes", "pbsa_attention_bwd", "pbsa_blockify",
+           "pbsa_unblockify", "pbsa_strerror", "pbsa_version")
 
 
 class pbsa_params(ctypes.Structure):
@@ -80,12 +81,15 @@ def lib() -> ctypes.CDLL:
         L.pbsa_mass_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.pbsa_attention_fwd_mass.argtypes = [pp] + [vp] * 13 + [sz, vp]
         L.pbsa_memory_update_fine.argtypes = [pp] + [vp] * 17 + [sz, vp]
+        L.pbsa_bwd_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+        L.pbsa_attention_bwd.argtypes = [pp] + [vp] * 18 + [sz, vp]
         pg = ctypes.POINTER(pbsa_grid)
         L.pbsa_blockify.argtypes = [pg, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_int64), vp]
         L.pbsa_unblockify.argtypes = [pg, vp, ctypes.c_int64, vp, vp]
         for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
                      "pbsa_memory_update", "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
-                     "pbsa_attention_fwd_mass", "pbsa_memory_update_fine", "pbsa_blockify", "pbsa_unblockify"):
+                     "pbsa_attention_fwd_mass", "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes",
+                     "pbsa_attention_bwd", "pbsa_blockify", "pbsa_unblockify"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -190,6 +194,19 @@ def pbsa_memory_update_fine(p, Mt, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt
                                          _ptr(p_len), _ptr(p_id), _ptr(S_sum), _ptr(S_cnt), _ptr(Kl), _ptr(Vl),
                                          _ptr(l_len), _ptr(l_map), _ptr(l_id), _ptr(scores), _ptr(slot_src), w, wb,
                                          _stream(stream)))
+
+
+def pbsa_bwd_workspace_bytes(p: pbsa_params) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().pbsa_bwd_workspace_bytes(ctypes.byref(p), ctypes.byref(out)))
+    return out.value
+
+
+def pbsa_attention_bwd(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, dO, lse, dQ, dKp, dVp, dKl, dVl, ws, stream=None):
+    w, wb = _ws(ws)
+    _check(lib().pbsa_attention_bwd(ctypes.byref(p), _ptr(Q), _ptr(Kp), _ptr(Vp), _ptr(p_len), _ptr(Kl), _ptr(Vl),
+                                    _ptr(l_len), _ptr(l_map), _ptr(sel), _ptr(O), _ptr(dO), _ptr(lse), _ptr(dQ),
+                                    _ptr(dKp), _ptr(dVp), _ptr(dKl), _ptr(dVl), w, wb, _stream(stream)))
 
 
 def pbsa_blockify(g, X, Xblk, blk_stride_h, stream=None):

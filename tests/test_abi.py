@@ -181,6 +181,24 @@ def test_fine_mass_argument_checks(L):
         assert e.value.code == code, (call.__name__, kw)
 
 
+def test_backward_argument_checks(L):
+    p = good()
+    need = pbsa.pbsa_bwd_workspace_bytes(p)
+    assert need >= 2 * 200 * 4 and need % 256 == 0
+
+    def bwd(p=p, dO=P, lse=P, dQ=P, dVl=P, ws=(0x10000, 1 << 30)):
+        pbsa.pbsa_attention_bwd(p, P, P, P, P, P, P, P, P, P, P, dO, lse, dQ, P, P, P, dVl, ws, stream=0)
+
+    for kw, code in [(dict(dO=None), pbsa.PBSA_EINVAL), (dict(lse=None), pbsa.PBSA_EINVAL), (dict(dVl=None), pbsa.PBSA_EINVAL),
+                     (dict(dQ=P + 4), pbsa.PBSA_EALIGN), (dict(dO=P + 2), pbsa.PBSA_EALIGN), (dict(ws=None), pbsa.PBSA_EWS),
+                     (dict(ws=(0x10000, need - 1)), pbsa.PBSA_EWS), (dict(ws=(0x10040, need)), pbsa.PBSA_EALIGN),
+                     (dict(p=good(d=96)), pbsa.PBSA_ESHAPE), (dict(p=good(causal=2)), pbsa.PBSA_EINVAL),
+                     (dict(p=good(q_strides=(1 << 30, 1 << 24))), pbsa.PBSA_ESHAPE)]:
+        with pytest.raises(pbsa.PbsaError) as e:
+            bwd(**kw)
+        assert e.value.code == code, kw
+
+
 def test_binding_refuses_host_tensors(L):
     import torch
     with pytest.raises(TypeError):
