@@ -178,6 +178,48 @@ def bench_blockify(dev, reps=50):
             "data": "synthetic", "dtype": "bf16", "n_gpus": 1, "rows": rows}
 
 
+def bench_backward(w, c, Q_at, g_next, n_ring, dev, K, W, settle):
+    """pbsa_attention_bwd on the steady-state cache of workload w: one selection + forward, then the backward
+    call repeated on the same inputs (it changes nothing it reads)."""
+    import numpy as np
+    import torch
+    from paper_2604_21221_amd import synth, workloads
+    c.adopt_chunk(g_next)
+    Qd = Q_at[(c.n_appended - 1) % n_ring]
+    c.select(Qd)
+    lse = torch.empty(w.H, w.Nq, dtype=torch.float32, device=dev)
+    O = c.attention(Qd, lse=lse)
+    dO = workloads.bf16_tensor(synth.to_bf16_bits(synth.normals(synth.stream_key(w.seed, "misc", 99), w.H * w.Nq * w.d)
+                                                  .reshape(w.H, w.Nq, w.d)), dev)
+    grads = c.attention_bwd(Qd, O, dO, lse)
+    stream = torch.cuda.current_stream()
+    for _ in range(settle // 3 + W):
+        c.attention_bwd(Qd, O, dO, lse, grads)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(stream)
+        c.attention_bwd(Qd, O, dO, lse, grads)
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / K
+    us = sum(a.elapsed_time(b) for a, b in ev) / K * 1e3
+    rows = torch.from_numpy(synth.block_lens(w)).to(dev)
+    l_len = torch.from_numpy(np.tile(synth.block_lens(w), n_ring)).to(dev)
+    fwd = executed_flops(c.sel, c.p_len, l_len, rows, w.d)
+    flops = 2.5 * fwd          # five products of the size of the forward's two: dV, dP, dQ, dK and the recomputed scores
+    out_bytes = 4 * (w.H * w.Nq * w.d + 2 * w.H * (w.C + 1 + n_ring * w.nqb) * w.B * w.d)
+    return {"metric": "pbsa_attention_bwd: effective TFLOP/s on 2.5 x the executed forward FLOPs", "value": round(flops / us / 1e6, 3),
+            "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(us / 1e3, 5),
+            "wall_ms_per_call": round(wall * 1e3, 5), "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"{w.name} steady state, backward of one attention call: H={w.H} d={w.d} B={w.B} "
+                                   f"Nq={w.Nq} C={w.C}+summary k={w.k}", "executed_gflop": round(flops / 1e9, 3),
+                       "kernels": "bwd_prep_kernel, bwd_kernel<dq>, bwd_kernel<dkv>", "gradient_bytes_written": out_bytes},
+            "roofline": {"bound": "mfma", "achieved": round(flops / us / 1e6, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(flops / us / 1e6 / PEAK_BF16_TFLOPS, 5), "traffic": None}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,6 +243,9 @@ def main():
                     help="the step with the persistent set ranked by the attention actually paid: after the attention "
                          "call pbsa_attention_mass sums the probabilities per key block and pbsa_memory_update_fine "
                          "ranks by them (select + attention + mass + update per step)")
+    ap.add_argument("--backward", action="store_true",
+                    help="instead of the step benchmark: pbsa_attention_bwd (dQ, dK, dV) on the workload's steady-state "
+                         "cache, after one forward call that supplies O and lse")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run three 1 GiB device copies and exit: the known-size kernel that the HBM byte "
                          "counters are scaled by")
@@ -250,6 +295,9 @@ def main():
     g_next = g0 + n_setup
     torch.cuda.synchronize()
 
+    if args.backward:
+        print(json.dumps(bench_backward(w, caches[0], Q_ats[0], g_next, n_ring, dev, K, W, args.settle_steps)))
+        return
     O = torch.empty(w.H, w.Nq, w.d, dtype=torch.bfloat16, device=dev)
     K2 = min(K, 20)            # extra steps after the timed region: per-call split of select and update
     n_total = W + K + K2

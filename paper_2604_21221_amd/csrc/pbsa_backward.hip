@@ -19,7 +19,7 @@
 //   second products are transposing LDS reads of the streamed tiles with the same enumeration:
 //          dq:  dQ^T += K^T dZ^T          dkv: dK^T += Q^T dZ,  dV^T += dO^T P
 // A workgroup is two waves; wave w owns fixed rows 32 w .. 32 w + 31.  Tiles go from global memory straight to
-// LDS (global_load_lds) into a ring of two, the next tile in flight while one is used; the 16-byte chunks of
+// LDS (global_load_lds), half a tile at a time into a ring of four; the 16-byte chunks of
 // a row are permuted by the row number so that the row-wise operand reads are free of bank conflicts (the
 // transposing reads then see two-way conflicts).  Rows past a tile's valid length are never loaded: their
 // lanes fetch the last valid row, and the elementwise stage zeroes what belongs to them.
@@ -70,6 +70,14 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
 // 16 bytes at lds_off + 16 i.  Completion is tracked by the issuing wave's vmcnt.
 __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_off), "v"(lane_off), "s"(base)
+               : "memory");
+}
+
+// the same with 4 bytes per lane: LDS bytes [lds_off, lds_off + 256)
+__device__ __forceinline__ void dma4(const void* base, uint32_t lane_off, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
                :
                : "s"(lds_off), "v"(lane_off), "s"(base)
                : "memory");
@@ -131,7 +139,7 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   constexpr int HI_XOR = CH == 16 ? 128 : 0;        // row + 8 flips bit 3 of the chunk permutation when it has 4 bits
   extern __shared__ __align__(1024) unsigned char smem[];
   __shared__ int cnt_s[2 * 12];
-  __shared__ __align__(16) float nl_s[2][kTile], d_s[2][kTile];   // dkv: per ring entry, -lse log2 e and D of the tile's rows
+  __shared__ __align__(256) float rows_f[4 * 128];  // dkv: per ring entry, lse (64 floats, 32 used) then D of the half tile's rows
   // ring: entry e holds T1 at e * 2 TILE and T2 behind it
   int* lst_a = reinterpret_cast<int*>(smem + 4 * TILE);   // per streamed tile: where it is
   const int SUB = a.B / kTile;
@@ -267,6 +275,7 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   // ---- LDS addresses of this lane's operand reads inside ring entry 0 -------------------------------
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
   const uint32_t ring_s = __builtin_amdgcn_readfirstlane(smem_lds);
+  const uint32_t rows_s = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)rows_f);
   uint32_t ra[KS], ta[DT];
   {
     const int kb = qn * ROW + ((half ^ (qn & (CH - 1))) << 4);           // row lane % 32, logical chunk 2 ks + half
@@ -280,125 +289,170 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   }
 
   // ---- staging -------------------------------------------------------------------------------------
+  // The unit that travels is a half tile: 32 streamed rows of T1 and of T2 (and, dkv, the lse and D of those
+  // rows), one ring entry of four.  Wave w brings rows 16 w .. 16 w + 15 of the half.  Every wave issues the same
+  // number of loads per half tile, so that one count serves the wait; past the end of the list the last half tile
+  // is fetched again into an entry whose contents are never used.
+  constexpr int HALF = TILE / 2, RING = 4, NH = NI / 2;    // NH: load instructions per wave, tensor and half tile
+  constexpr int PER = 2 * NH + (KV ? 2 : 0);               // loads per wave and half tile
   const int rl = lane / CH;
-  auto stage = [&](int t, int entry) {
+  const int n_half = 2 * n_tiles;
+  long st1, st2;                           // row strides of the streamed tensors in bytes
+  const unsigned char *b1l, *b2l, *b1p, *b2p;
+  if constexpr (!KV) {
+    st1 = st2 = ROW;
+    const size_t hl = (size_t)h * a.n_loc_cap * a.B * D * 2, hp = (size_t)h * (a.C + 1) * a.B * D * 2;
+    b1l = reinterpret_cast<const unsigned char*>(a.Kl) + hl;
+    b2l = reinterpret_cast<const unsigned char*>(a.Vl) + hl;
+    b1p = reinterpret_cast<const unsigned char*>(a.Kp) + hp;
+    b2p = reinterpret_cast<const unsigned char*>(a.Vp) + hp;
+  } else {
+    st1 = a.q_stride_t * 2;
+    st2 = a.o_stride_t * 2;
+    b1l = b1p = reinterpret_cast<const unsigned char*>(a.Q + (size_t)h * a.q_stride_h);
+    b2l = b2p = reinterpret_cast<const unsigned char*>(a.dO + (size_t)h * a.o_stride_h);
+  }
+  // per-lane source offsets of the wave's instructions within a half tile whose 32 rows all exist
+  uint32_t so1[NH], so2[NH];
+#pragma unroll
+  for (int k = 0; k < NH; ++k) {
+    const int r = 16 * wave + RPI * k + rl;
+    const uint32_t chunk = (uint32_t)(((lane % CH) ^ (r & (CH - 1))) << 4);
+    so1[k] = (uint32_t)(r * st1) + chunk;
+    so2[k] = (uint32_t)(r * st2) + chunk;
+  }
+  auto stage = [&](int u, int entry) {
+    const int t = u >> 1, mg = u & 1;
     const int where = __builtin_amdgcn_readfirstlane(lst_a[t]);
     const int last = __builtin_amdgcn_readfirstlane(lst_b[t]) - 1;
-    const unsigned char *s1, *s2;
-    long st1, st2;                         // row strides in bytes
-    if constexpr (!KV) {
-      const size_t off = where < 0 ? ((size_t)h * a.n_loc_cap * a.B + (size_t)(where & 0x7FFFFFFF) * kTile) * D * 2
-                                   : ((size_t)h * (a.C + 1) * a.B + (size_t)where * kTile) * D * 2;
-      s1 = reinterpret_cast<const unsigned char*>(where < 0 ? a.Kl : a.Kp) + off;
-      s2 = reinterpret_cast<const unsigned char*>(where < 0 ? a.Vl : a.Vp) + off;
-      st1 = st2 = ROW;
-    } else {
-      s1 = reinterpret_cast<const unsigned char*>(a.Q + (size_t)h * a.q_stride_h + (size_t)where * kTile * a.q_stride_t);
-      s2 = reinterpret_cast<const unsigned char*>(a.dO + (size_t)h * a.o_stride_h + (size_t)where * kTile * a.o_stride_t);
-      st1 = a.q_stride_t * 2;
-      st2 = a.o_stride_t * 2;
-    }
-    const uint32_t dst = ring_s + (uint32_t)(entry * 2 * TILE + wave * (TILE / 2));
+    const size_t tile = (size_t)(where & 0x7FFFFFFF) * kTile;          // first row of the tile in its tensor
+    const unsigned char* s1 = (where < 0 ? b1l : b1p) + tile * st1;
+    const unsigned char* s2 = (where < 0 ? b2l : b2p) + tile * st2;
+    const uint32_t dst = ring_s + (uint32_t)(entry * TILE + wave * (HALF / 2));
+    if (last >= 32 * mg + 31) {
+      s1 += (size_t)(32 * mg) * st1;
+      s2 += (size_t)(32 * mg) * st2;
 #pragma unroll
-    for (int k = 0; k < NI; ++k) {
-      const int row = 32 * wave + RPI * k + rl, src_row = min(row, last);
-      const uint32_t chunk = (uint32_t)(((lane % CH) ^ (row & (CH - 1))) << 4);
-      dma16(s1, (uint32_t)(src_row * st1) + chunk, dst + k * 1024);
-      dma16(s2, (uint32_t)(src_row * st2) + chunk, dst + TILE + k * 1024);
-    }
-  };
-
-  float nl_r = 0.0f, d_r = 0.0f;           // dkv: the coming tile's row scalars, one row per thread of wave 0
-  auto fetch_rows = [&](int t) {
-    if constexpr (KV) {
-      if (tid < kTile) {
-        const int tok = lst_a[t] * kTile + tid, tok_c = min(tok, a.Nq - 1);
-        const float l = a.lse[(size_t)h * a.Nq + tok_c];
-        nl_r = tok < a.Nq && l > -INFINITY ? -l * kLog2e : -INFINITY;
-        d_r = a.Dr[(size_t)h * a.Nq + tok_c];
+      for (int k = 0; k < NH; ++k) {
+        dma16(s1, so1[k], dst + k * 1024);
+        dma16(s2, so2[k], dst + HALF + k * 1024);
+      }
+    } else {                               // rows past the last one that exists are not touched: that row again
+#pragma unroll
+      for (int k = 0; k < NH; ++k) {
+        const int r = 16 * wave + RPI * k + rl, src_row = min(32 * mg + r, last);
+        const uint32_t chunk = (uint32_t)(((lane % CH) ^ (r & (CH - 1))) << 4);
+        dma16(s1, (uint32_t)(src_row * st1) + chunk, dst + k * 1024);
+        dma16(s2, (uint32_t)(src_row * st2) + chunk, dst + HALF + k * 1024);
       }
     }
+    if constexpr (KV) {
+      // lse and D of the half's 32 rows, as they are (lanes 32..63 repeat lanes 0..31; both waves bring the same)
+      const int tok = min(where * kTile + min(32 * mg + qn, last), a.Nq - 1);
+      dma4(a.lse + (size_t)h * a.Nq, (uint32_t)tok * 4u, rows_s + (uint32_t)(entry * 512));
+      dma4(a.Dr + (size_t)h * a.Nq, (uint32_t)tok * 4u, rows_s + (uint32_t)(entry * 512 + 256));
+    }
   };
 
-  if (n_tiles > 0) {
-    stage(0, 0);
-    fetch_rows(0);
+  // ---- the walk: a software pipeline over half tiles ---------------------------------------------------
+  // In turn u the wave runs the first products of half tile u+1 (A1, A2: 2 KS MFMAs) with the elementwise stage
+  // of half tile u cut into as many slices, one behind each MFMA, so that the vector unit works while the
+  // matrix pipe does; then the second products of half tile u.  Half tile u+1 must have landed when turn u
+  // starts, u+2 is on its way, u+3 is asked for at the start of the turn (into the entry u-1 has left).
+  constexpr int NS = 2 * KS, EPS = 16 / NS;                // slices, accumulator elements per slice
+  static_assert(EPS * NS == 16 && (EPS == 1 || EPS == 2), "slices cover the 16 elements, pairs stay together");
+  const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  f32x16 c1 = zero, c2a = zero;            // A1, A2 of the half tile whose elementwise stage comes next
+  if (n_half > 0) {
+    for (int j = 0; j < RING - 1; ++j) stage(min(j, n_half - 1), j);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((RING - 2) * PER) : "memory");
+    __syncthreads();
+    bf16x8 x1[KS], x2[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      x1[ks] = lds_read_row(ra[ks]);
+      x2[ks] = lds_read_row(ra[ks] + HALF);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[ks], f1[ks], c1, 0, 0, 0);
+      c2a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[ks], c2a, 0, 0, 0);
+    }
   }
-  for (int t = 0; t < n_tiles; ++t) {
-    const int e = t & 1;
-    if constexpr (KV) {
-      if (tid < kTile) {
-        nl_s[e][tid] = nl_r;
-        d_s[e][tid] = d_r;
-      }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // this wave's rows of tile t are in
-    __syncthreads();                                        // everybody's are, and tile t-1 has been used by all
-    if (t + 1 < n_tiles) {
-      stage(t + 1, e ^ 1);
-      fetch_rows(t + 1);
-    }
+  for (int u = 0; u < n_half; ++u) {
+    const int e = u % RING, en = (u + 1) % RING, t = u >> 1, mg = u & 1;
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((RING - 3) * PER) : "memory");   // this wave's rows of half tile u+1 are in
+    __syncthreads();                                        // everybody's are, and half tile u-1 has been used by all
+    stage(min(u + RING - 1, n_half - 1), (u + RING - 1) % RING);
     const int rows = __builtin_amdgcn_readfirstlane(lst_b[t]);
-    const uint32_t off1 = (uint32_t)(e * 2 * TILE), off2 = off1 + TILE;
+    const uint32_t off1 = (uint32_t)(e * TILE), off2 = off1 + HALF, offn = (uint32_t)(en * TILE);
+    // operand reads: the next half tile's rows for its first products, this one's transposed for its second ones
+    bf16x8 x1[KS], x2[KS];
 #pragma unroll
-    for (int mg = 0; mg < 2; ++mg) {
-      f32x16 a1, a2;
-      {
-        bf16x8 x1[KS], x2[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          x1[ks] = lds_read_row(ra[ks] + off1 + mg * 32 * ROW);
-          x2[ks] = lds_read_row(ra[ks] + off2 + mg * 32 * ROW);
-        }
-        const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[ks], f1[ks], ks == 0 ? zero : a1, 0, 0, 0);
-          a2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[ks], ks == 0 ? zero : a2, 0, 0, 0);
-        }
-      }
-      // accumulator element v: streamed row 32 mg + 8 (v / 4) + 4 half + v % 4, fixed row 32 w + lane % 32
-      u32x4 eP[2], eZ[2];
+    for (int ks = 0; ks < KS; ++ks) {
+      x1[ks] = lds_read_row(ra[ks] + offn);
+      x2[ks] = lds_read_row(ra[ks] + offn + HALF);
+    }
+    float nlv[16], dv[16];
+    if constexpr (KV) {
 #pragma unroll
       for (int v4 = 0; v4 < 4; ++v4) {
-        float nlv[4], dv[4];
-        if constexpr (KV) {
-          const float4 n4 = *reinterpret_cast<const float4*>(&nl_s[e][32 * mg + 8 * v4 + 4 * half]);
-          const float4 d4 = *reinterpret_cast<const float4*>(&d_s[e][32 * mg + 8 * v4 + 4 * half]);
-          nlv[0] = n4.x; nlv[1] = n4.y; nlv[2] = n4.z; nlv[3] = n4.w;
-          dv[0] = d4.x; dv[1] = d4.y; dv[2] = d4.z; dv[3] = d4.w;
-        }
-        float pz[4], zz[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          const int v = 4 * v4 + x;
-          const int srow = 32 * mg + 8 * v4 + 4 * half + x;              // streamed row of this element
-          const float nl = KV ? nlv[x] : nl_fix, dd = KV ? dv[x] : d_fix;
-          // what does not exist takes no part: streamed rows past the tile's length, fixed rows past theirs
-          const bool live = srow < rows && 32 * wave + qn < fixed_len;
-          const float p = live ? __builtin_amdgcn_exp2f(__builtin_fmaf(a1[v], c2, nl)) : 0.0f;
-          pz[x] = p;
-          zz[x] = live ? p * (a2[v] - dd) : 0.0f;
-        }
-        eP[v4 / 2][(v4 % 2) * 2 + 0] = pack2(pz[0], pz[1]);
-        eP[v4 / 2][(v4 % 2) * 2 + 1] = pack2(pz[2], pz[3]);
-        eZ[v4 / 2][(v4 % 2) * 2 + 0] = pack2(zz[0], zz[1]);
-        eZ[v4 / 2][(v4 % 2) * 2 + 1] = pack2(zz[2], zz[3]);
+        const float4 n4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 8 * v4 + 4 * half]);
+        const float4 d4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 64 + 8 * v4 + 4 * half]);
+        nlv[4 * v4] = n4.x; nlv[4 * v4 + 1] = n4.y; nlv[4 * v4 + 2] = n4.z; nlv[4 * v4 + 3] = n4.w;
+        dv[4 * v4] = d4.x; dv[4 * v4 + 1] = d4.y; dv[4 * v4 + 2] = d4.z; dv[4 * v4 + 3] = d4.w;
       }
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const uint32_t radd = smem_lds + (uint32_t)((32 * mg + 16 * j) * ROW);
-          const bf16x8 t1 = lds_read_tr<ROW, HI_XOR>(radd + off1, ta[dt]);
-          out1[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, as_bf16x8(eZ[j]), out1[dt], 0, 0, 0);
-          if constexpr (KV) {
-            const bf16x8 t2 = lds_read_tr<ROW, HI_XOR>(radd + off2, ta[dt]);
-            out2[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, as_bf16x8(eP[j]), out2[dt], 0, 0, 0);
-          }
-        }
     }
+    bf16x8 t1[2][DT], t2[KV ? 2 : 1][KV ? DT : 1];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const uint32_t radd = smem_lds + (uint32_t)(16 * j * ROW);
+        t1[j][dt] = lds_read_tr<ROW, HI_XOR>(radd + off1, ta[dt]);
+        if constexpr (KV) t2[j][dt] = lds_read_tr<ROW, HI_XOR>(radd + off2, ta[dt]);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    // accumulator element v: streamed row 32 mg + 8 (v / 4) + 4 half + v % 4, fixed row 32 w + lane % 32.  Streamed
+    // rows past the tile's length hold a copy of its last row and take no part; a fixed row that does not exist
+    // only fills its own column of the outputs, which is not written.
+    const int lim = rows - 32 * mg - 4 * half;
+    f32x16 n1, n2;
+    u32x4 eP[2], eZ[2];
+    float pz[16], zz[16];
+#pragma unroll
+    for (int sl = 0; sl < NS; ++sl) {
+      const int ks = sl / 2;
+      if (sl % 2 == 0) n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[ks], f1[ks], ks == 0 ? zero : n1, 0, 0, 0);
+      else n2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[ks], ks == 0 ? zero : n2, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);   // the MFMA first, then the slice
+#pragma unroll
+      for (int q = 0; q < EPS; ++q) {
+        const int v = sl * EPS + q;
+        const float nl = KV ? -nlv[v] * kLog2e : nl_fix, dd = KV ? dv[v] : d_fix;
+        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c1[v], c2, nl));
+        pz[v] = 8 * (v / 4) + (v % 4) < lim ? pe : 0.0f;
+        zz[v] = pz[v] * (c2a[v] - dd);
+        if (v % 2 == 1) {
+          if constexpr (KV) eP[v / 8][(v % 8) / 2] = pack2(pz[v - 1], pz[v]);
+          eZ[v / 8][(v % 8) / 2] = pack2(zz[v - 1], zz[v]);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        out1[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1[j][dt], as_bf16x8(eZ[j]), out1[dt], 0, 0, 0);
+        if constexpr (KV) out2[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2[j][dt], as_bf16x8(eP[j]), out2[dt], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    c1 = n1;
+    c2a = n2;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the trailing loads land before the workgroup goes
 
   // ---- outputs: element v of tile dt is dim 32 dt + 8 (v / 4) + 4 half + v % 4 of fixed row 32 w + lane % 32 ----
   const int frow = 32 * wave + qn;
