@@ -20,8 +20,8 @@
 //          dq:  dQ^T += K^T dZ^T          dkv: dK^T += Q^T dZ,  dV^T += dO^T P
 // A workgroup is two waves; wave w owns fixed rows 32 w .. 32 w + 31.  Tiles go from global memory straight to
 // LDS (global_load_lds), half a tile at a time into a ring of four; the 16-byte chunks of
-// a row are permuted by the row number so that the row-wise operand reads are free of bank conflicts (the
-// transposing reads then see two-way conflicts).  Rows past a tile's valid length are never loaded: their
+// a row are permuted by the row number so that both the row-wise and the transposing operand reads are free of
+// bank conflicts.  Rows past a tile's valid length are never loaded: their
 // lanes fetch the last valid row, and the elementwise stage zeroes what belongs to them.
 #include "pbsa_internal.h"
 
@@ -83,6 +83,16 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t lane_off, uint32
                : "memory");
 }
 
+// Where the 16-byte chunks of a tile row sit in LDS: logical chunk c of row r at chunk c ^ swz(r).  The row-wise
+// operand reads (16 consecutive rows, one logical chunk) need swz distinct over 16 consecutive rows (8 when a row
+// has 8 chunks); the transposing reads (4 consecutive rows from a multiple of 4, two adjacent chunks c, c + 1 with
+// c even, each) need swz(r) >> 1 distinct over those rows.  The row number rotated left by one bit does both.
+template <int CH>
+__device__ __forceinline__ int swz(int r) {
+  if constexpr (CH == 16) return ((r & 7) << 1) | ((r >> 3) & 1);
+  else return ((r & 3) << 1) | ((r >> 2) & 1);
+}
+
 typedef __attribute__((address_space(3))) const bf16x8* lds_b128_t;
 typedef __attribute__((address_space(3))) bf16x4* lds_tr_t;
 __device__ __forceinline__ bf16x8 lds_read_row(uint32_t addr) { return *(lds_b128_t)(uintptr_t)addr; }
@@ -136,7 +146,7 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   constexpr int KS = D / 16, DT = D / 32, ROW = D * 2, TILE = kTile * ROW;
   constexpr int CH = D / 8, RPI = 64 / CH;          // 16-byte chunks per row, rows per load instruction
   constexpr int NI = 32 / RPI;                      // load instructions per wave per tile (its 32 rows)
-  constexpr int HI_XOR = CH == 16 ? 128 : 0;        // row + 8 flips bit 3 of the chunk permutation when it has 4 bits
+  constexpr int HI_XOR = CH == 16 ? 16 : 0;         // row + 8 flips the lowest bit of the chunk permutation when it has 4 bits
   extern __shared__ __align__(1024) unsigned char smem[];
   __shared__ int cnt_s[2 * 12];
   __shared__ __align__(256) float rows_f[4 * 128];  // dkv: per ring entry, lse (64 floats, 32 used) then D of the half tile's rows
@@ -278,14 +288,14 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   const uint32_t rows_s = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)rows_f);
   uint32_t ra[KS], ta[DT];
   {
-    const int kb = qn * ROW + ((half ^ (qn & (CH - 1))) << 4);           // row lane % 32, logical chunk 2 ks + half
+    const int kb = qn * ROW + ((half ^ swz<CH>(qn)) << 4);              // row lane % 32, logical chunk 2 ks + half
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) ra[ks] = smem_lds + (uint32_t)(kb ^ (ks << 5));
     const int s16 = lane & 15, q16 = (lane >> 4) & 1;
     const int row0 = 4 * half + (s16 >> 2);                              // address row within 16 streamed rows
     const int sub = 2 * q16 + ((s16 & 3) >> 1), lo = (s16 & 1) * 8;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) ta[dt] = (uint32_t)(row0 * ROW + (((4 * dt + sub) ^ (row0 & (CH - 1))) << 4) + lo);
+    for (int dt = 0; dt < DT; ++dt) ta[dt] = (uint32_t)(row0 * ROW + (((4 * dt + sub) ^ swz<CH>(row0)) << 4) + lo);
   }
 
   // ---- staging -------------------------------------------------------------------------------------
@@ -317,7 +327,7 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
 #pragma unroll
   for (int k = 0; k < NH; ++k) {
     const int r = 16 * wave + RPI * k + rl;
-    const uint32_t chunk = (uint32_t)(((lane % CH) ^ (r & (CH - 1))) << 4);
+    const uint32_t chunk = (uint32_t)(((lane % CH) ^ swz<CH>(r)) << 4);
     so1[k] = (uint32_t)(r * st1) + chunk;
     so2[k] = (uint32_t)(r * st2) + chunk;
   }
@@ -341,7 +351,7 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
 #pragma unroll
       for (int k = 0; k < NH; ++k) {
         const int r = 16 * wave + RPI * k + rl, src_row = min(32 * mg + r, last);
-        const uint32_t chunk = (uint32_t)(((lane % CH) ^ (r & (CH - 1))) << 4);
+        const uint32_t chunk = (uint32_t)(((lane % CH) ^ swz<CH>(r)) << 4);
         dma16(s1, (uint32_t)(src_row * st1) + chunk, dst + k * 1024);
         dma16(s2, (uint32_t)(src_row * st2) + chunk, dst + HALF + k * 1024);
       }
