@@ -191,8 +191,17 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
       kv_slot_tile = (ok ? slot : 0) * SUB + sub;
       for (int i = tid; i < a.nqb; i += kThreads) flag_s[i] = 0;
       __syncthreads();
-      for (int e = tid; e < a.nqb * a.k; e += kThreads)
-        if (a.sel[(size_t)h * a.nqb * a.k + e] == l) flag_s[e / a.k] = 1;
+      // the head's rows of sel, eight loads in flight per thread (one at a time the scan is a chain of memory latencies)
+      const int32_t* sel_h = a.sel + (size_t)h * a.nqb * a.k;
+      const int n_sel = a.nqb * a.k;
+      for (int e0 = tid; e0 < n_sel; e0 += 8 * kThreads) {
+        int v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = e0 + j * kThreads < n_sel ? sel_h[e0 + j * kThreads] : -1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (v[j] == l) flag_s[(e0 + j * kThreads) / a.k] = 1;
+      }
       if (!ok) fixed_len = -1;             // a block that is nowhere: nothing to write either
     }
     __syncthreads();
@@ -224,24 +233,30 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
       return rows > 0;
     }
   };
-  const int n_rounds = (n_cand + kThreads - 1) / kThreads;     // at most 12 (host-checked)
-  for (int r = 0; r < n_rounds; ++r) {
-    int where, rows;
-    const unsigned long long m = __ballot(classify(r * kThreads + tid, where, rows));
-    if (lane == 0) cnt_s[r * 2 + wave] = __popcll(m);
+  constexpr int kMaxRounds = 12;           // (2 (C_max + 1) + 2 k_max) / 128 rounded up; dkv needs 8
+  const int n_rounds = min((n_cand + kThreads - 1) / kThreads, kMaxRounds);
+  // every candidate is looked at once (a look is a chain of dependent loads); what it found stays in registers
+  // until the counts of all rounds are known
+  int c_where[kMaxRounds], c_rows[kMaxRounds];
+  unsigned long long c_mask[kMaxRounds];
+#pragma unroll
+  for (int r = 0; r < kMaxRounds; ++r) {
+    c_where[r] = 0;
+    c_rows[r] = 0;
+    const bool on = r < n_rounds && classify(r * kThreads + tid, c_where[r], c_rows[r]);
+    c_mask[r] = __ballot(on);
+    if (r < n_rounds && lane == 0) cnt_s[r * 2 + wave] = __popcll(c_mask[r]);
   }
   __syncthreads();
   int n_tiles = 0;
   for (int q = 0; q < 2 * n_rounds; ++q) n_tiles += cnt_s[q];
-  for (int r = 0; r < n_rounds; ++r) {
-    int where = 0, rows = 0;
-    const bool on = classify(r * kThreads + tid, where, rows);
-    const unsigned long long m = __ballot(on);
-    if (on) {
-      int pos = lanes_below(m);
+#pragma unroll
+  for (int r = 0; r < kMaxRounds; ++r) {
+    if (r < n_rounds && ((c_mask[r] >> lane) & 1)) {
+      int pos = lanes_below(c_mask[r]);
       for (int q = 0; q < r * 2 + wave; ++q) pos += cnt_s[q];
-      lst_a[pos] = where;
-      lst_b[pos] = rows;
+      lst_a[pos] = c_where[r];
+      lst_b[pos] = c_rows[r];
     }
   }
   __syncthreads();
