@@ -20,7 +20,7 @@ SOURCES = {
     "pbsa_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "pbsa_layout.hip": [],
     "pbsa_mass.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-    "pbsa_backward.hip": [],
+    "pbsa_backward.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall", "-Wno-unused-command-line-argument",
           # keep the compiler from forming packed-fp32 instructions

@@ -23,6 +23,8 @@
 // a row are permuted by the row number so that both the row-wise and the transposing operand reads are free of
 // bank conflicts.  Rows past a tile's valid length are never loaded: their
 // lanes fetch the last valid row, and the elementwise stage zeroes what belongs to them.
+#include <type_traits>
+
 #include "pbsa_internal.h"
 
 namespace pbsa {
@@ -105,6 +107,9 @@ __device__ __forceinline__ bf16x8 lds_read_tr(uint32_t base, uint32_t off) {
   const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_tr_t)(uintptr_t)(base + off));
   const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_tr_t)(uintptr_t)(base + (off ^ HI_XOR) + 8 * ROW));
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+__device__ __forceinline__ void acc_mfma(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   bf16x2 pk;
@@ -296,6 +301,14 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int v = 0; v < 16; ++v) out1[dt][v] = out2[dt][v] = 0.0f;
+  // The output accumulators are only ever touched by the second products: they live in the accumulator half of the
+  // register file for the whole walk (the products are issued as instructions with an accumulator destination), which
+  // leaves the architectural half to the fragments, the first products' results and the elementwise stage.
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    asm volatile("" : "+a"(out1[dt]));
+    if constexpr (KV) asm volatile("" : "+a"(out2[dt]));
+  }
 
   // ---- LDS addresses of this lane's operand reads inside ring entry 0 -------------------------------
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -405,8 +418,10 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
       c2a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[ks], c2a, 0, 0, 0);
     }
   }
-  for (int u = 0; u < n_half; ++u) {
-    const int e = u % RING, en = (u + 1) % RING, t = u >> 1, mg = u & 1;
+  // Two turns per tile, so that the accumulator sets trade places by name (no copies) and the half is a constant.
+  auto turn = [&](auto MG, int t, const f32x16& c1, const f32x16& c2a, f32x16& n1, f32x16& n2) {
+    constexpr int mg = decltype(MG)::value;
+    const int u = 2 * t + mg, e = 2 * (t & 1) + mg, en = (e + 1) % RING;
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((RING - 3) * PER) : "memory");   // this wave's rows of half tile u+1 are in
     __syncthreads();                                        // everybody's are, and half tile u-1 has been used by all
     stage(min(u + RING - 1, n_half - 1), (u + RING - 1) % RING);
@@ -419,31 +434,27 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
       x1[ks] = lds_read_row(ra[ks] + offn);
       x2[ks] = lds_read_row(ra[ks] + offn + HALF);
     }
+    // Row scalars (dkv) and the transposed fragments are asked for inside the slices, shortly before they are
+    // needed: the scalars of four streamed rows two slices ahead of their first use, the fragments two (one) per
+    // slice over the second half of the slices, when the row fragments they replace in the register file are dead.
     float nlv[16], dv[16];
-    if constexpr (KV) {
-#pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        const float4 n4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 8 * v4 + 4 * half]);
-        const float4 d4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 64 + 8 * v4 + 4 * half]);
-        nlv[4 * v4] = n4.x; nlv[4 * v4 + 1] = n4.y; nlv[4 * v4 + 2] = n4.z; nlv[4 * v4 + 3] = n4.w;
-        dv[4 * v4] = d4.x; dv[4 * v4 + 1] = d4.y; dv[4 * v4 + 2] = d4.z; dv[4 * v4 + 3] = d4.w;
+    auto fetch_scalars = [&](int g) {      // rows 8 g + 4 half .. + 3 of the half tile: elements 4 g .. 4 g + 3
+      if constexpr (KV) {
+        const float4 n4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 8 * g + 4 * half]);
+        const float4 d4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 64 + 8 * g + 4 * half]);
+        nlv[4 * g] = n4.x; nlv[4 * g + 1] = n4.y; nlv[4 * g + 2] = n4.z; nlv[4 * g + 3] = n4.w;
+        dv[4 * g] = d4.x; dv[4 * g + 1] = d4.y; dv[4 * g + 2] = d4.z; dv[4 * g + 3] = d4.w;
       }
-    }
-    bf16x8 t1[2][DT], t2[KV ? 2 : 1][KV ? DT : 1];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const uint32_t radd = smem_lds + (uint32_t)(16 * j * ROW);
-        t1[j][dt] = lds_read_tr<ROW, HI_XOR>(radd + off1, ta[dt]);
-        if constexpr (KV) t2[j][dt] = lds_read_tr<ROW, HI_XOR>(radd + off2, ta[dt]);
-      }
+    };
+    constexpr int NTF = (KV ? 2 : 1) * 2 * DT, TPS = NTF / (NS / 2);   // transposed fragments, per slice of the second half
+    static_assert(TPS * (NS / 2) == NTF, "the transposed reads spread evenly");
+    bf16x8 tf[NTF];                        // [tensor][j][dt]
+    fetch_scalars(0);
     __builtin_amdgcn_sched_barrier(0);
     // accumulator element v: streamed row 32 mg + 8 (v / 4) + 4 half + v % 4, fixed row 32 w + lane % 32.  Streamed
     // rows past the tile's length hold a copy of its last row and take no part; a fixed row that does not exist
     // only fills its own column of the outputs, which is not written.
     const int lim = rows - 32 * mg - 4 * half;
-    f32x16 n1, n2;
     u32x4 eP[2], eZ[2];
     float pz[16], zz[16];
 #pragma unroll
@@ -452,6 +463,19 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
       if (sl % 2 == 0) n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[ks], f1[ks], ks == 0 ? zero : n1, 0, 0, 0);
       else n2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[ks], ks == 0 ? zero : n2, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);   // the MFMA first, then the slice
+      {
+        // scalars of the group whose first element comes two slices from now
+        const int v_ahead = (sl + 2) * EPS;
+        if (v_ahead < 16 && v_ahead % 4 == 0 && (sl + 1) * EPS % 4 != 0) fetch_scalars(v_ahead / 4);
+        else if (EPS == 2 && v_ahead < 16 && v_ahead % 4 == 0) fetch_scalars(v_ahead / 4);
+      }
+      if (sl >= NS / 2) {
+#pragma unroll
+        for (int q = 0; q < TPS; ++q) {
+          const int i = (sl - NS / 2) * TPS + q, tensor = i / (2 * DT), j = (i / DT) % 2, dt = i % DT;
+          tf[i] = lds_read_tr<ROW, HI_XOR>(smem_lds + (uint32_t)(16 * j * ROW) + (tensor ? off2 : off1), ta[dt]);
+        }
+      }
 #pragma unroll
       for (int q = 0; q < EPS; ++q) {
         const int v = sl * EPS + q;
@@ -466,18 +490,30 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    asm volatile("s_nop 4" ::: "memory");   // the last slice's operands are written before the products that read them issue
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        out1[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1[j][dt], as_bf16x8(eZ[j]), out1[dt], 0, 0, 0);
-        if constexpr (KV) out2[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2[j][dt], as_bf16x8(eP[j]), out2[dt], 0, 0, 0);
+        acc_mfma(out1[dt], tf[j * DT + dt], as_bf16x8(eZ[j]));
+        if constexpr (KV) acc_mfma(out2[dt], tf[(2 + j) * DT + dt], as_bf16x8(eP[j]));
       }
     __builtin_amdgcn_sched_barrier(0);
-    c1 = n1;
-    c2a = n2;
+  };
+  {
+    f32x16 d1, d2;                         // the other accumulator set
+    for (int t = 0; t < n_tiles; ++t) {
+      turn(std::integral_constant<int, 0>{}, t, c1, c2a, d1, d2);
+      turn(std::integral_constant<int, 1>{}, t, d1, d2, c1, c2a);
+    }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the trailing loads land before the workgroup goes
+  // the compiler does not see the matrix instructions that wrote the output accumulators: let the pipe drain
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(out1[dt]));
+    if constexpr (KV) asm volatile("" : "+a"(out2[dt]));
+  }
 
   // ---- outputs: element v of tile dt is dim 32 dt + 8 (v / 4) + 4 half + v % 4 of fixed row 32 w + lane % 32 ----
   const int frow = 32 * wave + qn;
