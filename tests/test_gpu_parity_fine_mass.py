@@ -261,3 +261,22 @@ def test_cfg5_full_size_sampled_blocks(gpu):
         sc_ref, src_ref = st.update()
         assert c.update() == ne
         compare_update(c, st, gpu["wl"], sc_ref, src_ref, ne, "cfg5")
+
+
+def test_mass_with_more_slots_than_the_update_maintains(gpu):
+    """100 persistent slots of every length from empty to full (the attention calls and the mass calls take up to
+    192; only the update stops at 64): every entry of the mass matrix from both routes."""
+    H, d, B, Nq, w, C, k = 1, 64, 64, 150, 1, 100, 2
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    Kp, Vp = rnd(801, H, C, B, d), rnd(802, H, C, B, d)
+    pl = np.tile((np.arange(C, dtype=np.int32) * 7) % (B + 1), (H, 1))
+    ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+    st.set_persistent(Kp, Vp, pl, ids)
+    c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                     torch.from_numpy(ids))
+    for g in range(2):
+        Q, K, V = rnd(810 + 3 * g, H, Nq, d), rnd(811 + 3 * g, H, Nq, d), rnd(812 + 3 * g, H, Nq, d)
+        _, got, ref = attend_both(gpu, c, st, Q, K, V, g, "100 slots")
+        check_mass(got, ref, st, f"100 slots chunk {g}")

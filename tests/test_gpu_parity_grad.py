@@ -154,3 +154,22 @@ def test_backward_full_size_sampled_heads(gpu, name, heads):
         sc_ref, src_ref = st.update()
         assert c.update() == ne
         compare_update(c, st, gpu["wl"], sc_ref, src_ref, ne, name)
+
+
+def test_backward_with_many_slots_and_all_blocks_selected(gpu):
+    """Edge shapes of the lists the two kernels build: 100 persistent slots of every length (dq walks them all, dkv
+    has a workgroup for each), and k larger than the number of local blocks (every block attended by every query
+    block it is visible to)."""
+    H, d, B, Nq, w, C, k = 1, 64, 64, 150, 1, 100, 64
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    Kp, Vp = rnd(821, H, C, B, d), rnd(822, H, C, B, d)
+    pl = np.tile((np.arange(C, dtype=np.int32) * 7) % (B + 1), (H, 1))
+    ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+    st.set_persistent(Kp, Vp, pl, ids)
+    c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                     torch.from_numpy(ids))
+    for g in range(2):
+        Q, K, V = rnd(830 + 3 * g, H, Nq, d), rnd(831 + 3 * g, H, Nq, d), rnd(832 + 3 * g, H, Nq, d)
+        backward_both(gpu, c, st, Q, K, V, g, "bwd 100 slots")
