@@ -239,6 +239,11 @@ def main():
                          "at top-k 6.25 / 12.5 / 25 % and with every block selected (the dense stand-in)")
     ap.add_argument("--blockify", action="store_true",
                     help="instead of the step benchmark: the block rearrange of a chunk's Q, K, V and its inverse")
+    ap.add_argument("--overlap-update", action="store_true",
+                    help="take the update's decisions on a second stream beside the attention kernel (pbsa_memory_update_plan, "
+                         "then pbsa_memory_update_apply after it) instead of pbsa_memory_update after the attention call; "
+                         "measured slower: the second queue's workgroups keep the attention launch from filling the chip "
+                         "in one round")
     ap.add_argument("--fine-mass", action="store_true",
                     help="the step with the persistent set ranked by the attention actually paid: after the attention "
                          "call pbsa_attention_mass sums the probabilities per key block and pbsa_memory_update_fine "
@@ -312,6 +317,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     n_done = [0]
+    overlap = args.overlap_update and not args.fine_mass      # the mass-ranked update needs the attention call's output
 
     def one_step(i, attn_ev=None, sel_ev=None, upd_ev=None, mass_ev=None):
         # the producer has written the next chunk's K/V into the ring position that was just freed
@@ -335,6 +341,8 @@ def main():
         if sel_ev is not None:
             sel_ev[1].record(stream)
         plen_hist[i].copy_(c.p_len, non_blocking=True)
+        if overlap:
+            c.mark_selection_done()
         if attn_ev is not None:
             attn_ev[0].record(stream)
         if args.fine_mass:
@@ -343,6 +351,8 @@ def main():
             c.attention(Qd, O)
         if attn_ev is not None:
             attn_ev[1].record(stream)
+        if overlap:
+            c.update_plan_on_side_stream()         # scoring and retention, beside the attention kernel just issued
         if args.fine_mass and mass_ev is not None:
             # for comparison only (the step does not need it): the same matrix by a separate pass over the keys
             mass_ev[0].record(stream)
@@ -352,6 +362,8 @@ def main():
             upd_ev[0].record(stream)
         if args.fine_mass:
             c.update_fine(Mt)
+        elif overlap:
+            c.update_apply()
         else:
             c.update()
         if upd_ev is not None:
@@ -397,7 +409,8 @@ def main():
         promoted = int((src_hist[i] >= 0).sum().item())
         folded = occupied + w.H * w.nqb - min(w.H * w.C, occupied + w.H * w.nqb)
         # what the ranking reads: the coarse logits, or the candidates' rows of the mass matrix
-        ranked = w.H * (w.C + w.nqb) * ((w.nqb + 3) & ~3) * 4 if args.fine_mass else w.H * w.nqb * n_loc * 4
+        ranked = (w.H * (w.C + w.nqb) * ((w.nqb + 3) & ~3) * 4 if args.fine_mass else
+                  0 if overlap else w.H * w.nqb * n_loc * 4)      # the apply call reads no scores
         upd_bytes.append(ranked + folded * 2 * blk + promoted * 4 * blk
                          + w.H * (2 * 2 * w.B * w.d * 4 + 2 * blk))
     upd_b = float(np.mean(upd_bytes))
@@ -424,6 +437,12 @@ def main():
                                    "unit": "GB/s", "frac": round(upd_b / upd_us / 1e3 / PEAK_HBM_GBS, 4)},
             "note": f"{K2} steps after the timed region, HIP events around each call"},
     }
+    if overlap:
+        out["config"]["schedule"] = ("pbsa_memory_update_plan (scoring, retention) on a second stream under the attention kernel, "
+                                     "pbsa_memory_update_apply (fold, promote) after it")
+        u = out["hbm_bound_calls"].pop("pbsa_memory_update")
+        u["note"] = "the apply call alone; the plan call is hidden under the attention kernel"
+        out["hbm_bound_calls"]["pbsa_memory_update_apply"] = u
     if args.fine_mass:
         mass_us = sum(a.elapsed_time(b) for a, b in ev_mass) / K2 * 1e3
         qk_flops = mean_flops / T / 2          # the first product of the attention only

@@ -156,6 +156,21 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
                        const int64_t* l_id, float* scores, int32_t* slot_src, void* ws, size_t ws_bytes,
                        void* hip_stream);
 
+/* pbsa_memory_update in two calls, for a caller that overlaps the update's decisions with the attention of the same
+ * chunk.  _plan scores and ranks (Eq. 7-9): it reads Qc, Kc_l, Zl, Kc_p, p_len and the local region's metadata and
+ * writes scores, slot_src, p_id, Kc_p, S_cnt (pass S_cnt = NULL to drop without compressing) and, into ws, what
+ * _apply needs; it touches neither K/V nor p_len, so it may run on another stream while pbsa_attention_fwd of the
+ * chunk runs (after the chunk's pbsa_select_blocks; the arrays it writes are not read by the attention call).
+ * _apply folds the dropped blocks into the summary, moves the promoted blocks into their slots and commits the
+ * new p_len; it must follow both the attention call and _plan, with the same p and ws (whose contents must have
+ * been left alone in between).  pbsa_memory_update is exactly the two in a row. */
+int pbsa_memory_update_plan(const pbsa_params* p, const float* Qc, const float* Kc_l, const float* Zl, float* Kc_p,
+                            const int32_t* p_len, int64_t* p_id, int32_t* S_cnt, const int32_t* l_len,
+                            const int32_t* l_map, const int64_t* l_id, float* scores, int32_t* slot_src, void* ws,
+                            size_t ws_bytes, void* hip_stream);
+int pbsa_memory_update_apply(const pbsa_params* p, void* Kp, void* Vp, int32_t* p_len, float* S_sum, const int32_t* S_cnt,
+                             const void* Kl, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Attention mass per key block (the fine-grained counterpart of Eq. 7: the attention of Eq. 3-5 as it was
  * actually paid, mask included, summed block by block).  Key blocks are numbered u = slot for the persistent
  * slots 0..C (the summary is u = C) and u = C + 1 + l for local block l.

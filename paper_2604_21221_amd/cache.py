@@ -245,6 +245,51 @@ class PbsaCache:
                                 grads["dQ"], grads["dKp"], grads["dVp"], grads["dKl"], grads["dVl"], self._bwd_ws)
         return grads
 
+    def mark_selection_done(self):
+        """Records, on the current stream, the point the plan call has to wait for (call right after select())."""
+        if getattr(self, "_side", None) is None:
+            self._side = torch.cuda.Stream(device=self.dev)          # default priority
+            self._ev_sel, self._ev_plan = torch.cuda.Event(), torch.cuda.Event()
+        self._ev_sel.record(torch.cuda.current_stream(self.dev))
+
+    def update_plan_on_side_stream(self):
+        """pbsa_memory_update_plan on a second stream, ordered after the point mark_selection_done() recorded.
+        Issued after the attention call, whose workgroups are then placed first (they need whole SIMDs; issued
+        before it, the plan's kernels take SIMDs the attention launch then cannot fill in one round) and the
+        plan's kernels run beside it in the SIMDs it leaves free.  update_apply() completes the update."""
+        l_map, l_len, l_id = self._device_maps(want_ids=True)
+        self._plan_p = self.params(n_evict=self.n_evict_now())
+        self._side.wait_event(self._ev_sel)
+        pbsa.pbsa_memory_update_plan(self._plan_p, self.Qc, self.Kc_l, self.Zl, self.Kc_p, self.p_len, self.p_id,
+                                     self.S_cnt, l_len, l_map, l_id, self.scores, self.slot_src, self.ws,
+                                     stream=self._side)
+        self._ev_plan.record(self._side)
+
+    def update_apply(self):
+        """Waits (on the device) for the plan, then fold, promote, commit; slides the window."""
+        torch.cuda.current_stream(self.dev).wait_event(self._ev_plan)
+        pbsa.pbsa_memory_update_apply(self._plan_p, self.Kp, self.Vp, self.p_len, self.S_sum, self.S_cnt, self.Kl, self.Vl,
+                                      self.ws)
+        ne = self._plan_p.n_evict
+        if ne:
+            self.chunk_pos.pop(0)
+            self.chunk_ids.pop(0)
+            self.stale_from = self.n_loc
+        return ne
+
+    def step_overlapped(self, Q, K=None, V=None, chunk_id=None, O=None, lse=None):
+        """The same step with the update's decisions taken on a second stream while the attention kernel runs
+        (they read only what the selection call left and the cache's metadata); fold, promote and the commit of
+        the slot lengths follow the attention call.  K = V = None: the chunk has been adopted already."""
+        if K is not None:
+            self.append_chunk(K, V, chunk_id)
+        self.select(Q)
+        self.mark_selection_done()
+        O = self.attention(Q, O, lse)
+        self.update_plan_on_side_stream()
+        self.update_apply()
+        return O
+
     def step(self, Q, K, V, chunk_id, O=None, lse=None):
         """One layer-chunk step: append the chunk, select, attend, update (all enqueued, no sync)."""
         self.append_chunk(K, V, chunk_id)

@@ -179,6 +179,39 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
+int pbsa_memory_update_plan(const pbsa_params* p, const float* Qc, const float* Kc_l, const float* Zl, float* Kc_p,
+                            const int32_t* p_len, int64_t* p_id, int32_t* S_cnt, const int32_t* l_len,
+                            const int32_t* l_map, const int64_t* l_id, float* scores, int32_t* slot_src, void* ws,
+                            size_t ws_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Qc || !Kc_l || !p_len || !l_len || !l_map || !l_id) return PBSA_EINVAL;
+  if (p->C > 0 && (!Kc_p || !p_id || !slot_src)) return PBSA_EINVAL;
+  if (!aligned16(Kc_l) || !aligned16(Kc_p) || !aligned16(Qc)) return PBSA_EALIGN;
+  if (!ws || ws_bytes < workspace_bytes(*p)) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  const pbsa::UpdateWs w = pbsa::carve_update_ws(*p, ws);
+  hipError_t e = pbsa::launch_update_plan(*p, Qc, Kc_l, Zl, Kc_p, p_len, p_id, S_cnt, S_cnt != nullptr, l_len, l_map, l_id,
+                                          scores, slot_src, w, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_memory_update_apply(const pbsa_params* p, void* Kp, void* Vp, int32_t* p_len, float* S_sum, const int32_t* S_cnt,
+                             const void* Kl, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Kp || !Vp || !p_len || !Kl || !Vl) return PBSA_EINVAL;
+  if ((S_sum == nullptr) != (S_cnt == nullptr)) return PBSA_EINVAL;
+  if (!aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(S_sum)) return PBSA_EALIGN;
+  if (!ws || ws_bytes < workspace_bytes(*p)) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  const pbsa::UpdateWs w = pbsa::carve_update_ws(*p, ws);
+  hipError_t e = pbsa::launch_update_apply(*p, static_cast<pbsa::bf16_t*>(Kp), static_cast<pbsa::bf16_t*>(Vp), p_len, S_sum,
+                                           S_cnt, static_cast<const pbsa::bf16_t*>(Kl), static_cast<const pbsa::bf16_t*>(Vl),
+                                           w, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
 int pbsa_attention_mass(const pbsa_params* p, const void* Q, const void* Kp, const int32_t* p_len, const void* Kl,
                         const int32_t* l_len, const int32_t* l_map, const int32_t* sel, const float* lse, float* Mt,
                         void* hip_stream) {

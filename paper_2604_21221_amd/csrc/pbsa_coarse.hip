@@ -487,7 +487,8 @@ struct RetainArgs {
   const float* A;           // A^T [H][nU_max][nqb_pad]
   const float* Kc_l;
   float* Kc_p;
-  int32_t* p_len;
+  const int32_t* p_len;
+  int32_t* p_len_out;       // [H][C + 1] lengths after the update (the fold kernel commits them)
   int64_t* p_id;
   int32_t* S_cnt;
   const int32_t* l_len;
@@ -523,7 +524,7 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
   __shared__ int nf_s, npos_s;
   const int h = blockIdx.x, C = a.C, C1 = a.C + 1;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int32_t* plen = a.p_len + (size_t)h * C1;
+  const int32_t* plen = a.p_len + (size_t)h * C1;
   for (int c = threadIdx.x; c < C1; c += kThreads) old_len[c] = plen[c];
   for (int e = threadIdx.x; e < a.n_evict; e += kThreads) {
     e_len[e] = max(0, min(a.l_len[e], a.B));
@@ -674,7 +675,7 @@ __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
     if (threadIdx.x == 0) old_len[C] = npos_s;
     __syncthreads();
   }
-  for (int c = threadIdx.x; c < C1; c += kThreads) plen[c] = old_len[c];
+  for (int c = threadIdx.x; c < C1; c += kThreads) a.p_len_out[(size_t)h * C1 + c] = old_len[c];
   for (int c = threadIdx.x; c < C; c += kThreads) {
     const int e = src_s[c];
     a.slot_src[(size_t)h * C + c] = e;
@@ -711,6 +712,8 @@ struct FoldArgs {
   const int32_t* fold_src;
   const int32_t* fold_len;
   const int32_t* promo_slot;
+  const int32_t* plen_new;  // the slots' lengths after the update ...
+  int32_t* p_len;           // ... which this kernel commits
 };
 
 constexpr int kFoldBatch = 40;
@@ -723,6 +726,8 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   __shared__ int promo_dst[PBSA_MAX_C], promo_src[PBSA_MAX_C], n_promo_s;   // refilled slots, compacted
   const int h = blockIdx.y;
   const int C = a.C, C1 = a.C + 1, ncand_max = a.C + a.n_evict;
+  if (blockIdx.x == 0)                     // nothing in this launch reads p_len: the lists carry the lengths they need
+    for (int c = threadIdx.x; c < C1; c += kThreads) a.p_len[(size_t)h * C1 + c] = a.plen_new[(size_t)h * C1 + c];
   const int nf = a.fold && a.S_sum ? a.fold_n[h] : 0;
   const size_t blk = (size_t)a.B * a.d;
   for (int f = threadIdx.x; f < nf; f += kThreads) {
@@ -835,6 +840,7 @@ UpdateWs carve_update_ws(const pbsa_params& p, void* base) {
   w.fold_src = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * ncand * 4);
   w.fold_len = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * ncand * 4);
   w.promo_slot = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * (p.C + 1) * 4);
+  w.plen_new = reinterpret_cast<int32_t*>(b + off); off += align256((size_t)p.H * (p.C + 1) * 4);
   w.bytes = off;
   return w;
 }
@@ -907,65 +913,72 @@ static hipError_t launch_rows_z_t(const ScoreArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-static hipError_t launch_retain_fold(const pbsa_params& p, const float* A, int n_rows, int fine, const float* Kc_l,
-                                     bf16_t* Kp, bf16_t* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum,
-                                     int32_t* S_cnt, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
-                                     const int32_t* l_map, const int64_t* l_id, float* scores, int32_t* slot_src,
-                                     const UpdateWs& ws, hipStream_t stream);
-
-hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, bf16_t* Kp,
-                         bf16_t* Vp,
-                         float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
-                         const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
-                         const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
-                         hipStream_t stream) {
+static hipError_t launch_scores(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl,
+                                const float* Kc_p, const int32_t* p_len, const int32_t* l_map, const UpdateWs& ws,
+                                hipStream_t stream) {
   const int nU_max = p.C + p.n_loc;
   const int nqb_pad = (p.nqb + 3) & ~3;
   ScoreArgs sa{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, nU_max, p.n_evict, p.scale, Kc_l, Kc_p, Qc, Zl, l_map, p_len, ws.A};
   const int nm = (nU_max + 63) / 64;
-  hipError_t e;
   if (Zl) {
     const int nml = (p.n_loc + 63) / 64;
     if (p.d == 128)
-      e = nml <= 2 ? launch_rows_z_t<128, 2>(sa, stream) : nml <= 5 ? launch_rows_z_t<128, 5>(sa, stream)
-                                                                   : launch_rows_z_t<128, 8>(sa, stream);
-    else
-      e = nml <= 2 ? launch_rows_z_t<64, 2>(sa, stream) : nml <= 5 ? launch_rows_z_t<64, 5>(sa, stream)
-                                                                  : launch_rows_z_t<64, 8>(sa, stream);
-  } else if (p.d == 128) {
-    e = nm <= 2 ? launch_rows_t<128, 2>(sa, stream) : nm <= 6 ? launch_rows_t<128, 6>(sa, stream)
-                                                              : launch_rows_t<128, 9>(sa, stream);
-  } else {
-    e = nm <= 2 ? launch_rows_t<64, 2>(sa, stream) : nm <= 6 ? launch_rows_t<64, 6>(sa, stream)
-                                                             : launch_rows_t<64, 9>(sa, stream);
+      return nml <= 2 ? launch_rows_z_t<128, 2>(sa, stream) : nml <= 5 ? launch_rows_z_t<128, 5>(sa, stream)
+                                                                      : launch_rows_z_t<128, 8>(sa, stream);
+    return nml <= 2 ? launch_rows_z_t<64, 2>(sa, stream) : nml <= 5 ? launch_rows_z_t<64, 5>(sa, stream)
+                                                                    : launch_rows_z_t<64, 8>(sa, stream);
   }
-  if (e != hipSuccess) return e;
-
-  return launch_retain_fold(p, ws.A, nU_max, 0, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id,
-                            scores, slot_src, ws, stream);
+  if (p.d == 128)
+    return nm <= 2 ? launch_rows_t<128, 2>(sa, stream) : nm <= 6 ? launch_rows_t<128, 6>(sa, stream)
+                                                                : launch_rows_t<128, 9>(sa, stream);
+  return nm <= 2 ? launch_rows_t<64, 2>(sa, stream) : nm <= 6 ? launch_rows_t<64, 6>(sa, stream)
+                                                              : launch_rows_t<64, 9>(sa, stream);
 }
 
-// Retention and fold given the matrix whose row sums are the scores
-static hipError_t launch_retain_fold(const pbsa_params& p, const float* A, int n_rows, int fine, const float* Kc_l, bf16_t* Kp,
-                              bf16_t* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
-                              const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
-                              const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
-                              hipStream_t stream) {
+// Retention given the matrix whose row sums are the scores (A: the coarse matrix in the workspace, or the mass matrix)
+static hipError_t launch_retain(const pbsa_params& p, const float* A, int n_rows, int fine, const float* Kc_l,
+                                float* Kc_p, const int32_t* p_len, int64_t* p_id, int32_t* S_cnt, int fold,
+                                const int32_t* l_len, const int32_t* l_map, const int64_t* l_id, float* scores,
+                                int32_t* slot_src, const UpdateWs& ws, hipStream_t stream) {
   const int nqb_pad = (p.nqb + 3) & ~3;
-  const int fold = S_sum != nullptr;
   RetainArgs ra{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, p.n_sink, p.n_evict, n_rows, p.d, p.B, fold, fine, p.Nq,
-                A, Kc_l, Kc_p, p_len, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n, ws.fold_src,
-                ws.fold_len, ws.promo_slot};
+                A, Kc_l, Kc_p, p_len, ws.plen_new, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n,
+                ws.fold_src, ws.fold_len, ws.promo_slot};
   hipLaunchKernelGGL(retain_kernel, dim3(p.H), dim3(kThreads), 0, stream, ra);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
 
+hipError_t launch_update_plan(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, float* Kc_p,
+                              const int32_t* p_len, int64_t* p_id, int32_t* S_cnt, int fold, const int32_t* l_len,
+                              const int32_t* l_map, const int64_t* l_id, float* scores, int32_t* slot_src,
+                              const UpdateWs& ws, hipStream_t stream) {
+  hipError_t e = launch_scores(p, Qc, Kc_l, Zl, Kc_p, p_len, l_map, ws, stream);
+  if (e != hipSuccess) return e;
+  return launch_retain(p, ws.A, p.C + p.n_loc, 0, Kc_l, Kc_p, p_len, p_id, S_cnt, fold, l_len, l_map, l_id, scores,
+                       slot_src, ws, stream);
+}
+
+hipError_t launch_update_apply(const pbsa_params& p, bf16_t* Kp, bf16_t* Vp, int32_t* p_len, float* S_sum,
+                               const int32_t* S_cnt, const bf16_t* Kl, const bf16_t* Vl, const UpdateWs& ws,
+                               hipStream_t stream) {
+  const int fold = S_sum != nullptr;
   FoldArgs fa{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, fold, Kp, Vp, Kl, Vl, S_sum, S_cnt, ws.fold_n,
-              ws.fold_src, ws.fold_len, ws.promo_slot};
+              ws.fold_src, ws.fold_len, ws.promo_slot, ws.plen_new, p_len};
   const int rows_per_wg = kThreads / (p.d / 4);
   hipLaunchKernelGGL(fold_promote_kernel, dim3((2 * p.B + rows_per_wg - 1) / rows_per_wg, p.H), dim3(kThreads), 0,
                      stream, fa);
   return hipGetLastError();
+}
+
+hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, bf16_t* Kp,
+                         bf16_t* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                         const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                         const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
+                         hipStream_t stream) {
+  hipError_t e = launch_update_plan(p, Qc, Kc_l, Zl, Kc_p, p_len, p_id, S_cnt, S_sum != nullptr, l_len, l_map, l_id, scores,
+                                    slot_src, ws, stream);
+  if (e != hipSuccess) return e;
+  return launch_update_apply(p, Kp, Vp, p_len, S_sum, S_cnt, Kl, Vl, ws, stream);
 }
 
 hipError_t launch_update_fine(const pbsa_params& p, const float* Mt, const float* Kc_l, bf16_t* Kp, bf16_t* Vp,
@@ -973,8 +986,10 @@ hipError_t launch_update_fine(const pbsa_params& p, const float* Mt, const float
                               const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
                               const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
                               hipStream_t stream) {
-  return launch_retain_fold(p, Mt, p.C + 1 + p.n_loc, 1, Kc_l, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len,
-                            l_map, l_id, scores, slot_src, ws, stream);
+  hipError_t e = launch_retain(p, Mt, p.C + 1 + p.n_loc, 1, Kc_l, Kc_p, p_len, p_id, S_cnt, S_sum != nullptr, l_len, l_map,
+                               l_id, scores, slot_src, ws, stream);
+  if (e != hipSuccess) return e;
+  return launch_update_apply(p, Kp, Vp, p_len, S_sum, S_cnt, Kl, Vl, ws, stream);
 }
 
 }  // namespace pbsa

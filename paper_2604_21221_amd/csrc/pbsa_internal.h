@@ -18,6 +18,7 @@ struct UpdateWs {
   int32_t* fold_src;  // [H][C + n_evict] dropped candidate: < C persistent slot, else C + physical local slot
   int32_t* promo_slot;  // [H][C] physical local slot a persistent slot is refilled from, or -1
   int32_t* fold_len;  // [H][C + n_evict] its valid tokens (read before p_len is rewritten)
+  int32_t* plen_new;  // [H][C + 1] the slots' lengths after the update, committed to p_len by the fold kernel
   size_t bytes;
 };
 UpdateWs carve_update_ws(const pbsa_params& p, void* base);
@@ -46,6 +47,17 @@ hipError_t launch_attention(const pbsa_params& p, const bf16_t* Q, const bf16_t*
                             hipStream_t stream);
 hipError_t launch_mass_reduce(const pbsa_params& p, const MassRows& rows, const float* lse, float* Mt,
                               hipStream_t stream);
+// The update in two parts.  plan: scoring and retention -- reads the cache's metadata and pooled keys, writes the
+// decisions (scores, slot_src, p_id, Kc_p, S_cnt, and into the workspace the fold list, the promotions and the new
+// slot lengths); touches neither K/V nor p_len, so it may run while the attention kernel of the same chunk does.
+// apply: fold, promote and the commit of p_len.  launch_update is the two in a row.
+hipError_t launch_update_plan(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, float* Kc_p,
+                              const int32_t* p_len, int64_t* p_id, int32_t* S_cnt, int fold, const int32_t* l_len,
+                              const int32_t* l_map, const int64_t* l_id, float* scores, int32_t* slot_src,
+                              const UpdateWs& ws, hipStream_t stream);
+hipError_t launch_update_apply(const pbsa_params& p, bf16_t* Kp, bf16_t* Vp, int32_t* p_len, float* S_sum,
+                               const int32_t* S_cnt, const bf16_t* Kl, const bf16_t* Vl, const UpdateWs& ws,
+                               hipStream_t stream);
 hipError_t launch_update(const pbsa_params& p, const float* Qc, const float* Kc_l, const float* Zl, bf16_t* Kp,
                          bf16_t* Vp,
                          float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,

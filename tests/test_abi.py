@@ -199,6 +199,27 @@ def test_backward_argument_checks(L):
         assert e.value.code == code, kw
 
 
+def test_plan_and_apply_argument_checks(L):
+    p = good(n_evict=4)
+    need = pbsa.pbsa_workspace_bytes(p)
+
+    def plan(p=p, Qc=P, p_len=P, ws=(0x10000, 1 << 30)):
+        pbsa.pbsa_memory_update_plan(p, Qc, P, None, P, p_len, P, P, P, P, P, None, P, ws, stream=0)
+
+    def apply(p=p, Kp=P, S_sum=P, S_cnt=P, ws=(0x10000, 1 << 30)):
+        pbsa.pbsa_memory_update_apply(p, Kp, P, P, S_sum, S_cnt, P, P, ws, stream=0)
+
+    for call, kw, code in [(plan, dict(Qc=None), pbsa.PBSA_EINVAL), (plan, dict(p_len=None), pbsa.PBSA_EINVAL),
+                           (plan, dict(Qc=P + 4), pbsa.PBSA_EALIGN), (plan, dict(ws=None), pbsa.PBSA_EWS),
+                           (plan, dict(ws=(0x10000, need - 1)), pbsa.PBSA_EWS), (plan, dict(p=good(C=65)), pbsa.PBSA_ESHAPE),
+                           (apply, dict(Kp=None), pbsa.PBSA_EINVAL), (apply, dict(S_cnt=None), pbsa.PBSA_EINVAL),
+                           (apply, dict(S_sum=P + 8), pbsa.PBSA_EALIGN), (apply, dict(ws=None), pbsa.PBSA_EWS),
+                           (apply, dict(ws=(0x10080, need)), pbsa.PBSA_EALIGN), (apply, dict(p=good(n_evict=17)), pbsa.PBSA_EINVAL)]:
+        with pytest.raises(pbsa.PbsaError) as e:
+            call(**kw)
+        assert e.value.code == code, (call.__name__, kw)
+
+
 def test_binding_refuses_host_tensors(L):
     import torch
     with pytest.raises(TypeError):

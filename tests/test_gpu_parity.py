@@ -269,6 +269,34 @@ def test_determinism(gpu):
         assert torch.equal(c.attention(Q), O0)
 
 
+def test_update_decisions_overlapped_with_attention(gpu):
+    """pbsa_memory_update_plan on a second stream while the attention kernel runs, pbsa_memory_update_apply after
+    both: outputs and cache state equal the oracle's, as with the sequential call, chunk after chunk."""
+    name, H, d, B, Nq, w, C, k, n_sink, causal, p_lens = SMALL[1]
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal, device=DEV)
+    Kp, Vp = rnd(1, H, C, B, d), rnd(2, H, C, B, d)
+    pl = np.tile(np.array(p_lens, np.int32), (H, 1))
+    ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+    st.set_persistent(Kp, Vp, pl, ids)
+    c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                     torch.from_numpy(ids))
+    lens = np.full(st.nqb, B, np.int32); lens[-1] = Nq - (st.nqb - 1) * B
+    for g in range(w + 5):
+        print(f"[case] overlapped update chunk {g}", flush=True)
+        Q, K, V = rnd(60 + 3 * g, H, Nq, d), rnd(61 + 3 * g, H, Nq, d, scale=1.5), rnd(62 + 3 * g, H, Nq, d)
+        st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * st.nqb + np.arange(st.nqb))
+        st.select(Q)
+        Oref, _ = st.attention(Q)
+        ne = st.n_evict_now()
+        sc_ref, src_ref = st.update()
+        O = c.step_overlapped(gpu["wl"].bf16_tensor(Q, DEV), gpu["wl"].bf16_tensor(K, DEV), gpu["wl"].bf16_tensor(V, DEV), g)
+        torch.cuda.synchronize()
+        check_attention(O.float().cpu().numpy(), Oref, "overlapped")
+        compare_update(c, st, gpu["wl"], sc_ref, src_ref, ne, "overlapped")
+
+
 def test_denoising_passes_share_the_cache(gpu):
     """T passes over one chunk (Sec. 3.1): between passes only the chunk's own K/V and the queries change.
     Every pass must match the oracle on every element, the update follows the last pass, and the pooled
