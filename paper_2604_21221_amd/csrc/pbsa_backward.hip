@@ -547,6 +547,264 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// dq with 64 query rows per wave.  One workgroup = one wave = 64 query rows (two MFMA column groups of 32), so
+// that every K or V fragment read from LDS -- row-wise for the first products, transposed for the second --
+// feeds two MFMAs: the kernel above, where a wave owns 32 rows, reads one fragment per MFMA and is bound by the
+// LDS bandwidth.  The wave stages its own half tiles (32 keys of K and of V per ring entry, two entries) and is
+// the only one to read them: no barrier anywhere.  Q and dO fragments and the dQ^T accumulators fill the
+// accumulator half of the register file (128 + 128 registers at d = 128).  A turn, on one half tile:
+//     first products of column group 0            (2 KS MFMAs)
+//     first products of column group 1            (2 KS MFMAs)  with the elementwise stage of group 0 behind them
+//     second products of group 0                  (2 DT MFMAs)  with the elementwise stage of group 1 behind them
+//     second products of group 1                  (2 DT MFMAs)
+// ------------------------------------------------------------------------------------------------
+template <int LDS_IMM>
+__device__ __forceinline__ void dma16x4(const void* base, uint32_t o0, uint32_t o1, uint32_t o2, uint32_t o3, uint32_t lds_base) {
+  // four loads 1 KiB apart in LDS and in memory alike: the instruction's offset moves both addresses
+  asm volatile("s_add_u32 m0, %0, %6\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %1, %5\n\t"
+               "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+               "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+               "global_load_lds_dwordx4 %4, %5 offset:3072"
+               :
+               : "s"(lds_base), "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(base), "n"(LDS_IMM)
+               : "memory", "scc");
+}
+
+template <int D>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) bwd_dq_kernel(BwdArgs a) {
+  constexpr int KS = D / 16, DT = D / 32, ROW = D * 2, TILE = kTile * ROW, HALF = TILE / 2;
+  constexpr int CH = D / 8, RPI = 64 / CH;          // 16-byte chunks per row, rows per load instruction
+  constexpr int NW = (32 / RPI) / 4;                // windows of four load instructions per tensor and half tile: 2 or 1
+  constexpr int HI_XOR = CH == 16 ? 16 : 0;
+  constexpr int NS = 2 * KS, EPS = 16 / NS;         // slices behind the first products, elements per slice
+  extern __shared__ __align__(1024) unsigned char smem[];
+  // ring: entry e holds 32 rows of K at e * TILE and 32 rows of V behind them
+  int* lst_a = reinterpret_cast<int*>(smem + 2 * TILE);
+  const int SUB = a.B / kTile;
+  const int lane = threadIdx.x;
+  const int qn = lane & 31, half = lane >> 5;
+  const int h = blockIdx.y, r_tile = blockIdx.x;
+  const float c2 = a.scale * kLog2e;
+  const int i_blk = r_tile * kTile / a.B;
+  const int n_pers = (a.C + 1) * SUB, n_cand = n_pers + a.k * SUB;
+  int* lst_b = lst_a + n_cand;
+  const int fixed_len = min(kTile, a.Nq - r_tile * kTile);
+
+  // ---- the tiles these rows attend: persistent slots, then the blocks of their row of sel -----------------
+  int n_tiles = 0;
+  for (int i0 = 0; i0 < n_cand; i0 += 64) {
+    const int i = i0 + lane;
+    int where = 0, rows = 0;
+    if (i < n_pers) {
+      const int c = i / SUB, sub = i % SUB;
+      rows = min(max(min(max(a.p_len[(size_t)h * (a.C + 1) + c], 0), a.B) - sub * kTile, 0), kTile);
+      where = i;
+    } else if (i < n_cand) {
+      const int jj = (i - n_pers) / SUB, sub = (i - n_pers) % SUB;
+      const int l = a.sel[((size_t)h * a.nqb + i_blk) * a.k + jj];
+      if (l >= 0 && l < a.n_loc) {
+        const int slot = a.l_map[l];
+        if (slot >= 0 && slot < a.n_loc_cap) {
+          rows = min(max(min(max(a.l_len[l], 0), a.B) - sub * kTile, 0), kTile);
+          where = (int)(0x80000000u | (uint32_t)(slot * SUB + sub));
+        }
+      }
+    }
+    const unsigned long long m = __ballot(rows > 0);
+    if (rows > 0) {
+      const int pos = n_tiles + lanes_below(m);
+      lst_a[pos] = where;
+      lst_b[pos] = rows;
+    }
+    n_tiles += __popcll(m);
+  }
+  n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
+
+  // ---- fixed fragments (B operands) of both column groups: row 32 n + lane % 32, dims 16 ks + 8 (lane / 32) .. + 8 ----
+  bf16x8 f1[2][KS], f2[2][KS];
+  float nl_fix[2], d_fix[2];
+#pragma unroll
+  for (int n = 0; n < 2; ++n) {
+    const int row = min(32 * n + qn, fixed_len - 1), tok = r_tile * kTile + row;
+    const bf16_t* p1 = a.Q + (size_t)h * a.q_stride_h + (size_t)tok * a.q_stride_t;
+    const bf16_t* p2 = a.dO + (size_t)h * a.o_stride_h + (size_t)tok * a.o_stride_t;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      f1[n][ks] = *reinterpret_cast<const bf16x8*>(p1 + 16 * ks + 8 * half);
+      f2[n][ks] = *reinterpret_cast<const bf16x8*>(p2 + 16 * ks + 8 * half);
+    }
+    const float l = a.lse[(size_t)h * a.Nq + tok];
+    nl_fix[n] = 32 * n + qn < fixed_len && l > -INFINITY ? -l * kLog2e : -INFINITY;
+    d_fix[n] = a.Dr[(size_t)h * a.Nq + tok];
+  }
+  // only ever MFMA operands: they live in the accumulator half of the register file (and have arrived: no wait
+  // for them inside the walk, where one would also wait for the tiles)
+#pragma unroll
+  for (int n = 0; n < 2; ++n) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(f1[n][ks]), "+a"(f2[n][ks]));
+    asm volatile("" : "+v"(nl_fix[n]), "+v"(d_fix[n]));
+  }
+  f32x16 out[2][DT];                       // dQ^T: 32 dims x 32 rows per tile
+#pragma unroll
+  for (int n = 0; n < 2; ++n)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) out[n][dt][v] = 0.0f;
+      asm volatile("" : "+a"(out[n][dt]));
+    }
+
+  // ---- LDS addresses of this lane's operand reads inside ring entry 0 ----------------------------------
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const uint32_t ring_s = __builtin_amdgcn_readfirstlane(smem_lds);
+  uint32_t ra[KS], ta[DT];
+  {
+    const int kb = qn * ROW + ((half ^ swz<CH>(qn)) << 4);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ra[ks] = smem_lds + (uint32_t)(kb ^ (ks << 5));
+    const int s16 = lane & 15, q16 = (lane >> 4) & 1;
+    const int row0 = 4 * half + (s16 >> 2);
+    const int sub = 2 * q16 + ((s16 & 3) >> 1), lo = (s16 & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) ta[dt] = (uint32_t)(row0 * ROW + (((4 * dt + sub) ^ swz<CH>(row0)) << 4) + lo);
+  }
+
+  // ---- staging: the wave brings whole half tiles (32 rows of K and of V, dense rows) ---------------------
+  const int rl = lane / CH;
+  uint32_t so[4];                          // per-lane source offsets of the four instructions of a window
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int r = RPI * k + rl;            // the permutation repeats every 16 rows (8 when a row has 8 chunks)
+    so[k] = (uint32_t)(r * ROW) + (uint32_t)(((lane % CH) ^ swz<CH>(r)) << 4) - (uint32_t)(k * 1024);
+  }
+  const size_t hl = (size_t)h * a.n_loc_cap * a.B * D * 2, hp = (size_t)h * (a.C + 1) * a.B * D * 2;
+  const unsigned char* kl = reinterpret_cast<const unsigned char*>(a.Kl) + hl;
+  const unsigned char* vl = reinterpret_cast<const unsigned char*>(a.Vl) + hl;
+  const unsigned char* kp = reinterpret_cast<const unsigned char*>(a.Kp) + hp;
+  const unsigned char* vp = reinterpret_cast<const unsigned char*>(a.Vp) + hp;
+  auto stage = [&](int u, int entry) {
+    const int t = u >> 1, mg = u & 1;
+    const int where = __builtin_amdgcn_readfirstlane(lst_a[t]);
+    const int last = __builtin_amdgcn_readfirstlane(lst_b[t]) - 1;
+    const size_t off = (size_t)(where & 0x7FFFFFFF) * TILE;
+    const unsigned char* s1 = (where < 0 ? kl : kp) + off;
+    const unsigned char* s2 = (where < 0 ? vl : vp) + off;
+    const uint32_t dst = ring_s + (uint32_t)(entry * TILE);
+    if (last >= 32 * mg + 31) {
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        dma16x4<0>(s1 + 32 * mg * ROW + w * 4096, so[0], so[1], so[2], so[3], dst + w * 4096);
+        dma16x4<0>(s2 + 32 * mg * ROW + w * 4096, so[0], so[1], so[2], so[3], dst + HALF + w * 4096);
+      }
+    } else {                               // rows past the last one that exists are not touched: that row again
+#pragma unroll
+      for (int k = 0; k < 4 * NW; ++k) {
+        const int r = RPI * k + rl, src_row = min(32 * mg + r, last);
+        const uint32_t chunk = (uint32_t)(((lane % CH) ^ swz<CH>(r)) << 4);
+        dma16(s1, (uint32_t)(src_row * ROW) + chunk, dst + k * 1024);
+        dma16(s2, (uint32_t)(src_row * ROW) + chunk, dst + HALF + k * 1024);
+      }
+    }
+  };
+
+  const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  const int n_half = 2 * n_tiles;
+  if (n_half > 0) stage(0, 0);
+  auto turn = [&](auto MG, int t) {
+    constexpr int mg = decltype(MG)::value;
+    const int u = 2 * t + mg, e = mg;      // two turns per tile: the entry is the half
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // half tile u is in (nobody else reads or writes the ring)
+    if (u + 1 < n_half) stage(u + 1, e ^ 1);
+    const int rows = __builtin_amdgcn_readfirstlane(lst_b[t]);
+    const int lim = rows - 32 * mg - 4 * half;
+    const uint32_t off1 = (uint32_t)(e * TILE), off2 = off1 + HALF;
+    bf16x8 x1[KS], x2[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      x1[ks] = lds_read_row(ra[ks] + off1);
+      x2[ks] = lds_read_row(ra[ks] + off2);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 a1[2], a2[2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      a1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[ks], f1[0][ks], ks == 0 ? zero : a1[0], 0, 0, 0);
+      a2[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[0][ks], ks == 0 ? zero : a2[0], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // accumulator element v: key 32 mg + 8 (v / 4) + 4 half + v % 4, query row 32 n + lane % 32.  Keys past the
+    // tile's length hold a copy of its last row and take no part; a query row that does not exist has nl = -inf.
+    u32x4 eZ[2][2];
+    bf16x8 tf[2][DT];
+    auto element = [&](int n, int v, float (&zz)[16]) {
+      const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(a1[n][v], c2, nl_fix[n]));
+      const float pm = 8 * (v / 4) + (v % 4) < lim ? pe : 0.0f;
+      zz[v] = pm * (a2[n][v] - d_fix[n]);
+      if (v % 2 == 1) eZ[n][v / 8][(v % 8) / 2] = pack2(zz[v - 1], zz[v]);
+    };
+    {
+      float zz[16];
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl) {
+        const int ks = sl / 2;
+        if (sl % 2 == 0) a1[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[ks], f1[1][ks], ks == 0 ? zero : a1[1], 0, 0, 0);
+        else a2[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x2[ks], f2[1][ks], ks == 0 ? zero : a2[1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (sl >= NS - 2 * DT) {           // the transposed fragments, asked for over the last slices
+          const int i = sl - (NS - 2 * DT);
+          tf[i / DT][i % DT] = lds_read_tr<ROW, HI_XOR>(smem_lds + (uint32_t)(16 * (i / DT) * ROW) + off1, ta[i % DT]);
+        }
+#pragma unroll
+        for (int q = 0; q < EPS; ++q) element(0, sl * EPS + q, zz);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    asm volatile("s_nop 4" ::: "memory");
+    {
+      float zz[16];
+      constexpr int EP2 = 16 / (2 * DT);   // elements of group 1 behind each second product of group 0
+#pragma unroll
+      for (int i = 0; i < 2 * DT; ++i) {
+        acc_mfma(out[0][i % DT], tf[i / DT][i % DT], as_bf16x8(eZ[0][i / DT]));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < EP2; ++q) element(1, i * EP2 + q, zz);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    asm volatile("s_nop 4" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 2 * DT; ++i) acc_mfma(out[1][i % DT], tf[i / DT][i % DT], as_bf16x8(eZ[1][i / DT]));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  for (int t = 0; t < n_tiles; ++t) {
+    turn(std::integral_constant<int, 0>{}, t);
+    turn(std::integral_constant<int, 1>{}, t);
+  }
+  // the compiler does not see the matrix instructions that wrote the output accumulators: let the pipe drain
+#pragma unroll
+  for (int n = 0; n < 2; ++n)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) asm volatile("s_nop 15\n\ts_nop 15" : "+a"(out[n][dt]));
+#pragma unroll
+  for (int n = 0; n < 2; ++n) {
+    const int frow = 32 * n + qn;
+    if (frow < fixed_len) {
+      float* o = a.dQ + ((size_t)h * a.Nq + (size_t)r_tile * kTile + frow) * D;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4)
+          *reinterpret_cast<float4*>(o + 32 * dt + 8 * v4 + 4 * half) =
+              make_float4(out[n][dt][4 * v4] * a.scale, out[n][dt][4 * v4 + 1] * a.scale, out[n][dt][4 * v4 + 2] * a.scale,
+                          out[n][dt][4 * v4 + 3] * a.scale);
+    }
+  }
+}
+
 template <int D, bool KV>
 hipError_t launch_bwd_t(const BwdArgs& a, dim3 grid, size_t lds, hipStream_t stream) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kernel<D, KV>),
@@ -578,8 +836,17 @@ hipError_t launch_attention_bwd(const pbsa_params& p, const bf16_t* Q, const bf1
   {
     const size_t n_cand = (size_t)(p.C + 1 + p.k) * sub;
     const dim3 grid((p.Nq + kTile - 1) / kTile, p.H);
-    const size_t lds = ring + n_cand * 8 + 16;
-    e = p.d == 128 ? launch_bwd_t<128, false>(a, grid, lds, stream) : launch_bwd_t<64, false>(a, grid, lds, stream);
+    const size_t lds = (size_t)2 * kTile * p.d * 2 + n_cand * 8 + 16;
+    if (p.d == 128) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(bwd_dq_kernel<128>, grid, dim3(64), lds, stream, a);
+    } else {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(bwd_dq_kernel<64>, grid, dim3(64), lds, stream, a);
+    }
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   {
