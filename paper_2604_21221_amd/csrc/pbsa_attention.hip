@@ -65,7 +65,7 @@ constexpr float kInitMax = -1.0e29f;       // reference of a row that has seen n
 // (softmax_settle).  Probabilities thus lie between 2^-126 and 2^kSlack, their sums and products below
 // about 2^90, and after the first sub-tile of a row a new reference needs scores that rise by a factor
 // of 2^(kLift + kSlack).
-constexpr float kSlack = 60.0f;
+[[maybe_unused]] constexpr float kSlack = 60.0f;
 constexpr float kBig = 0x1p60f;            // 2^kSlack
 constexpr float kLift = 40.0f;
 

@@ -5,12 +5,12 @@
 // P is recomputed from the forward's log-sum-exp: exp2(z c2 - lse log2 e); nothing of the forward's
 // probabilities is stored.  Three kernels, no atomics, every output element written by exactly one lane:
 //   prep   D[h][q] = sum_x dO[q][x] O[q][x]                                      (fp32, from the bf16 tensors)
-//   dq     one workgroup per 64 query rows: their Q and dO fragments stay in registers, the 64-key tiles they
-//          attend (persistent slots, then the blocks of their row of sel) stream through LDS
-//   dkv    one workgroup per 64-key tile: its K and V fragments stay in registers, the 64-row tiles of the query
-//          blocks that attend it (all of them for a persistent slot; those whose row of sel names the block
+//   dq     one single-wave workgroup per 64 query rows: their Q and dO fragments stay in registers, the 64-key tiles
+//          they attend (persistent slots, then the blocks of their row of sel) stream through LDS
+//   dkv    one two-wave workgroup per 64-key tile: its K and V fragments stay in registers, the 64-row tiles of the
+//          query blocks that attend it (all of them for a persistent slot; those whose row of sel names the block
 //          otherwise, found by scanning sel) stream through LDS
-// dq and dkv are one template: a fixed side in registers (B operands), a streamed side in LDS (A operands):
+// Both have a fixed side in registers (MFMA B operands) and a streamed side in LDS (A operands):
 //   A1 = T1 F1^T, A2 = T2 F2^T   32 streamed rows x 32 fixed rows per MFMA chain (v_mfma_f32_32x32x16_bf16)
 //          dq:  T1 = K, T2 = V, F1 = Q, F2 = dO   ->  A1 = Z^T / scale, A2 = dP^T     (keys x queries)
 //          dkv: T1 = Q, T2 = dO, F1 = K, F2 = V   ->  A1 = Z / scale,   A2 = dP       (queries x keys)
@@ -18,11 +18,12 @@
 //   accumulators hold them (the contraction index enumerated in accumulator order), and the A operands of the
 //   second products are transposing LDS reads of the streamed tiles with the same enumeration:
 //          dq:  dQ^T += K^T dZ^T          dkv: dK^T += Q^T dZ,  dV^T += dO^T P
-// A workgroup is two waves; wave w owns fixed rows 32 w .. 32 w + 31.  Tiles go from global memory straight to
-// LDS (global_load_lds), half a tile at a time into a ring of four; the 16-byte chunks of
-// a row are permuted by the row number so that both the row-wise and the transposing operand reads are free of
-// bank conflicts.  Rows past a tile's valid length are never loaded: their
-// lanes fetch the last valid row, and the elementwise stage zeroes what belongs to them.
+// Tiles go from global memory straight to LDS (global_load_lds), half a tile (32 streamed rows) per ring entry; the
+// 16-byte chunks of a row are permuted by the row number so that both the row-wise and the transposing operand
+// reads are free of bank conflicts.  Rows past a tile's valid length are never loaded: their lanes fetch the last
+// valid row, and the elementwise stage zeroes what belongs to them.  dq holds 64 fixed rows per wave, so every
+// fragment read from LDS feeds two MFMAs; dkv cannot at d = 128 (two outputs: 256 accumulator registers for 64
+// keys) and holds 32 per wave: it reads one fragment per MFMA and sits at the LDS bandwidth.
 #include <type_traits>
 
 #include "pbsa_internal.h"
@@ -144,17 +145,17 @@ __global__ void __launch_bounds__(256) bwd_prep_kernel(BwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// dq (KV = false) and dkv (KV = true)
+// dkv: one workgroup (two waves) per 64-key tile
 // ------------------------------------------------------------------------------------------------
-template <int D, bool KV>
-__global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
+template <int D>
+__global__ void __launch_bounds__(kThreads) bwd_dkv_kernel(BwdArgs a) {
   constexpr int KS = D / 16, DT = D / 32, ROW = D * 2, TILE = kTile * ROW;
   constexpr int CH = D / 8, RPI = 64 / CH;          // 16-byte chunks per row, rows per load instruction
   constexpr int NI = 32 / RPI;                      // load instructions per wave per tile (its 32 rows)
   constexpr int HI_XOR = CH == 16 ? 16 : 0;         // row + 8 flips the lowest bit of the chunk permutation when it has 4 bits
   extern __shared__ __align__(1024) unsigned char smem[];
   __shared__ int cnt_s[2 * 12];
-  __shared__ __align__(256) float rows_f[4 * 128];  // dkv: per ring entry, lse (64 floats, 32 used) then D of the half tile's rows
+  __shared__ __align__(256) float rows_f[4 * 128];  // per ring entry, lse (64 floats, 32 used) then D of the half tile's rows
   // ring: entry e holds T1 at e * 2 TILE and T2 behind it
   int* lst_a = reinterpret_cast<int*>(smem + 4 * TILE);   // per streamed tile: where it is
   const int SUB = a.B / kTile;
@@ -167,76 +168,50 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   // ---- what this workgroup is, and the list of streamed tiles ------------------------------------
   int n_cand;
   int* lst_b;                              // per streamed tile: its valid rows
-  int* flag_s;                             // dkv: query blocks that attend the key block
-  // dq: 64 query rows; dkv: one 64-key tile, persistent (slot c) or local (logical block l)
-  const int r_tile = blockIdx.x;           // dq: row tile; dkv: key tile index
-  int i_blk = 0, fixed_len = 0, kv_slot_tile = 0;
+  int* flag_s;                             // query blocks that attend the key block
+  // the workgroup's 64-key tile: persistent (slot c) or local (logical block l)
+  const int r_tile = blockIdx.x;
+  int fixed_len = 0, kv_slot_tile = 0;
   bool kv_local = false;
-  if constexpr (!KV) {
-    i_blk = r_tile * kTile / a.B;
-    n_cand = (a.C + 1) * SUB + a.k * SUB;
-    lst_b = lst_a + n_cand;
-    flag_s = lst_b + n_cand;
-    fixed_len = min(kTile, a.Nq - r_tile * kTile);
+  n_cand = a.nqb * SUB;
+  lst_b = lst_a + n_cand;
+  flag_s = lst_b + n_cand;
+  const int n_pers = (a.C + 1) * SUB;
+  kv_local = r_tile >= n_pers;
+  if (!kv_local) {
+    const int c = r_tile / SUB, sub = r_tile % SUB;
+    fixed_len = min(max(min(max(a.p_len[(size_t)h * (a.C + 1) + c], 0), a.B) - sub * kTile, 0), kTile);
+    kv_slot_tile = r_tile;
   } else {
-    n_cand = a.nqb * SUB;
-    lst_b = lst_a + n_cand;
-    flag_s = lst_b + n_cand;
-    const int n_pers = (a.C + 1) * SUB;
-    kv_local = r_tile >= n_pers;
-    if (!kv_local) {
-      const int c = r_tile / SUB, sub = r_tile % SUB;
-      fixed_len = min(max(min(max(a.p_len[(size_t)h * (a.C + 1) + c], 0), a.B) - sub * kTile, 0), kTile);
-      kv_slot_tile = r_tile;
-    } else {
-      const int l = (r_tile - n_pers) / SUB, sub = (r_tile - n_pers) % SUB;
-      const int slot = a.l_map[l];
-      const bool ok = slot >= 0 && slot < a.n_loc_cap;
-      fixed_len = ok ? min(max(min(max(a.l_len[l], 0), a.B) - sub * kTile, 0), kTile) : 0;
-      kv_slot_tile = (ok ? slot : 0) * SUB + sub;
-      for (int i = tid; i < a.nqb; i += kThreads) flag_s[i] = 0;
-      __syncthreads();
-      // the head's rows of sel, eight loads in flight per thread (one at a time the scan is a chain of memory latencies)
-      const int32_t* sel_h = a.sel + (size_t)h * a.nqb * a.k;
-      const int n_sel = a.nqb * a.k;
-      for (int e0 = tid; e0 < n_sel; e0 += 8 * kThreads) {
-        int v[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = e0 + j * kThreads < n_sel ? sel_h[e0 + j * kThreads] : -1;
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (v[j] == l) flag_s[(e0 + j * kThreads) / a.k] = 1;
-      }
-      if (!ok) fixed_len = -1;             // a block that is nowhere: nothing to write either
-    }
+    const int l = (r_tile - n_pers) / SUB, sub = (r_tile - n_pers) % SUB;
+    const int slot = a.l_map[l];
+    const bool ok = slot >= 0 && slot < a.n_loc_cap;
+    fixed_len = ok ? min(max(min(max(a.l_len[l], 0), a.B) - sub * kTile, 0), kTile) : 0;
+    kv_slot_tile = (ok ? slot : 0) * SUB + sub;
+    for (int i = tid; i < a.nqb; i += kThreads) flag_s[i] = 0;
     __syncthreads();
+    // the head's rows of sel, eight loads in flight per thread (one at a time the scan is a chain of memory latencies)
+    const int32_t* sel_h = a.sel + (size_t)h * a.nqb * a.k;
+    const int n_sel = a.nqb * a.k;
+    for (int e0 = tid; e0 < n_sel; e0 += 8 * kThreads) {
+      int v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = e0 + j * kThreads < n_sel ? sel_h[e0 + j * kThreads] : -1;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (v[j] == l) flag_s[(e0 + j * kThreads) / a.k] = 1;
+    }
+    if (!ok) fixed_len = -1;             // a block that is nowhere: nothing to write either
   }
-  if (KV && fixed_len < 0) return;
+  __syncthreads();
+  if (fixed_len < 0) return;
   auto classify = [&](int i, int& where, int& rows) -> bool {
     if (i >= n_cand) return false;
-    if constexpr (!KV) {
-      const int n_pers = (a.C + 1) * SUB;
-      if (i < n_pers) {
-        const int c = i / SUB, sub = i % SUB;
-        rows = min(max(min(max(a.p_len[(size_t)h * (a.C + 1) + c], 0), a.B) - sub * kTile, 0), kTile);
-        where = i;
-        return rows > 0;
-      }
-      const int jj = (i - n_pers) / SUB, sub = (i - n_pers) % SUB;
-      const int l = a.sel[((size_t)h * a.nqb + i_blk) * a.k + jj];
-      if (l < 0 || l >= a.n_loc) return false;
-      const int slot = a.l_map[l];
-      if (slot < 0 || slot >= a.n_loc_cap) return false;
-      rows = min(max(min(max(a.l_len[l], 0), a.B) - sub * kTile, 0), kTile);
-      where = (int)(0x80000000u | (uint32_t)(slot * SUB + sub));
-      return rows > 0;
-    } else {
-      const int ib = i / SUB;
-      if (fixed_len <= 0 || (kv_local && !flag_s[ib])) return false;
-      rows = min(kTile, a.Nq - i * kTile);            // row tile i covers tokens 64 i ..
-      where = i;
-      return rows > 0;
-    }
+    const int ib = i / SUB;
+    if (fixed_len <= 0 || (kv_local && !flag_s[ib])) return false;
+    rows = min(kTile, a.Nq - i * kTile);            // row tile i covers tokens 64 i ..
+    where = i;
+    return rows > 0;
   };
   constexpr int kMaxRounds = 12;           // (2 (C_max + 1) + 2 k_max) / 128 rounded up; dkv needs 8
   const int n_rounds = min((n_cand + kThreads - 1) / kThreads, kMaxRounds);
@@ -268,23 +243,14 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
 
   // ---- fixed fragments (B operands): fixed row 32 w + lane % 32, dims 16 ks + 8 (lane / 32) .. + 8 ----
   bf16x8 f1[KS], f2[KS];
-  float nl_fix = -INFINITY, d_fix = 0.0f;  // dq: this lane's query row
   {
     const int row = min(32 * wave + qn, max(fixed_len, 1) - 1);
     const bf16_t *p1, *p2;
-    if constexpr (!KV) {
-      const int tok = r_tile * kTile + row;
-      p1 = a.Q + (size_t)h * a.q_stride_h + (size_t)tok * a.q_stride_t;
-      p2 = a.dO + (size_t)h * a.o_stride_h + (size_t)tok * a.o_stride_t;
-      const float l = a.lse[(size_t)h * a.Nq + tok];
-      if (32 * wave + qn < fixed_len && l > -INFINITY) nl_fix = -l * kLog2e;
-      d_fix = a.Dr[(size_t)h * a.Nq + tok];
-    } else {
-      const size_t base = kv_local ? ((size_t)h * a.n_loc_cap * a.B + (size_t)kv_slot_tile * kTile) * D
-                                   : ((size_t)h * (a.C + 1) * a.B + (size_t)kv_slot_tile * kTile) * D;
-      p1 = (kv_local ? a.Kl : a.Kp) + base + (size_t)row * D;
-      p2 = (kv_local ? a.Vl : a.Vp) + base + (size_t)row * D;
-    }
+    const size_t base = kv_local ? ((size_t)h * a.n_loc_cap * a.B + (size_t)kv_slot_tile * kTile) * D
+                                 : ((size_t)h * (a.C + 1) * a.B + (size_t)kv_slot_tile * kTile) * D;
+    p1 = (kv_local ? a.Kl : a.Kp) + base + (size_t)row * D;
+    p2 = (kv_local ? a.Vl : a.Vp) + base + (size_t)row * D;
+  
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       f1[ks] = *reinterpret_cast<const bf16x8*>(p1 + 16 * ks + 8 * half);
@@ -294,9 +260,8 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   // they have arrived before the walk starts: no wait for them inside it, where one would also wait for the tiles
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(f1[ks]), "+v"(f2[ks]));
-  asm volatile("" : "+v"(nl_fix), "+v"(d_fix));
 
-  f32x16 out1[DT], out2[DT];               // dq: dQ^T; dkv: dK^T and dV^T   (32 dims x 32 fixed rows each)
+  f32x16 out1[DT], out2[DT];               // dK^T and dV^T   (32 dims x 32 keys each)
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -307,7 +272,7 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) {
     asm volatile("" : "+a"(out1[dt]));
-    if constexpr (KV) asm volatile("" : "+a"(out2[dt]));
+    asm volatile("" : "+a"(out2[dt]));
   }
 
   // ---- LDS addresses of this lane's operand reads inside ring entry 0 -------------------------------
@@ -332,24 +297,15 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
   // number of loads per half tile, so that one count serves the wait; past the end of the list the last half tile
   // is fetched again into an entry whose contents are never used.
   constexpr int HALF = TILE / 2, RING = 4, NH = NI / 2;    // NH: load instructions per wave, tensor and half tile
-  constexpr int PER = 2 * NH + (KV ? 2 : 0);               // loads per wave and half tile
+  constexpr int PER = 2 * NH + 2;               // loads per wave and half tile
   const int rl = lane / CH;
   const int n_half = 2 * n_tiles;
   long st1, st2;                           // row strides of the streamed tensors in bytes
   const unsigned char *b1l, *b2l, *b1p, *b2p;
-  if constexpr (!KV) {
-    st1 = st2 = ROW;
-    const size_t hl = (size_t)h * a.n_loc_cap * a.B * D * 2, hp = (size_t)h * (a.C + 1) * a.B * D * 2;
-    b1l = reinterpret_cast<const unsigned char*>(a.Kl) + hl;
-    b2l = reinterpret_cast<const unsigned char*>(a.Vl) + hl;
-    b1p = reinterpret_cast<const unsigned char*>(a.Kp) + hp;
-    b2p = reinterpret_cast<const unsigned char*>(a.Vp) + hp;
-  } else {
-    st1 = a.q_stride_t * 2;
-    st2 = a.o_stride_t * 2;
-    b1l = b1p = reinterpret_cast<const unsigned char*>(a.Q + (size_t)h * a.q_stride_h);
-    b2l = b2p = reinterpret_cast<const unsigned char*>(a.dO + (size_t)h * a.o_stride_h);
-  }
+  st1 = a.q_stride_t * 2;
+  st2 = a.o_stride_t * 2;
+  b1l = b1p = reinterpret_cast<const unsigned char*>(a.Q + (size_t)h * a.q_stride_h);
+  b2l = b2p = reinterpret_cast<const unsigned char*>(a.dO + (size_t)h * a.o_stride_h);
   // per-lane source offsets of the wave's instructions within a half tile whose 32 rows all exist
   uint32_t so1[NH], so2[NH];
 #pragma unroll
@@ -384,12 +340,11 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
         dma16(s2, (uint32_t)(src_row * st2) + chunk, dst + HALF + k * 1024);
       }
     }
-    if constexpr (KV) {
-      // lse and D of the half's 32 rows, as they are (lanes 32..63 repeat lanes 0..31; both waves bring the same)
-      const int tok = min(where * kTile + min(32 * mg + qn, last), a.Nq - 1);
-      dma4(a.lse + (size_t)h * a.Nq, (uint32_t)tok * 4u, rows_s + (uint32_t)(entry * 512));
-      dma4(a.Dr + (size_t)h * a.Nq, (uint32_t)tok * 4u, rows_s + (uint32_t)(entry * 512 + 256));
-    }
+    // lse and D of the half's 32 rows, as they are (lanes 32..63 repeat lanes 0..31; both waves bring the same)
+    const int tok = min(where * kTile + min(32 * mg + qn, last), a.Nq - 1);
+    dma4(a.lse + (size_t)h * a.Nq, (uint32_t)tok * 4u, rows_s + (uint32_t)(entry * 512));
+    dma4(a.Dr + (size_t)h * a.Nq, (uint32_t)tok * 4u, rows_s + (uint32_t)(entry * 512 + 256));
+  
   };
 
   // ---- the walk: a software pipeline over half tiles ---------------------------------------------------
@@ -434,19 +389,18 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
       x1[ks] = lds_read_row(ra[ks] + offn);
       x2[ks] = lds_read_row(ra[ks] + offn + HALF);
     }
-    // Row scalars (dkv) and the transposed fragments are asked for inside the slices, shortly before they are
+    // Row scalars and the transposed fragments are asked for inside the slices, shortly before they are
     // needed: the scalars of four streamed rows two slices ahead of their first use, the fragments two (one) per
     // slice over the second half of the slices, when the row fragments they replace in the register file are dead.
     float nlv[16], dv[16];
     auto fetch_scalars = [&](int g) {      // rows 8 g + 4 half .. + 3 of the half tile: elements 4 g .. 4 g + 3
-      if constexpr (KV) {
-        const float4 n4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 8 * g + 4 * half]);
-        const float4 d4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 64 + 8 * g + 4 * half]);
-        nlv[4 * g] = n4.x; nlv[4 * g + 1] = n4.y; nlv[4 * g + 2] = n4.z; nlv[4 * g + 3] = n4.w;
-        dv[4 * g] = d4.x; dv[4 * g + 1] = d4.y; dv[4 * g + 2] = d4.z; dv[4 * g + 3] = d4.w;
-      }
+      const float4 n4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 8 * g + 4 * half]);
+      const float4 d4 = *reinterpret_cast<const float4*>(&rows_f[e * 128 + 64 + 8 * g + 4 * half]);
+      nlv[4 * g] = n4.x; nlv[4 * g + 1] = n4.y; nlv[4 * g + 2] = n4.z; nlv[4 * g + 3] = n4.w;
+      dv[4 * g] = d4.x; dv[4 * g + 1] = d4.y; dv[4 * g + 2] = d4.z; dv[4 * g + 3] = d4.w;
+    
     };
-    constexpr int NTF = (KV ? 2 : 1) * 2 * DT, TPS = NTF / (NS / 2);   // transposed fragments, per slice of the second half
+    constexpr int NTF = 2 * 2 * DT, TPS = NTF / (NS / 2);   // transposed fragments, per slice of the second half
     static_assert(TPS * (NS / 2) == NTF, "the transposed reads spread evenly");
     bf16x8 tf[NTF];                        // [tensor][j][dt]
     fetch_scalars(0);
@@ -479,12 +433,12 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
 #pragma unroll
       for (int q = 0; q < EPS; ++q) {
         const int v = sl * EPS + q;
-        const float nl = KV ? -nlv[v] * kLog2e : nl_fix, dd = KV ? dv[v] : d_fix;
+        const float nl = -nlv[v] * kLog2e, dd = dv[v];
         const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c1[v], c2, nl));
         pz[v] = 8 * (v / 4) + (v % 4) < lim ? pe : 0.0f;
         zz[v] = pz[v] * (c2a[v] - dd);
         if (v % 2 == 1) {
-          if constexpr (KV) eP[v / 8][(v % 8) / 2] = pack2(pz[v - 1], pz[v]);
+          eP[v / 8][(v % 8) / 2] = pack2(pz[v - 1], pz[v]);
           eZ[v / 8][(v % 8) / 2] = pack2(zz[v - 1], zz[v]);
         }
       }
@@ -496,7 +450,7 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         acc_mfma(out1[dt], tf[j * DT + dt], as_bf16x8(eZ[j]));
-        if constexpr (KV) acc_mfma(out2[dt], tf[(2 + j) * DT + dt], as_bf16x8(eP[j]));
+        acc_mfma(out2[dt], tf[(2 + j) * DT + dt], as_bf16x8(eP[j]));
       }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -512,39 +466,26 @@ __global__ void __launch_bounds__(kThreads) bwd_kernel(BwdArgs a) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) {
     asm volatile("s_nop 15\n\ts_nop 15" : "+a"(out1[dt]));
-    if constexpr (KV) asm volatile("" : "+a"(out2[dt]));
+    asm volatile("" : "+a"(out2[dt]));
   }
 
   // ---- outputs: element v of tile dt is dim 32 dt + 8 (v / 4) + 4 half + v % 4 of fixed row 32 w + lane % 32 ----
   const int frow = 32 * wave + qn;
-  if constexpr (!KV) {
-    if (frow < fixed_len) {
-      float* o = a.dQ + ((size_t)h * a.Nq + (size_t)r_tile * kTile + frow) * D;
+  // every row of the tile's slot is written: zeros past the valid length and for a block nobody attends
+  const size_t base = kv_local ? ((size_t)h * a.n_loc_cap * a.B + (size_t)kv_slot_tile * kTile) * D
+                               : ((size_t)h * (a.C + 1) * a.B + (size_t)kv_slot_tile * kTile) * D;
+  float* ok_ = (kv_local ? a.dKl : a.dKp) + base + (size_t)frow * D;
+  float* ov_ = (kv_local ? a.dVl : a.dVp) + base + (size_t)frow * D;
+  const float sc = frow < fixed_len ? a.scale : 0.0f, one = frow < fixed_len ? 1.0f : 0.0f;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+  for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4)
-          *reinterpret_cast<float4*>(o + 32 * dt + 8 * v4 + 4 * half) =
-              make_float4(out1[dt][4 * v4] * a.scale, out1[dt][4 * v4 + 1] * a.scale, out1[dt][4 * v4 + 2] * a.scale,
-                          out1[dt][4 * v4 + 3] * a.scale);
+    for (int v4 = 0; v4 < 4; ++v4) {
+      *reinterpret_cast<float4*>(ok_ + 32 * dt + 8 * v4 + 4 * half) =
+          make_float4(out1[dt][4 * v4] * sc, out1[dt][4 * v4 + 1] * sc, out1[dt][4 * v4 + 2] * sc, out1[dt][4 * v4 + 3] * sc);
+      *reinterpret_cast<float4*>(ov_ + 32 * dt + 8 * v4 + 4 * half) =
+          make_float4(out2[dt][4 * v4] * one, out2[dt][4 * v4 + 1] * one, out2[dt][4 * v4 + 2] * one, out2[dt][4 * v4 + 3] * one);
     }
-  } else {
-    // every row of the tile's slot is written: zeros past the valid length and for a block nobody attends
-    const size_t base = kv_local ? ((size_t)h * a.n_loc_cap * a.B + (size_t)kv_slot_tile * kTile) * D
-                                 : ((size_t)h * (a.C + 1) * a.B + (size_t)kv_slot_tile * kTile) * D;
-    float* ok_ = (kv_local ? a.dKl : a.dKp) + base + (size_t)frow * D;
-    float* ov_ = (kv_local ? a.dVl : a.dVp) + base + (size_t)frow * D;
-    const float sc = frow < fixed_len ? a.scale : 0.0f, one = frow < fixed_len ? 1.0f : 0.0f;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        *reinterpret_cast<float4*>(ok_ + 32 * dt + 8 * v4 + 4 * half) =
-            make_float4(out1[dt][4 * v4] * sc, out1[dt][4 * v4 + 1] * sc, out1[dt][4 * v4 + 2] * sc, out1[dt][4 * v4 + 3] * sc);
-        *reinterpret_cast<float4*>(ov_ + 32 * dt + 8 * v4 + 4 * half) =
-            make_float4(out2[dt][4 * v4] * one, out2[dt][4 * v4 + 1] * one, out2[dt][4 * v4 + 2] * one, out2[dt][4 * v4 + 3] * one);
-      }
-  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -805,12 +746,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   }
 }
 
-template <int D, bool KV>
-hipError_t launch_bwd_t(const BwdArgs& a, dim3 grid, size_t lds, hipStream_t stream) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_kernel<D, KV>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+template <typename K>
+hipError_t launch_with_lds(K kernel, const BwdArgs& a, dim3 grid, int threads, size_t lds, hipStream_t stream) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_kernel<D, KV>), grid, dim3(kThreads), lds, stream, a);
+  hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, stream, a);
   return hipGetLastError();
 }
 
@@ -837,23 +777,16 @@ hipError_t launch_attention_bwd(const pbsa_params& p, const bf16_t* Q, const bf1
     const size_t n_cand = (size_t)(p.C + 1 + p.k) * sub;
     const dim3 grid((p.Nq + kTile - 1) / kTile, p.H);
     const size_t lds = (size_t)2 * kTile * p.d * 2 + n_cand * 8 + 16;
-    if (p.d == 128) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL(bwd_dq_kernel<128>, grid, dim3(64), lds, stream, a);
-    } else {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL(bwd_dq_kernel<64>, grid, dim3(64), lds, stream, a);
-    }
-    e = hipGetLastError();
+    e = p.d == 128 ? launch_with_lds(bwd_dq_kernel<128>, a, grid, 64, lds, stream)
+                   : launch_with_lds(bwd_dq_kernel<64>, a, grid, 64, lds, stream);
     if (e != hipSuccess) return e;
   }
   {
     const size_t n_cand = (size_t)p.nqb * sub;
     const dim3 grid((p.C + 1 + p.n_loc) * sub, p.H);
     const size_t lds = ring + n_cand * 8 + (size_t)p.nqb * 4 + 16;
-    e = p.d == 128 ? launch_bwd_t<128, true>(a, grid, lds, stream) : launch_bwd_t<64, true>(a, grid, lds, stream);
+    e = p.d == 128 ? launch_with_lds(bwd_dkv_kernel<128>, a, grid, kThreads, lds, stream)
+                   : launch_with_lds(bwd_dkv_kernel<64>, a, grid, kThreads, lds, stream);
   }
   return e;
 }
