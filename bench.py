@@ -215,7 +215,7 @@ def bench_backward(w, c, Q_at, g_next, n_ring, dev, K, W, settle):
             "wall_ms_per_call": round(wall * 1e3, 5), "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": f"{w.name} steady state, backward of one attention call: H={w.H} d={w.d} B={w.B} "
                                    f"Nq={w.Nq} C={w.C}+summary k={w.k}", "executed_gflop": round(flops / 1e9, 3),
-                       "kernels": "bwd_prep_kernel, bwd_kernel<dq>, bwd_kernel<dkv>", "gradient_bytes_written": out_bytes},
+                       "kernels": "bwd_prep_kernel, bwd_dq_kernel, bwd_dkv_kernel", "gradient_bytes_written": out_bytes},
             "roofline": {"bound": "mfma", "achieved": round(flops / us / 1e6, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(flops / us / 1e6 / PEAK_BF16_TFLOPS, 5), "traffic": None}}
 
