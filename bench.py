@@ -244,6 +244,10 @@ def main():
                          "then pbsa_memory_update_apply after it) instead of pbsa_memory_update after the attention call; "
                          "measured slower: the second queue's workgroups keep the attention launch from filling the chip "
                          "in one round")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="the step as three calls, pbsa_select_blocks -> pbsa_attention_fwd -> pbsa_memory_update, instead of "
+                         "the default pbsa_select_blocks -> pbsa_attention_fwd_plan (the attention launch with one more "
+                         "workgroup per head that takes the update's decisions) -> pbsa_memory_update_apply")
     ap.add_argument("--fine-mass", action="store_true",
                     help="the step with the persistent set ranked by the attention actually paid: after the attention "
                          "call pbsa_attention_mass sums the probabilities per key block and pbsa_memory_update_fine "
@@ -318,6 +322,7 @@ def main():
 
     n_done = [0]
     overlap = args.overlap_update and not args.fine_mass      # the mass-ranked update needs the attention call's output
+    fused = not (args.separate_update or overlap or args.fine_mass)
 
     def one_step(i, attn_ev=None, sel_ev=None, upd_ev=None, mass_ev=None):
         # the producer has written the next chunk's K/V into the ring position that was just freed
@@ -347,6 +352,8 @@ def main():
             attn_ev[0].record(stream)
         if args.fine_mass:
             _, Mt = c.attention_with_mass(Qd, O, lse)      # the attention kernel records the masses, a short kernel sums them
+        elif fused:
+            c.attention_with_plan(Qd, O)                   # scoring and retention by extra workgroups of this launch
         else:
             c.attention(Qd, O)
         if attn_ev is not None:
@@ -362,7 +369,7 @@ def main():
             upd_ev[0].record(stream)
         if args.fine_mass:
             c.update_fine(Mt)
-        elif overlap:
+        elif overlap or fused:
             c.update_apply()
         else:
             c.update()
@@ -410,7 +417,7 @@ def main():
         folded = occupied + w.H * w.nqb - min(w.H * w.C, occupied + w.H * w.nqb)
         # what the ranking reads: the coarse logits, or the candidates' rows of the mass matrix
         ranked = (w.H * (w.C + w.nqb) * ((w.nqb + 3) & ~3) * 4 if args.fine_mass else
-                  0 if overlap else w.H * w.nqb * n_loc * 4)      # the apply call reads no scores
+                  0 if overlap or fused else w.H * w.nqb * n_loc * 4)      # the apply call reads no scores
         upd_bytes.append(ranked + folded * 2 * blk + promoted * 4 * blk
                          + w.H * (2 * 2 * w.B * w.d * 4 + 2 * blk))
     upd_b = float(np.mean(upd_bytes))
@@ -437,6 +444,14 @@ def main():
                                    "unit": "GB/s", "frac": round(upd_b / upd_us / 1e3 / PEAK_HBM_GBS, 4)},
             "note": f"{K2} steps after the timed region, HIP events around each call"},
     }
+    if fused:
+        out["config"]["schedule"] = ("pbsa_select_blocks -> pbsa_attention_fwd_plan (attention + one workgroup per head taking the "
+                                     "update's decisions, Eq. 7-9) -> pbsa_memory_update_apply (fold, promote)")
+        out["roofline"]["kernel"] = ("pbsa_attention_fwd_plan: the attention kernel's launch, FLOPs of the attention only "
+                                     "(the decision workgroups run on SIMDs the attention leaves free)")
+        u = out["hbm_bound_calls"].pop("pbsa_memory_update")
+        u["note"] = "the apply call alone; the decisions are taken inside the attention launch"
+        out["hbm_bound_calls"]["pbsa_memory_update_apply"] = u
     if overlap:
         out["config"]["schedule"] = ("pbsa_memory_update_plan (scoring, retention) on a second stream under the attention kernel, "
                                      "pbsa_memory_update_apply (fold, promote) after it")

@@ -171,6 +171,20 @@ int pbsa_memory_update_plan(const pbsa_params* p, const float* Qc, const float* 
 int pbsa_memory_update_apply(const pbsa_params* p, void* Kp, void* Vp, int32_t* p_len, float* S_sum, const int32_t* S_cnt,
                              const void* Kl, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* pbsa_attention_fwd and pbsa_memory_update_plan of the same chunk as ONE launch (Alg. 1 with the update's
+ * decisions, Eq. 7-9, taken while the fine stage of Eq. 3-5 runs): the attention's grid gets H more workgroups, one
+ * per head, that do the plan call's work.  Nothing they read is written by the attention part and the other way
+ * round, so the results are those of the two calls, bit for bit; a launch whose attention workgroups do not fill
+ * the GPU (two workgroups of 128 query rows per compute unit) has the plan's work for free.  Arguments: those of
+ * pbsa_attention_fwd (p->C <= PBSA_MAX_C here), then those of pbsa_memory_update_plan that it does not have yet;
+ * Zl is required (PBSA_EINVAL without), ws as for pbsa_memory_update.  pbsa_memory_update_apply completes the
+ * update. */
+int pbsa_attention_fwd_plan(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                            const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                            const int32_t* sel, void* O, float* lse, const float* Qc, const float* Kc_l,
+                            const float* Zl, float* Kc_p, int64_t* p_id, int32_t* S_cnt, const int64_t* l_id,
+                            float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Attention mass per key block (the fine-grained counterpart of Eq. 7: the attention of Eq. 3-5 as it was
  * actually paid, mask included, summed block by block).  Key blocks are numbered u = slot for the persistent
  * slots 0..C (the summary is u = C) and u = C + 1 + l for local block l.

@@ -17,7 +17,8 @@ BUILD_DIR = os.path.join(ROOT, "_build")
 SOURCES = {
     "pbsa_api.hip": [],
     "pbsa_coarse.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
-    "pbsa_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    # the attention launch can carry the update's decisions (pbsa_plan_device.h): correctly rounded division for those
+    "pbsa_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fhip-fp32-correctly-rounded-divide-sqrt"],
     "pbsa_layout.hip": [],
     "pbsa_mass.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "pbsa_backward.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],

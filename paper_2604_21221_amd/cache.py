@@ -264,10 +264,12 @@ class PbsaCache:
                                      self.S_cnt, l_len, l_map, l_id, self.scores, self.slot_src, self.ws,
                                      stream=self._side)
         self._ev_plan.record(self._side)
+        self._plan_on_side = True
 
     def update_apply(self):
         """Waits (on the device) for the plan, then fold, promote, commit; slides the window."""
-        torch.cuda.current_stream(self.dev).wait_event(self._ev_plan)
+        if self._plan_on_side:                 # the plan ran on another stream
+            torch.cuda.current_stream(self.dev).wait_event(self._ev_plan)
         pbsa.pbsa_memory_update_apply(self._plan_p, self.Kp, self.Vp, self.p_len, self.S_sum, self.S_cnt, self.Kl, self.Vl,
                                       self.ws)
         ne = self._plan_p.n_evict
@@ -276,6 +278,30 @@ class PbsaCache:
             self.chunk_ids.pop(0)
             self.stale_from = self.n_loc
         return ne
+
+    def attention_with_plan(self, Q, O=None, lse=None):
+        """pbsa_attention_fwd_plan: the attention of the chunk and, by extra workgroups of the same launch, the
+        decisions of the update that follows it (needs the logits the selection call left).  update_apply()
+        completes the update."""
+        if O is None:
+            O = torch.empty_like(Q)
+        l_map, l_len, l_id = self._device_maps(want_ids=True)
+        self._plan_p = self.params(n_evict=self.n_evict_now(), Q=Q, O=O)
+        pbsa.pbsa_attention_fwd_plan(self._plan_p, Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map, self.sel,
+                                     O, lse, self.Qc, self.Kc_l, self.Zl, self.Kc_p, self.p_id, self.S_cnt, l_id,
+                                     self.scores, self.slot_src, self.ws)
+        self._plan_on_side = False
+        return O
+
+    def step_fused(self, Q, K=None, V=None, chunk_id=None, O=None, lse=None):
+        """The step as two launches after the selection: attention with the update's decisions, then fold /
+        promote.  K = V = None: the chunk has been adopted already."""
+        if K is not None:
+            self.append_chunk(K, V, chunk_id)
+        self.select(Q)
+        O = self.attention_with_plan(Q, O, lse)
+        self.update_apply()
+        return O
 
     def step_overlapped(self, Q, K=None, V=None, chunk_id=None, O=None, lse=None):
         """The same step with the update's decisions taken on a second stream while the attention kernel runs

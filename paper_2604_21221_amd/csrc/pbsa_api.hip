@@ -196,6 +196,35 @@ int pbsa_memory_update_plan(const pbsa_params* p, const float* Qc, const float* 
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
+int pbsa_attention_fwd_plan(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
+                            const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                            const int32_t* sel, void* O, float* lse, const float* Qc, const float* Kc_l,
+                            const float* Zl, float* Kc_p, int64_t* p_id, int32_t* S_cnt, const int64_t* l_id,
+                            float* scores, int32_t* slot_src, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O) return PBSA_EINVAL;
+  if (p->k > 0 && !sel) return PBSA_EINVAL;
+  if (!Qc || !Kc_l || !Zl || !l_id) return PBSA_EINVAL;
+  if (p->C > 0 && (!Kc_p || !p_id || !slot_src)) return PBSA_EINVAL;
+  rc = check_strides(p->q_stride_h, p->q_stride_t, p);
+  if (rc) return rc;
+  rc = check_strides(p->o_stride_h, p->o_stride_t, p);
+  if (rc) return rc;
+  if (!aligned16(Q) || !aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(O) ||
+      !aligned16(Kc_l) || !aligned16(Kc_p) || !aligned16(Qc))
+    return PBSA_EALIGN;
+  if (!ws || ws_bytes < workspace_bytes(*p)) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  const pbsa::UpdateWs w = pbsa::carve_update_ws(*p, ws);
+  hipError_t e = pbsa::launch_attention_plan(
+      *p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kp),
+      static_cast<const pbsa::bf16_t*>(Vp), p_len, static_cast<const pbsa::bf16_t*>(Kl),
+      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, sel, static_cast<pbsa::bf16_t*>(O), lse, Qc, Kc_l, Zl, Kc_p,
+      p_id, S_cnt, S_cnt != nullptr, l_id, scores, slot_src, w, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
 int pbsa_memory_update_apply(const pbsa_params* p, void* Kp, void* Vp, int32_t* p_len, float* S_sum, const int32_t* S_cnt,
                              const void* Kl, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream) {
   int rc = check_common(p);

@@ -40,6 +40,7 @@
 // the row sums (over the bf16-rounded probabilities, the numbers the second product uses) and the check
 // that the reference still serves come at the start of the next step (softmax_settle).
 #include "pbsa_internal.h"
+#include "pbsa_plan_device.h"
 
 namespace pbsa {
 namespace {
@@ -516,8 +517,23 @@ __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const 
 
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
-template <int D, int B, bool MASS>
-__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) attention_kernel(AttnArgs a) {
+// What the extra workgroups of a launch with PLAN need: the argument blocks of the update's decisions.
+template <bool PLAN>
+struct PlanArgs {};
+template <>
+struct PlanArgs<true> {
+  plan_dev::ScoreArgs sa;
+  plan_dev::RetainArgs ra;
+};
+
+// PLAN: the grid has H more workgroups behind those of the attention, one per head, which take the decisions of
+// the memory update (Eq. 7-9: scoring, retention, slot assignment) while the attention runs.  They read the
+// cache's metadata and pooled keys and what the selection call left, never K / V or the attention's output, and
+// a one-round launch leaves them SIMDs to run on (two workgroups per CU, 128 rows each: at 4680 rows and 12
+// heads 444 of 512 places are taken).
+template <int D, int B, bool MASS, bool PLAN>
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   constexpr int G = kRowsPerWg / B;        // query blocks per workgroup
   constexpr int SUB = B / kTile;           // 64-key tiles per block
   constexpr int KS = Geo<D>::KS, DT = Geo<D>::DT, TILE = Geo<D>::TILE_BYTES, ROW = Geo<D>::ROW;
@@ -540,6 +556,17 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
   const int n_qt = (a.Nq + kRowsPerWg - 1) / kRowsPerWg;
   const int n_wg = a.H * n_qt;
   const int per = (n_wg + 7) / 8;
+  if constexpr (PLAN) {
+    if ((int)blockIdx.x >= 8 * per) {
+      const int hp = (int)blockIdx.x - 8 * per;
+      static_assert(plan_dev::score_head_lds_bytes<D, kThreads>(PBSA_MAX_N_LOC) <= SMEM, "scoring scratch must fit");
+      static_assert(sizeof(plan_dev::RetainLds) <= SMEM, "retention scratch must fit");
+      plan_dev::score_head_body<D, kThreads>(pl.sa, hp, smem);
+      __syncthreads();                     // the head's rows are written, and the scoring scratch is dead
+      plan_dev::retain_body<kThreads>(pl.ra, hp, *reinterpret_cast<plan_dev::RetainLds*>(smem));
+      return;
+    }
+  }
   const int logical = (blockIdx.x % 8) * per + blockIdx.x / 8;
   if (logical >= n_wg) return;
   const int h = logical / n_qt;
@@ -916,27 +943,51 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1
 
 }  // namespace
 
-template <bool MASS>
-static void launch_attention_t(const pbsa_params& p, const AttnArgs& a, dim3 grid, hipStream_t stream) {
+template <bool MASS, bool PLAN>
+static void launch_attention_t(const pbsa_params& p, const AttnArgs& a, const PlanArgs<PLAN>& pl, dim3 grid,
+                               hipStream_t stream) {
   const dim3 block(kThreads);
-  if (p.d == 128 && p.B == 128) hipLaunchKernelGGL((attention_kernel<128, 128, MASS>), grid, block, 0, stream, a);
-  else if (p.d == 128 && p.B == 64) hipLaunchKernelGGL((attention_kernel<128, 64, MASS>), grid, block, 0, stream, a);
-  else if (p.d == 64 && p.B == 128) hipLaunchKernelGGL((attention_kernel<64, 128, MASS>), grid, block, 0, stream, a);
-  else hipLaunchKernelGGL((attention_kernel<64, 64, MASS>), grid, block, 0, stream, a);
+  if (p.d == 128 && p.B == 128) hipLaunchKernelGGL((attention_kernel<128, 128, MASS, PLAN>), grid, block, 0, stream, a, pl);
+  else if (p.d == 128 && p.B == 64) hipLaunchKernelGGL((attention_kernel<128, 64, MASS, PLAN>), grid, block, 0, stream, a, pl);
+  else if (p.d == 64 && p.B == 128) hipLaunchKernelGGL((attention_kernel<64, 128, MASS, PLAN>), grid, block, 0, stream, a, pl);
+  else hipLaunchKernelGGL((attention_kernel<64, 64, MASS, PLAN>), grid, block, 0, stream, a, pl);
+}
+
+static AttnArgs attn_args(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp, const int32_t* p_len,
+                          const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len, const int32_t* l_map,
+                          const int32_t* sel, bf16_t* O, float* lse, const MassRows* rows) {
+  return AttnArgs{p.H, p.Nq, p.nqb, p.n_loc, p.n_loc_cap, p.C, p.k, p.scale, p.q_stride_h, p.q_stride_t,
+                  p.o_stride_h, p.o_stride_t, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse,
+                  rows ? rows->R : nullptr, rows ? rows->list : nullptr, rows ? rows->r_slots : 0,
+                  rows ? rows->list_cap : 0};
 }
 
 hipError_t launch_attention(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
                             const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
                             const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, const MassRows* rows,
                             hipStream_t stream) {
-  AttnArgs a{p.H, p.Nq, p.nqb, p.n_loc, p.n_loc_cap, p.C, p.k, p.scale, p.q_stride_h, p.q_stride_t,
-             p.o_stride_h, p.o_stride_t, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse,
-             rows ? rows->R : nullptr, rows ? rows->list : nullptr, rows ? rows->r_slots : 0,
-             rows ? rows->list_cap : 0};
+  const AttnArgs a = attn_args(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse, rows);
   const int n_wg = p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
   const dim3 grid(8 * ((n_wg + 7) / 8));
-  if (rows) launch_attention_t<true>(p, a, grid, stream);
-  else launch_attention_t<false>(p, a, grid, stream);
+  if (rows) launch_attention_t<true, false>(p, a, PlanArgs<false>{}, grid, stream);
+  else launch_attention_t<false, false>(p, a, PlanArgs<false>{}, grid, stream);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_plan(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
+                                 const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
+                                 const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, const float* Qc,
+                                 const float* Kc_l, const float* Zl, float* Kc_p, int64_t* p_id, int32_t* S_cnt, int fold,
+                                 const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
+                                 hipStream_t stream) {
+  const AttnArgs a = attn_args(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse, nullptr);
+  PlanArgs<true> pl;
+  pl.sa = plan_dev::make_score_args(p, Qc, Kc_l, Zl, Kc_p, p_len, l_map, ws);
+  pl.ra = plan_dev::make_retain_args(p, ws.A, p.C + p.n_loc, 0, Kc_l, Kc_p, p_len, p_id, S_cnt, fold, l_len, l_map, l_id,
+                                     scores, slot_src, ws);
+  const int n_wg = p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
+  const dim3 grid(8 * ((n_wg + 7) / 8) + p.H);
+  launch_attention_t<false, true>(p, a, pl, grid, stream);
   return hipGetLastError();
 }
 

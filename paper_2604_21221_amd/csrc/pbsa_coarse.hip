@@ -10,9 +10,12 @@
 // written (the arithmetic that decides block sets and slots is specified operation by operation
 // in pbsa.h so that an independent implementation reproduces the integers bit for bit).
 #include "pbsa_internal.h"
+#include "pbsa_plan_device.h"
 
 namespace pbsa {
 namespace {
+
+using namespace plan_dev;
 
 constexpr int kThreads = 256;
 constexpr int kXC = 32;   // pooled-key dimensions staged through LDS per step
@@ -26,21 +29,6 @@ __device__ __forceinline__ uint32_t f2bf_rne(float f) {
   return u >> 16;
 }
 
-// exp(x) for x <= 0 from fp32 mul / fma / rint only (steps fixed in pbsa.h).
-__device__ __forceinline__ float pexp(float x) {
-  if (x < -64.0f) return 0.0f;
-  float n = __builtin_rintf(x * 0x1.715476p+0f);
-  float r = __builtin_fmaf(n, -0x1.630000p-1f, x);
-  r = __builtin_fmaf(n, 0x1.bd0106p-13f, r);
-  float p = 0x1.6c16c2p-10f;
-  p = __builtin_fmaf(p, r, 0x1.111112p-7f);
-  p = __builtin_fmaf(p, r, 0x1.555556p-5f);
-  p = __builtin_fmaf(p, r, 0x1.555556p-3f);
-  p = __builtin_fmaf(p, r, 0.5f);
-  p = __builtin_fmaf(p, r, 1.0f);
-  p = __builtin_fmaf(p, r, 1.0f);
-  return p * __uint_as_float((uint32_t)((int)n + 127) << 23);
-}
 
 // ------------------------------------------------------------------------------------------------
 // Pooling.  One job = one block; D/2 threads per job, each owning 2 dimensions (one 4-byte load per
@@ -169,9 +157,6 @@ __device__ __forceinline__ void coarse_dots(const float* const* cols, int n_cols
   }
 }
 
-__device__ __forceinline__ int lanes_below(uint64_t mask) {   // set bits of `mask` in lanes below this one
-  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-}
 
 struct SelectArgs {
   int H, nqb, n_loc, n_loc_cap, k, causal;
@@ -323,17 +308,6 @@ __global__ void __launch_bounds__(64 * NM) select_kernel(SelectArgs a) {
 // slot order, then all local blocks.  Row softmax in the pinned order; the sum runs sequentially
 // over the row in LDS.
 // ------------------------------------------------------------------------------------------------
-struct ScoreArgs {
-  int H, nqb, nqb_pad, n_loc, n_loc_cap, C, nU_max, n_evict;
-  float scale;
-  const float* Kc_l;
-  const float* Kc_p;
-  const float* Qc;
-  const float* Zl;          // optional: scaled local logits [H][nqb][n_loc] from the selection call
-  const int32_t* l_map;
-  const int32_t* p_len;
-  float* A;
-};
 
 template <int D, int NM>
 __global__ void __launch_bounds__(kThreads) score_rows_kernel(ScoreArgs a) {
@@ -476,222 +450,12 @@ __global__ void __launch_bounds__(kThreads) score_rows_z_kernel(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Retention (Eq. 8-9): one workgroup per head.
+// Retention (Eq. 8-9): one workgroup per head (the body is shared with the attention launch that takes the
+// decisions beside the attention: pbsa_plan_device.h).
 // ------------------------------------------------------------------------------------------------
-constexpr int kMaxCand = PBSA_MAX_C + PBSA_MAX_N_LOC;
-
-struct RetainArgs {
-  int H, nqb, nqb_pad, n_loc, n_loc_cap, C, n_sink, n_evict, nU_max, d, B, fold;
-  int fine, Nq;             // fine: A is the attention-mass matrix [H][C+1+n_loc][nqb_pad], one row per key block
-                            // (slots 0..C, then the local blocks), and a score is its row sum over Nq
-  const float* A;           // A^T [H][nU_max][nqb_pad]
-  const float* Kc_l;
-  float* Kc_p;
-  const int32_t* p_len;
-  int32_t* p_len_out;       // [H][C + 1] lengths after the update (the fold kernel commits them)
-  int64_t* p_id;
-  int32_t* S_cnt;
-  const int32_t* l_len;
-  const int32_t* l_map;
-  const int64_t* l_id;
-  float* scores;
-  int32_t* slot_src;
-  int32_t* fold_n;
-  int32_t* fold_src;        // dropped candidate: < C persistent slot, else C + PHYSICAL local slot
-  int32_t* fold_len;
-  int32_t* promo_slot;      // [H][C] physical local slot a persistent slot is refilled from, or -1
-};
-
-// position of the n-th (0-based) set bit of mask
-__device__ __forceinline__ int nth_set_bit(uint64_t mask, int n) {
-  for (int i = 0; i < n; ++i) mask &= mask - 1;
-  return __ffsll((unsigned long long)mask) - 1;
-}
-
 __global__ void __launch_bounds__(kThreads) retain_kernel(RetainArgs a) {
-  __shared__ __align__(16) float cs[kMaxCand + 4];   // candidate scores
-  __shared__ float s[kMaxCand];           // mean column score of slot / evicted-block columns, U order
-  __shared__ int cand[kMaxCand];          // < C: slot, else C + local block
-  __shared__ unsigned char win[kMaxCand];
-  __shared__ int rank_s[kMaxCand];
-  __shared__ unsigned char vac_s[PBSA_MAX_C];   // slot whose occupant is dropped
-  __shared__ int old_len[PBSA_MAX_C + 1];
-  __shared__ int src_s[PBSA_MAX_C];
-  __shared__ int flen[kMaxCand];          // valid tokens of each dropped candidate
-  __shared__ int e_len[PBSA_MAX_N_LOC];   // valid tokens / physical slot of the evicted blocks
-  __shared__ int e_map[PBSA_MAX_N_LOC];
-  __shared__ long long e_id[PBSA_MAX_N_LOC];   // global ids of the evicted blocks
-  __shared__ int nf_s, npos_s;
-  const int h = blockIdx.x, C = a.C, C1 = a.C + 1;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int32_t* plen = a.p_len + (size_t)h * C1;
-  for (int c = threadIdx.x; c < C1; c += kThreads) old_len[c] = plen[c];
-  for (int e = threadIdx.x; e < a.n_evict; e += kThreads) {
-    e_len[e] = max(0, min(a.l_len[e], a.B));
-    e_map[e] = min(max(a.l_map[e], 0), a.n_loc_cap - 1);
-    e_id[e] = a.l_id[e];
-  }
-  // the summary's counts are needed at the very end: ask for them now, not after everything else
-  static_assert(kThreads >= 128, "one thread per position of a block");
-  const int cnt_mine = a.fold && threadIdx.x < a.B ? a.S_cnt[(size_t)h * a.B + threadIdx.x] : 0;
-  if (threadIdx.x == 0) npos_s = 0;
-  __syncthreads();
-  // occupied slots: U position of slot c = number of occupied slots below it (C <= 64: one ballot)
-  const bool occ = lane < C && old_len[lane] > 0;
-  const uint64_t occ_mask = __ballot(occ);
-  const int nP = __popcll(occ_mask), u_pos = lanes_below(occ_mask);
-  // Column means (Eq. 8) of the columns that can be candidates: the occupied slots and the evicted
-  // blocks, i.e. the first nP + n_evict columns of U.
-  const int n_need = nP + a.n_evict;
-  // A column is contiguous in A^T: its rows are fetched 64 at a time and added in ascending order.
-  for (int j = threadIdx.x; j < n_need; j += kThreads) {
-    float acc = 0.0f;
-    // where column j of U sits: the coarse matrix is in U order (occupied slots, then local blocks); the mass
-    // matrix has a row for every slot, the summary included
-    const int at = !a.fine ? j : j < nP ? nth_set_bit(occ_mask, j) : C + 1 + (j - nP);
-    const float4* col = reinterpret_cast<const float4*>(a.A + ((size_t)h * a.nU_max + at) * a.nqb_pad);
-    for (int i0 = 0; i0 < a.nqb; i0 += 64) {
-      float4 v[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = i0 + 4 * u < a.nqb ? col[i0 / 4 + u] : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int i = i0 + 4 * u;
-        if (i + 0 < a.nqb) acc = acc + v[u].x;
-        if (i + 1 < a.nqb) acc = acc + v[u].y;
-        if (i + 2 < a.nqb) acc = acc + v[u].z;
-        if (i + 3 < a.nqb) acc = acc + v[u].w;
-      }
-    }
-    s[j] = acc / (float)(a.fine ? a.Nq : a.nqb);
-  }
-  __syncthreads();
-  // candidates: occupants of slots >= n_sink in slot order, then the evicted blocks
-  const int ncand_max = C + a.n_evict;
-  const bool is_cand = occ && lane >= a.n_sink;
-  const uint64_t cand_mask = __ballot(is_cand);
-  const int ncP = __popcll(cand_mask), nc = ncP + a.n_evict, places = C - a.n_sink;
-  if (wave == 0) {
-    if (lane < C && a.scores) a.scores[(size_t)h * ncand_max + lane] = occ ? s[u_pos] : 0.0f;
-    if (is_cand) {
-      const int x = lanes_below(cand_mask);
-      cand[x] = lane;
-      cs[x] = s[u_pos];
-    }
-  }
-  for (int e = threadIdx.x; e < a.n_evict; e += kThreads) {
-    if (a.scores) a.scores[(size_t)h * ncand_max + C + e] = s[nP + e];
-    cand[ncP + e] = C + e;
-    cs[ncP + e] = s[nP + e];
-  }
-  __syncthreads();
-  // rank of a candidate = how many beat it (higher score, or equal score and lower index).  All threads
-  // take part: with P = kThreads / nc threads per candidate each counts over its share of the others
-  // (several 16-byte reads in flight), and the shares meet in an integer counter.
-  for (int x = threadIdx.x; x < nc; x += kThreads) rank_s[x] = 0;
-  __syncthreads();
-  {
-    const int P = max(1, kThreads / max(nc, 1)), n4 = (nc + 3) / 4, per = (n4 + P - 1) / P;
-    const float4* c4 = reinterpret_cast<const float4*>(cs);
-    for (int idx = threadIdx.x; idx < nc * P; idx += kThreads) {
-      const int x = idx % nc, part = idx / nc;
-      const float mine = cs[x];
-      int rank = 0;
-      const int q_end = min(n4, (part + 1) * per);
-#pragma unroll 4
-      for (int q = part * per; q < q_end; ++q) {
-        const float4 v = c4[q];
-        const int y = 4 * q;
-        // without branches: (in range) and (higher, or equal and earlier)
-        rank += (int)(y + 0 < nc) & ((int)(v.x > mine) | ((int)(v.x == mine) & (int)(y + 0 < x)));
-        rank += (int)(y + 1 < nc) & ((int)(v.y > mine) | ((int)(v.y == mine) & (int)(y + 1 < x)));
-        rank += (int)(y + 2 < nc) & ((int)(v.z > mine) | ((int)(v.z == mine) & (int)(y + 2 < x)));
-        rank += (int)(y + 3 < nc) & ((int)(v.w > mine) | ((int)(v.w == mine) & (int)(y + 3 < x)));
-      }
-      if (rank) atomicAdd(&rank_s[x], rank);
-    }
-  }
-  __syncthreads();
-  for (int x = threadIdx.x; x < nc; x += kThreads) win[x] = rank_s[x] < places;
-  for (int c = threadIdx.x; c < C; c += kThreads) vac_s[c] = 0;
-  __syncthreads();
-  // wave 0: dropped candidates, in candidate order, go to the fold list; then kept newcomers, in
-  // ascending block order, take the vacated and empty slots in ascending slot order
-  if (wave == 0) {
-    int nf = 0;
-    for (int x0 = 0; x0 < nc; x0 += 64) {
-      const int x = x0 + lane;
-      const bool lose = x < nc && !win[x];
-      const uint64_t lm = __ballot(lose);
-      if (lose) {
-        const int f = nf + lanes_below(lm);
-        const bool slot_cand = cand[x] < C;
-        const int len = slot_cand ? old_len[cand[x]] : e_len[cand[x] - C];
-        a.fold_src[(size_t)h * ncand_max + f] = slot_cand ? cand[x] : C + e_map[cand[x] - C];
-        a.fold_len[(size_t)h * ncand_max + f] = len;
-        flen[f] = len;
-        if (slot_cand) vac_s[cand[x]] = 1;
-      }
-      nf += __popcll(lm);
-    }
-    if (lane == 0) { a.fold_n[h] = nf; nf_s = nf; }
-    // free slots = (empty or vacated) and >= n_sink (vac_s: written above by this wave, LDS keeps a wave's order)
-    const bool vacated = lane < C && vac_s[lane];
-    const bool is_free = lane < C && lane >= a.n_sink && (old_len[lane] <= 0 || vacated);
-    const uint64_t free_mask = __ballot(is_free);
-    if (lane < C) {
-      src_s[lane] = -1;
-      if (vacated) old_len[lane] = 0;
-    }
-    int taken = 0;
-    for (int x0 = ncP; x0 < nc; x0 += 64) {
-      const int x = x0 + lane;
-      const bool keep = x < nc && win[x];
-      const uint64_t km = __ballot(keep);
-      if (keep) {
-        const int r = taken + lanes_below(km);       // r-th kept newcomer takes the r-th free slot
-        if (r < __popcll(free_mask)) {
-          const int slot = nth_set_bit(free_mask, r);
-          const int e = cand[x] - C;
-          old_len[slot] = e_len[e];
-          src_s[slot] = e;
-        }
-      }
-      taken += __popcll(km);
-    }
-  }
-  __syncthreads();
-  // per-position counts of the summary: every dropped block adds one to each position it has
-  if (a.fold && nf_s > 0) {
-    if (threadIdx.x < a.B) {
-      const int t = threadIdx.x;
-      int cnt = cnt_mine;
-#pragma unroll 8
-      for (int f = 0; f < nf_s; ++f) cnt += (int)(t < flen[f]);
-      a.S_cnt[(size_t)h * a.B + t] = cnt;
-      if (cnt > 0) atomicAdd(&npos_s, 1);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) old_len[C] = npos_s;
-    __syncthreads();
-  }
-  for (int c = threadIdx.x; c < C1; c += kThreads) a.p_len_out[(size_t)h * C1 + c] = old_len[c];
-  for (int c = threadIdx.x; c < C; c += kThreads) {
-    const int e = src_s[c];
-    a.slot_src[(size_t)h * C + c] = e;
-    a.promo_slot[(size_t)h * C + c] = e >= 0 ? e_map[e] : -1;
-    if (e >= 0) a.p_id[(size_t)h * C + c] = e_id[e];
-    else if (c >= a.n_sink && old_len[c] == 0) a.p_id[(size_t)h * C + c] = -1;
-  }
-  // pooled keys move with the promoted blocks: independent float4 copies
-  const int d4 = a.d / 4;
-  for (int idx = threadIdx.x; idx < C * d4; idx += kThreads) {
-    const int c = idx / d4, x = idx % d4;
-    const int e = src_s[c];
-    if (e >= 0)
-      reinterpret_cast<float4*>(a.Kc_p + ((size_t)h * C + c) * a.d)[x] =
-          reinterpret_cast<const float4*>(a.Kc_l + ((size_t)h * a.n_loc_cap + e_map[e]) * a.d)[x];
-  }
+  __shared__ RetainLds L;
+  retain_body<kThreads>(a, blockIdx.x, L);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -917,8 +681,7 @@ static hipError_t launch_scores(const pbsa_params& p, const float* Qc, const flo
                                 const float* Kc_p, const int32_t* p_len, const int32_t* l_map, const UpdateWs& ws,
                                 hipStream_t stream) {
   const int nU_max = p.C + p.n_loc;
-  const int nqb_pad = (p.nqb + 3) & ~3;
-  ScoreArgs sa{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, nU_max, p.n_evict, p.scale, Kc_l, Kc_p, Qc, Zl, l_map, p_len, ws.A};
+  const ScoreArgs sa = make_score_args(p, Qc, Kc_l, Zl, Kc_p, p_len, l_map, ws);
   const int nm = (nU_max + 63) / 64;
   if (Zl) {
     const int nml = (p.n_loc + 63) / 64;
@@ -940,10 +703,8 @@ static hipError_t launch_retain(const pbsa_params& p, const float* A, int n_rows
                                 float* Kc_p, const int32_t* p_len, int64_t* p_id, int32_t* S_cnt, int fold,
                                 const int32_t* l_len, const int32_t* l_map, const int64_t* l_id, float* scores,
                                 int32_t* slot_src, const UpdateWs& ws, hipStream_t stream) {
-  const int nqb_pad = (p.nqb + 3) & ~3;
-  RetainArgs ra{p.H, p.nqb, nqb_pad, p.n_loc, p.n_loc_cap, p.C, p.n_sink, p.n_evict, n_rows, p.d, p.B, fold, fine, p.Nq,
-                A, Kc_l, Kc_p, p_len, ws.plen_new, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws.fold_n,
-                ws.fold_src, ws.fold_len, ws.promo_slot};
+  const RetainArgs ra = make_retain_args(p, A, n_rows, fine, Kc_l, Kc_p, p_len, p_id, S_cnt, fold, l_len, l_map, l_id,
+                                         scores, slot_src, ws);
   hipLaunchKernelGGL(retain_kernel, dim3(p.H), dim3(kThreads), 0, stream, ra);
   return hipGetLastError();
 }

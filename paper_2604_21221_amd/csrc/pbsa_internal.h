@@ -45,6 +45,14 @@ hipError_t launch_attention(const pbsa_params& p, const bf16_t* Q, const bf16_t*
                             const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
                             const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, const MassRows* rows,
                             hipStream_t stream);
+// The same launch with H more workgroups that take the decisions of the memory update (launch_update_plan's work)
+// while the attention runs; Zl is required.  launch_update_apply completes the update.
+hipError_t launch_attention_plan(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kp, const bf16_t* Vp,
+                                 const int32_t* p_len, const bf16_t* Kl, const bf16_t* Vl, const int32_t* l_len,
+                                 const int32_t* l_map, const int32_t* sel, bf16_t* O, float* lse, const float* Qc,
+                                 const float* Kc_l, const float* Zl, float* Kc_p, int64_t* p_id, int32_t* S_cnt, int fold,
+                                 const int64_t* l_id, float* scores, int32_t* slot_src, const UpdateWs& ws,
+                                 hipStream_t stream);
 hipError_t launch_mass_reduce(const pbsa_params& p, const MassRows& rows, const float* lse, float* Mt,
                               hipStream_t stream);
 // The update in two parts.  plan: scoring and retention -- reads the cache's metadata and pooled keys, writes the

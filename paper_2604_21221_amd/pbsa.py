@@ -16,7 +16,8 @@ PBSA_OK, PBSA_EINVAL, PBSA_ESHAPE, PBSA_EALIGN, PBSA_EWS, PBSA_EHIP = 0, -1, -2,
 PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 512, 64, 192, 512
 
 EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
-           "pbsa_memory_update", "pbsa_memory_update_plan", "pbsa_memory_update_apply", "pbsa_attention_mass", "pbsa_mass_workspace_bytes", "pbsa_attention_fwd_mass",
+           "pbsa_memory_update", "pbsa_memory_update_plan", "pbsa_memory_update_apply", "pbsa_attention_fwd_plan",
+           "pbsa_attention_mass", "pbsa_mass_workspace_bytes", "pbsa_attention_fwd_mass",
            "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes", "pbsa_attention_bwd", "pbsa_blockify",
            "pbsa_unblockify", "pbsa_strerror", "pbsa_version")
 
@@ -79,6 +80,7 @@ def lib() -> ctypes.CDLL:
         L.pbsa_memory_update.argtypes = [pp] + [vp] * 18 + [sz, vp]
         L.pbsa_memory_update_plan.argtypes = [pp] + [vp] * 13 + [sz, vp]
         L.pbsa_memory_update_apply.argtypes = [pp] + [vp] * 8 + [sz, vp]
+        L.pbsa_attention_fwd_plan.argtypes = [pp] + [vp] * 21 + [sz, vp]
         L.pbsa_attention_mass.argtypes = [pp] + [vp] * 10
         L.pbsa_mass_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.pbsa_attention_fwd_mass.argtypes = [pp] + [vp] * 13 + [sz, vp]
@@ -90,7 +92,7 @@ def lib() -> ctypes.CDLL:
         L.pbsa_unblockify.argtypes = [pg, vp, ctypes.c_int64, vp, vp]
         for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
                      "pbsa_memory_update", "pbsa_memory_update_plan", "pbsa_memory_update_apply",
-                     "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
+                     "pbsa_attention_fwd_plan", "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
                      "pbsa_attention_fwd_mass", "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes",
                      "pbsa_attention_bwd", "pbsa_blockify", "pbsa_unblockify"):
             getattr(L, name).restype = ctypes.c_int
@@ -177,6 +179,15 @@ def pbsa_memory_update_plan(p, Qc, Kc_l, Zl, Kc_p, p_len, p_id, S_cnt, l_len, l_
     w, wb = _ws(ws)
     _check(lib().pbsa_memory_update_plan(ctypes.byref(p), _ptr(Qc), _ptr(Kc_l), _ptr(Zl), _ptr(Kc_p), _ptr(p_len),
                                          _ptr(p_id), _ptr(S_cnt), _ptr(l_len), _ptr(l_map), _ptr(l_id), _ptr(scores),
+                                         _ptr(slot_src), w, wb, _stream(stream)))
+
+
+def pbsa_attention_fwd_plan(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse, Qc, Kc_l, Zl, Kc_p, p_id, S_cnt, l_id,
+                            scores, slot_src, ws, stream=None):
+    w, wb = _ws(ws)
+    _check(lib().pbsa_attention_fwd_plan(ctypes.byref(p), _ptr(Q), _ptr(Kp), _ptr(Vp), _ptr(p_len), _ptr(Kl), _ptr(Vl),
+                                         _ptr(l_len), _ptr(l_map), _ptr(sel), _ptr(O), _ptr(lse), _ptr(Qc), _ptr(Kc_l),
+                                         _ptr(Zl), _ptr(Kc_p), _ptr(p_id), _ptr(S_cnt), _ptr(l_id), _ptr(scores),
                                          _ptr(slot_src), w, wb, _stream(stream)))
 
 

@@ -211,7 +211,9 @@ def test_maximum_sizes(gpu, k):
     rows = sample_rows(H, Nq, B, per_head=64, seed=5)
     for g in range(w + 3):
         Q, K, V = rnd(200 + 3 * g, H, Nq, d), rnd(201 + 3 * g, H, Nq, d, scale=1.5), rnd(202 + 3 * g, H, Nq, d)
-        run_both(gpu, c, st, Q, K, V, g, rows if g >= w else None, "max_sizes")
+        # odd chunks take the update's decisions inside the attention launch (512 local columns, 64 slots: its
+        # largest scratch)
+        (fused_both if g % 2 else run_both)(gpu, c, st, Q, K, V, g, rows if g >= w else None, "max_sizes")
     assert (st.p_len[:, :C] > 0).all() and int(st.S_cnt.max()) > 0
 
 
@@ -295,6 +297,68 @@ def test_update_decisions_overlapped_with_attention(gpu):
         torch.cuda.synchronize()
         check_attention(O.float().cpu().numpy(), Oref, "overlapped")
         compare_update(c, st, gpu["wl"], sc_ref, src_ref, ne, "overlapped")
+
+
+def fused_both(gpu, c, st, Q, K, V, g, rows, what):
+    """One step on both sides with the GPU side taking the update's decisions inside the attention launch
+    (pbsa_attention_fwd_plan, then pbsa_memory_update_apply): everything compared as in run_both, and the output
+    of the fused launch must equal that of pbsa_attention_fwd on the same state bit for bit."""
+    wl = gpu["wl"]
+    B = st.B
+    lens = np.full(st.nqb, B, np.int32); lens[-1] = st.Nq - (st.nqb - 1) * B
+    print(f"[case] {what} chunk {g}", flush=True)
+    st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * st.nqb + np.arange(st.nqb))
+    Qd = wl.bf16_tensor(Q, DEV)
+    c.append_chunk(wl.bf16_tensor(K, DEV), wl.bf16_tensor(V, DEV), g)
+    st.select(Q)
+    c.select(Qd)
+    compare_select(c, st, what)
+    lse0 = torch.empty(st.H, st.Nq, dtype=torch.float32, device=DEV)
+    lse1 = torch.empty_like(lse0)
+    O0 = c.attention(Qd, lse=lse0).clone()
+    O1 = c.attention_with_plan(Qd, lse=lse1)
+    torch.cuda.synchronize()
+    assert torch.equal(O0, O1) and torch.equal(lse0, lse1), f"{what}: the fused launch changed the attention output"
+    if rows is not None:
+        Og = O1.float().cpu().numpy()
+        if isinstance(rows, str):
+            check_attention(Og, st.attention(Q)[0], what)
+        else:
+            check_attention(Og[rows[0], rows[1]], st.attention_rows(Q, rows[0], rows[1])[0], what)
+    ne = st.n_evict_now()
+    sc_ref, src_ref = st.update()
+    assert c.update_apply() == ne
+    compare_update(c, st, wl, sc_ref, src_ref, ne, what)
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_update_decisions_inside_the_attention_launch(gpu, case):
+    """pbsa_attention_fwd_plan + pbsa_memory_update_apply against the oracle's step, every element, on the small
+    roll-outs (ragged blocks, empty slots, sinks, no memory, k = 0, both head dims and block sizes)."""
+    name, H, d, B, Nq, w, C, k, n_sink, causal, p_lens = case
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal, device=DEV)
+    if C > 0:
+        Kp, Vp = rnd(1, H, C, B, d), rnd(2, H, C, B, d)
+        pl = np.tile(np.array(p_lens, np.int32), (H, 1))
+        ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+        st.set_persistent(Kp, Vp, pl, ids)
+        c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                         torch.from_numpy(ids))
+    for g in range(w + 4):
+        Q, K, V = rnd(10 + 3 * g, H, Nq, d), rnd(11 + 3 * g, H, Nq, d, scale=1.5), rnd(12 + 3 * g, H, Nq, d)
+        fused_both(gpu, c, st, Q, K, V, g, "all", f"fused {name}")
+
+
+def test_fused_step_needs_the_logits(gpu):
+    """Without the logits of the selection call the fused launch refuses (it does not recompute them)."""
+    c = gpu["cache"].PbsaCache(1, 64, 64, 100, 1, 2, 1, 0.125, device=DEV, pass_logits=False)
+    Q, K, V = (gpu["wl"].bf16_tensor(rnd(50 + i, 1, 100, 64), DEV) for i in range(3))
+    c.append_chunk(K, V, 0)
+    c.select(Q)
+    with pytest.raises(gpu["pbsa"].PbsaError):
+        c.attention_with_plan(Q)
 
 
 def test_denoising_passes_share_the_cache(gpu):
@@ -442,7 +506,8 @@ def test_full_size_single_step(gpu, name):
     rows = sample_rows(w.H, w.Nq, w.B)
     for g in range(g0, g0 + 2):
         Q, K, V = synth.chunk_qkv(w, 0, g)
-        run_both(gpu, c, st, Q, K, V, g, rows, name)
+        # the second step in the benchmark's schedule: decisions inside the attention launch, then fold / promote
+        (fused_both if g > g0 else run_both)(gpu, c, st, Q, K, V, g, rows, name)
 
 
 @pytest.mark.parametrize("shape", [(2, 0.25, 0.25), (4, 0.25, 0.0625), (2, 0.5, 1.0)],
@@ -485,7 +550,9 @@ def test_cfg5_rollout(gpu):
     assert n_chunks == 80
     for g in range(n_chunks):
         Q, K, V = synth.chunk_qkv(w, 0, g)
-        run_both(gpu, c, st, Q, K, V, g, rows if g in (0, 1, 3, 4, 39, 79) else None, "cfg5")
+        # every third chunk takes the update's decisions inside the attention launch
+        step = fused_both if g % 3 == 2 else run_both
+        step(gpu, c, st, Q, K, V, g, rows if g in (0, 1, 3, 4, 39, 79) else None, "cfg5")
     assert (st.p_len[:, :w.C] > 0).all()
     # every block that left the window and was not kept is in the summary: 77 evictions of 74 blocks
     assert int(st.S_cnt.max()) == 77 * w.nqb - w.C
