@@ -220,6 +220,27 @@ def test_plan_and_apply_argument_checks(L):
         assert e.value.code == code, (call.__name__, kw)
 
 
+def test_attention_with_plan_argument_checks(L):
+    """pbsa_attention_fwd_plan validates like pbsa_attention_fwd and pbsa_memory_update_plan together, and wants
+    the logits of the selection call."""
+    p = good(n_evict=4)
+    need = pbsa.pbsa_workspace_bytes(p)
+
+    def fused(p=p, Q=P, O=P, Qc=P, Zl=P, l_id=P, slot_src=P, ws=(0x10000, 1 << 30)):
+        pbsa.pbsa_attention_fwd_plan(p, Q, P, P, P, P, P, P, P, P, O, None, Qc, P, Zl, P, P, P, l_id, None, slot_src, ws,
+                                     stream=0)
+
+    for kw, code in [(dict(Q=None), pbsa.PBSA_EINVAL), (dict(O=None), pbsa.PBSA_EINVAL), (dict(Zl=None), pbsa.PBSA_EINVAL),
+                     (dict(l_id=None), pbsa.PBSA_EINVAL), (dict(slot_src=None), pbsa.PBSA_EINVAL),
+                     (dict(Q=P + 2), pbsa.PBSA_EALIGN), (dict(Qc=P + 4), pbsa.PBSA_EALIGN), (dict(ws=None), pbsa.PBSA_EWS),
+                     (dict(ws=(0x10000, need - 1)), pbsa.PBSA_EWS), (dict(ws=(0x10010, need)), pbsa.PBSA_EALIGN),
+                     (dict(p=good(C=65)), pbsa.PBSA_ESHAPE), (dict(p=good(n_evict=17)), pbsa.PBSA_EINVAL),
+                     (dict(p=good(q_strides=(200 * 132, 132))), pbsa.PBSA_EALIGN)]:
+        with pytest.raises(pbsa.PbsaError) as e:
+            fused(**kw)
+        assert e.value.code == code, kw
+
+
 def test_binding_refuses_host_tensors(L):
     import torch
     with pytest.raises(TypeError):
