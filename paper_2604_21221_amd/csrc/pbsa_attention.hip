@@ -526,7 +526,7 @@ struct PlanArgs<true> {
   plan_dev::RetainArgs ra;
 };
 
-// PLAN: the grid has H more workgroups behind those of the attention, one per head, which take the decisions of
+// PLAN: the grid has H more workgroups ahead of those of the attention, one per head, which take the decisions of
 // the memory update (Eq. 7-9: scoring, retention, slot assignment) while the attention runs.  They read the
 // cache's metadata and pooled keys and what the selection call left, never K / V or the attention's output, and
 // a one-round launch leaves them SIMDs to run on (two workgroups per CU, 128 rows each: at 4680 rows and 12
@@ -556,9 +556,13 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   const int n_qt = (a.Nq + kRowsPerWg - 1) / kRowsPerWg;
   const int n_wg = a.H * n_qt;
   const int per = (n_wg + 7) / 8;
+  // the workgroups that take the decisions come first in the grid (whole rows of 8, so that the XCD of the others is
+  // still their index mod 8): they start with the launch however many rounds the attention needs
+  const int n_plan = PLAN ? 8 * ((a.H + 7) / 8) : 0;
   if constexpr (PLAN) {
-    if ((int)blockIdx.x >= 8 * per) {
-      const int hp = (int)blockIdx.x - 8 * per;
+    if ((int)blockIdx.x < n_plan) {
+      const int hp = (int)blockIdx.x;
+      if (hp >= a.H) return;
       static_assert(plan_dev::score_head_lds_bytes<D, kThreads>(PBSA_MAX_N_LOC) <= SMEM, "scoring scratch must fit");
       static_assert(sizeof(plan_dev::RetainLds) <= SMEM, "retention scratch must fit");
       plan_dev::score_head_body<D, kThreads>(pl.sa, hp, smem);
@@ -567,7 +571,8 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
       return;
     }
   }
-  const int logical = (blockIdx.x % 8) * per + blockIdx.x / 8;
+  const int bx = (int)blockIdx.x - n_plan;
+  const int logical = (bx % 8) * per + bx / 8;
   if (logical >= n_wg) return;
   const int h = logical / n_qt;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -986,7 +991,7 @@ hipError_t launch_attention_plan(const pbsa_params& p, const bf16_t* Q, const bf
   pl.ra = plan_dev::make_retain_args(p, ws.A, p.C + p.n_loc, 0, Kc_l, Kc_p, p_len, p_id, S_cnt, fold, l_len, l_map, l_id,
                                      scores, slot_src, ws);
   const int n_wg = p.H * ((p.Nq + kRowsPerWg - 1) / kRowsPerWg);
-  const dim3 grid(8 * ((n_wg + 7) / 8) + p.H);
+  const dim3 grid(8 * ((n_wg + 7) / 8) + 8 * ((p.H + 7) / 8));
   launch_attention_t<false, true>(p, a, pl, grid, stream);
   return hipGetLastError();
 }
