@@ -351,6 +351,26 @@ def test_update_decisions_inside_the_attention_launch(gpu, case):
         fused_both(gpu, c, st, Q, K, V, g, "all", f"fused {name}")
 
 
+def test_fused_launch_with_many_heads_and_rounds(gpu):
+    """44 heads x 16 attention workgroups (more than the GPU holds at once) with 44 deciding workgroups ahead of them
+    in the grid (not a whole number of the mapping's rows of 8): selection and update exact, attention on sampled
+    rows of every head."""
+    H, d, B, Nq, w, C, k = 44, 64, 64, 2048, 1, 2, 4
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    Kp, Vp = rnd(901, H, C, B, d), rnd(902, H, C, B, d)
+    pl = np.tile(np.array([64, 33], np.int32), (H, 1))
+    ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+    st.set_persistent(Kp, Vp, pl, ids)
+    c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                     torch.from_numpy(ids))
+    rows = sample_rows(H, Nq, B, per_head=16, seed=9)
+    for g in range(3):
+        Q, K, V = rnd(910 + 3 * g, H, Nq, d), rnd(911 + 3 * g, H, Nq, d, scale=1.5), rnd(912 + 3 * g, H, Nq, d)
+        fused_both(gpu, c, st, Q, K, V, g, rows, "fused 44 heads")
+
+
 def test_fused_step_needs_the_logits(gpu):
     """Without the logits of the selection call the fused launch refuses (it does not recompute them)."""
     c = gpu["cache"].PbsaCache(1, 64, 64, 100, 1, 2, 1, 0.125, device=DEV, pass_logits=False)
