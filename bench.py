@@ -248,6 +248,10 @@ def main():
                     help="the step as three calls, pbsa_select_blocks -> pbsa_attention_fwd -> pbsa_memory_update, instead of "
                          "the default pbsa_select_blocks -> pbsa_attention_fwd_plan (the attention launch with one more "
                          "workgroup per head that takes the update's decisions) -> pbsa_memory_update_apply")
+    ap.add_argument("--chain-apply", action="store_true",
+                    help="two library calls per step: pbsa_select_blocks_apply (the selection, with the fold / promote of the "
+                         "previous step's update riding in its pooling launch; the ring gets a spare position so that the new "
+                         "chunk is not written over the blocks still to be folded) and pbsa_attention_fwd_plan")
     ap.add_argument("--fine-mass", action="store_true",
                     help="the step with the persistent set ranked by the attention actually paid: after the attention "
                          "call pbsa_attention_mass sums the probabilities per key block and pbsa_memory_update_fine "
@@ -287,17 +291,19 @@ def main():
     # ---- state: reach steady state (full window, full persistent set, non-empty summary) untimed ----
     # one cache and one set of inputs per layer; a step visits the layers in turn
     L, T = w.n_layers, max(1, args.denoise_steps)
-    n_ring = w.window_chunks + 1
-    n_setup = n_ring + 2 if w.cold_start else n_ring
+    n_ring = w.window_chunks + 1               # chunks in the local region during a step
+    chained = args.chain_apply and not (args.separate_update or args.overlap_update or args.fine_mass or args.backward)
+    n_pos = n_ring + 1 if chained else n_ring  # ring positions
+    n_setup = n_pos + 2 if w.cold_start else n_pos
     caches, Q_ats = [], []
     for layer in range(L):
-        cl, g0 = workloads.cache_for_workload(w, layer=layer, device=dev)
+        cl, g0 = workloads.cache_for_workload(w, layer=layer, device=dev, ring_chunks=n_pos)
         Q_at = {}              # ring position -> the query chunk that goes with the K/V sitting there
         for g in range(g0, g0 + n_setup):
             Q, Kc, Vc = synth.chunk_qkv(w, layer, g)
             Qd = workloads.bf16_tensor(Q, dev)
             cl.step(Qd, workloads.bf16_tensor(Kc, dev), workloads.bf16_tensor(Vc, dev), g)
-            Q_at[(cl.n_appended - 1) % n_ring] = Qd
+            Q_at[(cl.n_appended - 1) % n_pos] = Qd
         caches.append(cl)
         Q_ats.append(Q_at)
     c = caches[0]
@@ -332,7 +338,7 @@ def main():
         c = caches[n_done[0] % L]
         n_done[0] += 1
         c.adopt_chunk(g)
-        Qd = Q_ats[(n_done[0] - 1) % L][(c.n_appended - 1) % n_ring]
+        Qd = Q_ats[(n_done[0] - 1) % L][(c.n_appended - 1) % n_pos]
         c.sel, c.slot_src = sel_hist[i], src_hist[i]
         for _ in range(T - 1):
             # earlier denoising passes of this chunk: the chunk's own K/V (and so its pooled keys) change
@@ -369,6 +375,8 @@ def main():
             upd_ev[0].record(stream)
         if args.fine_mass:
             c.update_fine(Mt)
+        elif chained:
+            c.defer_apply()                        # fold / promote ride in the next step's selection call
         elif overlap or fused:
             c.update_apply()
         else:
@@ -390,6 +398,8 @@ def main():
     t1 = time.perf_counter()
     for i in range(K2):
         one_step(W + K + i, sel_ev=ev_sel[i], upd_ev=ev_upd[i], mass_ev=ev_mass[i])
+    for cl in caches:
+        cl.flush()
     torch.cuda.synchronize()
 
     step_s = (t1 - t0) / K
@@ -452,6 +462,15 @@ def main():
         u = out["hbm_bound_calls"].pop("pbsa_memory_update")
         u["note"] = "the apply call alone; the decisions are taken inside the attention launch"
         out["hbm_bound_calls"]["pbsa_memory_update_apply"] = u
+    if chained:
+        out["config"]["schedule"] = ("pbsa_select_blocks_apply (selection + fold / promote of the previous step's update in its pooling "
+                                     "launch; ring of window + 2 chunks) -> pbsa_attention_fwd_plan (attention + the update's decisions)")
+        out["hbm_bound_calls"].pop("pbsa_memory_update_apply")
+        u = out["hbm_bound_calls"].pop("pbsa_select_blocks")
+        u["algorithmic_bytes"] += int(upd_b)
+        u["achieved"] = round(u["algorithmic_bytes"] / u["us_per_call"] / 1e3, 1)
+        u["frac"] = round(u["achieved"] / PEAK_HBM_GBS, 4)
+        out["hbm_bound_calls"]["pbsa_select_blocks_apply"] = u
     if overlap:
         out["config"]["schedule"] = ("pbsa_memory_update_plan (scoring, retention) on a second stream under the attention kernel, "
                                      "pbsa_memory_update_apply (fold, promote) after it")

@@ -171,6 +171,20 @@ int pbsa_memory_update_plan(const pbsa_params* p, const float* Qc, const float* 
 int pbsa_memory_update_apply(const pbsa_params* p, void* Kp, void* Vp, int32_t* p_len, float* S_sum, const int32_t* S_cnt,
                              const void* Kl, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* pbsa_select_blocks of a chunk and pbsa_memory_update_apply of the update of the chunk BEFORE it, with the fold /
+ * promote workgroups riding in the selection's pooling launch (Alg. 1 over consecutive chunks: the data movement that
+ * ends one iteration and the coarse stage that starts the next touch disjoint data, and each alone is too short to
+ * fill the GPU).  p and the arguments up to Zl are those of pbsa_select_blocks for the new chunk; p_upd and the
+ * arguments after it are those of the pending pbsa_memory_update_apply (same Kl; same H, d, B, C, n_loc_cap, else
+ * PBSA_EINVAL).  Results are those of the two calls, bit for bit.  The CALLER guarantees what makes the two
+ * independent: the new chunk's K / V are not in the ring position whose blocks the pending update evicts (a ring of
+ * window + 2 chunks gives that), and nothing between the attention launch that took the decisions and this call has
+ * touched ws. */
+int pbsa_select_blocks_apply(const pbsa_params* p, const void* Q, const void* Kl, const int32_t* l_len,
+                             const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
+                             const pbsa_params* p_upd, void* Kp, void* Vp, int32_t* p_len, float* S_sum,
+                             const int32_t* S_cnt, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* pbsa_attention_fwd and pbsa_memory_update_plan of the same chunk as ONE launch (Alg. 1 with the update's
  * decisions, Eq. 7-9, taken while the fine stage of Eq. 3-5 runs): the attention's grid gets H more workgroups, one
  * per head, that do the plan call's work.  Nothing they read is written by the attention part and the other way

@@ -15,11 +15,17 @@ from . import pbsa
 
 class PbsaCache:
     def __init__(self, H, d, B, Nq, window_chunks, C, k, scale, n_sink=0, causal=1, fold=True, device="cuda:0",
-                 pass_logits=True):
+                 pass_logits=True, ring_chunks=None):
         self.H, self.d, self.B, self.Nq, self.C, self.k = H, d, B, Nq, C, k
         self.w, self.scale, self.n_sink, self.causal = window_chunks, float(scale), n_sink, causal
         self.nqb = -(-Nq // B)
-        self.cap = (window_chunks + 1) * self.nqb
+        # ring positions: the window and the current chunk, or one more -- then the chunk that follows is written
+        # to a position other than the one whose blocks the update of the current chunk still has to fold, and that
+        # update's data movement can ride in the next selection call (defer_apply)
+        self.ring = ring_chunks or window_chunks + 1
+        assert self.ring >= window_chunks + 1
+        self.cap = self.ring * self.nqb
+        self._pending = None         # params of an update whose apply call has been deferred
         self.dev = torch.device(device)
         z = lambda *s, dt=torch.bfloat16: torch.zeros(*s, dtype=dt, device=self.dev)
         self.Kl, self.Vl = z(H, self.cap, B, d), z(H, self.cap, B, d)
@@ -111,7 +117,7 @@ class PbsaCache:
     def append_chunk(self, K, V, chunk_id):
         """Copy a chunk's K/V ([H][Nq][d] bf16, token-major) into the next ring position, block-major."""
         assert len(self.chunk_pos) <= self.w, "update() slides the window before the next append"
-        pos = self.n_appended % (self.w + 1)
+        pos = self.n_appended % self.ring
         for dst, src in ((self.Kl, K), (self.Vl, V)):
             view = dst[:, pos * self.nqb:(pos + 1) * self.nqb].view(self.H, self.nqb * self.B, self.d)
             view[:, :self.Nq] = src
@@ -138,7 +144,7 @@ class PbsaCache:
         """Declare the next ring position to hold chunk `chunk_id` whose K/V the producer has already
         written there in block-major layout (zero-copy append)."""
         assert len(self.chunk_pos) <= self.w, "update() slides the window before the next append"
-        self.chunk_pos.append(self.n_appended % (self.w + 1))
+        self.chunk_pos.append(self.n_appended % self.ring)
         self.chunk_ids.append(chunk_id)
         self.n_appended += 1
         self.stale_from = min(self.stale_from, self.n_loc - self.nqb)
@@ -147,7 +153,12 @@ class PbsaCache:
     def select(self, Q):
         l_map, l_len, _ = self._device_maps()
         p = self.params(pool_from=self.stale_from, Q=Q)
-        pbsa.pbsa_select_blocks(p, Q, self.Kl, l_len, l_map, self.Kc_l, self.Qc, self.sel, self.Zl)
+        if self._pending is not None:            # with the data movement of the previous chunk's update in its pooling launch
+            pbsa.pbsa_select_blocks_apply(p, Q, self.Kl, l_len, l_map, self.Kc_l, self.Qc, self.sel, self.Zl, self._pending,
+                                          self.Kp, self.Vp, self.p_len, self.S_sum, self.S_cnt, self.Vl, self.ws)
+            self._pending = None
+        else:
+            pbsa.pbsa_select_blocks(p, Q, self.Kl, l_len, l_map, self.Kc_l, self.Qc, self.sel, self.Zl)
         self.stale_from = self.n_loc
         return self.sel
 
@@ -301,6 +312,36 @@ class PbsaCache:
         self.select(Q)
         O = self.attention_with_plan(Q, O, lse)
         self.update_apply()
+        return O
+
+    def defer_apply(self):
+        """After attention_with_plan(): slides the window now and leaves fold / promote to the next select() call, in
+        whose pooling launch they ride (or to flush()).  Needs the spare ring position (ring_chunks = window + 2)."""
+        assert self.ring >= self.w + 2, "the next chunk would overwrite the blocks that are still to be folded"
+        assert self._pending is None
+        self._pending = self._plan_p
+        ne = self._plan_p.n_evict
+        if ne:
+            self.chunk_pos.pop(0)
+            self.chunk_ids.pop(0)
+            self.stale_from = self.n_loc
+        return ne
+
+    def flush(self):
+        """Completes a deferred update now (pbsa_memory_update_apply)."""
+        if self._pending is not None:
+            pbsa.pbsa_memory_update_apply(self._pending, self.Kp, self.Vp, self.p_len, self.S_sum, self.S_cnt, self.Kl,
+                                          self.Vl, self.ws)
+            self._pending = None
+
+    def step_chained(self, Q, K=None, V=None, chunk_id=None, O=None, lse=None):
+        """Two library calls per step: selection (carrying the previous step's fold / promote), attention (carrying
+        this step's decisions).  flush() after the last step.  K = V = None: the chunk has been adopted already."""
+        if K is not None:
+            self.append_chunk(K, V, chunk_id)
+        self.select(Q)
+        O = self.attention_with_plan(Q, O, lse)
+        self.defer_apply()
         return O
 
     def step_overlapped(self, Q, K=None, V=None, chunk_id=None, O=None, lse=None):

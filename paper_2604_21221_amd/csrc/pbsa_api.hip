@@ -98,6 +98,35 @@ int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, cons
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
+int pbsa_select_blocks_apply(const pbsa_params* p, const void* Q, const void* Kl, const int32_t* l_len,
+                             const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
+                             const pbsa_params* p_upd, void* Kp, void* Vp, int32_t* p_len, float* S_sum,
+                             const int32_t* S_cnt, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  if (rc) return rc;
+  rc = check_common(p_upd);
+  if (rc) return rc;
+  if (p->H != p_upd->H || p->d != p_upd->d || p->B != p_upd->B || p->C != p_upd->C || p->n_loc_cap != p_upd->n_loc_cap)
+    return PBSA_EINVAL;
+  if (!Q || !Kl || !l_len || !l_map || !Kc_l || !Qc) return PBSA_EINVAL;
+  if (p->k > 0 && !sel) return PBSA_EINVAL;
+  if (!Kp || !Vp || !p_len || !Vl) return PBSA_EINVAL;
+  if ((S_sum == nullptr) != (S_cnt == nullptr)) return PBSA_EINVAL;
+  rc = check_strides(p->q_stride_h, p->q_stride_t, p);
+  if (rc) return rc;
+  if (!aligned16(Q) || !aligned16(Kl) || !aligned16(Kc_l) || !aligned16(Qc) || !aligned16(Kp) || !aligned16(Vp) ||
+      !aligned16(Vl) || !aligned16(S_sum))
+    return PBSA_EALIGN;
+  if (!ws || ws_bytes < workspace_bytes(*p_upd)) return PBSA_EWS;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return PBSA_EALIGN;
+  const pbsa::UpdateWs w = pbsa::carve_update_ws(*p_upd, ws);
+  hipError_t e = pbsa::launch_select_apply(
+      *p, static_cast<const pbsa::bf16_t*>(Q), static_cast<const pbsa::bf16_t*>(Kl), l_len, l_map, Kc_l, Qc, sel, Zl,
+      *p_upd, static_cast<pbsa::bf16_t*>(Kp), static_cast<pbsa::bf16_t*>(Vp), p_len, S_sum, S_cnt,
+      static_cast<const pbsa::bf16_t*>(Vl), w, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
 int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, const void* Vp, const int32_t* p_len,
                        const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
                        const int32_t* sel, void* O, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {

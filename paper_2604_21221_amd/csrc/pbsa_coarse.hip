@@ -48,9 +48,9 @@ struct PoolArgs {
 };
 
 template <int D>
-__global__ void __launch_bounds__(kThreads) pool_kernel(PoolArgs a) {
+__device__ __forceinline__ void pool_body(const PoolArgs& a, const int bx) {
   constexpr int TPJ = D / 2;
-  const int job = blockIdx.x * (kThreads / TPJ) + threadIdx.x / TPJ;
+  const int job = bx * (kThreads / TPJ) + threadIdx.x / TPJ;
   const int c = threadIdx.x % TPJ;
   if (job >= a.n_jobs) return;
   const bf16_t* src;
@@ -101,6 +101,11 @@ __global__ void __launch_bounds__(kThreads) pool_kernel(PoolArgs a) {
   o.x = len > 0 ? acc0 / fl : 0.0f;
   o.y = len > 0 ? acc1 / fl : 0.0f;
   *reinterpret_cast<float2*>(dst + c * 2) = o;
+}
+
+template <int D>
+__global__ void __launch_bounds__(kThreads) pool_kernel(PoolArgs a) {
+  pool_body<D>(a, blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -189,15 +194,14 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t 
 constexpr int kDX = 32;
 
 template <int D, int NM>
-__global__ void __launch_bounds__(64 * NM) select_kernel(SelectArgs a) {
-  extern __shared__ __align__(1024) unsigned char smem[];
+__device__ __forceinline__ void select_body(const SelectArgs& a, const int bx, const int h, unsigned char* smem) {
   constexpr int NCP = NM * 64;                        // padded columns
   constexpr int BUF = NCP * kDX * 4;                  // one round of every column
   constexpr int NR = D / kDX;
   float* qs = reinterpret_cast<float*>(smem + 2 * BUF);                         // [4][D]
   float* zs = qs + 4 * D;                                                       // [4][NCP]
-  const int h = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i0 = blockIdx.x * 4;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i0 = bx * 4;
 
   // this lane's share of the staging: instruction n fills columns 64 wave + 8 n + lane / 8, physical chunk lane % 8
   uint32_t goff[8];
@@ -301,6 +305,12 @@ __global__ void __launch_bounds__(64 * NM) select_kernel(SelectArgs a) {
     }
     for (int j = kk + lane; j < a.k; j += 64) out[j] = -1;
   }
+}
+
+template <int D, int NM>
+__global__ void __launch_bounds__(64 * NM) select_kernel(SelectArgs a) {
+  extern __shared__ __align__(1024) unsigned char smem[];
+  select_body<D, NM>(a, blockIdx.x, blockIdx.y, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -483,18 +493,18 @@ struct FoldArgs {
 constexpr int kFoldBatch = 40;
 constexpr int kPromoBatch = 8;
 
-__global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
+template <int NT>
+__device__ __forceinline__ void fold_promote_body(const FoldArgs& a, const int bx, const int h) {
   // per dropped candidate: its valid length and the address of its K and of its V block
   __shared__ const bf16_t* fptr_s[2][kMaxCand];
   __shared__ int flen_s[kMaxCand];
   __shared__ int promo_dst[PBSA_MAX_C], promo_src[PBSA_MAX_C], n_promo_s;   // refilled slots, compacted
-  const int h = blockIdx.y;
   const int C = a.C, C1 = a.C + 1, ncand_max = a.C + a.n_evict;
-  if (blockIdx.x == 0)                     // nothing in this launch reads p_len: the lists carry the lengths they need
-    for (int c = threadIdx.x; c < C1; c += kThreads) a.p_len[(size_t)h * C1 + c] = a.plen_new[(size_t)h * C1 + c];
+  if (bx == 0)                             // nothing in this launch reads p_len: the lists carry the lengths they need
+    for (int c = threadIdx.x; c < C1; c += NT) a.p_len[(size_t)h * C1 + c] = a.plen_new[(size_t)h * C1 + c];
   const int nf = a.fold && a.S_sum ? a.fold_n[h] : 0;
   const size_t blk = (size_t)a.B * a.d;
-  for (int f = threadIdx.x; f < nf; f += kThreads) {
+  for (int f = threadIdx.x; f < nf; f += NT) {
     const int src = a.fold_src[(size_t)h * ncand_max + f];
     flen_s[f] = a.fold_len[(size_t)h * ncand_max + f];
     fptr_s[0][f] = src < C ? a.Kp + ((size_t)h * C1 + src) * blk : a.Kl + ((size_t)h * a.n_loc_cap + (src - C)) * blk;
@@ -518,8 +528,8 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   __syncthreads();
   const int n_promo = n_promo_s;
   const int tpr = a.d / 4;                                     // threads per row: 4 dimensions each
-  const int rows_per_wg = kThreads / tpr;
-  const int row = blockIdx.x * rows_per_wg + threadIdx.x / tpr; // over [2][B]
+  const int rows_per_wg = NT / tpr;
+  const int row = bx * rows_per_wg + threadIdx.x / tpr;         // over [2][B]
   const int xc = (threadIdx.x % tpr) * 4;
   if (row >= 2 * a.B) return;
   const int kv = row / a.B, t = row % a.B;
@@ -576,6 +586,20 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   }
 }
 
+__global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
+  fold_promote_body<kThreads>(a, blockIdx.x, blockIdx.y);
+}
+
+// The pooling of one chunk's selection call and the fold / promote of the update of the chunk before it, as one
+// launch: the two touch disjoint data when the new chunk does not sit in the ring position whose blocks are being
+// folded, and each is too short to fill the GPU for long.  The n_fold_x * H fold workgroups come first.
+template <int D>
+__global__ void __launch_bounds__(kThreads) pool_fold_kernel(PoolArgs pa, FoldArgs fa, int n_fold_x) {
+  const int n_pool = (int)gridDim.x - n_fold_x * fa.H, b = (int)blockIdx.x - n_pool;
+  if (b < 0) pool_body<D>(pa, (int)blockIdx.x);
+  else fold_promote_body<kThreads>(fa, b % n_fold_x, b / n_fold_x);
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <typename K>
@@ -630,21 +654,59 @@ static hipError_t launch_select_t(const SelectArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
-                         const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
-                         hipStream_t stream) {
+static PoolArgs select_pool_args(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
+                                 const int32_t* l_map, float* Kc_l, float* Qc) {
   PoolArgs pa{};
   pa.mode = 1; pa.H = p.H; pa.B = p.B; pa.Nq = p.Nq; pa.nqb = p.nqb; pa.n_loc = p.n_loc; pa.n_loc_cap = p.n_loc_cap;
   pa.pool_from = p.pool_from; pa.n_kjobs_per_head = p.n_loc - p.pool_from;
   pa.n_jobs = p.H * (pa.n_kjobs_per_head + p.nqb);
   pa.q_stride_h = p.q_stride_h; pa.q_stride_t = p.q_stride_t;
   pa.X = Kl; pa.Q = Q; pa.len = l_len; pa.l_map = l_map; pa.out = Kc_l; pa.Qc = Qc;
+  return pa;
+}
+
+static FoldArgs fold_args(const pbsa_params& p, bf16_t* Kp, bf16_t* Vp, int32_t* p_len, float* S_sum,
+                          const int32_t* S_cnt, const bf16_t* Kl, const bf16_t* Vl, const UpdateWs& ws) {
+  return FoldArgs{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, S_sum != nullptr, Kp, Vp, Kl, Vl, S_sum, S_cnt, ws.fold_n,
+                  ws.fold_src, ws.fold_len, ws.promo_slot, ws.plen_new, p_len};
+}
+
+static hipError_t launch_select_logits(const pbsa_params& p, const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel,
+                                       float* Zl, hipStream_t stream);
+
+hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
+                         const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
+                         hipStream_t stream) {
+  const PoolArgs pa = select_pool_args(p, Q, Kl, l_len, l_map, Kc_l, Qc);
   const int jpw = kThreads / (p.d / 2);
   const dim3 grid((pa.n_jobs + jpw - 1) / jpw);
   if (p.d == 128) hipLaunchKernelGGL(pool_kernel<128>, grid, dim3(kThreads), 0, stream, pa);
   else hipLaunchKernelGGL(pool_kernel<64>, grid, dim3(kThreads), 0, stream, pa);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  return launch_select_logits(p, l_map, Kc_l, Qc, sel, Zl, stream);
+}
+
+hipError_t launch_select_apply(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
+                               const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
+                               const pbsa_params& pu, bf16_t* Kp, bf16_t* Vp, int32_t* p_len, float* S_sum,
+                               const int32_t* S_cnt, const bf16_t* Vl, const UpdateWs& ws, hipStream_t stream) {
+  const PoolArgs pa = select_pool_args(p, Q, Kl, l_len, l_map, Kc_l, Qc);
+  const FoldArgs fa = fold_args(pu, Kp, Vp, p_len, S_sum, S_cnt, Kl, Vl, ws);
+  // the fold / promote workgroups ride in the pooling launch: its workgroups have the same size and no LDS of their
+  // own (in the logits launch, 80 KB of LDS per workgroup, they would wait for places: measured slower)
+  const int jpw = kThreads / (p.d / 2), rows_per_wg = kThreads / (pu.d / 4);
+  const int n_fold_x = (2 * pu.B + rows_per_wg - 1) / rows_per_wg;
+  const dim3 grid(n_fold_x * pu.H + (pa.n_jobs + jpw - 1) / jpw);
+  if (p.d == 128) hipLaunchKernelGGL(pool_fold_kernel<128>, grid, dim3(kThreads), 0, stream, pa, fa, n_fold_x);
+  else hipLaunchKernelGGL(pool_fold_kernel<64>, grid, dim3(kThreads), 0, stream, pa, fa, n_fold_x);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_select_logits(p, l_map, Kc_l, Qc, sel, Zl, stream);
+}
+
+static hipError_t launch_select_logits(const pbsa_params& p, const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel,
+                                       float* Zl, hipStream_t stream) {
   if (p.k == 0 && !Zl) return hipSuccess;
 
   SelectArgs a{p.H, p.nqb, p.n_loc, p.n_loc_cap, p.k, p.causal, p.scale, Kc_l, Qc, l_map, sel, Zl};
@@ -722,9 +784,7 @@ hipError_t launch_update_plan(const pbsa_params& p, const float* Qc, const float
 hipError_t launch_update_apply(const pbsa_params& p, bf16_t* Kp, bf16_t* Vp, int32_t* p_len, float* S_sum,
                                const int32_t* S_cnt, const bf16_t* Kl, const bf16_t* Vl, const UpdateWs& ws,
                                hipStream_t stream) {
-  const int fold = S_sum != nullptr;
-  FoldArgs fa{p.H, p.B, p.d, p.C, p.n_loc_cap, p.n_evict, fold, Kp, Vp, Kl, Vl, S_sum, S_cnt, ws.fold_n,
-              ws.fold_src, ws.fold_len, ws.promo_slot, ws.plen_new, p_len};
+  const FoldArgs fa = fold_args(p, Kp, Vp, p_len, S_sum, S_cnt, Kl, Vl, ws);
   const int rows_per_wg = kThreads / (p.d / 4);
   hipLaunchKernelGGL(fold_promote_kernel, dim3((2 * p.B + rows_per_wg - 1) / rows_per_wg, p.H), dim3(kThreads), 0,
                      stream, fa);

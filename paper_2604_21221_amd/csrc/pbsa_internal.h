@@ -28,6 +28,12 @@ hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32
 hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
                          const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
                          hipStream_t stream);
+// launch_select of a chunk with launch_update_apply of the update of the chunk before it (parameters pu, same Kl) riding
+// in its pooling launch.  The caller guarantees that the new chunk's ring position is not the one being folded.
+hipError_t launch_select_apply(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
+                               const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
+                               const pbsa_params& pu, bf16_t* Kp, bf16_t* Vp, int32_t* p_len, float* S_sum,
+                               const int32_t* S_cnt, const bf16_t* Vl, const UpdateWs& ws, hipStream_t stream);
 // Scratch of the attention call that also produces the attention mass: what the attention kernel leaves for
 // the pass that follows it.  Per workgroup (128 query rows of a head) a tile list of list_cap ints: the ends of
 // the list's four parts, then a descriptor per tile; per wave r_slots records of 64 floats, one per tile in

@@ -17,6 +17,7 @@ PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 512, 64, 192, 512
 
 EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
            "pbsa_memory_update", "pbsa_memory_update_plan", "pbsa_memory_update_apply", "pbsa_attention_fwd_plan",
+           "pbsa_select_blocks_apply",
            "pbsa_attention_mass", "pbsa_mass_workspace_bytes", "pbsa_attention_fwd_mass",
            "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes", "pbsa_attention_bwd", "pbsa_blockify",
            "pbsa_unblockify", "pbsa_strerror", "pbsa_version")
@@ -81,6 +82,7 @@ def lib() -> ctypes.CDLL:
         L.pbsa_memory_update_plan.argtypes = [pp] + [vp] * 13 + [sz, vp]
         L.pbsa_memory_update_apply.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.pbsa_attention_fwd_plan.argtypes = [pp] + [vp] * 21 + [sz, vp]
+        L.pbsa_select_blocks_apply.argtypes = [pp] + [vp] * 8 + [pp] + [vp] * 7 + [sz, vp]
         L.pbsa_attention_mass.argtypes = [pp] + [vp] * 10
         L.pbsa_mass_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.pbsa_attention_fwd_mass.argtypes = [pp] + [vp] * 13 + [sz, vp]
@@ -92,7 +94,7 @@ def lib() -> ctypes.CDLL:
         L.pbsa_unblockify.argtypes = [pg, vp, ctypes.c_int64, vp, vp]
         for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
                      "pbsa_memory_update", "pbsa_memory_update_plan", "pbsa_memory_update_apply",
-                     "pbsa_attention_fwd_plan", "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
+                     "pbsa_attention_fwd_plan", "pbsa_select_blocks_apply", "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
                      "pbsa_attention_fwd_mass", "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes",
                      "pbsa_attention_bwd", "pbsa_blockify", "pbsa_unblockify"):
             getattr(L, name).restype = ctypes.c_int
@@ -157,6 +159,14 @@ def pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, Zl=None, ws=None, 
     w, wb = _ws(ws)
     _check(lib().pbsa_select_blocks(ctypes.byref(p), _ptr(Q), _ptr(Kl), _ptr(l_len), _ptr(l_map), _ptr(Kc_l),
                                     _ptr(Qc), _ptr(sel), _ptr(Zl), w, wb, _stream(stream)))
+
+
+def pbsa_select_blocks_apply(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, Zl, p_upd, Kp, Vp, p_len, S_sum, S_cnt, Vl, ws,
+                             stream=None):
+    w, wb = _ws(ws)
+    _check(lib().pbsa_select_blocks_apply(ctypes.byref(p), _ptr(Q), _ptr(Kl), _ptr(l_len), _ptr(l_map), _ptr(Kc_l),
+                                          _ptr(Qc), _ptr(sel), _ptr(Zl), ctypes.byref(p_upd), _ptr(Kp), _ptr(Vp),
+                                          _ptr(p_len), _ptr(S_sum), _ptr(S_cnt), _ptr(Vl), w, wb, _stream(stream)))
 
 
 def pbsa_attention_fwd(p, Q, Kp, Vp, p_len, Kl, Vl, l_len, l_map, sel, O, lse=None, ws=None, stream=None):

@@ -18,10 +18,11 @@ def bits_of(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def cache_for_workload(w: synth.Workload, layer: int = 0, device="cuda:0", fold=True):
+def cache_for_workload(w: synth.Workload, layer: int = 0, device="cuda:0", fold=True, ring_chunks=None):
     """Returns (cache, index of the first chunk to run).  Warm workloads get C seeded persistent slots,
     the pre-filled summary (if any) and their full window (global chunks 0..w-1); cold ones nothing."""
-    c = PbsaCache(w.H, w.d, w.B, w.Nq, w.window_chunks, w.C, w.k, np.float32(w.scale), fold=fold, device=device)
+    c = PbsaCache(w.H, w.d, w.B, w.Nq, w.window_chunks, w.C, w.k, np.float32(w.scale), fold=fold, device=device,
+                  ring_chunks=ring_chunks)
     if w.cold_start:
         return c, 0
     Kp, Vp = synth.persistent_init(w, layer)

@@ -241,6 +241,25 @@ def test_attention_with_plan_argument_checks(L):
         assert e.value.code == code, kw
 
 
+def test_select_with_pending_apply_argument_checks(L):
+    """pbsa_select_blocks_apply validates both halves and that the two parameter blocks describe the same cache."""
+    p, pu = good(), good(n_evict=4)
+    need = pbsa.pbsa_workspace_bytes(pu)
+
+    def both(p=p, pu=pu, Q=P, Kp=P, S_sum=P, S_cnt=P, Vl=P, ws=(0x10000, 1 << 30)):
+        pbsa.pbsa_select_blocks_apply(p, Q, P, P, P, P, P, P, None, pu, Kp, P, P, S_sum, S_cnt, Vl, ws, stream=0)
+
+    for kw, code in [(dict(Q=None), pbsa.PBSA_EINVAL), (dict(Kp=None), pbsa.PBSA_EINVAL), (dict(Vl=None), pbsa.PBSA_EINVAL),
+                     (dict(S_cnt=None), pbsa.PBSA_EINVAL), (dict(Q=P + 2), pbsa.PBSA_EALIGN), (dict(S_sum=P + 8), pbsa.PBSA_EALIGN),
+                     (dict(ws=None), pbsa.PBSA_EWS), (dict(ws=(0x10000, need - 1)), pbsa.PBSA_EWS),
+                     (dict(ws=(0x10040, need)), pbsa.PBSA_EALIGN), (dict(pu=good(n_evict=4, C=3)), pbsa.PBSA_EINVAL),
+                     (dict(pu=good(n_evict=4, H=3)), pbsa.PBSA_EINVAL), (dict(pu=good(C=65)), pbsa.PBSA_ESHAPE),
+                     (dict(p=good(k=513)), pbsa.PBSA_ESHAPE), (dict(pu=good(n_evict=17)), pbsa.PBSA_EINVAL)]:
+        with pytest.raises(pbsa.PbsaError) as e:
+            both(**kw)
+        assert e.value.code == code, kw
+
+
 def test_binding_refuses_host_tensors(L):
     import torch
     with pytest.raises(TypeError):
