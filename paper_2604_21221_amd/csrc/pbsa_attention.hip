@@ -810,11 +810,12 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
     d_vsrc = t_src[min((T_) + 1, n_tiles - 1)];                                                         \
     d_vmeta = t_meta[min((T_) + 1, n_tiles - 1)];                                                       \
   }
-#define PBSA_TURNOVER(T_)                                                                               \
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K(T_+1), V(T_) have landed */                     \
-  __syncthreads();                                                                                      \
+#define PBSA_NEXT_PLAN(T_)                                                                              \
   PBSA_PLAN_SHARED(d_ksrc, d_vsrc, d_vmeta, (T_) & 1, ((T_) + 1) & 1)                                   \
   PBSA_FETCH_DESC((T_) + 1)
+#define PBSA_TURNOVER(T_)                                                                               \
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K(T_+1), V(T_) have landed */                     \
+  __syncthreads();
 #define PBSA_RUN_SHARED(RAGGED, TB, TE)                                                                 \
   if ((TB) < (TE)) {                                                                                    \
     uint32_t kx[KS], vx[DT];                                                                            \
@@ -823,12 +824,16 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
     PBSA_ADDR_V(TB)                                                                                     \
     step<D, MASS, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo); \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
+    PBSA_NEXT_PLAN(TB)                                                                                  \
     step<D, MASS, false, true, true, RAGGED, kNoLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
     PBSA_TURNOVER(TB)                                                                                   \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
       PBSA_ADDR_V(t)                                                                                    \
       PBSA_ADDR_K(t + 1)                                                                                \
       step<D, MASS, true, true, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo); \
+      /* the plan of the next tile's loads, made while this step's last products are in the pipe (the step that   \
+         follows issues no loads) */                                                                    \
+      PBSA_NEXT_PLAN(t + 1)                                                                             \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
       step<D, MASS, true, true, true, RAGGED, kNoLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
       PBSA_TURNOVER(t + 1)                                                                              \
