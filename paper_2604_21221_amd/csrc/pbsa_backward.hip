@@ -162,21 +162,33 @@ __global__ void __launch_bounds__(kThreads) bwd_dkv_kernel(BwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qn = lane & 31, half = lane >> 5;
-  const int h = blockIdx.y;
   const float c2 = a.scale * kLog2e;
 
   // ---- what this workgroup is, and the list of streamed tiles ------------------------------------
   int n_cand;
   int* lst_b;                              // per streamed tile: its valid rows
   int* flag_s;                             // query blocks that attend the key block
-  // the workgroup's 64-key tile: persistent (slot c) or local (logical block l)
-  const int r_tile = blockIdx.x;
+  // The workgroup's 64-key tile: persistent (slot c) or local (logical block l).  The grid is one line with the
+  // persistent tiles of all heads first: every query block attends them, so their workgroups walk the whole chunk
+  // and run several times as long as a local block's, and a long workgroup that starts late ends the launch late.
+  const int n_pers = (a.C + 1) * SUB, n_locs = a.n_loc * SUB;
+  int h, r_tile;
+  {
+    int b = (int)blockIdx.x;
+    if (b < a.H * n_pers) {
+      h = b / n_pers;
+      r_tile = b % n_pers;
+    } else {
+      b -= a.H * n_pers;
+      h = b / n_locs;
+      r_tile = n_pers + b % n_locs;
+    }
+  }
   int fixed_len = 0, kv_slot_tile = 0;
   bool kv_local = false;
   n_cand = a.nqb * SUB;
   lst_b = lst_a + n_cand;
   flag_s = lst_b + n_cand;
-  const int n_pers = (a.C + 1) * SUB;
   kv_local = r_tile >= n_pers;
   if (!kv_local) {
     const int c = r_tile / SUB, sub = r_tile % SUB;
@@ -783,7 +795,7 @@ hipError_t launch_attention_bwd(const pbsa_params& p, const bf16_t* Q, const bf1
   }
   {
     const size_t n_cand = (size_t)p.nqb * sub;
-    const dim3 grid((p.C + 1 + p.n_loc) * sub, p.H);
+    const dim3 grid((unsigned)((p.C + 1 + p.n_loc) * sub * p.H));
     const size_t lds = ring + n_cand * 8 + (size_t)p.nqb * 4 + 16;
     e = p.d == 128 ? launch_with_lds(bwd_dkv_kernel<128>, a, grid, kThreads, lds, stream)
                    : launch_with_lds(bwd_dkv_kernel<64>, a, grid, kThreads, lds, stream);
