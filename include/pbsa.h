@@ -156,6 +156,21 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
                        const int64_t* l_id, float* scores, int32_t* slot_src, void* ws, size_t ws_bytes,
                        void* hip_stream);
 
+/* pbsa_memory_update for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without ws / ws_bytes, same
+ * results bit for bit (the same kernels run); the scratch is a fixed array of PBSA_STATIC_WS_BYTES inside the
+ * library's code object, of which every GPU the library runs on holds its own copy until the process ends.  The
+ * call allocates and frees nothing (the first call on a device looks the array's address up once).  Parameters
+ * whose pbsa_workspace_bytes() exceeds PBSA_STATIC_WS_BYTES are refused with PBSA_EWS before anything is enqueued.
+ * All calls on one GPU share that GPU's array: two of them that overlap in time (different streams, or different
+ * threads) race -- serialise them.  Nothing in the array has to survive between calls or start at zero (the
+ * kernels write every word before reading it). */
+#define PBSA_STATIC_WS_BYTES (4u << 20)
+int pbsa_memory_update_static(const pbsa_params* p, const float* Qc, const float* Kc_l, const float* Zl, void* Kp,
+                              void* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                              const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                              const int64_t* l_id, float* scores, int32_t* slot_src, void* hip_stream);
+
 /* pbsa_memory_update in two calls, for a caller that overlaps the update's decisions with the attention of the same
  * chunk.  _plan scores and ranks (Eq. 7-9): it reads Qc, Kc_l, Zl, Kc_p, p_len and the local region's metadata and
  * writes scores, slot_src, p_id, Kc_p, S_cnt (pass S_cnt = NULL to drop without compressing) and, into ws, what

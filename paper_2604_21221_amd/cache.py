@@ -173,12 +173,19 @@ class PbsaCache:
     def n_evict_now(self):
         return self.nqb if len(self.chunk_pos) == self.w + 1 else 0
 
-    def update(self):
+    def update(self, static_scratch=False):
+        """pbsa_memory_update; static_scratch: through pbsa_memory_update_static (the library's own scratch, no workspace)."""
         l_map, l_len, l_id = self._device_maps(want_ids=True)
         ne = self.n_evict_now()
         p = self.params(n_evict=ne)
-        pbsa.pbsa_memory_update(p, self.Qc, self.Kc_l, self.Zl, self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id, self.S_sum,
-                                self.S_cnt, self.Kl, self.Vl, l_len, l_map, l_id, self.scores, self.slot_src, self.ws)
+        if static_scratch:
+            pbsa.pbsa_memory_update_static(p, self.Qc, self.Kc_l, self.Zl, self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id,
+                                           self.S_sum, self.S_cnt, self.Kl, self.Vl, l_len, l_map, l_id, self.scores,
+                                           self.slot_src)
+        else:
+            pbsa.pbsa_memory_update(p, self.Qc, self.Kc_l, self.Zl, self.Kp, self.Vp, self.Kc_p, self.p_len, self.p_id,
+                                    self.S_sum, self.S_cnt, self.Kl, self.Vl, l_len, l_map, l_id, self.scores,
+                                    self.slot_src, self.ws)
         if ne:
             self.chunk_pos.pop(0)
             self.chunk_ids.pop(0)

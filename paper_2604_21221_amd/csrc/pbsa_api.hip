@@ -44,6 +44,35 @@ size_t workspace_bytes(const pbsa_params& p) { return pbsa::carve_update_ws(p, n
 
 }  // namespace
 
+// Scratch of pbsa_memory_update_static: device memory that belongs to the library, one copy per GPU, for callers
+// that cannot allocate.  Host code never uses the array's name as an address; it asks the runtime once per
+// device where that device's copy lives (static_scratch) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[PBSA_STATIC_WS_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};      // per device: address of its copy of `scratch`, once resolved
+
+// Address of the current device's copy of `scratch` (resolved on the first call on that device; no allocation).
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);   // every thread resolves the same address
+  }
+  *out = ptr;
+  return hipSuccess;
+}
+
+}  // namespace
+
 extern "C" {
 #pragma GCC visibility push(default)
 
@@ -55,7 +84,7 @@ const char* pbsa_strerror(int code) {
     case PBSA_EINVAL: return "invalid argument (NULL pointer, wrong params.size, or inconsistent counts)";
     case PBSA_ESHAPE: return "unsupported shape (d and B must be 64 or 128; n_loc, C, k within PBSA_MAX_*; a block shape must divide its grid)";
     case PBSA_EALIGN: return "misaligned pointer (16 bytes) or stride (multiple of 8 elements)";
-    case PBSA_EWS: return "workspace missing or too small (see pbsa_workspace_bytes)";
+    case PBSA_EWS: return "workspace missing or too small (see pbsa_workspace_bytes), or the call needs more than PBSA_STATIC_WS_BYTES of built-in scratch";
     case PBSA_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP call failed";
     default: return "unknown pbsa error code";
   }
@@ -205,6 +234,29 @@ int pbsa_memory_update(const pbsa_params* p, const float* Qc, const float* Kc_l,
                                      Kc_p, p_len, p_id, S_sum, S_cnt, static_cast<const pbsa::bf16_t*>(Kl),
                                      static_cast<const pbsa::bf16_t*>(Vl), l_len, l_map, l_id, scores, slot_src, w,
                                      static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
+int pbsa_memory_update_static(const pbsa_params* p, const float* Qc, const float* Kc_l, const float* Zl, void* Kp,
+                              void* Vp, float* Kc_p, int32_t* p_len, int64_t* p_id, float* S_sum, int32_t* S_cnt,
+                              const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
+                              const int64_t* l_id, float* scores, int32_t* slot_src, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc) return rc;
+  if (!Qc || !Kc_l || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !l_id) return PBSA_EINVAL;
+  if (p->C > 0 && (!Kc_p || !p_id || !slot_src)) return PBSA_EINVAL;
+  if ((S_sum == nullptr) != (S_cnt == nullptr)) return PBSA_EINVAL;
+  if (!aligned16(Kp) || !aligned16(Vp) || !aligned16(Kl) || !aligned16(Vl) || !aligned16(Kc_l) ||
+      !aligned16(Kc_p) || !aligned16(Qc) || !aligned16(S_sum))
+    return PBSA_EALIGN;
+  if (workspace_bytes(*p) > (size_t)PBSA_STATIC_WS_BYTES) return PBSA_EWS;   // before any HIP call
+  void* ws = nullptr;
+  hipError_t e = static_scratch(&ws);
+  if (e != hipSuccess) return hip_fail(e);
+  const pbsa::UpdateWs w = pbsa::carve_update_ws(*p, ws);
+  e = pbsa::launch_update(*p, Qc, Kc_l, Zl, static_cast<pbsa::bf16_t*>(Kp), static_cast<pbsa::bf16_t*>(Vp), Kc_p, p_len,
+                          p_id, S_sum, S_cnt, static_cast<const pbsa::bf16_t*>(Kl), static_cast<const pbsa::bf16_t*>(Vl),
+                          l_len, l_map, l_id, scores, slot_src, w, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 

@@ -14,9 +14,10 @@ LIB_PATH = os.path.join(_PKG, "libpbsa.so")
 
 PBSA_OK, PBSA_EINVAL, PBSA_ESHAPE, PBSA_EALIGN, PBSA_EWS, PBSA_EHIP = 0, -1, -2, -3, -4, -5
 PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 512, 64, 192, 512
+PBSA_STATIC_WS_BYTES = 4 << 20
 
 EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
-           "pbsa_memory_update", "pbsa_memory_update_plan", "pbsa_memory_update_apply", "pbsa_attention_fwd_plan",
+           "pbsa_memory_update", "pbsa_memory_update_static", "pbsa_memory_update_plan", "pbsa_memory_update_apply", "pbsa_attention_fwd_plan",
            "pbsa_select_blocks_apply",
            "pbsa_attention_mass", "pbsa_mass_workspace_bytes", "pbsa_attention_fwd_mass",
            "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes", "pbsa_attention_bwd", "pbsa_blockify",
@@ -79,6 +80,7 @@ def lib() -> ctypes.CDLL:
         L.pbsa_select_blocks.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.pbsa_attention_fwd.argtypes = [pp] + [vp] * 12 + [sz, vp]
         L.pbsa_memory_update.argtypes = [pp] + [vp] * 18 + [sz, vp]
+        L.pbsa_memory_update_static.argtypes = [pp] + [vp] * 18
         L.pbsa_memory_update_plan.argtypes = [pp] + [vp] * 13 + [sz, vp]
         L.pbsa_memory_update_apply.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.pbsa_attention_fwd_plan.argtypes = [pp] + [vp] * 21 + [sz, vp]
@@ -93,7 +95,7 @@ def lib() -> ctypes.CDLL:
         L.pbsa_blockify.argtypes = [pg, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_int64), vp]
         L.pbsa_unblockify.argtypes = [pg, vp, ctypes.c_int64, vp, vp]
         for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
-                     "pbsa_memory_update", "pbsa_memory_update_plan", "pbsa_memory_update_apply",
+                     "pbsa_memory_update", "pbsa_memory_update_static", "pbsa_memory_update_plan", "pbsa_memory_update_apply",
                      "pbsa_attention_fwd_plan", "pbsa_select_blocks_apply", "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
                      "pbsa_attention_fwd_mass", "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes",
                      "pbsa_attention_bwd", "pbsa_blockify", "pbsa_unblockify"):
@@ -182,6 +184,14 @@ def pbsa_memory_update(p, Qc, Kc_l, Zl, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt,
                                     _ptr(p_len), _ptr(p_id), _ptr(S_sum), _ptr(S_cnt), _ptr(Kl), _ptr(Vl),
                                     _ptr(l_len), _ptr(l_map), _ptr(l_id), _ptr(scores), _ptr(slot_src), w, wb,
                                     _stream(stream)))
+
+
+def pbsa_memory_update_static(p, Qc, Kc_l, Zl, Kp, Vp, Kc_p, p_len, p_id, S_sum, S_cnt, Kl, Vl, l_len, l_map, l_id, scores,
+                              slot_src, stream=None):
+    _check(lib().pbsa_memory_update_static(ctypes.byref(p), _ptr(Qc), _ptr(Kc_l), _ptr(Zl), _ptr(Kp), _ptr(Vp),
+                                           _ptr(Kc_p), _ptr(p_len), _ptr(p_id), _ptr(S_sum), _ptr(S_cnt), _ptr(Kl),
+                                           _ptr(Vl), _ptr(l_len), _ptr(l_map), _ptr(l_id), _ptr(scores),
+                                           _ptr(slot_src), _stream(stream)))
 
 
 def pbsa_memory_update_plan(p, Qc, Kc_l, Zl, Kc_p, p_len, p_id, S_cnt, l_len, l_map, l_id, scores, slot_src, ws,
