@@ -60,15 +60,16 @@ constexpr float kInitMax = -1.0e29f;       // reference of a row that has seen n
 // The softmax reference of a row is not its running max: probabilities only have to stay inside the
 // exponent range of bf16 / fp32, whose precision is relative.  The reference is set kLift base-2
 // exponent units above the row max of the sub-tile that sets it and is then used as it stands: a step
-// computes no row maximum.  Whether a reference still serves is read off the row sums, which are needed
-// anyway: a probability above 2^kSlack (or an overflow) makes its row's partial sum exceed kBig, and only
-// then is the sub-tile's softmax redone with a new reference and the output accumulators rescaled
-// (softmax_settle).  Probabilities thus lie between 2^-126 and 2^kSlack, their sums and products below
-// about 2^90, and after the first sub-tile of a row a new reference needs scores that rise by a factor
-// of 2^(kLift + kSlack).
-[[maybe_unused]] constexpr float kSlack = 60.0f;
-constexpr float kBig = 0x1p60f;            // 2^kSlack
-constexpr float kLift = 40.0f;
+// computes no row maximum.  Whether a reference still serves is read off the exponent fields of the rounded
+// probabilities: as long as every probability is below 2, the top exponent bit of every bf16 pattern is
+// clear, so the bitwise OR of all the pairs of a sub-tile has it clear in both halves; a probability of 2 or
+// more, an infinity or a NaN sets it (one three-input OR per two pairs, no false alarms).  Only then is the
+// sub-tile's softmax redone with a new reference and the output accumulators rescaled (softmax_redo).
+// Probabilities thus lie between 2^-126 and 2, a key more than 126 - kLift units below the score that set
+// the reference contributes nothing (less than 2^-76 of that score's weight), and after the first sub-tile
+// of a row a new reference needs scores that rise by a factor of 2^kLift.
+constexpr float kLift = 50.0f;
+constexpr uint32_t kTooBig = 0x40004000u;  // the top exponent bit of both halves of a bf16 pair
 
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {   // set bits of `mask` below this lane
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -160,7 +161,14 @@ __device__ __forceinline__ bf16x8 lds_read_vt(uint32_t addr) {
   const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_tr_t)(uintptr_t)(addr + 8 * ROW));
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
-__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& w) { return __builtin_bit_cast(bf16x8, w); }
+// P^T is kept as single registers (a bf16 pair each), put together into an operand where an MFMA uses them: the
+// rare redo of a sub-tile's softmax rewrites them, and whole-vector values merged after that branch cost the common
+// path a register copy per element
+typedef uint32_t PTile[2][2][4];
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint32_t (&w)[4]) {
+  const u32x4 v = {w[0], w[1], w[2], w[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
 
 // O^T accumulators live in the accumulator half of the register file for the whole kernel: the
 // second product is issued as an instruction with an accumulator-register destination, so the
@@ -206,28 +214,40 @@ __device__ __forceinline__ uint32_t prob_round(float e0, float e1) {
   pk[1] = (__bf16)e1;
   return __builtin_bit_cast(uint32_t, pk);
 }
-// Row sums are taken over the rounded values, the numbers the second product uses, one
-// v_dot2c_f32_bf16 per pair.  That instruction executes in the matrix pipeline: issued between MFMAs
-// it waits for the one in flight and holds up the next, and the wave, which issues in order, loses the
-// overlap of its vector work with the matrix pipe.  So the sums of a sub-tile are not taken in the step
-// that computes its probabilities but in one burst at the start of the next step, while that step's
-// first operand fragments are on their way from LDS and the matrix pipe has nothing to do.
-__device__ __forceinline__ void prob_sum(uint32_t w, float& psum) {
-  bf16x2 one;
-  one[0] = (__bf16)1.0f;
-  one[1] = (__bf16)1.0f;
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), one, psum, false);
+// Row sums are taken over the rounded values, the numbers the second product uses, by the matrix pipe: one
+// v_mfma_f32_16x16x32_bf16 per row group and 16 keys, whose B operand is the P^T operand of the second product
+// as it stands and whose A operand selects.  That instruction reads lane L's eight values as column L % 16,
+// contraction indices 8 (L / 16) ..: of the 32 query rows of a row group (row = L % 32, keys split over the two
+// half waves) rows r and r + 16 fall into the same column r % 16, on contraction groups {0, 2} and {1, 3}.  With
+// A[0][k] = 1 on groups 0 and 2, A[1][k] = 1 on groups 1 and 3 and zero elsewhere, output row 0 holds the sums
+// of rows 0..15 and output row 1 those of rows 16..31: lane n < 16 gets, in elements 0 and 1 of the result, the
+// complete sums (all 16 keys, both half waves) of rows n and n + 16.  Four instructions of 16 cycles per
+// 32-key sub-tile, against sixteen v_dot2c_f32_bf16 (which also run in the matrix pipe and stall the wave)
+// or thirty-two additions the vector unit has no slots for.
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+__device__ __forceinline__ bf16x8 sum_selector(int lane) {
+  const int m = lane & 15, kg = lane >> 4;
+  const bool on = (m == 0 && (kg & 1) == 0) || (m == 1 && (kg & 1) == 1);
+  const uint32_t w = on ? 0x3F803F80u : 0u;
+  const u32x4 v = {w, w, w, w};
+  return __builtin_bit_cast(bf16x8, v);
 }
-__device__ __forceinline__ void row_sums(const u32x4 (&p)[2][2], float (&psum)[2]) {
-  float ps[4] = {0.0f, 0.0f, 0.0f, 0.0f};    // two chains per row group
-#pragma unroll
-  for (int w = 0; w < 8; ++w)
-#pragma unroll
-    for (int g = 0; g < 2; ++g) prob_sum(p[g][w / 4][w % 4], ps[2 * g + (w & 1)]);
-  psum[0] = ps[0] + ps[1];
-  psum[1] = ps[2] + ps[3];
+// The instruction is written out so that its result register is its accumulator input (an MFMA's destination
+// must be the same registers as its addend or none of them; with the addend in the architectural half of the
+// register file the compiler's register assignment has let the two overlap by part).  The compiler does not
+// see a matrix instruction here: vector code that reads or rewrites the sums waits out the matrix pipe itself
+// (sum_settle).
+__device__ __forceinline__ void sum_mfma(f32x4& acc, const bf16x8& sel, const bf16x8& p) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(sel), "v"(p));
 }
-
+__device__ __forceinline__ void sum_settle(f32x4 (&l)[2]) {
+  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(l[0]), "+v"(l[1]));
+}
+__device__ __forceinline__ uint32_t or3(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_or3_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 template <int DT>
 __device__ __forceinline__ void rescale(f32x16 (&o)[2][DT], const float (&alpha)[2]) {
 #pragma unroll
@@ -304,27 +324,52 @@ __device__ __forceinline__ void dma_all(const DmaPlan<D>& p, bool k_too, bool v_
 }
 
 constexpr bool kLoads = true, kNoLoads = false;   // whether a step carries its plan's loads
-constexpr int kAhead = 4;     // MFMA pairs between an operand read and its use
+// Operand fragments.  A step finds the fragments of its first kPre MFMA pairs in registers: the step before it
+// read them from LDS under its last pairs (or, where a run of steps starts, a preload does).  The fragment of a
+// later pair r is read while pair max(0, r - kOwn) is issued.  So the matrix pipe never waits for LDS at the
+// start of a step, and a step has issued all its own LDS reads kOwn - kPre pairs before it starts reading
+// for the next one.
+constexpr int kPre = 4;
+constexpr int kOwn = 6;
+constexpr int issue_pair(int r) { return r - kOwn > 0 ? r - kOwn : 0; }
+
+// Which products a step has and where its sub-tiles lie: byte offsets of the K and V sub-tiles from the
+// tile the address registers point at.
+template <bool PV_, bool QK_, int K_OFF_, int V_OFF_>
+struct StepKind {
+  static constexpr bool PV = PV_, QK = QK_;
+  static constexpr int K_OFF = K_OFF_, V_OFF = V_OFF_;
+};
+// What a step does for the one that follows it: nothing; read its first fragments (same tile addresses); or
+// end the tile -- move the address registers to the next ring entries once their last read is issued, wait for
+// the staged tile and meet the other wave, then read the next tile's first fragments.
+constexpr int kNextNone = 0, kNextSame = 1, kNextTile = 2;
 
 template <int D, bool PV, bool QK, bool SM, bool RAGGED>
 struct StepCtx {
   static constexpr int NP = (PV ? Geo<D>::KS : 0) + (QK ? Geo<D>::KS : 0);   // MFMA pairs (PV has 2 DT = KS)
   static constexpr int NC = 2 * NP;                 // slots
   static constexpr int PRE = SM && RAGGED ? 2 : 0;  // slots that mask the keys that do not exist
-  const uint32_t (&vaddr)[Geo<D>::DT];
-  const uint32_t (&kaddr)[Geo<D>::KS];
+  uint32_t (&vaddr)[Geo<D>::DT];
+  uint32_t (&kaddr)[Geo<D>::KS];
   float c2;                      // log2(e) * softmax scale
   const bf16x8 (&qf)[2][Geo<D>::KS];
   f32x16 (&o)[2][Geo<D>::DT];
   f32x16 (&s_cur)[2];
   f32x16 (&s_next)[2];
-  u32x4 (&p_cur)[2][2];
-  const u32x4 (&p_prev)[2][2];
+  PTile& p_cur;
+  const PTile& p_prev;
   const float (&mc)[2];          // minus the softmax reference of each row group, times c2
   const int (&lim)[2];           // RAGGED: valid keys of the current sub-tile minus 4 * half, per row group
   const DmaPlan<D>& dma;
-  bf16x8 frag[2 * Geo<D>::KS];   // operand fragment of each MFMA pair
+  bf16x8 (&frag)[2 * Geo<D>::KS];   // operand fragment of each MFMA pair
+  int dk, dv;                    // kNextTile: what moves kaddr / vaddr to the next tile's ring entries
   float ex[32];                  // exp2 of the scores, row group g element v at 16 g + v, until they are rounded
+  f32x4 (&lsum)[2];              // PV: the running row sums, which take those of p_prev (see sum_selector)
+  f32x4 (&ltile)[2];             // PV, mass variant: the row sums of p_prev alone
+  bf16x8 sel;                    // the selecting operand of the row-sum instruction
+  uint32_t por;                  // SM: bitwise OR of the pairs of p_cur
+  uint32_t phold;                // SM: a pair waiting for the next one to share a three-input OR
 };
 
 // pair q: with both products, even q is PV pair q/2 and odd q is QK pair q/2
@@ -333,17 +378,51 @@ constexpr bool pair_is_pv(int q) { return PV && (!QK || q % 2 == 0); }
 template <bool PV, bool QK>
 constexpr int pair_index(int q) { return (PV && QK) ? q / 2 : q; }
 
-template <int D, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
-__device__ __forceinline__ void load_frag(StepCtx<D, PV, QK, SM, RAGGED>& c) {
-  if constexpr (Q < StepCtx<D, PV, QK, SM, RAGGED>::NP) {
-    constexpr int i = pair_index<PV, QK>(Q);
-    if constexpr (pair_is_pv<PV, QK>(Q)) {
+// reads the operand fragment of pair R of a step of kind KIND
+template <int D, class KIND, int R>
+__device__ __forceinline__ void load_pair(bf16x8 (&frag)[2 * Geo<D>::KS], const uint32_t (&vaddr)[Geo<D>::DT],
+                                          const uint32_t (&kaddr)[Geo<D>::KS]) {
+  constexpr int NP = (KIND::PV ? Geo<D>::KS : 0) + (KIND::QK ? Geo<D>::KS : 0);
+  if constexpr (R < NP) {
+    constexpr int i = pair_index<KIND::PV, KIND::QK>(R);
+    if constexpr (pair_is_pv<KIND::PV, KIND::QK>(R)) {
       constexpr int j = i / Geo<D>::DT, dt = i % Geo<D>::DT;
-      c.frag[Q] = lds_read_vt<Geo<D>::ROW>(c.vaddr[dt] + V_OFF + 16 * j * Geo<D>::ROW);
+      frag[R] = lds_read_vt<Geo<D>::ROW>(vaddr[dt] + KIND::V_OFF + 16 * j * Geo<D>::ROW);
     } else {
-      c.frag[Q] = lds_read_k(c.kaddr[i] + K_OFF);
+      frag[R] = lds_read_k(kaddr[i] + KIND::K_OFF);
     }
   }
+}
+template <int D, class KIND, int R = 0>
+__device__ __forceinline__ void preload_frags(bf16x8 (&frag)[2 * Geo<D>::KS], const uint32_t (&vaddr)[Geo<D>::DT],
+                                              const uint32_t (&kaddr)[Geo<D>::KS]) {
+  if constexpr (R < kPre) {
+    load_pair<D, KIND, R>(frag, vaddr, kaddr);
+    preload_frags<D, KIND, R + 1>(frag, vaddr, kaddr);
+  }
+}
+// the reads a step issues under pair Q for its own later pairs
+template <int D, class KIND, int Q, int R = kPre>
+__device__ __forceinline__ void own_loads(bf16x8 (&frag)[2 * Geo<D>::KS], const uint32_t (&vaddr)[Geo<D>::DT],
+                                          const uint32_t (&kaddr)[Geo<D>::KS]) {
+  constexpr int NP = (KIND::PV ? Geo<D>::KS : 0) + (KIND::QK ? Geo<D>::KS : 0);
+  if constexpr (R < NP) {
+    if constexpr (issue_pair(R) == Q) load_pair<D, KIND, R>(frag, vaddr, kaddr);
+    own_loads<D, KIND, Q, R + 1>(frag, vaddr, kaddr);
+  }
+}
+// the pair under which a step of kind KIND issues its last read through kaddr[ks] / vaddr[dt] (-1: only in a preload)
+template <int D, class KIND>
+constexpr int last_read_k(int ks) {
+  if (!KIND::QK) return -1;
+  const int r = KIND::PV ? 2 * ks + 1 : ks;
+  return r < kPre ? -1 : issue_pair(r);
+}
+template <int D, class KIND>
+constexpr int last_read_v(int dt) {
+  if (!KIND::PV) return -1;
+  const int i = Geo<D>::DT + dt, r = KIND::QK ? 2 * i : i;
+  return r < kPre ? -1 : issue_pair(r);
 }
 
 template <int D, bool PV, bool QK, bool SM, bool RAGGED, int Q, int GRP>
@@ -362,9 +441,11 @@ __device__ __forceinline__ void mfma_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
 // other NS slices share the 32 scores of a lane (score e in slice e NS / 32) and the 16 pairs: the
 // exponential of a score is issued in its slice and a pair is rounded one slice after its second
 // exponential (the last slice takes what would fall behind it), so every slice has about the same few
-// instructions and none of them waits for the previous one.
+// instructions and none of them waits for the previous one.  Every second pair is OR-ed, with the one before
+// it, into the word that decides in the last slice whether the reference served (returned as a wave mask of the
+// lanes that saw a probability of 2 or more, an infinity or a NaN).
 template <int D, bool PV, bool QK, bool SM, bool RAGGED, int C>
-__device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
+__device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c, unsigned long long& bad) {
   using S = StepCtx<D, PV, QK, SM, RAGGED>;
   if constexpr (!SM) {
   } else if constexpr (C < S::PRE) {
@@ -387,89 +468,40 @@ __device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c) {
       const int jr = (2 * n + 1) * NS / 32 + 1;
       if (jr == j || (last && jr > j)) {
         const uint32_t w = prob_round(c.ex[2 * n], c.ex[2 * n + 1]);
-        asm volatile("" ::"v"(w));
+        if (n % 2 == 0) {
+          c.phold = w;
+          asm volatile("" : "+v"(c.phold));          // keeps the conversion in this slot
+        } else {
+          c.por = n == 1 ? (c.phold | w) : or3(c.por, c.phold, w);
+          asm volatile("" : "+v"(c.por));
+        }
         c.p_cur[n / 8][(n % 8) / 4][n % 4] = w;
       }
     }
-  }
-}
-
-template <int D, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF, int I>
-__device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c) {
-  using S = StepCtx<D, PV, QK, SM, RAGGED>;
-  if constexpr (I < S::NC) {
-    constexpr int Q = I / 2, k = I % 2;
-    if constexpr (k == 0) load_frag<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + kAhead>(c);
-    mfma_slot<D, PV, QK, SM, RAGGED, Q, k>(c);
-    __builtin_amdgcn_sched_barrier(0);         // the MFMA first, then the slot's vector work
-    if constexpr (DMA) {
-      constexpr int every = (S::NC < 16 ? S::NC : 16) / DmaPlan<D>::NB;     // a burst every few slots of the first 16
-      static_assert(every >= 1, "a slot for every burst");
-      if constexpr (I % every == 0 && I / every < DmaPlan<D>::NB) dma_burst<D, I / every>(c.dma);
+    if constexpr (last) {
+      uint32_t top;
+      asm volatile("v_and_b32 %0, %3, %2\n\tv_cmp_ne_u32 %1, 0, %0" : "=&v"(top), "=s"(bad) : "v"(c.por), "s"(kTooBig));
     }
-    valu_slot<D, PV, QK, SM, RAGGED, I>(c);
-    __builtin_amdgcn_sched_barrier(0);
-    run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, I + 1>(c);
-  }
-}
-
-template <int D, bool PV, bool QK, bool SM, bool RAGGED, int K_OFF, int V_OFF, int Q>
-__device__ __forceinline__ void preload_frags(StepCtx<D, PV, QK, SM, RAGGED>& c) {
-  if constexpr (Q < kAhead) {
-    load_frag<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q>(c);
-    preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, Q + 1>(c);
   }
 }
 
 // Everything a step needs of the running softmax: per row group the reference (m_ref, and mc = -m_ref c2),
 // the running sum, and whether anything has been added to the output accumulators yet.
 struct SoftmaxRun {
-  float m_ref[2], mc[2], l_run[2];
+  float m_ref[2], mc[2];
+  f32x4 l_run[2];           // running row sums as the row-sum instruction leaves them: in lane n < 16 element 0 is
+                            // row n of the row group and element 1 row n + 16 (see sum_selector)
+  bf16x8 sel;               // sum_selector of this lane
+  unsigned long long bad;   // lanes in which the sub-tile whose softmax ran last needs another reference
   float c2, lift;
   bool o_live;
 };
-
-// The softmax of a sub-tile is settled at the start of the step that uses its probabilities (every step
-// with a second product).  Normally its row sums join the running sums and that is all.  If a sum says
-// that the reference of some row no longer serves (or was never set: a row's first keys), the softmax of
-// the sub-tile is redone here, outside the pipeline, for both row groups: row maxima, references raised
-// to kLift above them where that is higher than the old reference, probabilities, running sums; the caller then rescales the output accumulators by
-// alpha unless nothing has been added to them yet.  Returns whether the softmax was redone (the same
-// answer in every lane).  s is the sub-tile's S^T, which the coming step will overwrite, p its P^T.
-template <int D>
-__device__ __forceinline__ bool softmax_settle(const f32x16 (&s)[2], u32x4 (&p)[2][2], float (&m_ref)[2], float (&mc)[2],
-                                               float (&l_run)[2], float (&alpha)[2], float c2, float lift,
-                                               float (&psum)[2]) {
-  row_sums(p, psum);
-  if (__builtin_expect(__any(!(psum[0] <= kBig) || !(psum[1] <= kBig)), 0)) {
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-      const float tmax = row_max(s[g]);
-      // every row takes the occasion to move its reference up to kLift above what it sees now: the redo and the
-      // rescale cost the same, and a row that was drifting towards its own limit will not ask for another
-      const float m_new = tmax + lift > m_ref[g] ? tmax + lift : m_ref[g];
-      alpha[g] = __builtin_amdgcn_exp2f((m_ref[g] - m_new) * c2);
-      m_ref[g] = m_new;
-      mc[g] = -m_new * c2;
-#pragma unroll
-      for (int v = 0; v < 16; v += 2)
-        p[g][v / 8][(v % 8) / 2] = prob_round(prob_exp(s[g][v], c2, mc[g]), prob_exp(s[g][v + 1], c2, mc[g]));
-    }
-    row_sums(p, psum);
-    l_run[0] = l_run[0] * alpha[0] + psum[0];
-    l_run[1] = l_run[1] * alpha[1] + psum[1];
-    return true;
-  }
-  l_run[0] += psum[0];
-  l_run[1] += psum[1];
-  return false;
-}
 
 // The mass variant of the kernel also leaves, for every 64-key tile a wave walks and every one of its 64 rows,
 // the base-2 logarithm of the row's share of the softmax normaliser that falls on that tile, in absolute units
 // (independent of the reference in force at the time): log2(sum of the tile's probabilities) minus mc.  A later
 // pass turns them into attention mass per key block: 2^(that - log2 normaliser), summed over rows.  The sum of
-// a tile's first sub-tile is held until the second is settled; one 256-byte store per tile: lanes 0..31 hold
+// a tile's first sub-tile is held until the second is summed; one 256-byte store per tile: lanes 0..31 hold
 // rows 0..31, lanes 32..63 rows 32..63.
 struct MassOut {
   float* rp;        // where this wave's next 64 values go (uniform)
@@ -478,28 +510,143 @@ struct MassOut {
   float hold, hold_mc;   // the first sub-tile's row sum and the mc it is relative to
 };
 
-// K_OFF / V_OFF: byte offsets of the K and V sub-tiles from the tile the address arrays point at
-template <int D, bool MASS, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, int K_OFF, int V_OFF>
-__device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const uint32_t (&kaddr)[Geo<D>::KS],
+// What the slots of a step do beside the MFMA and the softmax slice.
+//  first slot of pair Q, before the MFMA: the LDS reads of the step's own later fragments.
+//  second slot of each of the last kPre pairs, after the MFMA: the read of one of the first fragments of the step
+//    that follows (NEXT); a step that ends a tile first waits for the staged tile and for its own reads and meets
+//    the other wave: from then on the ring entries it has been reading may be refilled, and the next tile's read.
+//  after the MFMA: staging loads (DMA), the caller's work for the next tile (MID, once, in slot 2), the move of
+//    the address registers to the next tile (each right after the pair that issued its last read), the slice
+//    of the softmax, and in four slots of the step a row-sum instruction of p_prev.
+template <int D, bool MASSV, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, class KIND, int NEXT, class NKIND, int I, class MID>
+__device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c, unsigned long long& bad, MID& mid) {
+  using S = StepCtx<D, PV, QK, SM, RAGGED>;
+  if constexpr (I < S::NC) {
+    constexpr int Q = I / 2, k = I % 2;
+    if constexpr (k == 0) own_loads<D, KIND, Q>(c.frag, c.vaddr, c.kaddr);
+    mfma_slot<D, PV, QK, SM, RAGGED, Q, k>(c);
+    __builtin_amdgcn_sched_barrier(0);         // the MFMA first, then the slot's vector work
+    if constexpr (k == 1 && NEXT != kNextNone && Q >= S::NP - kPre) {
+      // after both MFMAs of the pair: in a short step the fragment register read here may be this pair's own
+      if constexpr (NEXT == kNextTile && Q == S::NP - kPre) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      load_pair<D, NKIND, Q - (S::NP - kPre)>(c.frag, c.vaddr, c.kaddr);
+    }
+    if constexpr (DMA) {
+      constexpr int every = (S::NC < 16 ? S::NC : 16) / DmaPlan<D>::NB;     // a burst every few slots of the first 16
+      static_assert(every >= 1, "a slot for every burst");
+      if constexpr (I % every == 0 && I / every < DmaPlan<D>::NB) dma_burst<D, I / every>(c.dma);
+    }
+    if constexpr (I == 2) mid();
+    if constexpr (NEXT == kNextTile && k == 1) {
+      static_assert(NEXT != kNextTile || S::NP - kPre > issue_pair(S::NP - 1), "every address is free before the turnover");
+#pragma unroll
+      for (int ks = 0; ks < Geo<D>::KS; ++ks)
+        if (last_read_k<D, KIND>(ks) == Q || (Q == 0 && last_read_k<D, KIND>(ks) < 0)) {
+          c.kaddr[ks] += c.dk;
+          asm volatile("" : "+v"(c.kaddr[ks]));
+        }
+#pragma unroll
+      for (int dt = 0; dt < Geo<D>::DT; ++dt)
+        if (last_read_v<D, KIND>(dt) == Q || (Q == 0 && last_read_v<D, KIND>(dt) < 0)) {
+          c.vaddr[dt] += c.dv;
+          asm volatile("" : "+v"(c.vaddr[dt]));
+        }
+    }
+    valu_slot<D, PV, QK, SM, RAGGED, I>(c, bad);
+    if constexpr (PV) {
+      // the four row-sum instructions of p_prev (row group g, keys 16 j ..), spread over the step
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if ((2 * q + 1) * S::NC / 8 == I) {
+          sum_mfma(c.lsum[q / 2], c.sel, as_bf16x8(c.p_prev[q / 2][q % 2]));
+          // the mass variant wants the sub-tile's own sums as well, and the running sums exactly as without it
+          if constexpr (MASSV) sum_mfma(c.ltile[q / 2], c.sel, as_bf16x8(c.p_prev[q / 2][q % 2]));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    run_slots<D, MASSV, PV, QK, SM, RAGGED, DMA, KIND, NEXT, NKIND, I + 1, MID>(c, bad, mid);
+  }
+}
+
+// A sub-tile whose probabilities cannot be used (its step left sr.bad set: some probability came out above
+// 2, or the reference was never set: a row's first keys) gets its softmax redone here, outside the
+// pipeline and before anything uses it, for both row groups: row maxima, references raised to kLift above them
+// where that is higher than the old reference, the probabilities again, and the running sums and output
+// accumulators rescaled to the new references.  s is the sub-tile's S^T, which the coming step will overwrite,
+// p its P^T.  What this rare branch changes it changes in place (instructions whose result register is their
+// input's): values that merely merge with new ones after a branch cost the common path a register copy each.
+template <int D>
+__device__ __forceinline__ void softmax_redo(const f32x16 (&s)[2], PTile& p, SoftmaxRun& sr, f32x16 (&o)[2][Geo<D>::DT]) {
+  float alpha[2];
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    const float tmax = row_max(s[g]);
+    // every row takes the occasion to move its reference up to kLift above what it sees now: the redo and the
+    // rescale cost the same, and a row that was drifting towards its own limit will not ask for another
+    const float m_new = tmax + sr.lift > sr.m_ref[g] ? tmax + sr.lift : sr.m_ref[g];
+    alpha[g] = __builtin_amdgcn_exp2f((sr.m_ref[g] - m_new) * sr.c2);
+    const float mc_new = -m_new * sr.c2;
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) {
+      const float e0 = prob_exp(s[g][v], sr.c2, mc_new), e1 = prob_exp(s[g][v + 1], sr.c2, mc_new);
+      // (the wait states a vector instruction needs before it reads the result of a transcendental one are the
+      // compiler's business, but it cannot see what this instruction reads)
+      asm volatile("s_nop 3\n\tv_cvt_pk_bf16_f32 %0, %1, %2" : "+v"(p[g][v / 8][(v % 8) / 2]) : "v"(e0), "v"(e1));
+    }
+    asm volatile("v_mov_b32 %0, %1" : "+v"(sr.m_ref[g]) : "v"(m_new));
+    asm volatile("v_mov_b32 %0, %1" : "+v"(sr.mc[g]) : "v"(mc_new));
+  }
+  // the running sums live in lanes 0..15: row n in element 0 (this lane's own alpha), row n + 16 in element 1
+  sum_settle(sr.l_run);
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    sr.l_run[g][0] *= alpha[g];
+    sr.l_run[g][1] *= __shfl(alpha[g], (__lane_id() & 15) + 16, 64);
+  }
+  sum_settle(sr.l_run);
+  if (sr.o_live) rescale<Geo<D>::DT>(o, alpha);
+}
+
+// One step.  KIND: its products and sub-tile offsets.  PRELOADED: the fragments of its first kPre pairs are in
+// frag already.  NEXT / NKIND: what it does for the step after it (see run_slots).  mid() is called once, early
+// in the step.  dk, dv: kNextTile only.
+template <int D, bool MASS, bool SM, bool RAGGED, bool DMA, class KIND, bool PRELOADED, int NEXT, class NKIND, class MID>
+__device__ __forceinline__ void step(uint32_t (&vaddr)[Geo<D>::DT], uint32_t (&kaddr)[Geo<D>::KS],
                                      const bf16x8 (&qf)[2][Geo<D>::KS], f32x16 (&o)[2][Geo<D>::DT], f32x16 (&s_cur)[2],
-                                     f32x16 (&s_next)[2], u32x4 (&p_cur)[2][2], u32x4 (&p_prev)[2][2], SoftmaxRun& sr,
-                                     const int (&lim)[2], const DmaPlan<D>& dma, MassOut& mo) {
+                                     f32x16 (&s_next)[2], PTile& p_cur, PTile& p_prev, SoftmaxRun& sr,
+                                     const int (&lim)[2], const DmaPlan<D>& dma, MassOut& mo,
+                                     bf16x8 (&frag)[2 * Geo<D>::KS], int dk, int dv, MID& mid) {
   static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
-  StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, sr.c2, qf, o, s_cur, s_next, p_cur, p_prev, sr.mc, lim, dma, {}, {}};
-  preload_frags<D, PV, QK, SM, RAGGED, K_OFF, V_OFF, 0>(c);
+  constexpr bool PV = KIND::PV, QK = KIND::QK;
+  // the row sums of p_prev go straight into the running sums; the mass variant takes them per sub-tile as well
+  f32x4 pt[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+  StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, sr.c2, qf, o, s_cur, s_next, p_cur, p_prev, sr.mc, lim, dma, frag, dk, dv, {}, sr.l_run, pt, sr.sel, 0u, 0u};
+  if constexpr (!PRELOADED) preload_frags<D, KIND>(frag, vaddr, kaddr);
   if constexpr (PV) {
     // p_prev is the softmax of the sub-tile whose S^T still sits in s_next
-    float alpha[2], psum[2];
-    if (softmax_settle<D>(s_next, p_prev, sr.m_ref, sr.mc, sr.l_run, alpha, sr.c2, sr.lift, psum) && sr.o_live)
-      rescale<Geo<D>::DT>(o, alpha);
+    if (__builtin_expect(sr.bad != 0ull, 0)) softmax_redo<D>(s_next, p_prev, sr, o);
+    sr.bad = 0ull;
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  unsigned long long bad = 0ull;
+  run_slots<D, MASS, PV, QK, SM, RAGGED, DMA, KIND, NEXT, NKIND, 0, MID>(c, bad, mid);
+  if constexpr (SM) sr.bad = bad;
+  if constexpr (PV) {
+    sr.o_live = true;
     if constexpr (MASS) {
-      // psum[g] is this lane's half of the row sum of row group g (its 16 of the 32 keys).  Swapping the upper
-      // half of psum[0] with the lower half of psum[1] and adding gives lanes 0..31 the whole sum of group 0 and
-      // lanes 32..63 that of group 1: row 32 g + lane % 32 = lane.
-      const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(psum[0]), __float_as_uint(psum[1]), false, false);
-      const float tot = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+      sum_settle(pt);
+      // lanes 0..31 take the sums of rows 0..31 (row group 0), lanes 32..63 those of row group 1: row r of a
+      // group sits in lane r % 16, element r / 16
+      const int src = mo.lane & 15;
+      const float v00 = __shfl(pt[0][0], src, 64), v01 = __shfl(pt[0][1], src, 64);
+      const float v10 = __shfl(pt[1][0], src, 64), v11 = __shfl(pt[1][1], src, 64);
+      const float tot = mo.lane < 16 ? v00 : mo.lane < 32 ? v01 : mo.lane < 48 ? v10 : v11;
       const float mc_now = mo.hi ? sr.mc[1] : sr.mc[0];
-      if constexpr (V_OFF == 0) {          // the sub-tile settled is the one whose V the step multiplies: a tile's first
+      if constexpr (KIND::V_OFF == 0) {    // the sub-tile summed is the one whose V the step multiplied: a tile's first
         mo.hold = tot;
         mo.hold_mc = mc_now;
       } else {
@@ -510,11 +657,8 @@ __device__ __forceinline__ void step(const uint32_t (&vaddr)[Geo<D>::DT], const 
       }
     }
   }
-  __builtin_amdgcn_sched_barrier(0);
-  run_slots<D, PV, QK, SM, RAGGED, DMA, K_OFF, V_OFF, 0>(c);
-  if constexpr (PV) sr.o_live = true;
 }
-
+struct NoMid { __device__ __forceinline__ void operator()() const {} };
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
 // What the extra workgroups of a launch with PLAN need: the argument blocks of the update's decisions.
@@ -717,9 +861,12 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
       asm volatile("" : "+a"(o[g][dt]));
     }
   f32x16 sA[2], sB[2];                     // S^T of even / odd sub-tiles
-  u32x4 pA[2][2], pB[2][2];                // P^T of even / odd sub-tiles (bf16 pairs)
+  PTile pA, pB;                            // P^T of even / odd sub-tiles (bf16 pairs)
   const float c2 = a.scale * 1.4426950408889634f, lift = kLift / c2;
-  SoftmaxRun sr{{kInitMax, kInitMax}, {-kInitMax * c2, -kInitMax * c2}, {0.0f, 0.0f}, c2, lift, false};
+  SoftmaxRun sr{{kInitMax, kInitMax}, {-kInitMax * c2, -kInitMax * c2}, {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}},
+                sum_selector(lane), 0ull, c2, lift, false};
+  bf16x8 frag[2 * KS];                     // operand fragments, handed from step to step
+  NoMid nomid;
 
   // ---- operand addresses ------------------------------------------------------------------------
   // this lane's fragment addresses inside ring entry 0, sub-tile 0 (LDS byte addresses)
@@ -788,10 +935,19 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   // 2t+2 read the same two ring entries (V of t, K of t+1), so the loop body is that pair and takes one
   // set of addresses.  The ragged run masks, per tile, the keys that do not exist and the wave that does
   // not attend.
+  // The addresses are computed once per tile and kept in registers (the empty asm stops the compiler from
+  // recomputing them next to each use): an address made by a vector instruction right before the LDS read
+  // that uses it stalls the wave for about ten cycles per read.
 #define PBSA_ADDR_K(T_)                                                                                 \
-  _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) kx[ks] = ka0[ks] + ((T_) & 1) * TILE;
+  _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                   \
+    kx[ks] = ka0[ks] + ((T_) & 1) * TILE;                                                               \
+    asm volatile("" : "+v"(kx[ks]));                                                                    \
+  }
 #define PBSA_ADDR_V(T_)                                                                                 \
-  _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) vx[dt] = va0[dt] + ((T_) & 1) * TILE;
+  _Pragma("unroll") for (int dt = 0; dt < DT; ++dt) {                                                   \
+    vx[dt] = va0[dt] + ((T_) & 1) * TILE;                                                               \
+    asm volatile("" : "+v"(vx[dt]));                                                                    \
+  }
 #define PBSA_LIMITS(T_, RAGGED)                                                                         \
   if (RAGGED) {                                                                                         \
     const int meta_ = __builtin_amdgcn_readfirstlane(t_meta[T_]);                                       \
@@ -816,31 +972,45 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
 #define PBSA_TURNOVER(T_)                                                                               \
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K(T_+1), V(T_) have landed */                     \
   __syncthreads();
+  /* the query fragments stay in the accumulator half of the register file (only MFMAs read them) */
+#define PBSA_PIN_Q                                                                                      \
+  _Pragma("unroll") for (int g_ = 0; g_ < 2; ++g_)                                                      \
+    _Pragma("unroll") for (int ks_ = 0; ks_ < KS; ++ks_) asm volatile("" : "+a"(qf[g_][ks_]));
 #define PBSA_RUN_SHARED(RAGGED, TB, TE)                                                                 \
   if ((TB) < (TE)) {                                                                                    \
     uint32_t kx[KS], vx[DT];                                                                            \
     int lim0[2] = {0, 0}, lim1[2] = {0, 0};                                                             \
+    typedef StepKind<true, true, 0, 0> KindA;              /* the loop's first step of a tile */      \
+    typedef StepKind<true, true, SUB1, SUB1> KindB;        /* and its second */                        \
     PBSA_ADDR_K(TB)                                                                                     \
     PBSA_ADDR_V(TB)                                                                                     \
-    step<D, MASS, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo); \
+    step<D, MASS, false, false, kNoLoads, StepKind<false, true, 0, 0>, false, kNextNone, void, NoMid>(  \
+        vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo, frag, 0, 0, nomid);                          \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
     PBSA_NEXT_PLAN(TB)                                                                                  \
-    step<D, MASS, false, true, true, RAGGED, kNoLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
+    step<D, MASS, true, RAGGED, kNoLoads, StepKind<false, true, SUB1, 0>, false, kNextNone, void, NoMid>( \
+        vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, 0, 0, nomid);                          \
     PBSA_TURNOVER(TB)                                                                                   \
+    PBSA_ADDR_V(TB)                                                                                     \
+    PBSA_ADDR_K((TB) + 1)                                                                               \
+    /* (unconditional: fragments defined on one path only cost registers on all of them) */            \
+    preload_frags<D, KindA>(frag, vx, kx);                                                              \
     for (int t = (TB); t < (TE) - 1; ++t) {                                                             \
-      PBSA_ADDR_V(t)                                                                                    \
-      PBSA_ADDR_K(t + 1)                                                                                \
-      step<D, MASS, true, true, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo); \
-      /* the plan of the next tile's loads, made while this step's last products are in the pipe (the step that   \
-         follows issues no loads) */                                                                    \
-      PBSA_NEXT_PLAN(t + 1)                                                                             \
+      /* the tile's second step ends by moving the address registers to the other ring entries */       \
+      const int dv_ = (t & 1) ? -TILE : TILE;                                                           \
+      step<D, MASS, true, RAGGED, kLoads, KindA, true, kNextSame, KindB, NoMid>(                        \
+          vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo, frag, 0, 0, nomid);                        \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
-      step<D, MASS, true, true, true, RAGGED, kNoLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
-      PBSA_TURNOVER(t + 1)                                                                              \
+      /* the plan of the next tile's loads is made inside the second step, which issues no loads */     \
+      auto mid_ = [&]() { PBSA_NEXT_PLAN(t + 1) };                                                      \
+      step<D, MASS, true, RAGGED, kNoLoads, KindB, true, kNextTile, KindA, decltype(mid_)>(             \
+          vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, -dv_, dv_, mid_);                    \
     }                                                                                                   \
-    PBSA_ADDR_V((TE) - 1)                                                                               \
-    step<D, MASS, true, false, true, RAGGED, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo); \
-    step<D, MASS, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo); \
+    /* the address registers now point at V(TE-1) */                                                    \
+    step<D, MASS, true, RAGGED, kLoads, StepKind<true, false, 0, 0>, false, kNextSame,                  \
+         StepKind<true, false, 0, SUB1>, NoMid>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo, frag, 0, 0, nomid); \
+    step<D, MASS, false, false, kNoLoads, StepKind<true, false, 0, SUB1>, true, kNextNone, void, NoMid>( \
+        vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, 0, 0, nomid);                          \
     /* between runs the compiler may copy the accumulators to other registers: let the matrix pipe drain first */ \
     acc_settle<DT>(o[0]);                                                                               \
     acc_settle<DT>(o[1]);                                                                               \
@@ -885,9 +1055,15 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
       uint32_t kx[KS], vx[DT];
       const int lim0[2] = {0, 0};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kx[ks] = ka0[ks] + wave * TILE;
+      for (int ks = 0; ks < KS; ++ks) {
+        kx[ks] = ka0[ks] + wave * TILE;
+        asm volatile("" : "+v"(kx[ks]));
+      }
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) vx[dt] = va0[dt] + wave * TILE;
+      for (int dt = 0; dt < DT; ++dt) {
+        vx[dt] = va0[dt] + wave * TILE;
+        asm volatile("" : "+v"(vx[dt]));
+      }
       int d_cur = t_src[solo_b], d_next, d_nn;
       // sources of the loads of the steps of tile t: K from tile t+1, V from tile t; HALF picks the rows
 #define PBSA_SOLO_PLAN(HALF)                                                                            \
@@ -903,34 +1079,37 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
       dma_all<D>(plan, true, false);
       d_next = t_src[min(solo_b + 1, solo_e - 1)];
       PBSA_SOLO_LANDED
-      step<D, MASS, false, true, false, false, kNoLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo);
+      step<D, MASS, false, false, kNoLoads, StepKind<false, true, 0, 0>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo, frag, 0, 0, nomid);
       PBSA_SOLO_PLAN(0)
-      step<D, MASS, false, true, true, false, kLoads, SUB1, 0>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo);
+      step<D, MASS, true, false, kLoads, StepKind<false, true, SUB1, 0>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, 0, 0, nomid);
       PBSA_SOLO_LANDED
       for (int t = solo_b; t < solo_e - 1; ++t) {
         d_nn = t_src[min(t + 2, solo_e - 1)];
         PBSA_SOLO_PLAN(1)
-        step<D, MASS, true, true, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo);
+        step<D, MASS, true, false, kLoads, StepKind<true, true, 0, 0>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo, frag, 0, 0, nomid);
         PBSA_SOLO_LANDED
         d_cur = d_next;
         d_next = d_nn;
         PBSA_SOLO_PLAN(0)
-        step<D, MASS, true, true, true, false, kLoads, SUB1, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo);
+        step<D, MASS, true, false, kLoads, StepKind<true, true, SUB1, SUB1>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, 0, 0, nomid);
         PBSA_SOLO_LANDED
       }
       PBSA_SOLO_PLAN(1)
-      step<D, MASS, true, false, true, false, kLoads, 0, 0>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo);
+      step<D, MASS, true, false, kLoads, StepKind<true, false, 0, 0>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo, frag, 0, 0, nomid);
       PBSA_SOLO_LANDED
-      step<D, MASS, true, false, false, false, kNoLoads, 0, SUB1>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo);
+      step<D, MASS, false, false, kNoLoads, StepKind<true, false, 0, SUB1>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, 0, 0, nomid);
     }
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
   acc_settle<DT>(o[0]);
   acc_settle<DT>(o[1]);
+  sum_settle(sr.l_run);
 #pragma unroll
   for (int g = 0; g < 2; ++g) {
-    const float l_tot = sr.l_run[g] + __shfl_xor(sr.l_run[g], 32, 64);
+    // row r of the group: lane r % 16 of the running sums, element r / 16
+    const float l_lo = __shfl(sr.l_run[g][0], qn & 15, 64), l_hi = __shfl(sr.l_run[g][1], qn & 15, 64);
+    const float l_tot = qn < 16 ? l_lo : l_hi;
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     const int tok = tok0 + 32 * g;
     if (tok < a.Nq) {
