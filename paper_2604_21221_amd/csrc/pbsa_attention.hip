@@ -66,9 +66,9 @@ constexpr float kInitMax = -1.0e29f;       // reference of a row that has seen n
 // more, an infinity or a NaN sets it (one three-input OR per two pairs, no false alarms).  Only then is the
 // sub-tile's softmax redone with a new reference and the output accumulators rescaled (softmax_redo).
 // Probabilities thus lie between 2^-126 and 2, a key more than 126 - kLift units below the score that set
-// the reference contributes nothing (less than 2^-76 of that score's weight), and after the first sub-tile
+// the reference contributes nothing (less than 2^-46 of that score's weight), and after the first sub-tile
 // of a row a new reference needs scores that rise by a factor of 2^kLift.
-constexpr float kLift = 50.0f;
+constexpr float kLift = 80.0f;
 constexpr uint32_t kTooBig = 0x40004000u;  // the top exponent bit of both halves of a bf16 pair
 
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {   // set bits of `mask` below this lane
@@ -344,6 +344,7 @@ struct StepKind {
 // end the tile -- move the address registers to the next ring entries once their last read is issued, wait for
 // the staged tile and meet the other wave, then read the next tile's first fragments.
 constexpr int kNextNone = 0, kNextSame = 1, kNextTile = 2;
+constexpr int kMidPieces = 5;   // pieces of the caller's work inside a step (run_slots)
 
 template <int D, bool PV, bool QK, bool SM, bool RAGGED>
 struct StepCtx {
@@ -515,7 +516,7 @@ struct MassOut {
 //  second slot of each of the last kPre pairs, after the MFMA: the read of one of the first fragments of the step
 //    that follows (NEXT); a step that ends a tile first waits for the staged tile and for its own reads and meets
 //    the other wave: from then on the ring entries it has been reading may be refilled, and the next tile's read.
-//  after the MFMA: staging loads (DMA), the caller's work for the next tile (MID, once, in slot 2), the move of
+//  after the MFMA: staging loads (DMA), a piece of the caller's work for the next tile (MID, slots 2, 4, ...), the move of
 //    the address registers to the next tile (each right after the pair that issued its last read), the slice
 //    of the softmax, and in four slots of the step a row-sum instruction of p_prev.
 template <int D, bool MASSV, bool PV, bool QK, bool SM, bool RAGGED, bool DMA, class KIND, int NEXT, class NKIND, int I, class MID>
@@ -540,7 +541,9 @@ __device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c, uns
       static_assert(every >= 1, "a slot for every burst");
       if constexpr (I % every == 0 && I / every < DmaPlan<D>::NB) dma_burst<D, I / every>(c.dma);
     }
-    if constexpr (I == 2) mid();
+    // the caller's work for the next tile comes in kMidPieces pieces, one in each of the slots 2, 4, ...: scalar
+    // instructions issued in a lump hold the wave up for four to five cycles each, spread out for one or two
+    if constexpr (I >= 2 && I % 2 == 0 && (I - 2) / 2 < kMidPieces) mid(std::integral_constant<int, (I - 2) / 2>{});
     if constexpr (NEXT == kNextTile && k == 1) {
       static_assert(NEXT != kNextTile || S::NP - kPre > issue_pair(S::NP - 1), "every address is free before the turnover");
 #pragma unroll
@@ -658,7 +661,10 @@ __device__ __forceinline__ void step(uint32_t (&vaddr)[Geo<D>::DT], uint32_t (&k
     }
   }
 }
-struct NoMid { __device__ __forceinline__ void operator()() const {} };
+struct NoMid {
+  template <class PIECE>
+  __device__ __forceinline__ void operator()(PIECE) const {}
+};
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wuninitialized"
 // What the extra workgroups of a launch with PLAN need: the argument blocks of the update's decisions.
@@ -907,22 +913,32 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
              : reinterpret_cast<const unsigned char*>(BASE_P) + head_p + (size_t)(SRC) * (kTile * D * 2))
   // the plan that brings this wave's half of K tile KSRC into K ring entry KENTRY and of V tile VSRC
   // (descriptor words of the list) into V ring entry VENTRY
-#define PBSA_PLAN_SHARED(KSRC, VSRC, VMETA, KENTRY, VENTRY)                                             \
+#define PBSA_PLAN_K(KSRC, KENTRY)                                                                       \
   {                                                                                                     \
     const int ksrc_ = __builtin_amdgcn_readfirstlane(KSRC);                                             \
-    const int vsrc_ = __builtin_amdgcn_readfirstlane(VSRC);                                             \
-    const int vlast_ = (__builtin_amdgcn_readfirstlane(VMETA) & 0xFF) - 1;                              \
     plan.kp = PBSA_TILE_PTR(ksrc_, a.Kl, a.Kp) + wave * (TILE / 2);                                     \
+    plan.klds = smem_s + (KENTRY) * TILE + wave * (TILE / 2);                                           \
+  }
+#define PBSA_PLAN_V(VSRC, VENTRY)                                                                       \
+  {                                                                                                     \
+    const int vsrc_ = __builtin_amdgcn_readfirstlane(VSRC);                                             \
     plan.vtile = PBSA_TILE_PTR(vsrc_, a.Vl, a.Vp);                                                      \
     plan.vp = plan.vtile + wave * (TILE / 2);                                                           \
-    plan.klds = smem_s + (KENTRY) * TILE + wave * (TILE / 2);                                           \
     plan.vlds = smem_s + (2 + (VENTRY)) * TILE + wave * (TILE / 2);                                     \
+  }
+#define PBSA_PLAN_VRAGGED(VMETA)                                                                        \
+  {                                                                                                     \
+    const int vlast_ = (__builtin_amdgcn_readfirstlane(VMETA) & 0xFF) - 1;                              \
     plan.vragged = vlast_ < kTile - 1;                                                                  \
     if (plan.vragged) {                                                                                 \
       _Pragma("unroll") for (int i_ = 0; i_ < NIW; ++i_)                                                \
         plan.voff[i_] = min(32 * wave + RPI * i_ + rl, vlast_) * ROW + vchk;                            \
     }                                                                                                   \
   }
+#define PBSA_PLAN_SHARED(KSRC, VSRC, VMETA, KENTRY, VENTRY)                                             \
+  PBSA_PLAN_K(KSRC, KENTRY)                                                                             \
+  PBSA_PLAN_V(VSRC, VENTRY)                                                                             \
+  PBSA_PLAN_VRAGGED(VMETA)
 
   // One part of the shared list, tiles [TB, TE), as one pipelined run.  Tile t is sub-tiles 2t (buffers
   // A) and 2t+1 (buffers B):
@@ -1002,7 +1018,17 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
           vx, kx, qf, o, sB, sA, pB, pA, sr, lim1, plan, mo, frag, 0, 0, nomid);                        \
       PBSA_LIMITS(t + 1, RAGGED)                                                                        \
       /* the plan of the next tile's loads is made inside the second step, which issues no loads */     \
-      auto mid_ = [&]() { PBSA_NEXT_PLAN(t + 1) };                                                      \
+      auto mid_ = [&](auto piece_) {                                                                    \
+        constexpr int pc_ = decltype(piece_)::value;                                                    \
+        if constexpr (pc_ == 0) PBSA_PLAN_K(d_ksrc, (t + 1) & 1)                                        \
+        if constexpr (pc_ == 1) PBSA_PLAN_V(d_vsrc, (t + 2) & 1)                                        \
+        if constexpr (pc_ == 2) PBSA_PLAN_VRAGGED(d_vmeta)                                              \
+        if constexpr (pc_ == 3) d_ksrc = t_src[min(t + 4, n_tiles - 1)];                                \
+        if constexpr (pc_ == 4) {                                                                       \
+          d_vsrc = t_src[min(t + 3, n_tiles - 1)];                                                      \
+          d_vmeta = t_meta[min(t + 3, n_tiles - 1)];                                                    \
+        }                                                                                               \
+      };                                                                                                \
       step<D, MASS, true, RAGGED, kNoLoads, KindB, true, kNextTile, KindA, decltype(mid_)>(             \
           vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, -dv_, dv_, mid_);                    \
     }                                                                                                   \

@@ -84,11 +84,11 @@ def check_mass(got, ref, st, what):
     assert np.isfinite(got).all(), what
     assert (err <= bound).all(), what
     # exactly zero where nothing is attended, positive where something is -- unless it is below what the kernels
-    # hold: fp32 for the separate pass; in the attention kernel a probability is a bf16 number 2^50 below its
-    # row's reference, so whatever lies more than 2^-76 under the row's largest is flushed to zero (a block of
-    # 64 x 64 such entries stays below 6e-20)
+    # hold: fp32 for the separate pass; in the attention kernel a probability is a bf16 number 2^80 below its
+    # row's reference, so whatever lies more than 2^-46 under the score that set the reference is flushed to zero
+    # (a block of 128 x 128 such entries stays below 2.4e-10, four orders of magnitude under MASS_ATOL)
     assert (got[done][ref[done] == 0.0] == 0.0).all(), what
-    assert (got[done][ref[done] > 1e-18] > 0.0).all(), what
+    assert (got[done][ref[done] > 1e-9] > 0.0).all(), what
     rows = chunk_lens(st).astype(np.float64)
     np.testing.assert_allclose(got.sum(2), np.tile(rows, (st.H, 1)), rtol=MASS_RTOL, err_msg=what)
 
