@@ -42,7 +42,7 @@ def cpu_baseline(w, n_rows=1536):
     attention scaled to the whole chunk.  Runs on a steady-state state reached by the oracle itself."""
     import numpy as np
     from oracle import rollout
-    from paper_2604_21221_amd import synth
+    from harness import synth
     st, g0 = rollout.state_for_workload(w)
     lens = synth.block_lens(w)
     n_setup = (w.window_chunks + 2) if w.cold_start else 1
@@ -73,12 +73,11 @@ def sweep_kernel_grid(dev, reps=20):
     """pbsa_attention_fwd alone (block sets from pbsa_select_blocks on the same synthetic inputs) on the
     kernel-benchmark shapes of the paper's appendix: N_C = 5376 or 21504 query tokens (3 or 12 frames of
     1792 tokens), local KV N_L = 2 or 4 N_C, persistent KV N_P = 0.25 or 0.5 N_L, 12 heads of 128 (the
-    paper does not state heads), blocks of 128.  N_C = 21504 with N_L = 4 N_C needs 672 local blocks, more
-    than the interface allows, and is left out.  The dense stand-in is the same kernel with every visible
-    block selected (block-causal within the chunk)."""
+    paper does not state heads), blocks of 128: all eight shapes of the table.  The dense stand-in is the same
+    kernel with every visible block selected (block-causal within the chunk)."""
     import numpy as np
     import torch
-    from paper_2604_21221_amd import synth, workloads
+    from harness import synth, workloads
     rows = []
     memo = {}
     gen_qkv, gen_pers = synth.chunk_qkv, synth.persistent_init
@@ -92,7 +91,8 @@ def sweep_kernel_grid(dev, reps=20):
             return memo[key]
         return wrapped
     synth.chunk_qkv, synth.persistent_init = once(gen_qkv, "qkv"), once(gen_pers, "pers")
-    for frames, ratio_l, ratio_p in ((3, 2, 0.25), (3, 2, 0.5), (3, 4, 0.25), (3, 4, 0.5), (12, 2, 0.25), (12, 2, 0.5)):
+    for frames, ratio_l, ratio_p in ((3, 2, 0.25), (3, 2, 0.5), (3, 4, 0.25), (3, 4, 0.5), (12, 2, 0.25), (12, 2, 0.5),
+                                     (12, 4, 0.25), (12, 4, 0.5)):
         dense_us = None
         memo.clear()
         for topk in (1.0, 0.25, 0.125, 0.0625):
@@ -183,7 +183,7 @@ def bench_backward(w, c, Q_at, g_next, n_ring, dev, K, W, settle):
     call repeated on the same inputs (it changes nothing it reads)."""
     import numpy as np
     import torch
-    from paper_2604_21221_amd import synth, workloads
+    from harness import synth, workloads
     c.adopt_chunk(g_next)
     Qd = Q_at[(c.n_appended - 1) % n_ring]
     c.select(Qd)
@@ -220,79 +220,18 @@ def bench_backward(w, c, Q_at, g_next, n_ring, dev, K, W, settle):
                          "frac": round(flops / us / 1e6 / PEAK_BF16_TFLOPS, 5), "traffic": None}}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"],
-                    help="cfg3: the shapes of cfg2 on 30 layers, each with its own cache and inputs, visited in turn")
-    ap.add_argument("--denoise-steps", type=int, default=1,
-                    help="T: selection + attention passes per layer-chunk; the cache (persistent set, window, pooled keys "
-                         "of the window) is the same for all of them and the update follows the last one only")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--settle-steps", type=int, default=150,
-                    help="untimed steps before the warm-up steps, so that the GPU's clocks have settled under load")
-    ap.add_argument("--sweep-kernel-grid", action="store_true",
-                    help="instead of the step benchmark: pbsa_attention_fwd alone on the shapes of the paper's "
-                         "kernel benchmark (forward latency table of its appendix) that fit the interface limits, "
-                         "at top-k 6.25 / 12.5 / 25 % and with every block selected (the dense stand-in)")
-    ap.add_argument("--blockify", action="store_true",
-                    help="instead of the step benchmark: the block rearrange of a chunk's Q, K, V and its inverse")
-    ap.add_argument("--overlap-update", action="store_true",
-                    help="take the update's decisions on a second stream beside the attention kernel (pbsa_memory_update_plan, "
-                         "then pbsa_memory_update_apply after it) instead of pbsa_memory_update after the attention call; "
-                         "measured slower: the second queue's workgroups keep the attention launch from filling the chip "
-                         "in one round")
-    ap.add_argument("--separate-update", action="store_true",
-                    help="the step as three calls, pbsa_select_blocks -> pbsa_attention_fwd -> pbsa_memory_update, instead of "
-                         "the default pbsa_select_blocks -> pbsa_attention_fwd_plan (the attention launch with one more "
-                         "workgroup per head that takes the update's decisions) -> pbsa_memory_update_apply")
-    ap.add_argument("--chain-apply", action="store_true",
-                    help="two library calls per step: pbsa_select_blocks_apply (the selection, with the fold / promote of the "
-                         "previous step's update riding in its pooling launch; the ring gets a spare position so that the new "
-                         "chunk is not written over the blocks still to be folded) and pbsa_attention_fwd_plan")
-    ap.add_argument("--fine-mass", action="store_true",
-                    help="the step with the persistent set ranked by the attention actually paid: after the attention "
-                         "call pbsa_attention_mass sums the probabilities per key block and pbsa_memory_update_fine "
-                         "ranks by them (select + attention + mass + update per step)")
-    ap.add_argument("--backward", action="store_true",
-                    help="instead of the step benchmark: pbsa_attention_bwd (dQ, dK, dV) on the workload's steady-state "
-                         "cache, after one forward call that supplies O and lse")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="run three 1 GiB device copies and exit: the known-size kernel that the HBM byte "
-                         "counters are scaled by")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the path shards by head without exchange; "
-                 "no multi-GPU figure is produced). Use --gpus 1.")
+def bench_steps(w, args, K, W, settle, dev, layers=None):
+    """The step benchmark on workload w: K timed steps after `settle` + W untimed ones, on `layers` layers (the
+    workload's own count unless given).  Returns the fields of the JSON line (no CPU baseline)."""
     import numpy as np
     import torch
-    from paper_2604_21221_amd import synth, workloads
-    assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    dev = "cuda:0"
-    if args.calibrate_copy:
-        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        b = torch.empty_like(a)
-        for _ in range(3):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": b.numel() * 4, "copies": 3}))
-        return
-    if args.blockify:
-        print(json.dumps(bench_blockify(dev)))
-        return
-    if args.sweep_kernel_grid:
-        print(json.dumps(sweep_kernel_grid(dev, reps=max(args.steps, 10))))
-        return
-    w = synth.WORKLOADS[args.workload]
-    K, W = args.steps, args.warmup
+    from harness import synth, workloads
 
     # ---- state: reach steady state (full window, full persistent set, non-empty summary) untimed ----
     # one cache and one set of inputs per layer; a step visits the layers in turn
-    L, T = w.n_layers, max(1, args.denoise_steps)
+    L, T = layers or w.n_layers, max(1, args.denoise_steps)
     n_ring = w.window_chunks + 1               # chunks in the local region during a step
-    chained = args.chain_apply and not (args.separate_update or args.overlap_update or args.fine_mass or args.backward)
+    chained = not (args.three_launches or args.separate_update or args.fine_mass or args.backward)
     n_pos = n_ring + 1 if chained else n_ring  # ring positions
     n_setup = n_pos + 2 if w.cold_start else n_pos
     caches, Q_ats = [], []
@@ -311,8 +250,7 @@ def main():
     torch.cuda.synchronize()
 
     if args.backward:
-        print(json.dumps(bench_backward(w, caches[0], Q_ats[0], g_next, n_ring, dev, K, W, args.settle_steps)))
-        return
+        return bench_backward(w, caches[0], Q_ats[0], g_next, n_ring, dev, K, W, settle)
     O = torch.empty(w.H, w.Nq, w.d, dtype=torch.bfloat16, device=dev)
     K2 = min(K, 20)            # extra steps after the timed region: per-call split of select and update
     n_total = W + K + K2
@@ -327,8 +265,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     n_done = [0]
-    overlap = args.overlap_update and not args.fine_mass      # the mass-ranked update needs the attention call's output
-    fused = not (args.separate_update or overlap or args.fine_mass)
+    fused = not (args.separate_update or args.fine_mass)
 
     def one_step(i, attn_ev=None, sel_ev=None, upd_ev=None, mass_ev=None):
         # the producer has written the next chunk's K/V into the ring position that was just freed
@@ -352,8 +289,6 @@ def main():
         if sel_ev is not None:
             sel_ev[1].record(stream)
         plen_hist[i].copy_(c.p_len, non_blocking=True)
-        if overlap:
-            c.mark_selection_done()
         if attn_ev is not None:
             attn_ev[0].record(stream)
         if args.fine_mass:
@@ -364,8 +299,6 @@ def main():
             c.attention(Qd, O)
         if attn_ev is not None:
             attn_ev[1].record(stream)
-        if overlap:
-            c.update_plan_on_side_stream()         # scoring and retention, beside the attention kernel just issued
         if args.fine_mass and mass_ev is not None:
             # for comparison only (the step does not need it): the same matrix by a separate pass over the keys
             mass_ev[0].record(stream)
@@ -377,7 +310,7 @@ def main():
             c.update_fine(Mt)
         elif chained:
             c.defer_apply()                        # fold / promote ride in the next step's selection call
-        elif overlap or fused:
+        elif fused:
             c.update_apply()
         else:
             c.update()
@@ -386,7 +319,7 @@ def main():
 
     # The engine clock of an idle GPU takes some tens of milliseconds of load to settle (the first
     # ~50 steps run about 10 % slower): bring it there before the W warm-up steps, whatever W is.
-    for _ in range(args.settle_steps):
+    for _ in range(settle):
         one_step(0)
     for i in range(W):
         one_step(i)
@@ -427,7 +360,7 @@ def main():
         folded = occupied + w.H * w.nqb - min(w.H * w.C, occupied + w.H * w.nqb)
         # what the ranking reads: the coarse logits, or the candidates' rows of the mass matrix
         ranked = (w.H * (w.C + w.nqb) * ((w.nqb + 3) & ~3) * 4 if args.fine_mass else
-                  0 if overlap or fused else w.H * w.nqb * n_loc * 4)      # the apply call reads no scores
+                  0 if fused else w.H * w.nqb * n_loc * 4)      # the apply call reads no scores
         upd_bytes.append(ranked + folded * 2 * blk + promoted * 4 * blk
                          + w.H * (2 * 2 * w.B * w.d * 4 + 2 * blk))
     upd_b = float(np.mean(upd_bytes))
@@ -471,12 +404,6 @@ def main():
         u["achieved"] = round(u["algorithmic_bytes"] / u["us_per_call"] / 1e3, 1)
         u["frac"] = round(u["achieved"] / PEAK_HBM_GBS, 4)
         out["hbm_bound_calls"]["pbsa_select_blocks_apply"] = u
-    if overlap:
-        out["config"]["schedule"] = ("pbsa_memory_update_plan (scoring, retention) on a second stream under the attention kernel, "
-                                     "pbsa_memory_update_apply (fold, promote) after it")
-        u = out["hbm_bound_calls"].pop("pbsa_memory_update")
-        u["note"] = "the apply call alone; the plan call is hidden under the attention kernel"
-        out["hbm_bound_calls"]["pbsa_memory_update_apply"] = u
     if args.fine_mass:
         mass_us = sum(a.elapsed_time(b) for a, b in ev_mass) / K2 * 1e3
         qk_flops = mean_flops / T / 2          # the first product of the attention only
@@ -488,6 +415,95 @@ def main():
             "us_per_call": round(mass_us, 2), "executed_gflop": round(qk_flops / 1e9, 3),
             "achieved": round(qk_flops / mass_us / 1e6, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": round(qk_flops / mass_us / 1e6 / PEAK_BF16_TFLOPS, 5), "bound": "mfma"}}
+    out["_mean_flops"], out["_T"] = mean_flops, T
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="cfg3: the shapes of cfg2 on 30 layers, each with its own cache and inputs, visited in turn")
+    ap.add_argument("--denoise-steps", type=int, default=1,
+                    help="T: selection + attention passes per layer-chunk; the cache (persistent set, window, pooled keys "
+                         "of the window) is the same for all of them and the update follows the last one only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--settle-steps", type=int, default=150,
+                    help="untimed steps before the warm-up steps, so that the GPU's clocks have settled under load")
+    ap.add_argument("--sweep-kernel-grid", action="store_true",
+                    help="instead of the step benchmark: pbsa_attention_fwd alone on the shapes of the paper's "
+                         "kernel benchmark (forward latency table of its appendix) that fit the interface limits, "
+                         "at top-k 6.25 / 12.5 / 25 % and with every block selected (the dense stand-in)")
+    ap.add_argument("--blockify", action="store_true",
+                    help="instead of the step benchmark: the block rearrange of a chunk's Q, K, V and its inverse")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="the step as the three plain calls, pbsa_select_blocks -> pbsa_attention_fwd -> pbsa_memory_update")
+    ap.add_argument("--three-launches", action="store_true",
+                    help="self-contained steps: pbsa_select_blocks -> pbsa_attention_fwd_plan (the attention launch with one more "
+                         "workgroup per head that takes the update's decisions) -> pbsa_memory_update_apply, instead of the "
+                         "default of two library calls per step: pbsa_select_blocks_apply (the selection, with the fold / "
+                         "promote of the previous step's update riding in its pooling launch; the ring gets a spare position "
+                         "so that the new chunk is not written over the blocks still to be folded) and pbsa_attention_fwd_plan")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the short runs of cfg2, cfg3 and cfg4 that follow the timed region of cfg5")
+    ap.add_argument("--per-config-layers", type=int, default=8,
+                    help="layers of cfg3 in its short run (each needs its own synthetic inputs, generated on the host)")
+    ap.add_argument("--fine-mass", action="store_true",
+                    help="the step with the persistent set ranked by the attention actually paid: after the attention "
+                         "call pbsa_attention_mass sums the probabilities per key block and pbsa_memory_update_fine "
+                         "ranks by them (select + attention + mass + update per step)")
+    ap.add_argument("--backward", action="store_true",
+                    help="instead of the step benchmark: pbsa_attention_bwd (dQ, dK, dV) on the workload's steady-state "
+                         "cache, after one forward call that supplies O and lse")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run three 1 GiB device copies and exit: the known-size kernel that the HBM byte "
+                         "counters are scaled by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards by head without exchange; "
+                 "no multi-GPU figure is produced). Use --gpus 1.")
+    import numpy as np
+    import torch
+    from harness import synth, workloads
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = "cuda:0"
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": b.numel() * 4, "copies": 3}))
+        return
+    if args.blockify:
+        print(json.dumps(bench_blockify(dev)))
+        return
+    if args.sweep_kernel_grid:
+        print(json.dumps(sweep_kernel_grid(dev, reps=max(args.steps, 10))))
+        return
+    w = synth.WORKLOADS[args.workload]
+    out = bench_steps(w, args, args.steps, args.warmup, args.settle_steps, dev)
+    if args.backward:
+        print(json.dumps(out))
+        return
+    mean_flops, T = out.pop("_mean_flops"), out.pop("_T")
+    if args.workload == "cfg5" and not (args.no_per_config or args.fine_mass or args.separate_update):
+        # the other configurations, after the timed region of the headline one (the chip is warm: short settling)
+        out["per_config"] = {}
+        for name in ("cfg2", "cfg3", "cfg4"):
+            w2 = synth.WORKLOADS[name]
+            layers = min(w2.n_layers, args.per_config_layers)
+            r = bench_steps(w2, args, max(args.steps, 3 * layers), 5, 40, dev, layers=layers)
+            row = {"us_per_layer_chunk": r["us_per_layer_chunk"], "value": r["value"], "unit": "TFLOP/s",
+                   "attention_us_per_launch": r["roofline"]["us_per_launch"], "frac": r["roofline"]["frac"],
+                   "executed_gflop_per_step": r["config"]["executed_gflop_per_step"], "steps": r["steps"]}
+            if w2.n_layers > 1:
+                row["layers"] = layers
+                row["note"] = (f"{layers} of the {w2.n_layers} independently seeded layers, visited in turn: their caches "
+                               "(86 MB of K/V each) already exceed what the chip keeps between visits")
+            out["per_config"][name] = row
     if not args.no_cpu_baseline:
         from oracle import pbsa_oracle as orc
         t_sel, t_att, t_upd, n_rows = cpu_baseline(w)

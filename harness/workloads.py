@@ -5,7 +5,7 @@ import numpy as np
 import torch
 
 from . import synth
-from .cache import PbsaCache
+from paper_2604_21221_amd.cache import PbsaCache
 
 
 def bf16_tensor(bits: np.ndarray, device) -> torch.Tensor:
@@ -31,10 +31,7 @@ def cache_for_workload(w: synth.Workload, layer: int = 0, device="cuda:0", fold=
                      torch.full((w.H, w.C), w.B, dtype=torch.int32, device=device), ids)
     if w.summary_prefill:
         S_sum, S_cnt = synth.summary_init(w, layer)
-        s = torch.from_numpy(S_sum).to(device)
-        n = torch.from_numpy(S_cnt).to(device)
-        mean = (s / n.clamp(min=1).to(torch.float32)[:, None, :, None]).to(torch.bfloat16)
-        c.set_summary(s, n, mean[:, 0], mean[:, 1], (n > 0).sum(1).to(torch.int32))
+        c.set_summary(torch.from_numpy(S_sum).to(device), torch.from_numpy(S_cnt).to(device))
     for g in range(w.window_chunks):
         _, K, V = synth.chunk_qkv(w, layer, g)
         c.append_chunk(bf16_tensor(K, device), bf16_tensor(V, device), g)

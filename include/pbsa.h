@@ -76,11 +76,18 @@ extern "C" {
 #define PBSA_EWS    (-4) /* workspace missing or smaller than pbsa_workspace_bytes()            */
 #define PBSA_EHIP   (-5) /* a HIP call or kernel launch failed                                   */
 
-#define PBSA_MAX_N_LOC 512 /* logical local blocks          */
-#define PBSA_MAX_C      64 /* persistent slots that pbsa_memory_update can maintain */
-#define PBSA_MAX_C_ATTEND 192 /* persistent slots that pbsa_attention_fwd can attend (pbsa_select_blocks does not
+/* Limits of pbsa_select_blocks and pbsa_attention_fwd (the largest shape of the paper's kernel benchmark,
+ * N_C = 21504 queries against N_L = 4 N_C local and N_P = N_L / 2 persistent tokens in blocks of 128, fits). */
+#define PBSA_MAX_N_LOC 672 /* logical local blocks          */
+#define PBSA_MAX_K     672 /* selected blocks per query block */
+#define PBSA_MAX_C_ATTEND 336 /* persistent slots that pbsa_attention_fwd can attend (pbsa_select_blocks does not
                                * look at them); above PBSA_MAX_C the caller maintains the set itself */
-#define PBSA_MAX_K     512 /* selected blocks per query block */
+/* Limits of every other entry point (the memory update in all its forms, pbsa_select_blocks_apply,
+ * pbsa_attention_fwd_plan, pbsa_attention_fwd_mass, pbsa_attention_mass, pbsa_attention_bwd): */
+#define PBSA_MAX_N_LOC_AUX 512
+#define PBSA_MAX_K_AUX     512
+#define PBSA_MAX_C_AUX     192 /* slots attended, where the call attends                      */
+#define PBSA_MAX_C          64 /* persistent slots that pbsa_memory_update can maintain       */
 
 typedef struct pbsa_params {
   uint32_t size;            /* sizeof(pbsa_params); guards against ABI drift                        */
@@ -114,6 +121,15 @@ int pbsa_workspace_bytes(const pbsa_params* p, size_t* out);
  * pooled keys of persistent blocks the caller installs by hand. */
 int pbsa_pool_blocks(const pbsa_params* p, const void* X, const int32_t* len, int32_t n_blocks, float* out,
                      void* hip_stream);
+
+/* The bf16 view of a compressed-history block from its running sums and counts (the pooling of the evicted blocks,
+ * Sec. 3.3 "compressed global memory"; the same arithmetic as the fold of pbsa_memory_update): for every head, row t
+ * of slot C of Kp and of Vp becomes S_sum[h][0 / 1][t][:] / S_cnt[h][t] (fp32 division, rounded to nearest even) where
+ * S_cnt[h][t] > 0, other rows are left as they are, and p_len[h][C] becomes the number of such rows.  For a caller
+ * that installs a summary by hand (a resumed roll-out).  S_sum [H][2][B][d] fp32 and S_cnt [H][B] int32 are read,
+ * Kp, Vp [H][C+1][B][d] bf16 and p_len [H][C+1] int32 are written; all device memory.  Uses p->H, B, d, C only. */
+int pbsa_summary_view(const pbsa_params* p, const float* S_sum, const int32_t* S_cnt, void* Kp, void* Vp,
+                      int32_t* p_len, void* hip_stream);
 
 /* Coarse routing inside the local region (Eq. 10-11).  Pools the chunk's queries into Qc, refreshes
  * the pooled keys Kc_l of logical blocks >= pool_from, scores every visible local block of every

@@ -151,7 +151,7 @@ def state_for_workload(w, layer=0, fold=True):
     """OracleState primed for a synth.Workload: warm workloads get their full window (global chunks
     0..w-1), C seeded persistent slots and the pre-filled summary; cold-start workloads get nothing.
     Returns (state, index of the first chunk to run)."""
-    from paper_2604_21221_amd import synth
+    from harness import synth
     st = OracleState(w.H, w.d, w.B, w.Nq, w.window_chunks, w.C, w.k, np.float32(w.scale), fold=fold)
     if w.cold_start:
         return st, 0
@@ -168,7 +168,7 @@ def state_for_workload(w, layer=0, fold=True):
 
 def run_chunk(st, w, layer, g, rows=None):
     """One layer-chunk step on global chunk g: append K/V, select, (attention rows), update. Returns dict."""
-    from paper_2604_21221_amd import synth
+    from harness import synth
     Q, K, V = synth.chunk_qkv(w, layer, g)
     st.append_chunk(synth.to_blocks(K, w.B), synth.to_blocks(V, w.B), synth.block_lens(w), g * w.nqb + np.arange(w.nqb))
     sel, _ = st.select(Q)

@@ -29,6 +29,20 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=h
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# The attention, mass and backward kernels issue some matrix instructions as inline assembly with hand-placed wait
+# states: the compiler these were checked with (every-element GPU tests of all <D, B> instances).  Another
+# compiler may schedule around them differently: the build warns, and the GPU tests decide.
+CHECKED_HIPCC = "7.2.26015"
+
+
+def hipcc_version() -> str:
+    out = subprocess.run(["hipcc", "--version"], check=True, capture_output=True, text=True).stdout
+    for line in out.splitlines():
+        if line.startswith("HIP version:"):
+            return line.split(":", 1)[1].strip()
+    return "unknown"
+
+
 def _compile(name: str, flags, keep_asm: bool) -> str:
     obj = os.path.join(BUILD_DIR, name.replace(".hip", ".o"))
     cmd = ["hipcc", *COMMON, *flags, "-c", os.path.join(CSRC, name), "-o", obj]
@@ -40,6 +54,10 @@ def _compile(name: str, flags, keep_asm: bool) -> str:
 
 def build(keep_asm: bool = False) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
+    ver = hipcc_version()
+    if not ver.startswith(CHECKED_HIPCC):
+        print(f"build.py: hipcc {ver} is not the checked {CHECKED_HIPCC}: run the GPU tests (pytest -m gpu) before "
+              "trusting the inline-assembly kernels", file=sys.stderr)
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(lambda kv: _compile(kv[0], kv[1], keep_asm), SOURCES.items()))
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)

@@ -106,13 +106,12 @@ class PbsaCache:
         pbsa.pbsa_pool_blocks(self.params(), X, flat_len, self.H * c, out)
         self.Kc_p[:, :c] = out.view(self.H, c, self.d)
 
-    def set_summary(self, S_sum, S_cnt, Ks_bf16, Vs_bf16, length):
-        """Install a pre-filled compressed-history state (sums, counts and the bf16 view of slot C)."""
+    def set_summary(self, S_sum, S_cnt):
+        """Install a pre-filled compressed-history state: sums and counts; pbsa_summary_view derives the bf16 view
+        in slot C and its length."""
         self.S_sum.copy_(S_sum)
         self.S_cnt.copy_(S_cnt)
-        self.Kp[:, self.C] = Ks_bf16
-        self.Vp[:, self.C] = Vs_bf16
-        self.p_len[:, self.C] = length
+        pbsa.pbsa_summary_view(self.params(), self.S_sum, self.S_cnt, self.Kp, self.Vp, self.p_len)
 
     def append_chunk(self, K, V, chunk_id):
         """Copy a chunk's K/V ([H][Nq][d] bf16, token-major) into the next ring position, block-major."""
@@ -170,11 +169,16 @@ class PbsaCache:
         pbsa.pbsa_attention_fwd(p, Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map, self.sel, O, lse)
         return O
 
+    def _no_pending(self):
+        # a deferred apply still owns the workspace and the slot lengths it will commit
+        assert self._pending is None, "a deferred update is pending: select() or flush() completes it first"
+
     def n_evict_now(self):
         return self.nqb if len(self.chunk_pos) == self.w + 1 else 0
 
     def update(self, static_scratch=False):
         """pbsa_memory_update; static_scratch: through pbsa_memory_update_static (the library's own scratch, no workspace)."""
+        self._no_pending()
         l_map, l_len, l_id = self._device_maps(want_ids=True)
         ne = self.n_evict_now()
         p = self.params(n_evict=ne)
@@ -228,6 +232,7 @@ class PbsaCache:
         return O, Mt
 
     def update_fine(self, Mt):
+        self._no_pending()
         l_map, l_len, l_id = self._device_maps(want_ids=True)
         ne = self.n_evict_now()
         pbsa.pbsa_memory_update_fine(self.params(n_evict=ne), Mt, self.Kc_l, self.Kp, self.Vp, self.Kc_p, self.p_len,
@@ -263,31 +268,18 @@ class PbsaCache:
                                 grads["dQ"], grads["dKp"], grads["dVp"], grads["dKl"], grads["dVl"], self._bwd_ws)
         return grads
 
-    def mark_selection_done(self):
-        """Records, on the current stream, the point the plan call has to wait for (call right after select())."""
-        if getattr(self, "_side", None) is None:
-            self._side = torch.cuda.Stream(device=self.dev)          # default priority
-            self._ev_sel, self._ev_plan = torch.cuda.Event(), torch.cuda.Event()
-        self._ev_sel.record(torch.cuda.current_stream(self.dev))
-
-    def update_plan_on_side_stream(self):
-        """pbsa_memory_update_plan on a second stream, ordered after the point mark_selection_done() recorded.
-        Issued after the attention call, whose workgroups are then placed first (they need whole SIMDs; issued
-        before it, the plan's kernels take SIMDs the attention launch then cannot fill in one round) and the
-        plan's kernels run beside it in the SIMDs it leaves free.  update_apply() completes the update."""
+    def update_plan(self):
+        """pbsa_memory_update_plan: the update's decisions alone (scores, retention, slot sources); update_apply()
+        moves the data."""
+        self._no_pending()
         l_map, l_len, l_id = self._device_maps(want_ids=True)
         self._plan_p = self.params(n_evict=self.n_evict_now())
-        self._side.wait_event(self._ev_sel)
         pbsa.pbsa_memory_update_plan(self._plan_p, self.Qc, self.Kc_l, self.Zl, self.Kc_p, self.p_len, self.p_id,
-                                     self.S_cnt, l_len, l_map, l_id, self.scores, self.slot_src, self.ws,
-                                     stream=self._side)
-        self._ev_plan.record(self._side)
-        self._plan_on_side = True
+                                     self.S_cnt, l_len, l_map, l_id, self.scores, self.slot_src, self.ws)
 
     def update_apply(self):
-        """Waits (on the device) for the plan, then fold, promote, commit; slides the window."""
-        if self._plan_on_side:                 # the plan ran on another stream
-            torch.cuda.current_stream(self.dev).wait_event(self._ev_plan)
+        """After attention_with_plan() or update_plan(): fold, promote, commit; slides the window."""
+        self._no_pending()
         pbsa.pbsa_memory_update_apply(self._plan_p, self.Kp, self.Vp, self.p_len, self.S_sum, self.S_cnt, self.Kl, self.Vl,
                                       self.ws)
         ne = self._plan_p.n_evict
@@ -301,6 +293,7 @@ class PbsaCache:
         """pbsa_attention_fwd_plan: the attention of the chunk and, by extra workgroups of the same launch, the
         decisions of the update that follows it (needs the logits the selection call left).  update_apply()
         completes the update."""
+        self._no_pending()
         if O is None:
             O = torch.empty_like(Q)
         l_map, l_len, l_id = self._device_maps(want_ids=True)
@@ -308,7 +301,6 @@ class PbsaCache:
         pbsa.pbsa_attention_fwd_plan(self._plan_p, Q, self.Kp, self.Vp, self.p_len, self.Kl, self.Vl, l_len, l_map, self.sel,
                                      O, lse, self.Qc, self.Kc_l, self.Zl, self.Kc_p, self.p_id, self.S_cnt, l_id,
                                      self.scores, self.slot_src, self.ws)
-        self._plan_on_side = False
         return O
 
     def step_fused(self, Q, K=None, V=None, chunk_id=None, O=None, lse=None):
@@ -349,19 +341,6 @@ class PbsaCache:
         self.select(Q)
         O = self.attention_with_plan(Q, O, lse)
         self.defer_apply()
-        return O
-
-    def step_overlapped(self, Q, K=None, V=None, chunk_id=None, O=None, lse=None):
-        """The same step with the update's decisions taken on a second stream while the attention kernel runs
-        (they read only what the selection call left and the cache's metadata); fold, promote and the commit of
-        the slot lengths follow the attention call.  K = V = None: the chunk has been adopted already."""
-        if K is not None:
-            self.append_chunk(K, V, chunk_id)
-        self.select(Q)
-        self.mark_selection_done()
-        O = self.attention(Q, O, lse)
-        self.update_plan_on_side_stream()
-        self.update_apply()
         return O
 
     def step(self, Q, K, V, chunk_id, O=None, lse=None):

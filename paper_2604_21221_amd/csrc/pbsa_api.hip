@@ -16,7 +16,8 @@ int hip_fail(hipError_t e) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Checks that do not depend on which call is made, but for the number of persistent slots it can handle.
-int check_common(const pbsa_params* p, int max_c = PBSA_MAX_C) {
+int check_common(const pbsa_params* p, int max_c = PBSA_MAX_C, int max_n_loc = PBSA_MAX_N_LOC_AUX,
+                 int max_k = PBSA_MAX_K_AUX) {
   if (!p) return PBSA_EINVAL;
   if (p->size != sizeof(pbsa_params)) return PBSA_EINVAL;
   if (p->H < 1 || p->Nq < 1 || p->n_loc < 0 || p->C < 0 || p->k < 0 || p->n_sink < 0 || p->n_evict < 0 ||
@@ -29,8 +30,12 @@ int check_common(const pbsa_params* p, int max_c = PBSA_MAX_C) {
   if (p->n_sink > p->C || p->n_evict > p->n_loc || p->pool_from > p->n_loc) return PBSA_EINVAL;
   if (p->causal != 0 && p->causal != 1) return PBSA_EINVAL;
   if (!(p->scale > 0.0f) || !(p->scale < 1e30f)) return PBSA_EINVAL;
-  if (p->n_loc > PBSA_MAX_N_LOC || p->C > max_c || p->k > PBSA_MAX_K) return PBSA_ESHAPE;
+  if (p->n_loc > max_n_loc || p->C > max_c || p->k > max_k) return PBSA_ESHAPE;
   if ((int64_t)p->H * p->n_loc_cap * p->B * p->d >= ((int64_t)1 << 40)) return PBSA_ESHAPE;
+  // heads are a grid dimension of the selection, scoring and fold launches, and the selection forms 32-bit byte
+  // offsets into the pooled keys
+  if (p->H > 65535) return PBSA_ESHAPE;
+  if ((int64_t)p->H * p->n_loc_cap * p->d * 4 >= ((int64_t)1 << 32)) return PBSA_ESHAPE;
   return PBSA_OK;
 }
 
@@ -111,11 +116,25 @@ int pbsa_pool_blocks(const pbsa_params* p, const void* X, const int32_t* len, in
   return e == hipSuccess ? PBSA_OK : hip_fail(e);
 }
 
+int pbsa_summary_view(const pbsa_params* p, const float* S_sum, const int32_t* S_cnt, void* Kp, void* Vp, int32_t* p_len,
+                      void* hip_stream) {
+  if (!p || p->size != sizeof(pbsa_params)) return PBSA_EINVAL;
+  if (p->H < 1 || p->C < 0) return PBSA_EINVAL;
+  if (p->d != 64 && p->d != 128) return PBSA_ESHAPE;
+  if (p->B != 64 && p->B != 128) return PBSA_ESHAPE;
+  if (p->H > 65535 || p->C > PBSA_MAX_C_ATTEND) return PBSA_ESHAPE;
+  if (!S_sum || !S_cnt || !Kp || !Vp || !p_len) return PBSA_EINVAL;
+  if (!aligned16(S_sum) || !aligned16(Kp) || !aligned16(Vp)) return PBSA_EALIGN;
+  hipError_t e = pbsa::launch_summary_view(*p, S_sum, S_cnt, static_cast<pbsa::bf16_t*>(Kp),
+                                           static_cast<pbsa::bf16_t*>(Vp), p_len, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PBSA_OK : hip_fail(e);
+}
+
 int pbsa_select_blocks(const pbsa_params* p, const void* Q, const void* Kl, const int32_t* l_len,
                        const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl, void* ws,
                        size_t ws_bytes, void* hip_stream) {
   (void)ws; (void)ws_bytes;
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_ATTEND, PBSA_MAX_N_LOC, PBSA_MAX_K);
   if (rc) return rc;
   if (!Q || !Kl || !l_len || !l_map || !Kc_l || !Qc) return PBSA_EINVAL;
   if (p->k > 0 && !sel) return PBSA_EINVAL;
@@ -131,7 +150,7 @@ int pbsa_select_blocks_apply(const pbsa_params* p, const void* Q, const void* Kl
                              const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
                              const pbsa_params* p_upd, void* Kp, void* Vp, int32_t* p_len, float* S_sum,
                              const int32_t* S_cnt, const void* Vl, void* ws, size_t ws_bytes, void* hip_stream) {
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_AUX);
   if (rc) return rc;
   rc = check_common(p_upd);
   if (rc) return rc;
@@ -160,7 +179,7 @@ int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, cons
                        const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
                        const int32_t* sel, void* O, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
   (void)ws; (void)ws_bytes;
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_ATTEND, PBSA_MAX_N_LOC, PBSA_MAX_K);
   if (rc) return rc;
   if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O) return PBSA_EINVAL;
   if (p->k > 0 && !sel) return PBSA_EINVAL;
@@ -180,7 +199,7 @@ int pbsa_attention_fwd(const pbsa_params* p, const void* Q, const void* Kp, cons
 
 int pbsa_mass_workspace_bytes(const pbsa_params* p, size_t* out) {
   if (!out) return PBSA_EINVAL;
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_AUX);
   if (rc) return rc;
   *out = pbsa::carve_mass_ws(*p, nullptr).bytes;
   return PBSA_OK;
@@ -190,7 +209,7 @@ int pbsa_attention_fwd_mass(const pbsa_params* p, const void* Q, const void* Kp,
                             const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map,
                             const int32_t* sel, void* O, float* lse, float* Mt, void* ws, size_t ws_bytes,
                             void* hip_stream) {
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_AUX);
   if (rc) return rc;
   if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O || !lse || !Mt) return PBSA_EINVAL;
   if (p->k > 0 && !sel) return PBSA_EINVAL;
@@ -325,7 +344,7 @@ int pbsa_memory_update_apply(const pbsa_params* p, void* Kp, void* Vp, int32_t* 
 int pbsa_attention_mass(const pbsa_params* p, const void* Q, const void* Kp, const int32_t* p_len, const void* Kl,
                         const int32_t* l_len, const int32_t* l_map, const int32_t* sel, const float* lse, float* Mt,
                         void* hip_stream) {
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_AUX);
   if (rc) return rc;
   if (!Q || !Kp || !p_len || !Kl || !l_len || !l_map || !lse || !Mt) return PBSA_EINVAL;
   if (p->k > 0 && !sel) return PBSA_EINVAL;
@@ -362,7 +381,7 @@ int pbsa_memory_update_fine(const pbsa_params* p, const float* Mt, const float* 
 
 int pbsa_bwd_workspace_bytes(const pbsa_params* p, size_t* out) {
   if (!out) return PBSA_EINVAL;
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_AUX);
   if (rc) return rc;
   *out = pbsa::bwd_workspace_bytes(*p);
   return PBSA_OK;
@@ -372,7 +391,7 @@ int pbsa_attention_bwd(const pbsa_params* p, const void* Q, const void* Kp, cons
                        const void* Kl, const void* Vl, const int32_t* l_len, const int32_t* l_map, const int32_t* sel,
                        const void* O, const void* dO, const float* lse, float* dQ, float* dKp, float* dVp, float* dKl,
                        float* dVl, void* ws, size_t ws_bytes, void* hip_stream) {
-  int rc = check_common(p, PBSA_MAX_C_ATTEND);
+  int rc = check_common(p, PBSA_MAX_C_AUX);
   if (rc) return rc;
   if (!Q || !Kp || !Vp || !p_len || !Kl || !Vl || !l_len || !l_map || !O || !dO || !lse || !dQ || !dKp || !dVp ||
       !dKl || !dVl)

@@ -39,6 +39,8 @@
 // fp32, base 2 (scale and log2 e folded into one fma), against a reference that a step takes as given;
 // the row sums (over the bf16-rounded probabilities, the numbers the second product uses) and the check
 // that the reference still serves come at the start of the next step (softmax_settle).
+#include <type_traits>
+
 #include "pbsa_internal.h"
 #include "pbsa_plan_device.h"
 
@@ -54,7 +56,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kThreads = 128;
 constexpr int kRowsPerWg = 128;
 constexpr int kTile = 64;                 // keys per staged tile
-constexpr int kMaxTiles = 2 * (PBSA_MAX_C_ATTEND + 1) + 2 * PBSA_MAX_N_LOC;   // persistent + local 64-key tiles
+// persistent + local 64-key tiles: of the plain attention call, and of the variants that also score or take decisions
+constexpr int kMaxTiles = 2 * (PBSA_MAX_C_ATTEND + 1) + 2 * PBSA_MAX_N_LOC;
+constexpr int kMaxTilesAux = 2 * (PBSA_MAX_C_AUX + 1) + 2 * PBSA_MAX_N_LOC_AUX;
 constexpr float kMasked = -1.0e30f;        // score of a key that does not exist
 constexpr float kInitMax = -1.0e29f;       // reference of a row that has seen no key: above kMasked, below any score
 // The softmax reference of a row is not its running max: probabilities only have to stay inside the
@@ -122,7 +126,7 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint3
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_off), "v"(lane_off), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 // Four such loads of consecutive KiB: the instruction's offset field moves the LDS address and the
 // global address alike, so one setting of M0 and one scalar base serve four loads whose sources are
@@ -138,7 +142,7 @@ __device__ __forceinline__ void dma16x4(const void* base, uint32_t o0, uint32_t 
                "global_load_lds_dwordx4 %4, %5 offset:3072"
                :
                : "s"(lds_base), "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(base), "n"(LDS_IMM)
-               : "memory", "scc");
+               : "memory", "scc", "m0");
 }
 
 template <int D>
@@ -692,12 +696,18 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   constexpr int NIW = (kTile / RPI) / 2;            // global_load_lds instructions per wave per tile
   constexpr int SMEM = 4 * TILE;                    // K ring (2 tiles), V ring (2 tiles)
   static_assert((3 * PBSA_MAX_N_LOC + PBSA_MAX_C_ATTEND + 1) * 4 <= SMEM, "setup scratch must fit");
+  // the plain call takes the larger limits and keeps the list within two workgroups' share of a CU's LDS by
+  // storing 16-bit descriptors (the mass variant's carry the key block as well)
+  constexpr bool kAux = MASS || PLAN;
+  constexpr int kTilesMax = kAux ? kMaxTilesAux : kMaxTiles;
+  constexpr int kLocMax = kAux ? PBSA_MAX_N_LOC_AUX : PBSA_MAX_N_LOC;
+  using meta_t = std::conditional_t<kAux, int, uint16_t>;
 
   __shared__ __align__(1024) unsigned char smem[SMEM];
-  __shared__ int t_src[kMaxTiles];         // bit 31: local, bits 0..: (slot * SUB + sub)
-  __shared__ int t_meta[kMaxTiles];        // valid keys (bits 0..7) | waves that attend (bits 8, 9)
+  __shared__ int t_src[kTilesMax];         // bit 31: local, bits 0..: (slot * SUB + sub)
+  __shared__ meta_t t_meta[kTilesMax];     // valid keys (bits 0..7) | waves that attend (bits 8, 9)
   __shared__ int cls_end_s[4];             // end of each part of the list
-  constexpr int kMaxRounds = (kMaxTiles + kThreads - 1) / kThreads;
+  constexpr int kMaxRounds = (kTilesMax + kThreads - 1) / kThreads;
   __shared__ int cnt_s[kMaxRounds * 2 * 4], off_s[kMaxRounds * 2 * 4];   // per round, wave and class: tiles, first place
   int* lflag = reinterpret_cast<int*>(smem);        // setup scratch, dead before the first tile is staged
 
@@ -713,7 +723,7 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
     if ((int)blockIdx.x < n_plan) {
       const int hp = (int)blockIdx.x;
       if (hp >= a.H) return;
-      static_assert(plan_dev::score_head_lds_bytes<D, kThreads>(PBSA_MAX_N_LOC) <= SMEM, "scoring scratch must fit");
+      static_assert(plan_dev::score_head_lds_bytes<D, kThreads>(PBSA_MAX_N_LOC_AUX) <= SMEM, "scoring scratch must fit");
       static_assert(sizeof(plan_dev::RetainLds) <= SMEM, "retention scratch must fit");
       plan_dev::score_head_body<D, kThreads>(pl.sa, hp, smem);
       __syncthreads();                     // the head's rows are written, and the scoring scratch is dead
@@ -740,9 +750,9 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   // wave 1 only.  A first pass counts each class per round and wave (ballots), one thread per class
   // turns the counts into offsets, a second pass classifies again and writes each tile to its place:
   // every part of the list is in ascending candidate order.
-  int* llen_s = lflag + PBSA_MAX_N_LOC;
-  int* lmap_s = llen_s + PBSA_MAX_N_LOC;
-  int* plen_s = lmap_s + PBSA_MAX_N_LOC;
+  int* llen_s = lflag + kLocMax;
+  int* lmap_s = llen_s + kLocMax;
+  int* plen_s = lmap_s + kLocMax;
   for (int l = tid; l < a.n_loc; l += kThreads) {
     lflag[l] = 0;
     llen_s[l] = a.l_len[l];
@@ -751,7 +761,7 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   for (int c = tid; c <= a.C; c += kThreads) plen_s[c] = a.p_len[(size_t)h * (a.C + 1) + c];
   // the selections of this workgroup's query blocks, fetched now (loads return in order: anything asked
   // for after the queries would wait for them) and turned into flags once the flags are zeroed
-  constexpr int kSelPer = (2 * PBSA_MAX_K + kThreads - 1) / kThreads;
+  constexpr int kSelPer = (2 * (kAux ? PBSA_MAX_K_AUX : PBSA_MAX_K) + kThreads - 1) / kThreads;
   int selv[kSelPer];
 #pragma unroll
   for (int u = 0; u < kSelPer; ++u) {
@@ -832,7 +842,7 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
       if (cls == c) {
         const int pos = off_s[(r * 2 + wave) * 4 + c] + lanes_below(m);
         t_src[pos] = src;
-        t_meta[pos] = meta;
+        t_meta[pos] = (meta_t)meta;
       }
     }
   }

@@ -75,7 +75,7 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint3
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_off), "v"(lane_off), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 
 // the same with 4 bytes per lane: LDS bytes [lds_off, lds_off + 256)
@@ -83,7 +83,7 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t lane_off, uint32
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
                :
                : "s"(lds_off), "v"(lane_off), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 
 // Where the 16-byte chunks of a tile row sit in LDS: logical chunk c of row r at chunk c ^ swz(r).  The row-wise
@@ -522,7 +522,7 @@ __device__ __forceinline__ void dma16x4(const void* base, uint32_t o0, uint32_t 
                "global_load_lds_dwordx4 %4, %5 offset:3072"
                :
                : "s"(lds_base), "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(base), "n"(LDS_IMM)
-               : "memory", "scc");
+               : "memory", "scc", "m0");
 }
 
 template <int D>

@@ -180,45 +180,47 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t 
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_off), "v"(voff), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 
 // Selection (Eq. 10-11).  A workgroup handles 4 query blocks of one head; its NM waves split the local
 // blocks: lane `lane` of wave w owns column j = 64 w + lane and runs the four chains
 // acc_r = fma(q_r[x], k_j[x], acc_r), x ascending.  The pooled keys reach LDS by direct global -> LDS
-// loads, kDX dimensions (128 bytes per column) per round, double buffered; a wave stages exactly the 64
-// columns it consumes, so the rounds need no workgroup barrier.  Within a column's 128 bytes the
-// 16-byte chunks are permuted (logical chunk c of column j sits at c ^ ((j / 2) % 8)), which makes the
-// per-lane 16-byte reads of 16 consecutive columns hit 16 distinct bank groups.  The logits then go
-// to LDS and wave r ranks row r.
-constexpr int kDX = 32;
-
-template <int D, int NM>
+// loads, DX dimensions (4 DX bytes per column) per round, double buffered; a wave stages exactly the 64
+// columns it consumes, so the rounds need no workgroup barrier.  Within a column's round the 16-byte
+// chunks are permuted (logical chunk c of column j sits at c ^ ((j / 2) % (DX / 4))), which spreads the
+// per-lane 16-byte reads of consecutive columns over the bank groups.  The logits then go to LDS and wave
+// r ranks row r.  DX = 32 up to 8 waves; 16 beyond, where two rounds of 32 would not fit in LDS.
+template <int D, int NM, int DX>
 __device__ __forceinline__ void select_body(const SelectArgs& a, const int bx, const int h, unsigned char* smem) {
   constexpr int NCP = NM * 64;                        // padded columns
-  constexpr int BUF = NCP * kDX * 4;                  // one round of every column
-  constexpr int NR = D / kDX;
+  constexpr int BUF = NCP * DX * 4;                   // one round of every column
+  constexpr int NR = D / DX;
+  constexpr int CPC = DX / 4;                         // 16-byte chunks per column and round
+  constexpr int NI = 64 * CPC / 64;                   // load instructions per wave and round (64 columns)
+  constexpr int CPI = 64 / CPC;                       // columns per instruction
   float* qs = reinterpret_cast<float*>(smem + 2 * BUF);                         // [4][D]
   float* zs = qs + 4 * D;                                                       // [4][NCP]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i0 = bx * 4;
 
-  // this lane's share of the staging: instruction n fills columns 64 wave + 8 n + lane / 8, physical chunk lane % 8
-  uint32_t goff[8];
+  // this lane's share of the staging: instruction n fills columns 64 wave + CPI n + lane / CPC, physical chunk
+  // lane % CPC
+  uint32_t goff[NI];
 #pragma unroll
-  for (int n = 0; n < 8; ++n) {
-    const int j = 64 * wave + 8 * n + (lane >> 3);
+  for (int n = 0; n < NI; ++n) {
+    const int j = 64 * wave + CPI * n + lane / CPC;
     int slot = a.l_map[min(j, a.n_loc - 1)];
     slot = min(max(slot, 0), a.n_loc_cap - 1);
-    const int chunk = (lane & 7) ^ ((j >> 1) & 7);
+    const int chunk = (lane % CPC) ^ ((j >> 1) % CPC);
     goff[n] = (uint32_t)(((size_t)h * a.n_loc_cap + slot) * D * 4 + chunk * 16);
   }
   const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_lds + wave * (64 * kDX * 4));
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_lds + wave * (64 * DX * 4));
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(a.Kc_l);
 #define PBSA_STAGE(R_)                                                                                 \
-  _Pragma("unroll") for (int n_ = 0; n_ < 8; ++n_)                                                      \
-      dma16(kbase + (R_) * (kDX * 4), goff[n_], wave_lds + ((R_) & 1) * BUF + n_ * 1024);
+  _Pragma("unroll") for (int n_ = 0; n_ < NI; ++n_)                                                     \
+      dma16(kbase + (R_) * (DX * 4), goff[n_], wave_lds + ((R_) & 1) * BUF + n_ * 1024);
   PBSA_STAGE(0)
   if (NR > 1) PBSA_STAGE(1)
 
@@ -230,18 +232,22 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int bx, c
 
   float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   const int jcol = 64 * wave + lane;
-  const int sw = (jcol >> 1) & 7;
+  const int sw = (jcol >> 1) % CPC;
 #pragma unroll 1
   for (int r0 = 0; r0 < NR; ++r0) {
-    if (r0 + 1 < NR) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    const unsigned char* kb = smem + (r0 & 1) * BUF + jcol * (kDX * 4);
+    if (r0 + 1 < NR) {
+      if constexpr (NI == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    const unsigned char* kb = smem + (r0 & 1) * BUF + jcol * (DX * 4);
 #pragma unroll
-    for (int c = 0; c < kDX / 4; ++c) {
+    for (int c = 0; c < CPC; ++c) {
       const float4 k4 = *reinterpret_cast<const float4*>(kb + ((c ^ sw) << 4));
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float4 q4 = *reinterpret_cast<const float4*>(qs + r * D + r0 * kDX + 4 * c);
+        const float4 q4 = *reinterpret_cast<const float4*>(qs + r * D + r0 * DX + 4 * c);
         acc[r] = __builtin_fmaf(q4.x, k4.x, acc[r]);
         acc[r] = __builtin_fmaf(q4.y, k4.y, acc[r]);
         acc[r] = __builtin_fmaf(q4.z, k4.z, acc[r]);
@@ -307,10 +313,11 @@ __device__ __forceinline__ void select_body(const SelectArgs& a, const int bx, c
   }
 }
 
-template <int D, int NM>
+template <int D, int NM, int DX>
 __global__ void __launch_bounds__(64 * NM) select_kernel(SelectArgs a) {
+  static_assert(DX == 32 || DX == 16, "a round is 8 or 4 load instructions per wave");
   extern __shared__ __align__(1024) unsigned char smem[];
-  select_body<D, NM>(a, blockIdx.x, blockIdx.y, smem);
+  select_body<D, NM, DX>(a, blockIdx.x, blockIdx.y, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -586,6 +593,36 @@ __device__ __forceinline__ void fold_promote_body(const FoldArgs& a, const int b
   }
 }
 
+// The bf16 view of a summary given by its running sums and counts (slot C of every head): row t of K and of V is
+// S_sum[t] / S_cnt[t], divided in fp32 and rounded to nearest even, where S_cnt[t] > 0; other rows stay as they are;
+// the slot's length is the number of such rows.  One thread per 4 dimensions of a row, as in the fold.
+__global__ void __launch_bounds__(kThreads) summary_view_kernel(int H, int B, int d, int C, const float* S_sum,
+                                                                const int32_t* S_cnt, bf16_t* Kp, bf16_t* Vp,
+                                                                int32_t* p_len) {
+  const int h = blockIdx.y, C1 = C + 1;
+  if (blockIdx.x == 0 && threadIdx.x < 64) {
+    int n = 0;
+    for (int t0 = 0; t0 < B; t0 += 64) {
+      const int t = t0 + (int)threadIdx.x;
+      n += __popcll(__ballot(t < B && S_cnt[(size_t)h * B + t] > 0));
+    }
+    if (threadIdx.x == 0) p_len[(size_t)h * C1 + C] = n;
+  }
+  const int tpr = d / 4, rows_per_wg = kThreads / tpr;
+  const int row = blockIdx.x * rows_per_wg + threadIdx.x / tpr;
+  if (row >= 2 * B) return;
+  const int kv = row / B, t = row % B, xc = (threadIdx.x % tpr) * 4;
+  const int cnt = S_cnt[(size_t)h * B + t];
+  if (cnt <= 0) return;
+  const size_t blk = (size_t)B * d, rowoff = (size_t)t * d + xc;
+  const float4 acc = *reinterpret_cast<const float4*>(S_sum + ((size_t)h * 2 + kv) * blk + rowoff);
+  const float fc = (float)cnt;
+  uint2 w;
+  w.x = f2bf_rne(acc.x / fc) | (f2bf_rne(acc.y / fc) << 16);
+  w.y = f2bf_rne(acc.z / fc) | (f2bf_rne(acc.w / fc) << 16);
+  *reinterpret_cast<uint2*>((kv ? Vp : Kp) + ((size_t)h * C1 + C) * blk + rowoff) = w;
+}
+
 __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
   fold_promote_body<kThreads>(a, blockIdx.x, blockIdx.y);
 }
@@ -645,12 +682,21 @@ hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32
   return hipGetLastError();
 }
 
-template <int D, int NM>
+hipError_t launch_summary_view(const pbsa_params& p, const float* S_sum, const int32_t* S_cnt, bf16_t* Kp, bf16_t* Vp,
+                               int32_t* p_len, hipStream_t stream) {
+  const int rows_per_wg = kThreads / (p.d / 4);
+  hipLaunchKernelGGL(summary_view_kernel, dim3((2 * p.B + rows_per_wg - 1) / rows_per_wg, p.H), dim3(kThreads), 0, stream,
+                     p.H, p.B, p.d, p.C, S_sum, S_cnt, Kp, Vp, p_len);
+  return hipGetLastError();
+}
+
+template <int D, int NM, int DX = 32>
 static hipError_t launch_select_t(const SelectArgs& a, hipStream_t stream) {
-  const size_t lds = (size_t)2 * NM * 64 * kDX * 4 + (size_t)4 * D * 4 + (size_t)4 * NM * 64 * 4;
-  hipError_t e = allow_lds(select_kernel<D, NM>, lds);
+  constexpr size_t lds = (size_t)2 * NM * 64 * DX * 4 + (size_t)4 * D * 4 + (size_t)4 * NM * 64 * 4;
+  static_assert(lds <= 160 * 1024, "two rounds of every column, the queries and the logits must fit in LDS");
+  hipError_t e = allow_lds(select_kernel<D, NM, DX>, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((select_kernel<D, NM>), dim3((a.nqb + 3) / 4, a.H), dim3(64 * NM), lds, stream, a);
+  hipLaunchKernelGGL((select_kernel<D, NM, DX>), dim3((a.nqb + 3) / 4, a.H), dim3(64 * NM), lds, stream, a);
   return hipGetLastError();
 }
 
@@ -714,11 +760,14 @@ static hipError_t launch_select_logits(const pbsa_params& p, const int32_t* l_ma
   if (p.d == 128) {
     if (nm <= 2) return launch_select_t<128, 2>(a, stream);
     if (nm <= 5) return launch_select_t<128, 5>(a, stream);
-    return launch_select_t<128, 8>(a, stream);
+    if (nm <= 8) return launch_select_t<128, 8>(a, stream);
+    return launch_select_t<128, 11, 16>(a, stream);
   }
+  static_assert(PBSA_MAX_N_LOC <= 11 * 64, "one lane per local block");
   if (nm <= 2) return launch_select_t<64, 2>(a, stream);
   if (nm <= 5) return launch_select_t<64, 5>(a, stream);
-  return launch_select_t<64, 8>(a, stream);
+  if (nm <= 8) return launch_select_t<64, 8>(a, stream);
+  return launch_select_t<64, 11, 16>(a, stream);
 }
 
 template <int D, int NM>

@@ -25,6 +25,8 @@ UpdateWs carve_update_ws(const pbsa_params& p, void* base);
 
 hipError_t launch_pool_blocks(const pbsa_params& p, const bf16_t* X, const int32_t* len, int32_t n_blocks,
                               float* out, hipStream_t stream);
+hipError_t launch_summary_view(const pbsa_params& p, const float* S_sum, const int32_t* S_cnt, bf16_t* Kp, bf16_t* Vp,
+                               int32_t* p_len, hipStream_t stream);
 hipError_t launch_select(const pbsa_params& p, const bf16_t* Q, const bf16_t* Kl, const int32_t* l_len,
                          const int32_t* l_map, float* Kc_l, float* Qc, int32_t* sel, float* Zl,
                          hipStream_t stream);

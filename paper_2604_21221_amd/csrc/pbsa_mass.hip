@@ -29,7 +29,7 @@ constexpr int kThreads = 256;
 constexpr int kRowsPerWg = 128;
 constexpr int kTile = 64;
 constexpr int kRingBytes = 48 * 1024;
-constexpr int kMaxCand = 2 * (PBSA_MAX_C_ATTEND + 1) + 2 * PBSA_MAX_N_LOC;
+constexpr int kMaxCand = 2 * (PBSA_MAX_C_AUX + 1) + 2 * PBSA_MAX_N_LOC_AUX;
 constexpr int kMaxRounds = (kMaxCand + kThreads - 1) / kThreads;
 
 struct MassArgs {
@@ -57,7 +57,7 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint3
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_off), "v"(lane_off), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 
 typedef __attribute__((address_space(3))) const bf16x8* lds_b128_t;
@@ -92,7 +92,7 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
   constexpr int CH = D / 8, RPI = 64 / CH; // 16-byte chunks per row, rows per wave instruction
   constexpr int NI = (kTile / RPI) / 4;    // load instructions per wave per tile: 4 or 2
   static_assert(RING >= 3, "two tiles on their way while one is read");
-  static_assert((3 * PBSA_MAX_N_LOC + PBSA_MAX_C_ATTEND + 1) * 4 <= kRingBytes, "setup scratch must fit");
+  static_assert((3 * PBSA_MAX_N_LOC_AUX + PBSA_MAX_C_AUX + 1) * 4 <= kRingBytes, "setup scratch must fit");
 
   extern __shared__ __align__(1024) unsigned char smem[];
   __shared__ int cnt_s[kMaxRounds * 4];
@@ -103,9 +103,9 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
   int* t_meta = t_src + n_cand;                            // valid keys | row halves that attend << 8 | key block << 10
   int* pos_s = t_meta + n_cand;                            // [n_u] first tile of a key block in the list, or -1
   int* lflag = reinterpret_cast<int*>(smem);               // setup scratch, dead before the first tile is staged
-  int* llen_s = lflag + PBSA_MAX_N_LOC;
-  int* lmap_s = llen_s + PBSA_MAX_N_LOC;
-  int* plen_s = lmap_s + PBSA_MAX_N_LOC;
+  int* llen_s = lflag + PBSA_MAX_N_LOC_AUX;
+  int* lmap_s = llen_s + PBSA_MAX_N_LOC_AUX;
+  int* plen_s = lmap_s + PBSA_MAX_N_LOC_AUX;
 
   // consecutive workgroup ids go round-robin to the 8 XCDs: XCD x gets a contiguous range of (head, row tile)
   const int n_qt = (a.Nq + kRowsPerWg - 1) / kRowsPerWg;
@@ -128,7 +128,7 @@ __global__ void __launch_bounds__(kThreads) mass_kernel(MassArgs a) {
   }
   for (int c = tid; c <= a.C; c += kThreads) plen_s[c] = a.p_len[(size_t)h * (a.C + 1) + c];
   for (int u = tid; u < n_u; u += kThreads) pos_s[u] = -1;
-  constexpr int kSelPer = (2 * PBSA_MAX_K + kThreads - 1) / kThreads;
+  constexpr int kSelPer = (2 * PBSA_MAX_K_AUX + kThreads - 1) / kThreads;
   int selv[kSelPer];
 #pragma unroll
   for (int u = 0; u < kSelPer; ++u) {

@@ -44,7 +44,7 @@ struct ScoreArgs {
   float* A;
 };
 
-constexpr int kMaxCand = PBSA_MAX_C + PBSA_MAX_N_LOC;
+constexpr int kMaxCand = PBSA_MAX_C + PBSA_MAX_N_LOC_AUX;
 
 struct RetainArgs {
   int H, nqb, nqb_pad, n_loc, n_loc_cap, C, n_sink, n_evict, nU_max, d, B, fold;
@@ -85,9 +85,9 @@ struct RetainLds {
   int old_len[PBSA_MAX_C + 1];
   int src_s[PBSA_MAX_C];
   int flen[kMaxCand];   // valid tokens of each dropped candidate
-  int e_len[PBSA_MAX_N_LOC];   // valid tokens / physical slot of the evicted blocks
-  int e_map[PBSA_MAX_N_LOC];
-  long long e_id[PBSA_MAX_N_LOC];   // global ids of the evicted blocks
+  int e_len[PBSA_MAX_N_LOC_AUX];   // valid tokens / physical slot of the evicted blocks
+  int e_map[PBSA_MAX_N_LOC_AUX];
+  long long e_id[PBSA_MAX_N_LOC_AUX];   // global ids of the evicted blocks
   int nf_s, npos_s;
 };
 
@@ -298,7 +298,7 @@ template <int D, int NT>
 __device__ inline void score_head_body(const ScoreArgs& a, const int h, unsigned char* lds) {
 #pragma clang fp contract(off)
   constexpr int R = score_head_rows<D>(), NW = NT / 64, KP = D + 4, D4 = D / 4;
-  constexpr int NML_MAX = (PBSA_MAX_N_LOC + 63) / 64;
+  constexpr int NML_MAX = (PBSA_MAX_N_LOC_AUX + 63) / 64;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nml = (a.n_loc + 63) / 64, EP = 64 + 64 * nml;
   float* kct = reinterpret_cast<float*>(lds);            // [64][KP]

@@ -13,10 +13,11 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libpbsa.so")
 
 PBSA_OK, PBSA_EINVAL, PBSA_ESHAPE, PBSA_EALIGN, PBSA_EWS, PBSA_EHIP = 0, -1, -2, -3, -4, -5
-PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 512, 64, 192, 512
+PBSA_MAX_N_LOC, PBSA_MAX_C, PBSA_MAX_C_ATTEND, PBSA_MAX_K = 672, 64, 336, 672
+PBSA_MAX_N_LOC_AUX, PBSA_MAX_C_AUX, PBSA_MAX_K_AUX = 512, 192, 512
 PBSA_STATIC_WS_BYTES = 4 << 20
 
-EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
+EXPORTS = ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_summary_view", "pbsa_select_blocks", "pbsa_attention_fwd",
            "pbsa_memory_update", "pbsa_memory_update_static", "pbsa_memory_update_plan", "pbsa_memory_update_apply", "pbsa_attention_fwd_plan",
            "pbsa_select_blocks_apply",
            "pbsa_attention_mass", "pbsa_mass_workspace_bytes", "pbsa_attention_fwd_mass",
@@ -77,6 +78,7 @@ def lib() -> ctypes.CDLL:
         L.pbsa_strerror.argtypes = [ctypes.c_int]
         L.pbsa_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.pbsa_pool_blocks.argtypes = [pp, vp, vp, i32, vp, vp]
+        L.pbsa_summary_view.argtypes = [pp] + [vp] * 6
         L.pbsa_select_blocks.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.pbsa_attention_fwd.argtypes = [pp] + [vp] * 12 + [sz, vp]
         L.pbsa_memory_update.argtypes = [pp] + [vp] * 18 + [sz, vp]
@@ -94,7 +96,7 @@ def lib() -> ctypes.CDLL:
         pg = ctypes.POINTER(pbsa_grid)
         L.pbsa_blockify.argtypes = [pg, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_int64), vp]
         L.pbsa_unblockify.argtypes = [pg, vp, ctypes.c_int64, vp, vp]
-        for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_select_blocks", "pbsa_attention_fwd",
+        for name in ("pbsa_workspace_bytes", "pbsa_pool_blocks", "pbsa_summary_view", "pbsa_select_blocks", "pbsa_attention_fwd",
                      "pbsa_memory_update", "pbsa_memory_update_static", "pbsa_memory_update_plan", "pbsa_memory_update_apply",
                      "pbsa_attention_fwd_plan", "pbsa_select_blocks_apply", "pbsa_attention_mass", "pbsa_mass_workspace_bytes",
                      "pbsa_attention_fwd_mass", "pbsa_memory_update_fine", "pbsa_bwd_workspace_bytes",
@@ -155,6 +157,10 @@ def pbsa_workspace_bytes(p: pbsa_params) -> int:
 
 def pbsa_pool_blocks(p, X, length, n_blocks, out, stream=None):
     _check(lib().pbsa_pool_blocks(ctypes.byref(p), _ptr(X), _ptr(length), n_blocks, _ptr(out), _stream(stream)))
+
+
+def pbsa_summary_view(p, S_sum, S_cnt, Kp, Vp, p_len, stream=None):
+    _check(lib().pbsa_summary_view(ctypes.byref(p), _ptr(S_sum), _ptr(S_cnt), _ptr(Kp), _ptr(Vp), _ptr(p_len), _stream(stream)))
 
 
 def pbsa_select_blocks(p, Q, Kl, l_len, l_map, Kc_l, Qc, sel, Zl=None, ws=None, stream=None):

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 sys.path.insert(0, ROOT)
 
 from oracle.rollout import run_chunk, state_for_workload  # noqa: E402
-from paper_2604_21221_amd import synth  # noqa: E402
+from harness import synth  # noqa: E402
 
 ROWS_T = [0, 63, 64, 130, 255]      # tokens whose attention rows are stored (both heads)
 DIMS = [0, 1, 31, 63]               # output dimensions stored per row

@@ -39,7 +39,8 @@ def test_exports_match_header(L):
 
 def test_header_constants_match_binding():
     text = open(os.path.join(ROOT, "include", "pbsa.h")).read()
-    for name in ("PBSA_MAX_N_LOC", "PBSA_MAX_C", "PBSA_MAX_C_ATTEND", "PBSA_MAX_K"):
+    for name in ("PBSA_MAX_N_LOC", "PBSA_MAX_C", "PBSA_MAX_C_ATTEND", "PBSA_MAX_K", "PBSA_MAX_N_LOC_AUX",
+                 "PBSA_MAX_C_AUX", "PBSA_MAX_K_AUX"):
         assert int(re.search(rf"#define {name}\s+(\d+)", text).group(1)) == getattr(pbsa, name)
     for name in ("PBSA_EINVAL", "PBSA_ESHAPE", "PBSA_EALIGN", "PBSA_EWS", "PBSA_EHIP"):
         assert int(re.search(rf"#define {name}\s+\((-\d+)\)", text).group(1)) == getattr(pbsa, name)
@@ -69,8 +70,9 @@ def call_update(p, ws=(0x10000, 1 << 30), S_sum=P, S_cnt=P, Qc=P):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(d=96), pbsa.PBSA_ESHAPE), (dict(B=32), pbsa.PBSA_ESHAPE), (dict(k=513), pbsa.PBSA_ESHAPE),
-    (dict(C=193), pbsa.PBSA_ESHAPE), (dict(n_loc=513, n_loc_cap=513), pbsa.PBSA_ESHAPE),
+    (dict(d=96), pbsa.PBSA_ESHAPE), (dict(B=32), pbsa.PBSA_ESHAPE), (dict(k=673), pbsa.PBSA_ESHAPE),
+    (dict(C=337), pbsa.PBSA_ESHAPE), (dict(n_loc=673, n_loc_cap=673), pbsa.PBSA_ESHAPE),
+    (dict(H=65536), pbsa.PBSA_ESHAPE), (dict(H=40000, n_loc_cap=256, n_loc=16), pbsa.PBSA_ESHAPE),
     (dict(n_loc=2), pbsa.PBSA_EINVAL),               # fewer local blocks than the chunk itself has
     (dict(n_loc=17), pbsa.PBSA_EINVAL),              # more than the physical capacity
     (dict(n_sink=5), pbsa.PBSA_EINVAL), (dict(n_evict=17), pbsa.PBSA_EINVAL), (dict(causal=2), pbsa.PBSA_EINVAL),
@@ -87,6 +89,30 @@ def test_bad_params_rejected_by_every_call(L, kw, code):
         with pytest.raises(pbsa.PbsaError) as e:
             call_update(p)
         assert e.value.code == code
+
+
+def test_summary_view_validates_before_touching_memory(L):
+    for kw, args, code in [(dict(d=96), (P, P, P, P, P), pbsa.PBSA_ESHAPE), (dict(B=32), (P, P, P, P, P), pbsa.PBSA_ESHAPE),
+                           (dict(), (None, P, P, P, P), pbsa.PBSA_EINVAL), (dict(), (P, P, P, P, None), pbsa.PBSA_EINVAL),
+                           (dict(), (P + 4, P, P, P, P), pbsa.PBSA_EALIGN), (dict(), (P, P, P, P + 8, P), pbsa.PBSA_EALIGN),
+                           (dict(C=337), (P, P, P, P, P), pbsa.PBSA_ESHAPE)]:
+        with pytest.raises(pbsa.PbsaError) as e:
+            pbsa.pbsa_summary_view(good(**kw), *args, stream=0)
+        assert e.value.code == code
+
+
+def test_only_selection_and_plain_attention_take_the_largest_shapes(L):
+    """Between the two sets of limits: every call but pbsa_select_blocks and pbsa_attention_fwd refuses (that those two
+    accept is a GPU test: with valid parameters they launch)."""
+    for kw in (dict(k=513), dict(C=193), dict(n_loc=513, n_loc_cap=513)):
+        p = good(**kw)
+        with pytest.raises(pbsa.PbsaError) as e:
+            call_update(p)
+        assert e.value.code == pbsa.PBSA_ESHAPE
+        for fn in (pbsa.pbsa_mass_workspace_bytes, pbsa.pbsa_bwd_workspace_bytes):
+            with pytest.raises(pbsa.PbsaError) as e:
+                fn(p)
+            assert e.value.code == pbsa.PBSA_ESHAPE
 
 
 def test_update_maintains_fewer_slots_than_attention_attends(L):

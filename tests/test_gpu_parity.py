@@ -13,7 +13,7 @@ import pytest
 torch = pytest.importorskip("torch")
 
 from oracle.rollout import OracleState, state_for_workload  # noqa: E402
-from paper_2604_21221_amd import synth  # noqa: E402
+from harness import synth  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
@@ -28,7 +28,8 @@ DEV = "cuda:0"
 @pytest.fixture(scope="module")
 def gpu():
     assert torch.cuda.is_available(), "these tests need the MI355X"
-    from paper_2604_21221_amd import cache, pbsa, workloads
+    from harness import workloads
+    from paper_2604_21221_amd import cache, pbsa
     pbsa.lib()
     return dict(cache=cache, pbsa=pbsa, wl=workloads)
 
@@ -68,8 +69,9 @@ def compare_update(c, st, wl, sc_ref, src_ref, ne, what):
         assert np.array_equal(c.S_sum.cpu().numpy().view(np.uint32), st.S_sum.view(np.uint32)), f"{what}: sums differ"
 
 
-def run_both(gpu, c, st, Q, K, V, g, rows, what, lse_check=True):
-    """One layer-chunk step on both sides; compares everything; rows = 'all' or (heads, tokens)."""
+def run_both(gpu, c, st, Q, K, V, g, rows, what, lse_check=True, update=True):
+    """One layer-chunk step on both sides; compares everything; rows = 'all' or (heads, tokens).  update=False: the
+    shape is beyond what the memory update maintains, selection and attention only."""
     wl = gpu["wl"]
     B = st.B
     lens = np.full(st.nqb, B, np.int32); lens[-1] = st.Nq - (st.nqb - 1) * B
@@ -96,6 +98,8 @@ def run_both(gpu, c, st, Q, K, V, g, rows, what, lse_check=True):
             fin = np.isfinite(lref)
             assert np.array_equal(np.isfinite(lg), fin)
             assert np.abs(lg[fin] - lref[fin]).max() < LSE_ABS, what
+    if not update:
+        return
     ne = st.n_evict_now()
     sc_ref, src_ref = st.update()
     assert c.update() == ne
@@ -273,9 +277,29 @@ def test_determinism(gpu):
         assert torch.equal(c.attention(Q), O0)
 
 
-def test_update_decisions_overlapped_with_attention(gpu):
-    """pbsa_memory_update_plan on a second stream while the attention kernel runs, pbsa_memory_update_apply after
-    both: outputs and cache state equal the oracle's, as with the sequential call, chunk after chunk."""
+@pytest.mark.parametrize("d,B", [(64, 64), (128, 128), (128, 64)])
+def test_summary_view_of_installed_sums(gpu, d, B):
+    """pbsa_summary_view against the oracle's seeding of a compressed-history block: bit-exact bf16 rows where the
+    count is positive, rows without a count untouched, the slot's length."""
+    H, C, Nq = 3, 2, 2 * B
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, 1, C, 1, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, 1, C, 1, scale, device=DEV)
+    S_sum = (7.0 * synth.normals(synth.stream_key(99, "misc", d + B), H * 2 * B * d)).astype(np.float32).reshape(H, 2, B, d)
+    S_cnt = np.zeros((H, B), np.int32)
+    S_cnt[0, :B // 2] = 3; S_cnt[1, ::3] = 946; S_cnt[2, :] = np.arange(B) % 5     # a head with gaps, one with zeros inside
+    st.set_summary(S_sum, S_cnt)
+    c.Kp[:, C] = 1.5                      # rows without a count must keep what they hold
+    st.Kp[:, C][S_cnt == 0] = 0x3FC0
+    c.set_summary(torch.from_numpy(S_sum).to(DEV), torch.from_numpy(S_cnt).to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(c.p_len.cpu().numpy(), st.p_len)
+    assert np.array_equal(gpu["wl"].bits_of(c.Kp), st.Kp) and np.array_equal(gpu["wl"].bits_of(c.Vp), st.Vp)
+
+
+def test_update_as_plan_then_apply(gpu):
+    """The update as its two halves, pbsa_memory_update_plan (decisions) then pbsa_memory_update_apply (data
+    movement): outputs and cache state equal the oracle's, as with the single call, chunk after chunk."""
     name, H, d, B, Nq, w, C, k, n_sink, causal, p_lens = SMALL[1]
     scale = np.float32(1.0 / math.sqrt(d))
     st = OracleState(H, d, B, Nq, w, C, k, scale, n_sink=n_sink, causal=causal)
@@ -288,17 +312,22 @@ def test_update_decisions_overlapped_with_attention(gpu):
                      torch.from_numpy(ids))
     lens = np.full(st.nqb, B, np.int32); lens[-1] = Nq - (st.nqb - 1) * B
     for g in range(w + 5):
-        print(f"[case] overlapped update chunk {g}", flush=True)
+        print(f"[case] plan / apply update chunk {g}", flush=True)
         Q, K, V = rnd(60 + 3 * g, H, Nq, d), rnd(61 + 3 * g, H, Nq, d, scale=1.5), rnd(62 + 3 * g, H, Nq, d)
         st.append_chunk(synth.to_blocks(K, B), synth.to_blocks(V, B), lens, g * st.nqb + np.arange(st.nqb))
         st.select(Q)
         Oref, _ = st.attention(Q)
         ne = st.n_evict_now()
         sc_ref, src_ref = st.update()
-        O = c.step_overlapped(gpu["wl"].bf16_tensor(Q, DEV), gpu["wl"].bf16_tensor(K, DEV), gpu["wl"].bf16_tensor(V, DEV), g)
+        Qd = gpu["wl"].bf16_tensor(Q, DEV)
+        c.append_chunk(gpu["wl"].bf16_tensor(K, DEV), gpu["wl"].bf16_tensor(V, DEV), g)
+        c.select(Qd)
+        O = c.attention(Qd)
+        c.update_plan()
+        assert c.update_apply() == ne
         torch.cuda.synchronize()
-        check_attention(O.float().cpu().numpy(), Oref, "overlapped")
-        compare_update(c, st, gpu["wl"], sc_ref, src_ref, ne, "overlapped")
+        check_attention(O.float().cpu().numpy(), Oref, "plan / apply")
+        compare_update(c, st, gpu["wl"], sc_ref, src_ref, ne, "plan / apply")
 
 
 def fused_both(gpu, c, st, Q, K, V, g, rows, what):
@@ -596,17 +625,19 @@ def test_full_size_single_step(gpu, name):
         (fused_both if g > g0 else run_both)(gpu, c, st, Q, K, V, g, rows, name)
 
 
-@pytest.mark.parametrize("shape", [(2, 0.25, 0.25), (4, 0.25, 0.0625), (2, 0.5, 1.0)],
-                         ids=["L2_P25_top25", "L4_P25_top6", "L2_P50_all"])
+@pytest.mark.parametrize("shape", [(2, 0.25, 0.25), (4, 0.25, 0.0625), (2, 0.5, 1.0), (4, 0.5, 0.125, 128, 12)],
+                         ids=["L2_P25_top25", "L4_P25_top6", "L2_P50_all", "C12_L4_P50_top12"])
 def test_kernel_grid_shapes(gpu, shape):
     """Shapes of the paper's kernel benchmark (1792-token frames, blocks divide the chunk exactly), as the
-    sweep of bench.py runs them; selection and update exact, attention on sampled rows."""
+    sweep of bench.py runs them; selection and update exact, attention on sampled rows.  The largest shape of the
+    table (672 local blocks, 336 persistent slots) is selected from and attended only: the update maintains at
+    most PBSA_MAX_C slots."""
     w = synth.t7_workload(*shape)
     st, g0 = state_for_workload(w)
     c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
     rows = sample_rows(w.H, w.Nq, w.B, per_head=16)
     Q, K, V = synth.chunk_qkv(w, 0, g0)
-    run_both(gpu, c, st, Q, K, V, g0, rows, w.name)
+    run_both(gpu, c, st, Q, K, V, g0, rows, w.name, update=w.C <= gpu["pbsa"].PBSA_MAX_C)
 
 
 def test_cfg3_layers(gpu):

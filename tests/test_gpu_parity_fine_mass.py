@@ -17,7 +17,7 @@ import pytest
 torch = pytest.importorskip("torch")
 
 from oracle.rollout import OracleState, state_for_workload  # noqa: E402
-from paper_2604_21221_amd import synth  # noqa: E402
+from harness import synth  # noqa: E402
 from tests.test_gpu_parity import DEV, check_attention, compare_select, compare_update, rnd  # noqa: E402
 
 pytestmark = pytest.mark.gpu
@@ -28,7 +28,8 @@ MASS_RTOL, MASS_ATOL = 6e-3, 1e-6
 @pytest.fixture(scope="module")
 def gpu():
     assert torch.cuda.is_available(), "these tests need the MI355X"
-    from paper_2604_21221_amd import cache, pbsa, workloads
+    from harness import workloads
+    from paper_2604_21221_amd import cache, pbsa
     pbsa.lib()
     return dict(cache=cache, pbsa=pbsa, wl=workloads)
 

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 from oracle.rollout import OracleState
-from paper_2604_21221_amd import synth
+from harness import synth
 
 
 def bf(x):

@@ -9,7 +9,7 @@ import pytest
 
 torch = pytest.importorskip("torch")
 
-from paper_2604_21221_amd import synth  # noqa: E402
+from harness import synth  # noqa: E402
 
 DEV = "cuda:0"
 
@@ -53,7 +53,8 @@ def _rollout(cache, pbsa, wl, H, d, B, Nq, w, C, k, n_chunks, seed):
 @pytest.mark.gpu
 def test_static_scratch_matches_workspace_twice_second_smaller():
     assert torch.cuda.is_available(), "this test needs the MI355X"
-    from paper_2604_21221_amd import cache, pbsa, workloads
+    from harness import workloads
+    from paper_2604_21221_amd import cache, pbsa
     pbsa.lib()
     _rollout(cache, pbsa, workloads, H=3, d=128, B=64, Nq=333, w=2, C=4, k=5, n_chunks=5, seed=11)
     _rollout(cache, pbsa, workloads, H=1, d=64, B=64, Nq=130, w=1, C=2, k=2, n_chunks=4, seed=12)
