@@ -107,12 +107,18 @@ def run_both(gpu, c, st, Q, K, V, g, rows, what, lse_check=True, update=True):
 
 
 def sample_rows(H, Nq, B, per_head=48, seed=0):
-    """Rows spread over every head: the first and last rows of the chunk, block edges, and random ones."""
+    """Rows spread over every head: the first and last rows of the chunk, block edges, per_head random ones, and one
+    random row out of every 32 consecutive rows (the rows one MFMA tile of one wave holds), so that every workgroup,
+    wave and row group of the attention launch is looked at in every head."""
     u = synth.uniforms(synth.stream_key(seed, "misc", 77), H * per_head).reshape(H, per_head)
     toks = (u * Nq).astype(np.int32)
     toks[:, 0] = 0; toks[:, 1] = Nq - 1; toks[:, 2] = B - 1; toks[:, 3] = B; toks[:, 4] = ((Nq - 1) // B) * B
     toks[:, 5] = 127; toks[:, 6] = 128; toks[:, 7] = Nq // 2
-    hh = np.repeat(np.arange(H, dtype=np.int32), per_head)
+    n_grp = (Nq + 31) // 32
+    v = synth.uniforms(synth.stream_key(seed, "misc", 78), H * n_grp).reshape(H, n_grp)
+    strat = 32 * np.arange(n_grp, dtype=np.int32)[None, :] + (v * 32).astype(np.int32)
+    toks = np.concatenate([toks, strat], axis=1)
+    hh = np.repeat(np.arange(H, dtype=np.int32), toks.shape[1])
     return hh, np.minimum(toks, Nq - 1).ravel().astype(np.int32)
 
 
@@ -614,7 +620,8 @@ def test_cfg1_every_element(gpu):
 
 @pytest.mark.parametrize("name", ["cfg2", "cfg4"])
 def test_full_size_single_step(gpu, name):
-    """Full BASELINE shapes, the launch configuration the benchmark times; attention on sampled rows."""
+    """Full BASELINE shapes, the launch configuration the benchmark times; every row of the attention output on
+    the first step, sampled rows on the second."""
     w = synth.WORKLOADS[name]
     st, g0 = state_for_workload(w)
     c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
@@ -622,20 +629,24 @@ def test_full_size_single_step(gpu, name):
     for g in range(g0, g0 + 2):
         Q, K, V = synth.chunk_qkv(w, 0, g)
         # the second step in the benchmark's schedule: decisions inside the attention launch, then fold / promote
-        (fused_both if g > g0 else run_both)(gpu, c, st, Q, K, V, g, rows, name)
+        if g == g0:
+            run_both(gpu, c, st, Q, K, V, g, "all", f"{name} every row")
+        else:
+            fused_both(gpu, c, st, Q, K, V, g, rows, name)
 
 
 @pytest.mark.parametrize("shape", [(2, 0.25, 0.25), (4, 0.25, 0.0625), (2, 0.5, 1.0), (4, 0.5, 0.125, 128, 12)],
                          ids=["L2_P25_top25", "L4_P25_top6", "L2_P50_all", "C12_L4_P50_top12"])
 def test_kernel_grid_shapes(gpu, shape):
     """Shapes of the paper's kernel benchmark (1792-token frames, blocks divide the chunk exactly), as the
-    sweep of bench.py runs them; selection and update exact, attention on sampled rows.  The largest shape of the
+    sweep of bench.py runs them; selection and update exact, attention on every row for the first shape and on
+    sampled rows (one per 32 at least) for the others.  The largest shape of the
     table (672 local blocks, 336 persistent slots) is selected from and attended only: the update maintains at
     most PBSA_MAX_C slots."""
     w = synth.t7_workload(*shape)
     st, g0 = state_for_workload(w)
     c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
-    rows = sample_rows(w.H, w.Nq, w.B, per_head=16)
+    rows = "all" if shape == (2, 0.25, 0.25) else sample_rows(w.H, w.Nq, w.B, per_head=16)
     Q, K, V = synth.chunk_qkv(w, 0, g0)
     run_both(gpu, c, st, Q, K, V, g0, rows, w.name, update=w.C <= gpu["pbsa"].PBSA_MAX_C)
 
@@ -658,7 +669,8 @@ def test_cfg5_rollout(gpu):
     """Cold start at the 1-minute shape, all 80 chunks (240 latent frames): the window and the persistent
     set fill during chunks 0-3, eviction and compression start at chunk 3 and run on every chunk after.
     Selection and update exact on every chunk; attention rows sampled on a cold, a filling, the first
-    evicting, and steady-state chunks up to the last."""
+    evicting and a steady-state chunk, every row on chunk 4 (the first with the full window and a summary) and on
+    the last one."""
     w = synth.WORKLOADS["cfg5"]
     st, g0 = state_for_workload(w)
     c, _ = gpu["wl"].cache_for_workload(w, device=DEV)
@@ -669,7 +681,8 @@ def test_cfg5_rollout(gpu):
         Q, K, V = synth.chunk_qkv(w, 0, g)
         # every third chunk takes the update's decisions inside the attention launch
         step = fused_both if g % 3 == 2 else run_both
-        step(gpu, c, st, Q, K, V, g, rows if g in (0, 1, 3, 4, 39, 79) else None, "cfg5")
+        step(gpu, c, st, Q, K, V, g, "all" if g in (4, 79) else rows if g in (0, 1, 3, 39) else None,
+             "cfg5 every row" if g in (4, 79) else "cfg5")
     assert (st.p_len[:, :w.C] > 0).all()
     # every block that left the window and was not kept is in the summary: 77 evictions of 74 blocks
     assert int(st.S_cnt.max()) == 77 * w.nqb - w.C
