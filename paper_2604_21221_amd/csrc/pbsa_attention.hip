@@ -706,9 +706,6 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   __shared__ __align__(1024) unsigned char smem[SMEM];
   __shared__ int t_src[kTilesMax];         // bit 31: local, bits 0..: (slot * SUB + sub)
   __shared__ meta_t t_meta[kTilesMax];     // valid keys (bits 0..7) | waves that attend (bits 8, 9)
-  __shared__ int cls_end_s[4];             // end of each part of the list
-  constexpr int kMaxRounds = (kTilesMax + kThreads - 1) / kThreads;
-  __shared__ int cnt_s[kMaxRounds * 2 * 4], off_s[kMaxRounds * 2 * 4];   // per round, wave and class: tiles, first place
   int* lflag = reinterpret_cast<int*>(smem);        // setup scratch, dead before the first tile is staged
 
   // XCD-aware mapping: consecutive workgroup ids go round-robin to the 8 XCDs, so give XCD x the
@@ -745,11 +742,9 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   // Everything the list needs is fetched from global memory in one parallel round into LDS scratch:
   // per local block the set of waves whose query block selected it, its length and its physical slot;
   // per persistent slot its length.  The candidates -- the 64-key tiles of the persistent slots, then
-  // of the local blocks, in ascending order -- are then classified by all threads, candidate i by thread
-  // i mod 128 in round i / 128: full tiles of both waves, ragged tiles, full tiles of wave 0 only, of
-  // wave 1 only.  A first pass counts each class per round and wave (ballots), one thread per class
-  // turns the counts into offsets, a second pass classifies again and writes each tile to its place:
-  // every part of the list is in ascending candidate order.
+  // of the local blocks, in ascending order -- are then classified by every wave, candidate i by lane
+  // i mod 64 in round i / 64: full tiles of both waves, ragged tiles, full tiles of wave 0 only, of
+  // wave 1 only.  Every part of the list is in ascending candidate order.
   int* llen_s = lflag + kLocMax;
   int* lmap_s = llen_s + kLocMax;
   int* plen_s = lmap_s + kLocMax;
@@ -811,39 +806,32 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
     if constexpr (MASS) meta |= ((a.C + 1 + l) << 10) | (sub << 20);
     return tl == 0 ? -1 : tl < kTile ? 1 : f == 3 ? 0 : f + 1;      // f is 1 or 2 otherwise
   };
-  const int n_rounds = (n_cand + kThreads - 1) / kThreads;
+  // Every wave classifies every candidate, 64 per round, twice: the first sweep gives the sizes of the four parts, the
+  // second the places, with the running counts in scalar registers (ballots only: no barrier and no LDS traffic
+  // between the sweeps).  The waves take turns writing the rounds.
+  const int n_rounds = (n_cand + 63) / 64;
+  int tot[4] = {0, 0, 0, 0};
   for (int r = 0; r < n_rounds; ++r) {
     int src, meta;
-    const int cls = classify(r * kThreads + tid, src, meta);
+    const int cls = classify(r * 64 + lane, src, meta);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const unsigned long long m = __ballot(cls == c);
-      if (lane == 0) cnt_s[(r * 2 + wave) * 4 + c] = __popcll(m);
-    }
+    for (int c = 0; c < 4; ++c) tot[c] += __popcll(__ballot(cls == c));
   }
-  __syncthreads();
-  if (tid < 4) {                           // class tid: its range in the list, and where each round and wave writes
-    int n = 0;
-    for (int c = 0; c < tid; ++c)
-      for (int q = 0; q < 2 * n_rounds; ++q) n += cnt_s[q * 4 + c];
-    for (int q = 0; q < 2 * n_rounds; ++q) {
-      off_s[q * 4 + tid] = n;
-      n += cnt_s[q * 4 + tid];
-    }
-    cls_end_s[tid] = n;
-  }
-  __syncthreads();
+  int base[4] = {0, tot[0], tot[0] + tot[1], tot[0] + tot[1] + tot[2]};
+  const int cls_end[4] = {base[1], base[2], base[3], base[3] + tot[3]};
   for (int r = 0; r < n_rounds; ++r) {
     int src = 0, meta = 0;
-    const int cls = classify(r * kThreads + tid, src, meta);
+    const int cls = classify(r * 64 + lane, src, meta);
+    const bool mine = (r & 1) == wave;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const unsigned long long m = __ballot(cls == c);
-      if (cls == c) {
-        const int pos = off_s[(r * 2 + wave) * 4 + c] + lanes_below(m);
+      if (cls == c && mine) {
+        const int pos = base[c] + lanes_below(m);
         t_src[pos] = src;
         t_meta[pos] = (meta_t)meta;
       }
+      base[c] += __popcll(m);
     }
   }
   __syncthreads();
@@ -858,14 +846,16 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   if constexpr (MASS) {
     // the later pass walks the same list: the ends of its four parts, then a descriptor per tile
     int32_t* out = a.Rlist + (size_t)logical * a.list_cap;
-    if (tid < 4) out[tid] = cls_end_s[tid];
-    for (int i = tid; i < cls_end_s[3] && i < a.list_cap - 4; i += kThreads) out[4 + i] = t_meta[i];
+    if (tid == 0) {
+      out[0] = cls_end[0]; out[1] = cls_end[1]; out[2] = cls_end[2]; out[3] = cls_end[3];
+    }
+    for (int i = tid; i < cls_end[3] && i < a.list_cap - 4; i += kThreads) out[4 + i] = t_meta[i];
     mo.rp = a.R + ((size_t)logical * 2 + wave) * a.r_slots * 64;
   }
-  const int e0 = cls_end_s[0];             // shared full tiles [0, e0)
-  const int n_tiles = cls_end_s[1];        // shared ragged tiles [e0, n_tiles): the end of the shared list
-  const int solo_b = wave == 0 ? n_tiles : cls_end_s[2];       // this wave's solo tiles [solo_b, solo_e)
-  const int solo_e = wave == 0 ? cls_end_s[2] : cls_end_s[3];
+  const int e0 = cls_end[0];               // shared full tiles [0, e0)
+  const int n_tiles = cls_end[1];          // shared ragged tiles [e0, n_tiles): the end of the shared list
+  const int solo_b = wave == 0 ? n_tiles : cls_end[2];         // this wave's solo tiles [solo_b, solo_e)
+  const int solo_e = wave == 0 ? cls_end[2] : cls_end[3];
 
   f32x16 o[2][DT];
 #pragma unroll
