@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # WRITE_SIZE, KiB per dispatch, each scaled by what the same counter reads for a 1 GiB copy:
 # FETCH_SIZE reads half the bytes there, WRITE_SIZE all of them).  Counters cannot be read from inside
 # this process, so the figures are the ones of the summaries under profiles/ for the same command.
-HBM_TRAFFIC_BYTES = {"cfg5": int((206551 * 2.0 + 14682 * 1.0) * 1024)}
+HBM_TRAFFIC_BYTES = {"cfg5": int((205779 * 2.0 + 14686 * 1.0) * 1024)}
 
 
 def executed_flops(sel, p_len, l_len_by_block, rows_per_qblock, d):
