@@ -27,8 +27,10 @@
 //                 from the S^T accumulators: the contraction index (key) is enumerated in the order
 //                 the accumulator holds it, and V^T is read from LDS with the same enumeration.
 //   A K or V^T fragment read from LDS feeds the MFMAs of both row groups, which halves the LDS
-//   traffic per flop: at one fragment per MFMA the LDS (128 bytes per clock per CU) cannot keep four
-//   matrix pipes busy.
+//   traffic per flop.  (At one fragment per MFMA -- 32 rows per wave, two waves per SIMD -- four matrix
+//   pipes ask the LDS for 128 bytes per clock, about half of what it delivers to reads alone; with the
+//   staging loads and the barrier beside them that arrangement measured no faster in a probe, and it
+//   needs the whole step in 256 registers.)
 //
 // Software pipeline.  The unit is a sub-tile of 32 keys.  In step u a wave runs, as one straight
 // stretch of code cut into slots (one MFMA plus a slice of vector work each), the softmax of
@@ -36,9 +38,13 @@
 // the MFMAs that do not depend on it: O^T += V^T P^T of sub-tile u-1 and S^T = K Q^T of sub-tile u+1.
 // S^T and P^T are double buffered.  Each part of the list (shared full, shared ragged, solo) is one
 // pipelined run with its own template instance; the pipeline drains between them.  Softmax is online,
-// fp32, base 2 (scale and log2 e folded into one fma), against a reference that a step takes as given;
-// the row sums (over the bf16-rounded probabilities, the numbers the second product uses) and the check
-// that the reference still serves come at the start of the next step (softmax_settle).
+// fp32, base 2 (scale and log2 e folded into one fma), against a reference that a step takes as given.
+// The row sums (over the bf16-rounded probabilities, the numbers the second product uses) are four small
+// MFMAs per step whose A operand selects the rows (sum_mfma); the check that the reference still serves is
+// one OR per two pairs inside the slots and one compare at the end of the step, and the rare step that
+// fails it is redone in place (softmax_redo).  A step loads the first operand fragments of the step after
+// it during its last slots and hands them over in registers, so no step starts by waiting for LDS; the
+// barrier that turns the rings over sits in the middle of a tile's second step, under its MFMAs.
 #include <type_traits>
 
 #include "pbsa_internal.h"
