@@ -229,15 +229,17 @@ __device__ __forceinline__ uint32_t prob_round(float e0, float e1) {
 // as it stands and whose A operand selects.  That instruction reads lane L's eight values as column L % 16,
 // contraction indices 8 (L / 16) ..: of the 32 query rows of a row group (row = L % 32, keys split over the two
 // half waves) rows r and r + 16 fall into the same column r % 16, on contraction groups {0, 2} and {1, 3}.  With
-// A[0][k] = 1 on groups 0 and 2, A[1][k] = 1 on groups 1 and 3 and zero elsewhere, output row 0 holds the sums
-// of rows 0..15 and output row 1 those of rows 16..31: lane n < 16 gets, in elements 0 and 1 of the result, the
-// complete sums (all 16 keys, both half waves) of rows n and n + 16.  Four instructions of 16 cycles per
-// 32-key sub-tile, against sixteen v_dot2c_f32_bf16 (which also run in the matrix pipe and stall the wave)
-// or thirty-two additions the vector unit has no slots for.
+// A[m0][k] = 1 on groups 0 and 2, A[m0 + 4][k] = 1 on groups 1 and 3 and zero elsewhere, output row m0 holds the
+// sums of rows 0..15 and output row m0 + 4 those of rows 16..31, and the instruction leaves output row m in element
+// m % 4 of lanes 16 (m / 4) ..+15: with m0 = 8 g for row group g, element 0 of the result holds, in lane L, the
+// complete sum (all 16 keys, both half waves) of row L % 32 of row group L / 32 -- one register for the wave's 64
+// rows, the other three elements stay zero.  Four instructions of 16 cycles per 32-key sub-tile, against sixteen
+// v_dot2c_f32_bf16 (which also run in the matrix pipe and stall the wave) or thirty-two additions the vector unit
+// has no slots for.
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-__device__ __forceinline__ bf16x8 sum_selector(int lane) {
+__device__ __forceinline__ bf16x8 sum_selector(int lane, int g) {
   const int m = lane & 15, kg = lane >> 4;
-  const bool on = (m == 0 && (kg & 1) == 0) || (m == 1 && (kg & 1) == 1);
+  const bool on = (m == 8 * g && (kg & 1) == 0) || (m == 8 * g + 4 && (kg & 1) == 1);
   const uint32_t w = on ? 0x3F803F80u : 0u;
   const u32x4 v = {w, w, w, w};
   return __builtin_bit_cast(bf16x8, v);
@@ -250,8 +252,8 @@ __device__ __forceinline__ bf16x8 sum_selector(int lane) {
 __device__ __forceinline__ void sum_mfma(f32x4& acc, const bf16x8& sel, const bf16x8& p) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(sel), "v"(p));
 }
-__device__ __forceinline__ void sum_settle(f32x4 (&l)[2]) {
-  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(l[0]), "+v"(l[1]));
+__device__ __forceinline__ void sum_settle(f32x4& l) {
+  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(l));
 }
 __device__ __forceinline__ uint32_t or3(uint32_t a, uint32_t b, uint32_t c) {
   uint32_t r;
@@ -376,9 +378,9 @@ struct StepCtx {
   bf16x8 (&frag)[2 * Geo<D>::KS];   // operand fragment of each MFMA pair
   int dk, dv;                    // kNextTile: what moves kaddr / vaddr to the next tile's ring entries
   float ex[32];                  // exp2 of the scores, row group g element v at 16 g + v, until they are rounded
-  f32x4 (&lsum)[2];              // PV: the running row sums, which take those of p_prev (see sum_selector)
-  f32x4 (&ltile)[2];             // PV, mass variant: the row sums of p_prev alone
-  bf16x8 sel;                    // the selecting operand of the row-sum instruction
+  f32x4& lsum;                   // PV: the running row sums, which take those of p_prev (see sum_selector)
+  f32x4& ltile;                  // PV, mass variant: the row sums of p_prev alone
+  const bf16x8 (&sel)[2];        // the selecting operands of the row-sum instruction, per row group
   uint32_t por;                  // SM: bitwise OR of the pairs of p_cur
   uint32_t phold;                // SM: a pair waiting for the next one to share a three-input OR
 };
@@ -500,9 +502,9 @@ __device__ __forceinline__ void valu_slot(StepCtx<D, PV, QK, SM, RAGGED>& c, uns
 // the running sum, and whether anything has been added to the output accumulators yet.
 struct SoftmaxRun {
   float m_ref[2], mc[2];
-  f32x4 l_run[2];           // running row sums as the row-sum instruction leaves them: in lane n < 16 element 0 is
-                            // row n of the row group and element 1 row n + 16 (see sum_selector)
-  bf16x8 sel;               // sum_selector of this lane
+  f32x4 l_run;              // running row sums as the row-sum instruction leaves them: element 0 of lane L is row
+                            // L % 32 of row group L / 32 (see sum_selector)
+  bf16x8 sel[2];            // sum_selector of this lane, per row group
   unsigned long long bad;   // lanes in which the sub-tile whose softmax ran last needs another reference
   float c2, lift;
   bool o_live;
@@ -575,9 +577,9 @@ __device__ __forceinline__ void run_slots(StepCtx<D, PV, QK, SM, RAGGED>& c, uns
 #pragma unroll
       for (int q = 0; q < 4; ++q)
         if ((2 * q + 1) * S::NC / 8 == I) {
-          sum_mfma(c.lsum[q / 2], c.sel, as_bf16x8(c.p_prev[q / 2][q % 2]));
+          sum_mfma(c.lsum, c.sel[q / 2], as_bf16x8(c.p_prev[q / 2][q % 2]));
           // the mass variant wants the sub-tile's own sums as well, and the running sums exactly as without it
-          if constexpr (MASSV) sum_mfma(c.ltile[q / 2], c.sel, as_bf16x8(c.p_prev[q / 2][q % 2]));
+          if constexpr (MASSV) sum_mfma(c.ltile, c.sel[q / 2], as_bf16x8(c.p_prev[q / 2][q % 2]));
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -613,13 +615,9 @@ __device__ __forceinline__ void softmax_redo(const f32x16 (&s)[2], PTile& p, Sof
     asm volatile("v_mov_b32 %0, %1" : "+v"(sr.m_ref[g]) : "v"(m_new));
     asm volatile("v_mov_b32 %0, %1" : "+v"(sr.mc[g]) : "v"(mc_new));
   }
-  // the running sums live in lanes 0..15: row n in element 0 (this lane's own alpha), row n + 16 in element 1
+  // the running sum of lane L is that of row L % 32 of row group L / 32: this lane's own alpha of that group
   sum_settle(sr.l_run);
-#pragma unroll
-  for (int g = 0; g < 2; ++g) {
-    sr.l_run[g][0] *= alpha[g];
-    sr.l_run[g][1] *= __shfl(alpha[g], (__lane_id() & 15) + 16, 64);
-  }
+  sr.l_run[0] *= __lane_id() < 32 ? alpha[0] : alpha[1];
   sum_settle(sr.l_run);
   if (sr.o_live) rescale<Geo<D>::DT>(o, alpha);
 }
@@ -636,7 +634,7 @@ __device__ __forceinline__ void step(uint32_t (&vaddr)[Geo<D>::DT], uint32_t (&k
   static_assert(2 * Geo<D>::DT == Geo<D>::KS, "PV and QK pairs alternate one to one");
   constexpr bool PV = KIND::PV, QK = KIND::QK;
   // the row sums of p_prev go straight into the running sums; the mass variant takes them per sub-tile as well
-  f32x4 pt[2] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+  f32x4 pt = {0.0f, 0.0f, 0.0f, 0.0f};
   StepCtx<D, PV, QK, SM, RAGGED> c{vaddr, kaddr, sr.c2, qf, o, s_cur, s_next, p_cur, p_prev, sr.mc, lim, dma, frag, dk, dv, {}, sr.l_run, pt, sr.sel, 0u, 0u};
   if constexpr (!PRELOADED) preload_frags<D, KIND>(frag, vaddr, kaddr);
   if constexpr (PV) {
@@ -652,12 +650,8 @@ __device__ __forceinline__ void step(uint32_t (&vaddr)[Geo<D>::DT], uint32_t (&k
     sr.o_live = true;
     if constexpr (MASS) {
       sum_settle(pt);
-      // lanes 0..31 take the sums of rows 0..31 (row group 0), lanes 32..63 those of row group 1: row r of a
-      // group sits in lane r % 16, element r / 16
-      const int src = mo.lane & 15;
-      const float v00 = __shfl(pt[0][0], src, 64), v01 = __shfl(pt[0][1], src, 64);
-      const float v10 = __shfl(pt[1][0], src, 64), v11 = __shfl(pt[1][1], src, 64);
-      const float tot = mo.lane < 16 ? v00 : mo.lane < 32 ? v01 : mo.lane < 48 ? v10 : v11;
+      // lanes 0..31 hold the sums of rows 0..31 (row group 0), lanes 32..63 those of row group 1
+      const float tot = pt[0];
       const float mc_now = mo.hi ? sr.mc[1] : sr.mc[0];
       if constexpr (KIND::V_OFF == 0) {    // the sub-tile summed is the one whose V the step multiplied: a tile's first
         mo.hold = tot;
@@ -875,8 +869,8 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   f32x16 sA[2], sB[2];                     // S^T of even / odd sub-tiles
   PTile pA, pB;                            // P^T of even / odd sub-tiles (bf16 pairs)
   const float c2 = a.scale * 1.4426950408889634f, lift = kLift / c2;
-  SoftmaxRun sr{{kInitMax, kInitMax}, {-kInitMax * c2, -kInitMax * c2}, {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}},
-                sum_selector(lane), 0ull, c2, lift, false};
+  SoftmaxRun sr{{kInitMax, kInitMax}, {-kInitMax * c2, -kInitMax * c2}, {0.0f, 0.0f, 0.0f, 0.0f},
+                {sum_selector(lane, 0), sum_selector(lane, 1)}, 0ull, c2, lift, false};
   bf16x8 frag[2 * KS];                     // operand fragments, handed from step to step
   NoMid nomid;
 
@@ -1139,9 +1133,8 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
   sum_settle(sr.l_run);
 #pragma unroll
   for (int g = 0; g < 2; ++g) {
-    // row r of the group: lane r % 16 of the running sums, element r / 16
-    const float l_lo = __shfl(sr.l_run[g][0], qn & 15, 64), l_hi = __shfl(sr.l_run[g][1], qn & 15, 64);
-    const float l_tot = qn < 16 ? l_lo : l_hi;
+    // row r of the group: lane 32 g + r of the running sums
+    const float l_tot = __shfl(sr.l_run[0], 32 * g + qn, 64);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     const int tok = tok0 + 32 * g;
     if (tok < a.Nq) {
