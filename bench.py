@@ -20,11 +20,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per pbsa_attention_fwd launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE, KiB per dispatch, each scaled by what the same counter reads for a 1 GiB copy:
-# FETCH_SIZE reads half the bytes there, WRITE_SIZE all of them).  Counters cannot be read from inside
-# this process, so the figures are the ones of the summaries under profiles/ for the same command.
-HBM_TRAFFIC_BYTES = {"cfg5": int((205779 * 2.0 + 14686 * 1.0) * 1024)}
+def hbm_traffic_bytes(workload):
+    """HBM-side bytes per attention launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE,
+    KiB per dispatch, each scaled by what the same counter reads for a 1 GiB copy).  Counters cannot be read from
+    inside this process, so the figure is taken from the committed summary of the profile runs of this same command,
+    profiles/attention_<workload>_hbm_counters.txt (its line "-> F KiB * a + W KiB * b = ..."); None without one."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"attention_{workload}_hbm_counters.txt")
+    try:
+        m = re.search(r"->\s*([\d,]+) KiB \* ([\d.]+) \+ ([\d,]+) KiB \* ([\d.]+)", open(path).read())
+    except OSError:
+        return None
+    if not m:
+        return None
+    f, a, w, b = (float(x.replace(",", "")) for x in m.groups())
+    return int((f * a + w * b) * 1024)
 
 
 def executed_flops(sel, p_len, l_len_by_block, rows_per_qblock, d):
@@ -376,7 +386,7 @@ def bench_steps(w, args, K, W, settle, dev, layers=None):
                    "layers": L, "denoise_steps": T, "executed_gflop_per_step": round(mean_flops / 1e9, 3)},
         "roofline": {"kernel": "pbsa_attention_fwd", "bound": "mfma", "achieved": round(tflops_attn, 3),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops_attn / PEAK_BF16_TFLOPS, 5),
-                     "traffic": HBM_TRAFFIC_BYTES.get(w.name), "traffic_unit": "bytes per launch",
+                     "traffic": hbm_traffic_bytes(w.name), "traffic_unit": "bytes per launch",
                      "us_per_launch": round(attn_ms * 1e3, 2)},
         "hbm_bound_calls": {
             "pbsa_select_blocks": {"us_per_call": round(sel_us, 2), "algorithmic_bytes": sel_bytes,

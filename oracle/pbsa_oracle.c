@@ -66,26 +66,21 @@ static inline uint16_t f2bf(float f) { /* round to nearest even; inputs are fini
   return (uint16_t)(u >> 16);
 }
 
-/* exp(x) for x <= 0, built from fp32 mul / fma / round-to-nearest-integer only, so that another
- * implementation of the same steps gives the same bits.  x < -64 gives exactly 0.
- *   n = rint(x * log2e); r = x - n*ln2 (two-constant split); p = degree-6 Taylor of e^r by
- *   Horner; result = p * 2^n. */
+/* exp(x) for x <= 0 as the interface's arithmetic contract words it (fp32 multiply, fused multiply-add and
+ * round-to-nearest-integer only, so that any implementation of the same steps gives the same bits):
+ * 0 below -64; otherwise n = the integer nearest to x * log2(e); the remainder r = x - n ln 2 with ln 2 split into
+ * 0.693359375 (so that n times it is exact) and the correction -2.12194440e-4; e^r by the Taylor polynomial of
+ * degree 6, coefficients rounded to fp32, evaluated by Horner's rule from the highest term; scaled by 2^n. */
 float orc_pexp(float x) {
+  static const float taylor[7] = {(float)(1.0 / 720.0), (float)(1.0 / 120.0), (float)(1.0 / 24.0), (float)(1.0 / 6.0),
+                                  0.5f, 1.0f, 1.0f};
+  const float log2e = (float)1.4426950408889634, ln2_head = 0.693359375f, ln2_tail = -2.12194440e-4f;
   if (x < -64.0f) return 0.0f;
-  float n = rintf(x * 0x1.715476p+0f);
-  float r = fmaf(n, -0x1.630000p-1f, x);   /* 0.693359375, exact product */
-  r = fmaf(n, 0x1.bd0106p-13f, r);         /* + n * 2.12194440e-4        */
-  float p = 0x1.6c16c2p-10f;               /* 1/720 */
-  p = fmaf(p, r, 0x1.111112p-7f);          /* 1/120 */
-  p = fmaf(p, r, 0x1.555556p-5f);          /* 1/24  */
-  p = fmaf(p, r, 0x1.555556p-3f);          /* 1/6   */
-  p = fmaf(p, r, 0.5f);
-  p = fmaf(p, r, 1.0f);
-  p = fmaf(p, r, 1.0f);
-  uint32_t sb = (uint32_t)((int32_t)n + 127) << 23;
-  float s;
-  memcpy(&s, &sb, 4);
-  return p * s;
+  const float n = nearbyintf(x * log2e);
+  const float r = fmaf(n, -ln2_tail, fmaf(n, -ln2_head, x));
+  float poly = taylor[0];
+  for (int i = 1; i < 7; ++i) poly = fmaf(poly, r, taylor[i]);
+  return ldexpf(poly, (int)n);          /* poly is in [0.5, 1.5] and n >= -93: the scaling is exact */
 }
 
 /* Block representative by average pooling (Eq. 6 with the pooling operator of Sec. 4.1):
