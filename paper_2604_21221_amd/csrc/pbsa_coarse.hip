@@ -632,8 +632,8 @@ __global__ void __launch_bounds__(kThreads) fold_promote_kernel(FoldArgs a) {
 // folded, and each is too short to fill the GPU for long.  The n_fold_x * H fold workgroups come first.
 template <int D>
 __global__ void __launch_bounds__(kThreads) pool_fold_kernel(PoolArgs pa, FoldArgs fa, int n_fold_x) {
-  const int n_pool = (int)gridDim.x - n_fold_x * fa.H, b = (int)blockIdx.x - n_pool;
-  if (b < 0) pool_body<D>(pa, (int)blockIdx.x);
+  const int n_fold = n_fold_x * fa.H, b = (int)blockIdx.x;      // the fold's workgroups run longest: they start first
+  if (b >= n_fold) pool_body<D>(pa, b - n_fold);
   else fold_promote_body<kThreads>(fa, b % n_fold_x, b / n_fold_x);
 }
 
