@@ -622,6 +622,20 @@ __device__ __forceinline__ void softmax_redo(const f32x16 (&s)[2], PTile& p, Sof
   if (sr.o_live) rescale<Geo<D>::DT>(o, alpha);
 }
 
+// Before the first softmax of a run: a row that has no reference yet -- and so nothing accumulated: whatever it has
+// met so far was masked -- takes kLift above the row maximum of the scores just computed.  Without this the first
+// sub-tile of every wave would be computed against the initial reference, overflow, and be redone.
+__device__ __forceinline__ void seed_reference(const f32x16 (&s)[2], SoftmaxRun& sr) {
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    const float tmax = row_max(s[g]);
+    const bool fresh = sr.m_ref[g] == kInitMax && tmax > kInitMax;     // (false for a NaN as well)
+    const float m_new = fresh ? tmax + sr.lift : sr.m_ref[g];
+    sr.m_ref[g] = m_new;
+    sr.mc[g] = -m_new * sr.c2;
+  }
+}
+
 // One step.  KIND: its products and sub-tile offsets.  PRELOADED: the fragments of its first kPre pairs are in
 // frag already.  NEXT / NKIND: what it does for the step after it (see run_slots).  mid() is called once, early
 // in the step.  dk, dv: kNextTile only.
@@ -1002,6 +1016,7 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
     PBSA_ADDR_V(TB)                                                                                     \
     step<D, MASS, false, false, kNoLoads, StepKind<false, true, 0, 0>, false, kNextNone, void, NoMid>(  \
         vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo, frag, 0, 0, nomid);                          \
+    if (!(RAGGED)) seed_reference(sA, sr);   /* (a ragged tile's scores are not masked yet) */          \
     PBSA_LIMITS(TB, RAGGED)                                                                             \
     PBSA_NEXT_PLAN(TB)                                                                                  \
     step<D, MASS, true, RAGGED, kNoLoads, StepKind<false, true, SUB1, 0>, false, kNextNone, void, NoMid>( \
@@ -1106,6 +1121,7 @@ attention_kernel(AttnArgs a, PlanArgs<PLAN> pl) {
       d_next = t_src[min(solo_b + 1, solo_e - 1)];
       PBSA_SOLO_LANDED
       step<D, MASS, false, false, kNoLoads, StepKind<false, true, 0, 0>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sB, sA, pB, pA, sr, lim0, plan, mo, frag, 0, 0, nomid);
+      seed_reference(sA, sr);
       PBSA_SOLO_PLAN(0)
       step<D, MASS, true, false, kLoads, StepKind<false, true, SUB1, 0>, false, kNextNone, void, NoMid>(vx, kx, qf, o, sA, sB, pA, pB, sr, lim0, plan, mo, frag, 0, 0, nomid);
       PBSA_SOLO_LANDED

@@ -229,6 +229,34 @@ def test_maximum_sizes(gpu, k):
     assert (st.p_len[:, :C] > 0).all() and int(st.S_cnt.max()) > 0
 
 
+@pytest.mark.parametrize("d,B,k", [(64, 64, 672), (128, 128, 50)], ids=["d64_all_selected", "d128_top50"])
+def test_largest_selection_and_attention_shapes(gpu, d, B, k):
+    """The limits of pbsa_select_blocks and pbsa_attention_fwd: 672 local blocks (the selection kernel's eleven-wave
+    instance, 16 dimensions per round), k up to 672 (every visible block), more attended slots than the update
+    maintains; the last block ragged.  Selection exact, attention rows sampled (one per 32 and the block edges); the
+    update, whose limits are lower, is not run."""
+    H, w, C = 1, 3, 70
+    nqb = 168
+    Nq = nqb * B - 29
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale, fold=False)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, fold=False, device=DEV)
+    assert c.cap == 672 == gpu["pbsa"].PBSA_MAX_N_LOC
+    Kp, Vp = rnd(1, H, C, B, d), rnd(2, H, C, B, d)
+    pl = np.full((H, C), B, np.int32); pl[:, 5] = 3; pl[:, 6] = 0
+    ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+    st.set_persistent(Kp, Vp, pl, ids)
+    c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                     torch.from_numpy(ids))
+    lens = np.full(nqb, B, np.int32); lens[-1] = Nq - (nqb - 1) * B
+    for g in range(w):                     # the window, then the chunk that is selected from and attended
+        Kw, Vw = rnd(300 + 2 * g, H, Nq, d, scale=1.5), rnd(301 + 2 * g, H, Nq, d)
+        st.append_chunk(synth.to_blocks(Kw, B), synth.to_blocks(Vw, B), lens, g * nqb + np.arange(nqb))
+        c.append_chunk(gpu["wl"].bf16_tensor(Kw, DEV), gpu["wl"].bf16_tensor(Vw, DEV), g)
+    Q, K, V = rnd(310, H, Nq, d), rnd(311, H, Nq, d, scale=1.5), rnd(312, H, Nq, d)
+    run_both(gpu, c, st, Q, K, V, w, sample_rows(H, Nq, B, per_head=32, seed=11), f"largest d{d} B{B} k{k}", update=False)
+
+
 def test_empty_memory_and_no_selection_gives_zero(gpu):
     """No persistent block and k = 0: no key is visible; O = 0 and lse = -inf."""
     H, d, B, Nq = 1, 64, 64, 100
