@@ -161,6 +161,30 @@ def test_small_rollout_every_element(gpu, case):
         run_both(gpu, c, st, Q, K, V, g, "all", name)
 
 
+@pytest.mark.parametrize("d,B,qk", [(128, 64, 6.0), (64, 128, 8.0), (128, 128, 0.05)], ids=["peaked_d128", "peaked_d64", "flat"])
+def test_extreme_score_ranges(gpu, d, B, qk):
+    """Scores spread over hundreds of base-2 exponent units (queries and keys scaled up: the softmax is almost a
+    maximum, references are reset again and again, most probabilities underflow), and the opposite, scores that hardly
+    differ (every key counts the same): every element against the oracle, several chunks, a key block whose tokens
+    grow along the block so that a row's largest score comes late."""
+    H, Nq, w, C, k = 2, 333, 2, 3, 4
+    scale = np.float32(1.0 / math.sqrt(d))
+    st = OracleState(H, d, B, Nq, w, C, k, scale)
+    c = gpu["cache"].PbsaCache(H, d, B, Nq, w, C, k, scale, device=DEV)
+    Kp, Vp = rnd(901, H, C, B, d, scale=qk), rnd(902, H, C, B, d)
+    pl = np.tile(np.array([B, B // 3, B], np.int32), (H, 1))
+    ids = -100 - np.arange(C)[None, :].repeat(H, 0)
+    st.set_persistent(Kp, Vp, pl, ids)
+    c.set_persistent(gpu["wl"].bf16_tensor(Kp, DEV), gpu["wl"].bf16_tensor(Vp, DEV), torch.from_numpy(pl).to(DEV),
+                     torch.from_numpy(ids))
+    for g in range(w + 2):
+        Qf = qk * synth.normals(synth.stream_key(4321, "misc", 910 + 3 * g), H * Nq * d).reshape(H, Nq, d)
+        Kf = qk * synth.normals(synth.stream_key(4321, "misc", 911 + 3 * g), H * Nq * d).reshape(H, Nq, d)
+        Kf *= (0.25 + 1.5 * (np.arange(Nq) % B) / B)[None, :, None]        # late tokens of a block score higher
+        run_both(gpu, c, st, synth.to_bf16_bits(Qf), synth.to_bf16_bits(Kf), rnd(912 + 3 * g, H, Nq, d), g, "all",
+                 f"extreme d{d} B{B} x{qk}")
+
+
 def test_more_persistent_slots_than_the_update_maintains(gpu):
     """Selection and attention with 100 persistent slots (the update stops at 64): lengths from empty to
     full, compared with the oracle on every element."""
